@@ -1,0 +1,178 @@
+"""CPU oracle for GEMM (ctypes front end of ``ref_gemm.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this package; the GPU library never does, and
+this package imports nothing from it.
+
+The arithmetic lives in ``ref_gemm.c`` (plain C, triple loops; see its header
+for the definition it writes out, paper Sec. 2.1).  This module only compiles
+it with gcc, marshals numpy arrays, and offers the element-wise bound check
+``|C - C_ref| <= 4 k u G``.
+
+All matrices are column-major: a numpy array ``X`` of shape ``(cols, ld)`` in C
+order holds element (i, j) at ``X[j, i]`` which is flat index ``i + j*ld``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ref_gemm.c")
+_LIB = os.path.join(_HERE, "libref_gemm.so")
+
+U64 = 2.0 ** -53  # unit roundoff, fp64
+U32 = 2.0 ** -24  # unit roundoff, fp32
+
+
+def build(force: bool = False) -> str:
+    """Compile ref_gemm.c into libref_gemm.so (gcc, OpenMP, no FMA contraction)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+           "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _declare(_lib)
+    return _lib
+
+
+_i64 = ctypes.c_longlong
+_p = ctypes.c_void_p
+
+
+def _declare(L):
+    for name, sc in (("ref_dgemm_work", ctypes.c_double), ("ref_sgemm_work", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, sc, _p, _i64, _p, _i64,
+                      sc, _p, _i64]
+    for name, sc in (("ref_dgemm_ext", ctypes.c_double), ("ref_sgemm_ext", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, sc, _p, _i64, _p, _i64,
+                      sc, _p, _i64, _p, _p]
+    for name, sc in (("ref_dgemm_samples", ctypes.c_double), ("ref_sgemm_samples", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, sc, _p, _i64, _p, _i64,
+                      sc, _p, _i64, _i64, _p, _p, _p, _p]
+    L.ref_zgemm_split_ext.restype = ctypes.c_int
+    L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
+                                      _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
+                                      _p, _p, _p, _p]
+    L.ref_zgemm_split_work.restype = ctypes.c_int
+    L.ref_zgemm_split_work.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
+                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64]
+    L.ref_num_threads.restype = ctypes.c_int
+    L.ref_set_num_threads.argtypes = [ctypes.c_int]
+
+
+def num_threads() -> int:
+    return int(lib().ref_num_threads())
+
+
+def set_num_threads(t: int) -> None:
+    lib().ref_set_num_threads(int(t))
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    assert isinstance(a, np.ndarray) and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data
+
+
+def _ch(t: str):
+    return ctypes.c_char(t.encode("ascii"))
+
+
+def _names(dtype):
+    dtype = np.dtype(dtype)
+    if dtype == np.float64:
+        return "d", np.longdouble
+    if dtype == np.float32:
+        return "s", np.float64
+    raise TypeError(f"unsupported dtype {dtype}")
+
+
+def gemm_work(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc) -> int:
+    """In-place working-precision GEMM on C (numpy, column-major flat storage)."""
+    pre, _ = _names(C.dtype if C is not None else (A.dtype if A is not None else np.float64))
+    f = getattr(lib(), f"ref_{pre}gemm_work")
+    return int(f(_ch(ta), _ch(tb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc))
+
+
+def gemm_ext(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc):
+    """Extended-precision reference.  Returns (info, Cref, G); Cref/G have shape
+    (n, m) in C order (= m x n column-major, ld = m) in the wide dtype."""
+    pre, wide = _names(C.dtype)
+    Cref = np.zeros((max(n, 0), max(m, 0)), dtype=wide)
+    G = np.zeros_like(Cref)
+    f = getattr(lib(), f"ref_{pre}gemm_ext")
+    info = int(f(_ch(ta), _ch(tb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                 _ptr(Cref), _ptr(G)))
+    return info, Cref, G
+
+
+def gemm_samples(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, I, J):
+    """Extended-precision reference for entries (I[s], J[s]).  Returns (info, cref, g)."""
+    pre, wide = _names(C.dtype)
+    I = np.ascontiguousarray(I, dtype=np.int64)
+    J = np.ascontiguousarray(J, dtype=np.int64)
+    ns = I.size
+    cref = np.zeros(ns, dtype=wide)
+    g = np.zeros(ns, dtype=wide)
+    f = getattr(lib(), f"ref_{pre}gemm_samples")
+    info = int(f(_ch(ta), _ch(tb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                 ns, _ptr(I), _ptr(J), _ptr(cref), _ptr(g)))
+    return info, cref, g
+
+
+def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc):
+    """Complex reference on split planes.  Returns (info, Rr, Ri, Gr, Gi), long double, (n, m)."""
+    al = np.array(alpha, dtype=np.float64)
+    be = np.array(beta, dtype=np.float64)
+    shp = (max(n, 0), max(m, 0))
+    Rr, Ri, Gr, Gi = (np.zeros(shp, dtype=np.longdouble) for _ in range(4))
+    info = int(lib().ref_zgemm_split_ext(_ch(ta), _ch(tb), m, n, k, _ptr(al), _ptr(Ar), _ptr(Ai), lda,
+                                         _ptr(Br), _ptr(Bi), ldb, _ptr(be), _ptr(Cr), _ptr(Ci), ldc,
+                                         _ptr(Rr), _ptr(Ri), _ptr(Gr), _ptr(Gi)))
+    return info, Rr, Ri, Gr, Gi
+
+
+def zgemm_split_work(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc) -> int:
+    al = np.array(alpha, dtype=np.float64)
+    be = np.array(beta, dtype=np.float64)
+    return int(lib().ref_zgemm_split_work(_ch(ta), _ch(tb), m, n, k, _ptr(al), _ptr(Ar), _ptr(Ai), lda,
+                                          _ptr(Br), _ptr(Bi), ldb, _ptr(be), _ptr(Cr), _ptr(Ci), ldc))
+
+
+def bound_violations(C_test, C_ref, G, k, u, factor=4.0):
+    """Element-wise check |C_test - C_ref| <= factor * k * u * G, evaluated in the
+    wide dtype of C_ref.  Returns (number of violations, max of err / bound with
+    0/0 counted as 0).  ``k`` below 1 is treated as 1 (the alpha/beta roundings
+    remain when the product term is absent)."""
+    wide = C_ref.dtype
+    err = np.abs(C_test.astype(wide) - C_ref)
+    bnd = wide.type(factor * max(int(k), 1) * u) * G
+    viol = err > bnd
+    # NaN in the tested values must count as a violation.
+    viol |= ~np.isfinite(C_test)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(bnd > 0, err / bnd, np.where(err > 0, np.inf, 0.0))
+    return int(viol.sum()), float(ratio.max()) if ratio.size else 0.0

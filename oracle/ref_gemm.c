@@ -1,0 +1,396 @@
+/*
+ * ref_gemm.c -- CPU oracle for the real and split-plane complex GEMM.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, obviously-correct
+ * definition that the GPU library is compared against.  It shares no code with
+ * the GPU path and must never be called from it.  Only the tests, the smoke
+ * check and the benchmark's cpu_baseline leg use it.
+ *
+ * What it computes.  The paper (Sec. 2.1) writes the micro-kernel as
+ *     C += A B = sum_{p=0}^{k_c-1} a_p b_p^T          (a_p column of A, b_p^T row of B)
+ * and the loop nest of Fig. 1 sums those micro-kernel calls over all blocks.
+ * Blocking, packing and unit updates (Sec. 2.2) only change the ORDER of the
+ * k-sum, never its exact-arithmetic value, so the oracle is that value written
+ * out as a triple loop with the k-sum taken in natural order p = 0..k-1:
+ *
+ *     C[i + j*ldc] <- alpha * sum_p opA(i,p) * opB(p,j) + beta * C[i + j*ldc]
+ *     opA(i,p) = A[i + p*lda]  (trans 'N')   or  A[p + i*lda]  (trans 'T'/'C')
+ *     opB(p,j) = B[p + j*ldb]  (trans 'N')   or  B[j + p*ldb]  (trans 'T'/'C')
+ *
+ * The scalars alpha/beta, transposes, leading dimensions and argument checks
+ * are not in the paper (its kernel is C += AB); they follow the column-major
+ * BLAS convention:
+ *   - beta == 0  : C is write-only (NaN/Inf in C do not propagate);
+ *   - alpha == 0 or k == 0 : A and B are not read;
+ *   - m == 0 or n == 0 : nothing is touched;
+ *   - rows m..ldc-1 of every column of C are never touched;
+ *   - return 0, or -(1-based index) of the first illegal argument in the order
+ *     transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc.
+ *
+ * Two accumulation modes:
+ *   *_work : accumulator in the working precision, separate multiply and add
+ *            (build with -ffp-contract=off).  In place on C.  This is the timed
+ *            CPU baseline and the reference for the bit-exact integer cases.
+ *   *_ext  : accumulator one level wider (float -> double, double -> x87
+ *            long double with a 64-bit significand).  Writes the reference
+ *            value and the magnitude G = |alpha| |opA| |opB| + |beta| |C_in|
+ *            to separate dense m x n arrays of the wide type, so the
+ *            comparison  |C_gpu - C_ref| <= 4 k u G  sees a reference whose own
+ *            error is far below the bound.
+ *
+ * Loop order is j (column of C), p, i: each C(i,j) still receives its products
+ * in the order p = 0,1,..,k-1; the i loop is innermost only so that the
+ * column-major operands are walked with unit stride.  OpenMP splits the j
+ * loop; every thread owns whole columns of C, so results do not depend on the
+ * thread count.
+ */
+#include <stddef.h>
+#include <stdlib.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef long long i64;
+
+static int is_n(char t) { return t == 'N' || t == 'n'; }
+static int is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; }
+static int is_conj(char t) { return t == 'C' || t == 'c'; }
+static i64 max64(i64 a, i64 b) { return a > b ? a : b; }
+
+/* Argument check shared by all entry points (BLAS xerbla numbering). */
+static int check_args(char ta, char tb, i64 m, i64 n, i64 k,
+                      const void *A, i64 lda, const void *B, i64 ldb,
+                      const void *C, i64 ldc, int ab_needed)
+{
+    if (!is_n(ta) && !is_t(ta)) return -1;
+    if (!is_n(tb) && !is_t(tb)) return -2;
+    if (m < 0) return -3;
+    if (n < 0) return -4;
+    if (k < 0) return -5;
+    i64 rows_a = is_n(ta) ? m : k;
+    i64 rows_b = is_n(tb) ? k : n;
+    if (ab_needed && m > 0 && n > 0 && k > 0 && A == NULL) return -7;
+    if (lda < max64(1, rows_a)) return -8;
+    if (ab_needed && m > 0 && n > 0 && k > 0 && B == NULL) return -9;
+    if (ldb < max64(1, rows_b)) return -10;
+    if (m > 0 && n > 0 && C == NULL) return -12;
+    if (ldc < max64(1, m)) return -13;
+    return 0;
+}
+
+int ref_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void ref_set_num_threads(int t)
+{
+#ifdef _OPENMP
+    if (t > 0) omp_set_num_threads(t);
+#else
+    (void)t;
+#endif
+}
+
+#define OPA(i, p) (an ? A[(i) + (p) * lda] : A[(p) + (i) * lda])
+#define OPB(p, j) (bn ? B[(p) + (j) * ldb] : B[(j) + (p) * ldb])
+
+/* ------------------------------------------------------------------ */
+/* Working-precision GEMM, in place.                                    */
+/* ------------------------------------------------------------------ */
+#define DEFINE_REF_GEMM_WORK(NAME, T)                                          \
+int NAME(char ta, char tb, i64 m, i64 n, i64 k, T alpha, const T *A, i64 lda,  \
+         const T *B, i64 ldb, T beta, T *C, i64 ldc)                           \
+{                                                                              \
+    int need_ab = (alpha != (T)0);                                             \
+    int info = check_args(ta, tb, m, n, k, A, lda, B, ldb, C, ldc, need_ab);   \
+    if (info) return info;                                                     \
+    if (m == 0 || n == 0) return 0;                                            \
+    if ((alpha == (T)0 || k == 0) && beta == (T)1) return 0;                   \
+    const int an = is_n(ta), bn = is_n(tb);                                    \
+    int failed = 0;                                                            \
+    _Pragma("omp parallel")                                                    \
+    {                                                                          \
+        T *acc = (T *)malloc((size_t)m * sizeof(T));                           \
+        if (!acc) {                                                            \
+            _Pragma("omp atomic write")                                        \
+            failed = 1;                                                        \
+        }                                                                      \
+        _Pragma("omp for schedule(static)")                                    \
+        for (i64 j = 0; j < n; ++j) {                                          \
+            if (!acc) continue;                                                \
+            T *Cj = C + j * ldc;                                               \
+            if (alpha == (T)0 || k == 0) {                                     \
+                for (i64 i = 0; i < m; ++i)                                    \
+                    Cj[i] = (beta == (T)0) ? (T)0 : beta * Cj[i];              \
+                continue;                                                      \
+            }                                                                  \
+            for (i64 i = 0; i < m; ++i) acc[i] = (T)0;                         \
+            for (i64 p = 0; p < k; ++p) {                                      \
+                const T b = OPB(p, j);                                         \
+                for (i64 i = 0; i < m; ++i) {                                  \
+                    T prod = OPA(i, p) * b;                                    \
+                    acc[i] = acc[i] + prod;                                    \
+                }                                                              \
+            }                                                                  \
+            for (i64 i = 0; i < m; ++i) {                                      \
+                T t = alpha * acc[i];                                          \
+                if (beta == (T)0) Cj[i] = t;                                   \
+                else { T bc = beta * Cj[i]; Cj[i] = t + bc; }                  \
+            }                                                                  \
+        }                                                                      \
+        free(acc);                                                             \
+    }                                                                          \
+    return failed ? 1000 : 0;                                                  \
+}
+
+DEFINE_REF_GEMM_WORK(ref_dgemm_work, double)
+DEFINE_REF_GEMM_WORK(ref_sgemm_work, float)
+
+/* ------------------------------------------------------------------ */
+/* Extended-precision GEMM: reference value and magnitude G.            */
+/* Cref and G are dense m x n, column-major, leading dimension m.       */
+/* C_in is read only when beta != 0.                                    */
+/* ------------------------------------------------------------------ */
+#define DEFINE_REF_GEMM_EXT(NAME, T, W, WABS)                                  \
+int NAME(char ta, char tb, i64 m, i64 n, i64 k, T alpha, const T *A, i64 lda,  \
+         const T *B, i64 ldb, T beta, const T *C, i64 ldc, W *Cref, W *G)      \
+{                                                                              \
+    int need_ab = (alpha != (T)0);                                             \
+    int info = check_args(ta, tb, m, n, k, A, lda, B, ldb, C, ldc, need_ab);   \
+    if (info) return info;                                                     \
+    if (m == 0 || n == 0) return 0;                                            \
+    const int an = is_n(ta), bn = is_n(tb);                                    \
+    const int use_ab = (alpha != (T)0 && k > 0);                               \
+    int failed = 0;                                                            \
+    _Pragma("omp parallel")                                                    \
+    {                                                                          \
+        W *acc = (W *)malloc((size_t)m * sizeof(W));                           \
+        W *mag = (W *)malloc((size_t)m * sizeof(W));                           \
+        if (!acc || !mag) {                                                    \
+            _Pragma("omp atomic write")                                        \
+            failed = 1;                                                        \
+        }                                                                      \
+        _Pragma("omp for schedule(static)")                                    \
+        for (i64 j = 0; j < n; ++j) {                                          \
+            if (!acc || !mag) continue;                                        \
+            for (i64 i = 0; i < m; ++i) { acc[i] = 0; mag[i] = 0; }            \
+            if (use_ab) {                                                      \
+                for (i64 p = 0; p < k; ++p) {                                  \
+                    const W b = (W)OPB(p, j);                                  \
+                    for (i64 i = 0; i < m; ++i) {                              \
+                        W prod = (W)OPA(i, p) * b;                             \
+                        acc[i] += prod;                                        \
+                        mag[i] += WABS(prod);                                  \
+                    }                                                          \
+                }                                                              \
+            }                                                                  \
+            for (i64 i = 0; i < m; ++i) {                                      \
+                W r = (W)alpha * acc[i];                                       \
+                W g = WABS((W)alpha) * mag[i];                                 \
+                if (beta != (T)0) {                                            \
+                    W c = (W)C[i + j * ldc];                                   \
+                    r += (W)beta * c;                                          \
+                    g += WABS((W)beta) * WABS(c);                              \
+                }                                                              \
+                Cref[i + j * m] = r;                                           \
+                G[i + j * m] = g;                                              \
+            }                                                                  \
+        }                                                                      \
+        free(acc);                                                             \
+        free(mag);                                                             \
+    }                                                                          \
+    return failed ? 1000 : 0;                                                  \
+}
+
+DEFINE_REF_GEMM_EXT(ref_dgemm_ext, double, long double, fabsl)
+DEFINE_REF_GEMM_EXT(ref_sgemm_ext, float, double, fabs)
+
+/* ------------------------------------------------------------------ */
+/* Single entries in extended precision: for parity at sizes where the  */
+/* full triple loop is too slow.  Entry s is C(I[s], J[s]).             */
+/* ------------------------------------------------------------------ */
+#define DEFINE_REF_GEMM_SAMPLES(NAME, T, W, WABS)                              \
+int NAME(char ta, char tb, i64 m, i64 n, i64 k, T alpha, const T *A, i64 lda,  \
+         const T *B, i64 ldb, T beta, const T *C, i64 ldc, i64 ns,             \
+         const i64 *I, const i64 *J, W *cref, W *g)                            \
+{                                                                              \
+    int need_ab = (alpha != (T)0);                                             \
+    int info = check_args(ta, tb, m, n, k, A, lda, B, ldb, C, ldc, need_ab);   \
+    if (info) return info;                                                     \
+    const int an = is_n(ta), bn = is_n(tb);                                    \
+    const int use_ab = (alpha != (T)0 && k > 0);                               \
+    int bad = 0;                                                               \
+    _Pragma("omp parallel for schedule(static)")                               \
+    for (i64 s = 0; s < ns; ++s) {                                             \
+        const i64 i = I[s], j = J[s];                                          \
+        if (i < 0 || i >= m || j < 0 || j >= n) {                              \
+            _Pragma("omp atomic write")                                        \
+            bad = 1;                                                           \
+            continue;                                                          \
+        }                                                                      \
+        W acc = 0, mag = 0;                                                    \
+        if (use_ab) {                                                          \
+            for (i64 p = 0; p < k; ++p) {                                      \
+                W prod = (W)OPA(i, p) * (W)OPB(p, j);                          \
+                acc += prod;                                                   \
+                mag += WABS(prod);                                             \
+            }                                                                  \
+        }                                                                      \
+        W r = (W)alpha * acc;                                                  \
+        W gg = WABS((W)alpha) * mag;                                           \
+        if (beta != (T)0) {                                                    \
+            W c = (W)C[i + j * ldc];                                           \
+            r += (W)beta * c;                                                  \
+            gg += WABS((W)beta) * WABS(c);                                     \
+        }                                                                      \
+        cref[s] = r;                                                           \
+        g[s] = gg;                                                             \
+    }                                                                          \
+    return bad ? -14 : 0;                                                      \
+}
+
+DEFINE_REF_GEMM_SAMPLES(ref_dgemm_samples, double, long double, fabsl)
+DEFINE_REF_GEMM_SAMPLES(ref_sgemm_samples, float, double, fabs)
+
+/* ------------------------------------------------------------------ */
+/* Complex GEMM on split real/imaginary planes.                         */
+/*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/
+/* Each complex product is written out as 4 real multiplies and 2       */
+/* add/subs; the k-sum of each component runs in natural order.         */
+/* alpha = (alpha[0], alpha[1]), beta likewise.                         */
+/* beta == (0,0): C is write-only.  alpha == (0,0) or k == 0: A, B not  */
+/* read.  Argument numbering for errors: transa 1, transb 2, m 3, n 4,  */
+/* k 5, alpha 6, Ar 7, Ai 8, lda 9, Br 10, Bi 11, ldb 12, beta 13,      */
+/* Cr 14, Ci 15, ldc 16.                                                */
+/* ------------------------------------------------------------------ */
+static int check_args_z(char ta, char tb, i64 m, i64 n, i64 k, const double *alpha,
+                        const void *Ar, const void *Ai, i64 lda,
+                        const void *Br, const void *Bi, i64 ldb, const double *beta,
+                        const void *Cr, const void *Ci, i64 ldc)
+{
+    if (!is_n(ta) && !is_t(ta)) return -1;
+    if (!is_n(tb) && !is_t(tb)) return -2;
+    if (m < 0) return -3;
+    if (n < 0) return -4;
+    if (k < 0) return -5;
+    if (!alpha) return -6;
+    if (!beta) return -13;
+    int need_ab = (alpha[0] != 0.0 || alpha[1] != 0.0) && m > 0 && n > 0 && k > 0;
+    i64 rows_a = is_n(ta) ? m : k;
+    i64 rows_b = is_n(tb) ? k : n;
+    if (need_ab && !Ar) return -7;
+    if (need_ab && !Ai) return -8;
+    if (lda < max64(1, rows_a)) return -9;
+    if (need_ab && !Br) return -10;
+    if (need_ab && !Bi) return -11;
+    if (ldb < max64(1, rows_b)) return -12;
+    if (m > 0 && n > 0 && !Cr) return -14;
+    if (m > 0 && n > 0 && !Ci) return -15;
+    if (ldc < max64(1, m)) return -16;
+    return 0;
+}
+
+#define ZA(P, i, p) (an ? P[(i) + (p) * lda] : P[(p) + (i) * lda])
+#define ZB(P, p, j) (bn ? P[(p) + (j) * ldb] : P[(j) + (p) * ldb])
+
+/* Extended precision; outputs dense m x n (ld = m) long double planes:
+ * reference (Rr, Ri) and magnitudes (Gr, Gi) where
+ *   Gr = |alpha| (|Ar||Br| + |Ai||Bi|) + |beta| (|Cr| + |Ci|)   (component-wise |.| sums)
+ * is the sum of the absolute values of every real product that enters Cr
+ * (|alpha| taken as |alpha_r| + |alpha_i|, same for beta), and Gi likewise. */
+int ref_zgemm_split_ext(char ta, char tb, i64 m, i64 n, i64 k, const double *alpha,
+                        const double *Ar, const double *Ai, i64 lda,
+                        const double *Br, const double *Bi, i64 ldb, const double *beta,
+                        const double *Cr, const double *Ci, i64 ldc,
+                        long double *Rr, long double *Ri, long double *Gr, long double *Gi)
+{
+    int info = check_args_z(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc);
+    if (info) return info;
+    if (m == 0 || n == 0) return 0;
+    const int an = is_n(ta), bn = is_n(tb);
+    const long double sa = is_conj(ta) ? -1.0L : 1.0L; /* sign of Im(op(A)) */
+    const long double sb = is_conj(tb) ? -1.0L : 1.0L;
+    const long double alr = alpha[0], ali = alpha[1], ber = beta[0], bei = beta[1];
+    const int use_ab = (alr != 0 || ali != 0) && k > 0;
+    const int use_c = (ber != 0 || bei != 0);
+#pragma omp parallel for schedule(static)
+    for (i64 j = 0; j < n; ++j) {
+        for (i64 i = 0; i < m; ++i) {
+            long double pr = 0, pi = 0, mr = 0, mi = 0;
+            if (use_ab) {
+                for (i64 p = 0; p < k; ++p) {
+                    long double ar = ZA(Ar, i, p), ai = sa * ZA(Ai, i, p);
+                    long double br = ZB(Br, p, j), bi = sb * ZB(Bi, p, j);
+                    long double rr = ar * br, ii = ai * bi, ri = ar * bi, ir = ai * br;
+                    pr += rr - ii;
+                    pi += ri + ir;
+                    mr += fabsl(rr) + fabsl(ii);
+                    mi += fabsl(ri) + fabsl(ir);
+                }
+            }
+            long double cr = alr * pr - ali * pi;
+            long double ci = alr * pi + ali * pr;
+            long double gr = fabsl(alr) * mr + fabsl(ali) * mi;
+            long double gi = fabsl(alr) * mi + fabsl(ali) * mr;
+            if (use_c) {
+                long double c0 = Cr[i + j * ldc], c1 = Ci[i + j * ldc];
+                cr += ber * c0 - bei * c1;
+                ci += ber * c1 + bei * c0;
+                gr += fabsl(ber) * fabsl(c0) + fabsl(bei) * fabsl(c1);
+                gi += fabsl(ber) * fabsl(c1) + fabsl(bei) * fabsl(c0);
+            }
+            Rr[i + j * m] = cr; Ri[i + j * m] = ci;
+            Gr[i + j * m] = gr; Gi[i + j * m] = gi;
+        }
+    }
+    return 0;
+}
+
+/* Working precision (double), in place on (Cr, Ci). */
+int ref_zgemm_split_work(char ta, char tb, i64 m, i64 n, i64 k, const double *alpha,
+                         const double *Ar, const double *Ai, i64 lda,
+                         const double *Br, const double *Bi, i64 ldb, const double *beta,
+                         double *Cr, double *Ci, i64 ldc)
+{
+    int info = check_args_z(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc);
+    if (info) return info;
+    if (m == 0 || n == 0) return 0;
+    const int an = is_n(ta), bn = is_n(tb);
+    const double sa = is_conj(ta) ? -1.0 : 1.0;
+    const double sb = is_conj(tb) ? -1.0 : 1.0;
+    const double alr = alpha[0], ali = alpha[1], ber = beta[0], bei = beta[1];
+    const int use_ab = (alr != 0 || ali != 0) && k > 0;
+    const int use_c = (ber != 0 || bei != 0);
+    if (!use_ab && ber == 1.0 && bei == 0.0) return 0;
+#pragma omp parallel for schedule(static)
+    for (i64 j = 0; j < n; ++j) {
+        for (i64 i = 0; i < m; ++i) {
+            double pr = 0, pi = 0;
+            if (use_ab) {
+                for (i64 p = 0; p < k; ++p) {
+                    double ar = ZA(Ar, i, p), ai = sa * ZA(Ai, i, p);
+                    double br = ZB(Br, p, j), bi = sb * ZB(Bi, p, j);
+                    double rr = ar * br, ii = ai * bi, ri = ar * bi, ir = ai * br;
+                    pr = pr + (rr - ii);
+                    pi = pi + (ri + ir);
+                }
+            }
+            double cr = alr * pr - ali * pi;
+            double ci = alr * pi + ali * pr;
+            if (use_c) {
+                double c0 = Cr[i + j * ldc], c1 = Ci[i + j * ldc];
+                cr = cr + (ber * c0 - bei * c1);
+                ci = ci + (ber * c1 + bei * c0);
+            }
+            Cr[i + j * ldc] = cr;
+            Ci[i + j * ldc] = ci;
+        }
+    }
+    return 0;
+}
