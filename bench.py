@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep]
+
+One "step" is one call of the library's dgemm on the headline workload
+(m = n = k = 8192, column-major, alpha = 1.5, beta = -0.5, leading dimensions
+8200, entries uniform[-1, 1] from a fixed seed), operands already resident in
+HBM.  Prints ONE JSON line on stdout.  ``--sweep`` additionally times the other
+workload shapes and prints one JSON line per shape on stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "dgemm GFLOP/s and % of FP64 MFMA peak at m=n=k=8192 (1 GPU)"
+PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}   # MI355X dense MFMA peaks
+HBM_TBPS = 8.0
+
+
+def time_calls(torch, fn, steps, warmup):
+    """Wall time (host clock, synchronised both sides) and device time (events
+    on the stream the kernels are launched on) of `steps` calls."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def device_operands(torch, np, si, dtype, ta, tb, m, n, k, lda, ldb, ldc, seed_cfg, kind="uniform"):
+    rng = si.rng_for(seed_cfg, m + n + k)
+    gen = si.uniform if kind == "uniform" else si.normal
+    ra, ca = si.operand_shape(ta, m, k)
+    rb, cb = si.operand_shape(tb, k, n)
+    A = gen(rng, ra, ca, lda, dtype, sentinel=0.0)
+    B = gen(rng, rb, cb, ldb, dtype, sentinel=0.0)
+    C = gen(rng, m, n, ldc, dtype, sentinel=0.0)
+    return (A, B, C), tuple(torch.from_numpy(X).cuda() for X in (A, B, C))
+
+
+def cpu_baseline(np, oracle, host_ops, m, k, lda, ldb, ldc, alpha, beta, budget_s=15.0):
+    """Time the oracle (working precision, as it stands) on the first columns
+    of the same workload: C[:, :ns] = alpha A B[:, :ns] + beta C[:, :ns]."""
+    A, B, C = host_ops
+    cores = oracle.num_threads()
+
+    def run(ns):
+        Cs = C[:ns].copy()
+        t0 = time.perf_counter()
+        info = oracle.gemm_work("N", "N", m, ns, k, alpha, A, lda, B, ldb, beta, Cs, ldc)
+        dt = time.perf_counter() - t0
+        assert info == 0
+        return dt
+
+    ns = max(cores, 16)
+    dt = run(ns)
+    rate = 2.0 * m * ns * k / dt
+    ns2 = int(min(C.shape[0], max(ns, budget_s * rate / (2.0 * m * k))))
+    ns2 -= ns2 % cores or 0
+    ns2 = max(ns2, ns)
+    dt2 = run(ns2)
+    return {"value": round(2.0 * m * ns2 * k / dt2 / 1e9, 3), "unit": "GFLOP/s", "cores": cores,
+            "kind": "oracle",
+            "sample": f"first {ns2} of {C.shape[0]} columns of C of the same dgemm "
+                      f"(m={m}, k={k}), {dt2:.1f} s, working-precision triple loop"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--size", type=int, default=8192, help="m = n = k of the headline dgemm")
+    ap.add_argument("--variant", type=int, default=-1, help="force a tile variant (tuning)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--sweep", action="store_true", help="also time the other shapes (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
+                 "the GEMM path has no multi-GPU part.")
+
+    import numpy as np
+    import torch
+
+    import paper_1611_08035_amd as xg
+    import synth_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    xg.lib()
+    xg.xgemm_force_variant(args.variant)
+
+    nsz = args.size
+    ld = si.padded_ld(nsz)
+    alpha, beta = 1.5, -0.5
+    host_ops, (dA, dB, dC) = device_operands(torch, np, si, np.float64, "N", "N", nsz, nsz, nsz, ld, ld, ld, 2)
+
+    def step():
+        rc = xg.xgemm_dgemm("N", "N", nsz, nsz, nsz, alpha, dA, ld, dB, ld, beta, dC, ld)
+        if rc:
+            raise RuntimeError(f"xgemm_dgemm returned {rc}")
+
+    wall, dev = time_calls(torch, step, args.steps, args.warmup)
+    kernel = xg.xgemm_last_kernel_name()
+    flops = 2.0 * nsz ** 3
+    gflops = flops / wall / 1e9
+    achieved = flops / dev / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "dgemm_8192_hbm_traffic.json")
+    if nsz == 8192 and os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": METRIC, "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"dgemm NN m=n=k={nsz} alpha=1.5 beta=-0.5 lda=ldb=ldc={ld} uniform[-1,1]",
+                   "kernel": kernel},
+        "pct_of_fp64_mfma_peak": round(100.0 * gflops / 1e3 / PEAK_TFLOPS["f64"], 2),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS["f64"],
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["f64"], 4),
+                     "traffic": traffic, "kernel": kernel, "avg_launch_ms": round(dev * 1e3, 4)},
+    }
+    if not args.no_cpu:
+        import oracle
+        out["cpu_baseline"] = cpu_baseline(np, oracle, host_ops, nsz, nsz, ld, ld, ld, alpha, beta)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+    if args.sweep:
+        del dA, dB, dC, host_ops
+        sweep(torch, np, xg, si, args)
+
+
+def sweep(torch, np, xg, si, args):
+    """Other workload shapes, reported the same way (GFLOP/s, fraction of the
+    bound that applies: MFMA peak, or HBM for the thin rank-k updates)."""
+    rows = []
+    for nsz in (512, 1024, 2048, 4096):
+        ld = si.padded_ld(nsz)
+        rows.append(("d", "N", "N", nsz, nsz, nsz, ld, ld, ld, 1.5, -0.5, 2, "uniform"))
+    for nsz in (1024, 4096, 8192, 16384):
+        rows.append(("s", "N", "N", nsz, nsz, nsz, nsz, nsz, nsz, 1.0, 1.0, 3, "uniform"))
+    for ta, tb in (("N", "T"), ("T", "N"), ("T", "T")):
+        rows.append(("s", ta, tb, 4096, 4096, 4096, 4096, 4096, 4096, 1.0, 1.0, 3, "uniform"))
+    for mn in (4096, 16384):
+        for k in (64, 128, 256):
+            rows.append(("d", "N", "N", mn, mn, k, mn, k, mn, -1.0, 1.0, 4, "normal"))
+    rows.append(("d", "N", "N", 4097, 3001, 257, 4097, 257, 4097, -1.0, 1.0, 4, "normal"))
+    for prec, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, cfg, kind in rows:
+        dtype = np.float64 if prec == "d" else np.float32
+        es = 8 if prec == "d" else 4
+        _, (dA, dB, dC) = device_operands(torch, np, si, dtype, ta, tb, m, n, k, lda, ldb, ldc, cfg, kind)
+        f = xg.xgemm_dgemm if prec == "d" else xg.xgemm_sgemm
+
+        def step():
+            rc = f(ta, tb, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, ldc)
+            if rc:
+                raise RuntimeError(rc)
+
+        flops = 2.0 * m * n * k
+        steps = max(5, min(50, int(2e12 / flops)))
+        wall, dev = time_calls(torch, step, steps, 3)
+        peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
+        bytes_alg = es * (m * k + k * n + m * n * (2 if beta != 0 else 1))
+        bound = min(peak, flops / bytes_alg * HBM_TBPS * 1e12)
+        print(json.dumps({"shape": f"{prec}gemm {ta}{tb} {m}x{n}x{k}", "kernel": xg.xgemm_last_kernel_name(),
+                          "ms": round(dev * 1e3, 4), "GFLOP/s": round(flops / dev / 1e9, 1),
+                          "frac_of_mfma_peak": round(flops / dev / peak, 4),
+                          "frac_of_min_mfma_hbm_bound": round(flops / dev / bound, 4),
+                          "GB/s_algorithmic": round(bytes_alg / dev / 1e9, 1)}), file=sys.stderr, flush=True)
+        del dA, dB, dC
+    # zgemm 4096^3 on split planes: four real launches, 8 m n k flops
+    nsz = 4096
+    rng = si.rng_for(5, nsz)
+    planes = [torch.from_numpy(si.uniform(rng, nsz, nsz)).cuda() for _ in range(6)]
+
+    def zstep():
+        rc = xg.xgemm_zgemm_split("N", "N", nsz, nsz, nsz, (1.0, 0.0), planes[0], planes[1], nsz, planes[2],
+                                  planes[3], nsz, (0.0, 0.0), planes[4], planes[5], nsz, None, 0)
+        if rc:
+            raise RuntimeError(rc)
+
+    wall, dev = time_calls(torch, zstep, 10, 2)
+    flops = 8.0 * nsz ** 3
+    print(json.dumps({"shape": f"zgemm(4m) NN {nsz}^3", "ms": round(dev * 1e3, 4),
+                      "GFLOP/s": round(flops / dev / 1e9, 1),
+                      "frac_of_mfma_peak": round(flops / dev / (PEAK_TFLOPS['f64'] * 1e12), 4)}),
+          file=sys.stderr, flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,130 @@
+/*
+ * xgemm.h -- C ABI of the MI355X (gfx950) GEMM library.
+ *
+ * The operation is the one the paper reduces to its micro-kernel (Sec. 2.1):
+ *     C += A B = sum_p a_p b_p^T     (a_p: column p of A, b_p^T: row p of B)
+ * carried by the Goto/BLIS loop nest of Fig. 1, here with the column-major
+ * BLAS scalars, transposes and leading dimensions around it:
+ *
+ *     C := alpha * op(A) * op(B) + beta * C
+ *     op(A) is m x k, op(B) is k x n, C is m x n; op(X) = X or X^T.
+ *
+ * Conventions common to every entry point
+ *   - Storage is column-major: element (i, j) of X lives at X[i + j*ldx].
+ *   - Every matrix pointer is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or keeps them.  A and B must not overlap
+ *     C.  Scalars are passed by value from the host.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work; they do not synchronise.
+ *   - trans is one of N n T t C c.  For the real routines C means T.
+ *   - beta == 0: C is write-only; whatever it held (NaN, Inf) is overwritten.
+ *     alpha == 0 or k == 0: A and B are not read (and may be NULL).
+ *     m == 0 or n == 0, or (alpha == 0 or k == 0) and beta == 1: nothing is done.
+ *     Rows m..ldc-1 of each column of C are never written.
+ *   - Return value: 0 on success; -i if argument i (1-based, in the order of
+ *     the prototype) is illegal, in which case nothing was enqueued; a positive
+ *     value is the hipError_t of a failed launch.
+ *   - Thread-safe and re-entrant; no global state except the name of the kernel
+ *     variant last chosen by the calling thread (see xgemm_last_kernel_name).
+ */
+#ifndef XGEMM_H
+#define XGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Double-precision real GEMM (the micro-kernel sum of Sec. 2.1 in fp64, FP64 MFMA).
+ * Illegal-argument numbering: transa 1, transb 2, m 3, n 4, k 5, alpha 6, A 7,
+ * lda 8, B 9, ldb 10, beta 11, C 12, ldc 13.
+ *   m, n, k >= 0;  lda >= max(1, rows of stored A) where stored A is m x k for
+ *   transa = N and k x m otherwise; ldb likewise for stored B (k x n or n x k);
+ *   ldc >= max(1, m).  A, B non-NULL when they are read; C non-NULL when m, n > 0.
+ */
+int xgemm_dgemm(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                double alpha, const double *A, int64_t lda,
+                const double *B, int64_t ldb,
+                double beta, double *C, int64_t ldc, void *stream);
+
+/* Single-precision real GEMM; same contract as xgemm_dgemm (FP32 MFMA). */
+int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                float alpha, const float *A, int64_t lda,
+                const float *B, int64_t ldb,
+                float beta, float *C, int64_t ldc, void *stream);
+
+/*
+ * Double-precision complex GEMM on split planes, built from the real kernel
+ * (the paper's point that real GEMM carries complex GEMM, Abstract and Sec. 1;
+ * the "4m" arrangement: four real products per complex product):
+ *     Pr = Ar Br - Ai Bi,   Pi = Ar Bi + Ai Br,   C := alpha P + beta C.
+ * Xr / Xi are the real / imaginary planes of X, each column-major with the
+ * same leading dimension.  trans = C takes the conjugate transpose.
+ * alpha and beta are host arrays {re, im}.
+ * When alpha and beta are both real the routine is four real GEMM launches and
+ * needs no workspace.  Otherwise it needs `work`: a device buffer of `lwork`
+ * doubles, lwork >= xgemm_zgemm_worksize(m, n, alpha, beta); it holds Pr and Pi
+ * and its contents are undefined afterwards.
+ * Illegal-argument numbering: transa 1, transb 2, m 3, n 4, k 5, alpha 6, Ar 7,
+ * Ai 8, lda 9, Br 10, Bi 11, ldb 12, beta 13, Cr 14, Ci 15, ldc 16, work 17,
+ * lwork 18.
+ */
+int xgemm_zgemm_split(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                      const double alpha[2],
+                      const double *Ar, const double *Ai, int64_t lda,
+                      const double *Br, const double *Bi, int64_t ldb,
+                      const double beta[2],
+                      double *Cr, double *Ci, int64_t ldc,
+                      double *work, int64_t lwork, void *stream);
+
+/* Number of doubles of workspace xgemm_zgemm_split needs (0 when alpha and
+ * beta are real, else 2*m*n).  Host-only; touches no device. */
+size_t xgemm_zgemm_worksize(int64_t m, int64_t n, const double alpha[2], const double beta[2]);
+
+/* Library version string (static storage). */
+const char *xgemm_version(void);
+
+/* Name of the kernel variant chosen by the last xgemm_* call on the calling
+ * thread ("" before the first call, "scale" for the alpha == 0 / k == 0 path,
+ * "none" for a quick return).  For benchmarks and profiles.  Static storage. */
+const char *xgemm_last_kernel_name(void);
+
+/*
+ * Benchmark/tuning control: force the tile variant used by the real GEMM
+ * entry points on the calling thread.  `variant` is an index into the list
+ * reported by xgemm_variant_name(); -1 restores automatic selection.
+ * Returns 0, or -1 if the index is out of range.
+ */
+int xgemm_force_variant(int variant);
+
+/* Name of tile variant `variant` for precision `prec` ('d' or 's'), or NULL
+ * past the end of the list. */
+const char *xgemm_variant_name(char prec, int variant);
+
+/*
+ * MFMA-only micro-benchmark (confirms the matrix-core peak that percentages
+ * are quoted against): launches `blocks` workgroups of 256 threads, each wave
+ * issuing `iters` x 16 back-to-back register-resident MFMAs (FP64 16x16x4 for
+ * prec 'd', FP32 32x32x2 for 's') with no memory traffic in the loop.  `sink`
+ * is a device buffer of at least blocks*256 elements of that precision, written
+ * once at the end.  Returns 0 or a hipError_t.  flops per launch =
+ * blocks * 4 waves * iters * 16 * (2*16*16*4 for 'd', 2*32*32*2 for 's').
+ */
+int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *stream);
+
+/*
+ * Writes the register layout of one MFMA result to `out` (device, 64*R ints
+ * where R = 4 for 'd', 16 for 's'): out[lane*R + r] = 256*i + j for the matrix
+ * element D(i, j) held by lane `lane`, register r, found by multiplying one-hot
+ * operands.  Used by the tests to confirm the accumulator layout the kernels
+ * assume.  Returns 0 or a hipError_t.
+ */
+int xgemm_mfma_layout_probe(char prec, int *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XGEMM_H */

@@ -75,6 +75,10 @@ def _declare(L):
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
                                       _p, _p, _p, _p]
+    L.ref_zgemm_split_samples.restype = ctypes.c_int
+    L.ref_zgemm_split_samples.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
+                                          _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
+                                          _i64, _p, _p, _p, _p, _p, _p]
     L.ref_zgemm_split_work.restype = ctypes.c_int
     L.ref_zgemm_split_work.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                        _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64]
@@ -153,6 +157,19 @@ def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, 
                                          _ptr(Br), _ptr(Bi), ldb, _ptr(be), _ptr(Cr), _ptr(Ci), ldc,
                                          _ptr(Rr), _ptr(Ri), _ptr(Gr), _ptr(Gi)))
     return info, Rr, Ri, Gr, Gi
+
+
+def zgemm_split_samples(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc, I, J):
+    """Entries (I[s], J[s]) of the complex reference.  Returns (info, rr, ri, gr, gi)."""
+    al = np.array(alpha, dtype=np.float64)
+    be = np.array(beta, dtype=np.float64)
+    I = np.ascontiguousarray(I, dtype=np.int64)
+    J = np.ascontiguousarray(J, dtype=np.int64)
+    rr, ri, gr, gi = (np.zeros(I.size, dtype=np.longdouble) for _ in range(4))
+    info = int(lib().ref_zgemm_split_samples(_ch(ta), _ch(tb), m, n, k, _ptr(al), _ptr(Ar), _ptr(Ai), lda,
+                                             _ptr(Br), _ptr(Bi), ldb, _ptr(be), _ptr(Cr), _ptr(Ci), ldc,
+                                             I.size, _ptr(I), _ptr(J), _ptr(rr), _ptr(ri), _ptr(gr), _ptr(gi)))
+    return info, rr, ri, gr, gi
 
 
 def zgemm_split_work(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc) -> int:

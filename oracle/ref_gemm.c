@@ -301,9 +301,9 @@ static int check_args_z(char ta, char tb, i64 m, i64 n, i64 k, const double *alp
 
 /* Extended precision; outputs dense m x n (ld = m) long double planes:
  * reference (Rr, Ri) and magnitudes (Gr, Gi) where
- *   Gr = |alpha| (|Ar||Br| + |Ai||Bi|) + |beta| (|Cr| + |Ci|)   (component-wise |.| sums)
- * is the sum of the absolute values of every real product that enters Cr
- * (|alpha| taken as |alpha_r| + |alpha_i|, same for beta), and Gi likewise. */
+ *   Gr = |al_r| (|Ar||Br| + |Ai||Bi|) + |al_i| (|Ar||Bi| + |Ai||Br|) + |be_r||Cr| + |be_i||Ci|
+ * i.e. the sum of the absolute values of every real product that enters Cr,
+ * and Gi likewise with the roles of the real and imaginary parts exchanged. */
 int ref_zgemm_split_ext(char ta, char tb, i64 m, i64 n, i64 k, const double *alpha,
                         const double *Ar, const double *Ai, i64 lda,
                         const double *Br, const double *Bi, i64 ldb, const double *beta,
@@ -350,6 +350,58 @@ int ref_zgemm_split_ext(char ta, char tb, i64 m, i64 n, i64 k, const double *alp
         }
     }
     return 0;
+}
+
+/* Single entries (I[s], J[s]) of the complex reference, extended precision. */
+int ref_zgemm_split_samples(char ta, char tb, i64 m, i64 n, i64 k, const double *alpha,
+                            const double *Ar, const double *Ai, i64 lda,
+                            const double *Br, const double *Bi, i64 ldb, const double *beta,
+                            const double *Cr, const double *Ci, i64 ldc, i64 ns, const i64 *I, const i64 *J,
+                            long double *rr_out, long double *ri_out, long double *gr_out, long double *gi_out)
+{
+    int info = check_args_z(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc);
+    if (info) return info;
+    const int an = is_n(ta), bn = is_n(tb);
+    const long double sa = is_conj(ta) ? -1.0L : 1.0L;
+    const long double sb = is_conj(tb) ? -1.0L : 1.0L;
+    const long double alr = alpha[0], ali = alpha[1], ber = beta[0], bei = beta[1];
+    const int use_ab = (alr != 0 || ali != 0) && k > 0;
+    const int use_c = (ber != 0 || bei != 0);
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (i64 s = 0; s < ns; ++s) {
+        const i64 i = I[s], j = J[s];
+        if (i < 0 || i >= m || j < 0 || j >= n) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
+        long double pr = 0, pi = 0, mr = 0, mi = 0;
+        if (use_ab) {
+            for (i64 p = 0; p < k; ++p) {
+                long double ar = ZA(Ar, i, p), ai = sa * ZA(Ai, i, p);
+                long double br = ZB(Br, p, j), bi = sb * ZB(Bi, p, j);
+                long double rr = ar * br, ii = ai * bi, ri = ar * bi, ir = ai * br;
+                pr += rr - ii;
+                pi += ri + ir;
+                mr += fabsl(rr) + fabsl(ii);
+                mi += fabsl(ri) + fabsl(ir);
+            }
+        }
+        long double cr = alr * pr - ali * pi;
+        long double ci = alr * pi + ali * pr;
+        long double gr = fabsl(alr) * mr + fabsl(ali) * mi;
+        long double gi = fabsl(alr) * mi + fabsl(ali) * mr;
+        if (use_c) {
+            long double c0 = Cr[i + j * ldc], c1 = Ci[i + j * ldc];
+            cr += ber * c0 - bei * c1;
+            ci += ber * c1 + bei * c0;
+            gr += fabsl(ber) * fabsl(c0) + fabsl(bei) * fabsl(c1);
+            gi += fabsl(ber) * fabsl(c1) + fabsl(bei) * fabsl(c0);
+        }
+        rr_out[s] = cr; ri_out[s] = ci; gr_out[s] = gr; gi_out[s] = gi;
+    }
+    return bad ? -19 : 0;
 }
 
 /* Working precision (double), in place on (Cr, Ci). */

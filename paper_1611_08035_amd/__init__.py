@@ -1,0 +1,24 @@
+"""MI355X-native GEMM (dgemm / sgemm / split-plane zgemm) behind a C ABI.
+
+The compute lives in ``libxgemm.so`` (hand-written HIP for gfx950, built by
+``python -m paper_1611_08035_amd.build``).  This package is only the thin
+binding: argument marshalling from torch tensors (device memory, streams) to
+the C entry points declared in ``include/xgemm.h``.  There is no CPU fallback:
+if the library is missing, every call raises.
+"""
+from .xgemm import (  # noqa: F401
+    XgemmError,
+    lib,
+    library_path,
+    xgemm_dgemm,
+    xgemm_sgemm,
+    xgemm_zgemm_split,
+    xgemm_zgemm_worksize,
+    xgemm_version,
+    xgemm_last_kernel_name,
+    xgemm_force_variant,
+    xgemm_variant_name,
+    xgemm_mfma_peak_probe,
+    xgemm_mfma_layout_probe,
+    EXPORTS,
+)

@@ -1,0 +1,352 @@
+// gemm_kernel.hip.h -- the GEMM macro/micro-kernel for CDNA4 (gfx950).
+//
+// The structure is the Goto/BLIS loop nest of the paper's Fig. 1 re-derived for
+// the GPU memory hierarchy:
+//
+//   paper (CPU)                          here (MI355X)
+//   ---------------------------------    -----------------------------------------
+//   loops over n_c, m_c blocks of C      one workgroup per MT_M x MT_N macro-tile
+//   loop over k_c + packing of A, B      K loop over KT-deep slabs; each slab of
+//     into contiguous micro-panels         op(A), op(B) is staged HBM/L2 -> LDS in
+//     (A column-major, B row-major,        [k][m] / [k][n] order (the same two
+//     Sec. 2.1)                            layouts as the packed micro-panels)
+//   micro-kernel: m_r x n_r block of C   one wavefront owns a WT_M x WT_N block of
+//     in registers, loop of rank-1         C in accumulator registers for the whole
+//     updates C += a_p b_p^T               K loop
+//   unit update m_v x n_u (Sec. 2.2)     one MFMA instruction: a 16x16 (fp64) or
+//                                          32x32 (fp32) block of C, rank-4 / rank-2
+//   register budget (Sec. 5.4, the       accumulators + two operand fragment sets +
+//     N_updates equation), no spills       in-flight global loads <= 256 VGPRs so two
+//                                          waves share a SIMD; zero scratch
+//   software pipelining: ramp-up /       global loads of slab t+1 are issued before
+//     steady state / flush (Sec. 1,        the MFMAs of slab t and written to the
+//     Sec. 5.5)                            other LDS buffer after them; one barrier
+//                                          per slab
+//   C += c_reg (Fig. "code skeleton")    epilogue C = alpha*acc + beta*C, predicated
+//                                          on the ragged edges
+//
+// Accumulator layout need not be the memory layout (the lesson of the paper's
+// shuffle kernels, Sec. 3.2): the MFMA is fed op(B) as its row operand and
+// op(A) as its column operand, i.e. it computes a block of C^T, so that the 16
+// (or 32) consecutive lanes that hold one accumulator row map to consecutive
+// rows m of column-major C and the epilogue's loads and stores are contiguous.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace xg {
+
+typedef double acc_d4 __attribute__((ext_vector_type(4)));
+typedef float acc_f16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------
+// MFMA traits: operand and accumulator register layouts (wave64).
+//   operand:  lane l supplies element (idx = op_idx(l), k = op_k(l)) of the
+//             MI x KI row operand, and (k = op_k(l), idx = op_idx(l)) of the
+//             KI x MI column operand.
+//   result :  register r of lane l holds D(d_row(l, r), d_col(l)).
+// ---------------------------------------------------------------------------
+template <typename T> struct Mfma;
+
+template <> struct Mfma<double> {
+    static constexpr int MI = 16, KI = 4, NR = 4;
+    using acc_t = acc_d4;
+    static __device__ __forceinline__ acc_t mma(double row_op, double col_op, acc_t c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(row_op, col_op, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int op_idx(int lane) { return lane & 15; }
+    static __device__ __forceinline__ int op_k(int lane) { return lane >> 4; }
+    static __device__ __forceinline__ int d_row(int lane, int r) { return (lane >> 4) + 4 * r; }
+    static __device__ __forceinline__ int d_col(int lane) { return lane & 15; }
+};
+
+template <> struct Mfma<float> {
+    static constexpr int MI = 32, KI = 2, NR = 16;
+    using acc_t = acc_f16;
+    static __device__ __forceinline__ acc_t mma(float row_op, float col_op, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(row_op, col_op, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int op_idx(int lane) { return lane & 31; }
+    static __device__ __forceinline__ int op_k(int lane) { return lane >> 5; }
+    static __device__ __forceinline__ int d_row(int lane, int r) {
+        return (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
+    }
+    static __device__ __forceinline__ int d_col(int lane) { return lane & 31; }
+};
+
+template <typename T> struct GemmArgs {
+    const T *A, *B;
+    T *C;
+    int64_t lda, ldb, ldc;
+    int m, n, k;
+    T alpha, beta;
+    int ntm, ntn;   // macro-tiles along m and n
+};
+
+// ---------------------------------------------------------------------------
+// Staging of one MT x KT slab of an operand from global memory into LDS in
+// [k][mn] order with row stride S (the GPU form of the paper's packing).
+//   KCONTIG == false: element (mn, p) is at base[mn + p*ld]  (A with trans=N, B with trans=T)
+//   KCONTIG == true : element (mn, p) is at base[p + mn*ld]  (A with trans=T, B with trans=N)
+// `base` points at the slab origin (tile row/col mn0, depth p0).
+// Each thread moves NV vectors of 16 bytes; they sit in registers between the
+// load (issued before the MFMAs of the current slab) and the LDS write (after).
+// ---------------------------------------------------------------------------
+template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager {
+    static constexpr int V = 16 / (int)sizeof(T);
+    static constexpr int NV = (MT * KT) / (NT * V);
+    static_assert((MT * KT) % (NT * V) == 0, "slab must divide evenly over the threads");
+    static_assert(KT % V == 0 && MT % V == 0, "vector width must divide the slab");
+    typedef T vec_t __attribute__((ext_vector_type(V)));
+
+    // position of vector q of thread tid inside the slab: first element (mn, p)
+    static __device__ __forceinline__ void pos(int tid, int q, int &mn, int &p) {
+        const int v = tid + q * NT;
+        if (!KCONTIG) {
+            mn = (v % (MT / V)) * V;
+            p = v / (MT / V);
+        } else {
+            p = (v % (KT / V)) * V;
+            mn = v / (KT / V);
+        }
+    }
+
+    // all of the slab is in bounds and 16-byte aligned
+    static __device__ __forceinline__ void load_fast(vec_t (&r)[NV], const T *base, int64_t ld, int tid) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            int mn, p;
+            pos(tid, q, mn, p);
+            const T *src = KCONTIG ? base + p + (int64_t)mn * ld : base + mn + (int64_t)p * ld;
+            r[q] = *reinterpret_cast<const vec_t *>(src);
+        }
+    }
+
+    // element-wise, zero-filled outside [0, mn_lim) x [0, k_lim); no alignment assumed
+    static __device__ __forceinline__ void load_guarded(vec_t (&r)[NV], const T *base, int64_t ld, int tid,
+                                                        int mn_lim, int k_lim) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            int mn, p;
+            pos(tid, q, mn, p);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int mne = KCONTIG ? mn : mn + e;
+                const int pe = KCONTIG ? p + e : p;
+                T x = T(0);
+                if (mne < mn_lim && pe < k_lim)
+                    x = KCONTIG ? base[pe + (int64_t)mne * ld] : base[mne + (int64_t)pe * ld];
+                r[q][e] = x;
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void store(const vec_t (&r)[NV], T *s, int tid) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            int mn, p;
+            pos(tid, q, mn, p);
+            if (!KCONTIG) {
+                *reinterpret_cast<vec_t *>(s + p * S + mn) = r[q];
+            } else {
+#pragma unroll
+                for (int e = 0; e < V; ++e) s[(p + e) * S + mn] = r[q][e];
+            }
+        }
+    }
+};
+
+// blockIdx -> macro-tile.  Workgroups are dealt round-robin to the 8 XCDs, each
+// with its own L2: give every XCD one contiguous run of the tile order, and
+// walk that order in bands of GROUP_M tile-rows so that the tiles resident on
+// an XCD at one time share A row-panels and B column-panels.
+static constexpr int NUM_XCD = 8;
+static constexpr int GROUP_M = 8;
+
+static __device__ __forceinline__ void tile_of_block(int bid, int ntm, int ntn, int &tm, int &tn) {
+    const int nt = ntm * ntn;
+    const int per = (nt + NUM_XCD - 1) / NUM_XCD;
+    int tall = nt % NUM_XCD;
+    if (tall == 0) tall = NUM_XCD;
+    const int xcd = bid % NUM_XCD, loc = bid / NUM_XCD;
+    const int lin = xcd < tall ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
+    const int width = GROUP_M * ntn;
+    const int grp = lin / width;
+    const int first = grp * GROUP_M;
+    const int gsz = (ntm - first) < GROUP_M ? (ntm - first) : GROUP_M;
+    const int in = lin - grp * width;
+    tm = first + in % gsz;
+    tn = in / gsz;
+}
+
+// ---------------------------------------------------------------------------
+// Tile configuration.
+// ---------------------------------------------------------------------------
+template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC_> struct TileCfg {
+    using M = Mfma<T>;
+    static constexpr int MT_M = MT_M_, MT_N = MT_N_, KT = KT_, WGM = WGM_, WGN = WGN_, OCC = OCC_;
+    static constexpr int NT = WGM * WGN * 64;
+    static constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
+    static constexpr int TM = WT_M / M::MI, TN = WT_N / M::MI;
+    static_assert(WT_M % M::MI == 0 && WT_N % M::MI == 0, "wave tile must be whole MFMA tiles");
+    static_assert(KT % M::KI == 0, "slab depth must be whole MFMA depths");
+    // LDS row strides.  Rows are read 16/32 consecutive elements at a time
+    // (conflict-free for any stride); the stride only has to keep 16-byte
+    // alignment for the vector writes of MN-contiguous slabs.
+    static constexpr int SA = MT_M, SB = MT_N;
+    static constexpr size_t LDS_BYTES = 2 * (size_t)KT * (SA + SB) * sizeof(T);
+};
+
+template <typename T, typename Cfg, bool AK, bool BK, bool FAST>
+__global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<T> g) {
+    using M = Mfma<T>;
+    constexpr int MT_M = Cfg::MT_M, MT_N = Cfg::MT_N, KT = Cfg::KT, NT = Cfg::NT;
+    constexpr int SA = Cfg::SA, SB = Cfg::SB, TM = Cfg::TM, TN = Cfg::TN;
+    using StA = Stager<T, MT_M, KT, SA, NT, AK>;
+    using StB = Stager<T, MT_N, KT, SB, NT, BK>;
+
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    T *const lds = reinterpret_cast<T *>(lds_raw);
+    // [buffer][A slab | B slab]
+    constexpr int BUF = KT * (SA + SB);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm0 = (wave % Cfg::WGM) * Cfg::WT_M;
+    const int wn0 = (wave / Cfg::WGM) * Cfg::WT_N;
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.ntm, g.ntn, tm, tn);
+    const int m0 = tm * MT_M, n0 = tn * MT_N;
+    const int m_lim = g.m - m0, n_lim = g.n - n0;   // rows / cols of this tile inside C
+    const bool interior = FAST && m_lim >= MT_M && n_lim >= MT_N;
+
+    // slab origins at depth 0
+    const T *pa = AK ? g.A + (int64_t)m0 * g.lda : g.A + m0;
+    const T *pb = BK ? g.B + (int64_t)n0 * g.ldb : g.B + (int64_t)n0;
+    const int64_t step_a = AK ? (int64_t)KT : (int64_t)KT * g.lda;
+    const int64_t step_b = BK ? (int64_t)KT : (int64_t)KT * g.ldb;
+
+    typename M::acc_t acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < M::NR; ++r) acc[j][i][r] = T(0);
+
+    typename StA::vec_t ra[StA::NV];
+    typename StB::vec_t rb[StB::NV];
+
+    const int nslab = (g.k + KT - 1) / KT;
+
+    auto fetch = [&](int t) {
+        const int k_lim = g.k - t * KT;
+        if (interior && k_lim >= KT) {
+            StA::load_fast(ra, pa, g.lda, tid);
+            StB::load_fast(rb, pb, g.ldb, tid);
+        } else {
+            StA::load_guarded(ra, pa, g.lda, tid, m_lim, k_lim);
+            StB::load_guarded(rb, pb, g.ldb, tid, n_lim, k_lim);
+        }
+        pa += step_a;
+        pb += step_b;
+    };
+    auto stash = [&](int buf) {
+        StA::store(ra, lds + buf * BUF, tid);
+        StB::store(rb, lds + buf * BUF + KT * SA, tid);
+    };
+
+    // ramp-up: slab 0 into LDS buffer 0
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    const int kq = M::op_k(lane), iq = M::op_idx(lane);
+
+    for (int t = 0; t < nslab; ++t) {
+        const bool more = (t + 1 < nslab);
+        if (more) fetch(t + 1);   // global loads in flight under the MFMAs below
+
+        const T *sa = lds + (t & 1) * BUF + kq * SA + wm0 + iq;
+        const T *sb = lds + (t & 1) * BUF + KT * SA + kq * SB + wn0 + iq;
+#pragma unroll
+        for (int kk = 0; kk < KT; kk += M::KI) {
+            T fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = sa[kk * SA + i * M::MI];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = sb[kk * SB + j * M::MI];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[j][i] = M::mma(fb[j], fa[i], acc[j][i]);
+        }
+
+        if (more) stash((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // flush: C = alpha*acc + beta*C on the part of the tile inside C
+    const T alpha = g.alpha, beta = g.beta;
+    const bool use_c = (beta != T(0));
+    const int mc = wm0 + M::d_col(lane);
+    if (m_lim >= MT_M && n_lim >= MT_N) {
+        // whole tile inside C: no predicates; the loads of one accumulator
+        // row-block are all issued before the first dependent store
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            T *cp[M::NR];
+            T cold[M::NR][TM];
+#pragma unroll
+            for (int r = 0; r < M::NR; ++r)
+                cp[r] = g.C + (int64_t)(n0 + wn0 + j * M::MI + M::d_row(lane, r)) * g.ldc + m0 + mc;
+            if (use_c) {
+#pragma unroll
+                for (int r = 0; r < M::NR; ++r)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) cold[r][i] = cp[r][i * M::MI];
+            }
+#pragma unroll
+            for (int r = 0; r < M::NR; ++r)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    T v = alpha * acc[j][i][r];
+                    if (use_c) v += beta * cold[r][i];
+                    cp[r][i * M::MI] = v;
+                }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int r = 0; r < M::NR; ++r) {
+                const int nn = wn0 + j * M::MI + M::d_row(lane, r);
+                T *crow = g.C + (int64_t)(n0 + nn) * g.ldc + m0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int mm = mc + i * M::MI;
+                    if (mm < m_lim && nn < n_lim) {
+                        T v = alpha * acc[j][i][r];
+                        if (use_c) v += beta * crow[mm];
+                        crow[mm] = v;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// C := beta * C (beta == 0 stores zeros without reading), the alpha == 0 / k == 0 path.
+template <typename T>
+__global__ void __launch_bounds__(256) scale_kernel(T *C, int64_t ldc, int m, int n, T beta) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= m) return;
+    for (int j = blockIdx.y; j < n; j += gridDim.y) {
+        T *p = C + i + (int64_t)j * ldc;
+        *p = (beta == T(0)) ? T(0) : beta * *p;
+    }
+}
+
+}  // namespace xg

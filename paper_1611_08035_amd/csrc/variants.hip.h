@@ -1,0 +1,48 @@
+// variants.hip.h -- table of tile variants and the launcher shared by the
+// per-precision translation units.  Included once per precision with T fixed.
+#pragma once
+#include "gemm_kernel.hip.h"
+
+namespace xg {
+
+template <typename T> struct VariantEntry {
+    const char *name;
+    int mt_m, mt_n;
+    // launch(transA is K-contiguous, transB is K-contiguous, fast path allowed, args, stream)
+    hipError_t (*launch)(bool ak, bool bk, bool fast, const GemmArgs<T> &g, hipStream_t st);
+};
+
+template <typename T, typename Cfg, bool AK, bool BK, bool FAST>
+static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
+    auto kern = gemm_kernel<T, Cfg, AK, BK, FAST>;
+    // LDS beyond 64 KiB has to be requested explicitly; done once per kernel.
+    static hipError_t attr = (Cfg::LDS_BYTES > 65536)
+                                 ? hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)Cfg::LDS_BYTES)
+                                 : hipSuccess;
+    if (attr != hipSuccess) return attr;
+    const dim3 grid((unsigned)(g.ntm * g.ntn)), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, st, g);
+    return hipGetLastError();
+}
+
+template <typename T, typename Cfg>
+static hipError_t launch_cfg(bool ak, bool bk, bool fast, const GemmArgs<T> &g0, hipStream_t st) {
+    GemmArgs<T> g = g0;
+    g.ntm = (g.m + Cfg::MT_M - 1) / Cfg::MT_M;
+    g.ntn = (g.n + Cfg::MT_N - 1) / Cfg::MT_N;
+    const int sel = (ak ? 4 : 0) | (bk ? 2 : 0) | (fast ? 1 : 0);
+    switch (sel) {
+        case 0: return launch_one<T, Cfg, false, false, false>(g, st);
+        case 1: return launch_one<T, Cfg, false, false, true>(g, st);
+        case 2: return launch_one<T, Cfg, false, true, false>(g, st);
+        case 3: return launch_one<T, Cfg, false, true, true>(g, st);
+        case 4: return launch_one<T, Cfg, true, false, false>(g, st);
+        case 5: return launch_one<T, Cfg, true, false, true>(g, st);
+        case 6: return launch_one<T, Cfg, true, true, false>(g, st);
+        default: return launch_one<T, Cfg, true, true, true>(g, st);
+    }
+}
+
+}  // namespace xg

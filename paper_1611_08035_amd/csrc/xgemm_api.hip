@@ -1,0 +1,278 @@
+// xgemm_api.hip -- the C ABI: argument checks, quick returns, variant choice,
+// launches; the split-plane complex GEMM as four real GEMMs; probes.
+#include "../../include/xgemm.h"
+#include "tables.h"
+
+#include <string.h>
+
+namespace {
+
+using namespace xg;
+
+thread_local const char *t_last_kernel = "";
+thread_local int t_forced_variant = -1;
+
+inline bool is_n(char t) { return t == 'N' || t == 'n'; }
+inline bool is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; }
+inline bool is_c(char t) { return t == 'C' || t == 'c'; }
+inline int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
+constexpr int64_t DIM_MAX = 0x7fffffff;   // tile indices and extents are 32-bit inside the kernels
+
+template <typename T> const VariantEntry<T> *table(int *n);
+template <> const VariantEntry<double> *table<double>(int *n) { return d_variant_table(n); }
+template <> const VariantEntry<float> *table<float>(int *n) { return s_variant_table(n); }
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Pick a tile variant: the largest macro-tile that still gives every compute
+// unit work (256 CUs, two workgroups resident on each), else the smallest.
+template <typename T> int choose_variant(int64_t m, int64_t n, const VariantEntry<T> *tab, int nv) {
+    if (t_forced_variant >= 0 && t_forced_variant < nv) return t_forced_variant;
+    int best = 0;
+    for (int v = 0; v < nv; ++v) {
+        const int64_t tiles = ((m + tab[v].mt_m - 1) / tab[v].mt_m) * ((n + tab[v].mt_n - 1) / tab[v].mt_n);
+        if (tiles >= 256) return v;      // table is ordered by preference
+        best = v;
+    }
+    return best;
+}
+
+template <typename T>
+int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
+              const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream) {
+    t_last_kernel = "none";
+    if (!is_n(ta) && !is_t(ta)) return -1;
+    if (!is_n(tb) && !is_t(tb)) return -2;
+    if (m < 0 || m > DIM_MAX) return -3;
+    if (n < 0 || n > DIM_MAX) return -4;
+    if (k < 0 || k > DIM_MAX) return -5;
+    const bool ab_read = (alpha != T(0)) && m > 0 && n > 0 && k > 0;
+    const int64_t rows_a = is_n(ta) ? m : k, rows_b = is_n(tb) ? k : n;
+    if (ab_read && !A) return -7;
+    if (lda < max64(1, rows_a)) return -8;
+    if (ab_read && !B) return -9;
+    if (ldb < max64(1, rows_b)) return -10;
+    if (m > 0 && n > 0 && !C) return -12;
+    if (ldc < max64(1, m)) return -13;
+
+    if (m == 0 || n == 0) return 0;
+    if (!ab_read && beta == T(1)) return 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (!ab_read) {
+        t_last_kernel = "scale";
+        const dim3 grid((unsigned)((m + 255) / 256), (unsigned)(n < 1024 ? n : 1024));
+        hipLaunchKernelGGL(scale_kernel<T>, grid, dim3(256), 0, st, C, ldc, (int)m, (int)n, beta);
+        return (int)hipGetLastError();
+    }
+
+    int nv = 0;
+    const VariantEntry<T> *tab = table<T>(&nv);
+    const int v = choose_variant<T>(m, n, tab, nv);
+    GemmArgs<T> g;
+    g.A = A; g.B = B; g.C = C;
+    g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+    g.m = (int)m; g.n = (int)n; g.k = (int)k;
+    g.alpha = alpha; g.beta = beta;
+    g.ntm = g.ntn = 0;
+    // 16-byte vector loads need aligned bases and column strides
+    const bool fast = aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0;
+    t_last_kernel = tab[v].name;
+    // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
+    return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
+}
+
+// Elementwise combine for the complex path with complex scalars:
+//   Cr = ar Pr - ai Pi + br Cr - bi Ci,   Ci = ar Pi + ai Pr + br Ci + bi Cr
+// have_p == 0: the product term is absent (alpha == 0 or k == 0), P is not read.
+// beta == 0: C is not read.
+__global__ void __launch_bounds__(256) zcombine_kernel(double *Cr, double *Ci, int64_t ldc, const double *Pr,
+                                                      const double *Pi, int m, int n, double ar, double ai,
+                                                      double br, double bi, int have_p) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= m) return;
+    const bool use_c = (br != 0.0 || bi != 0.0);
+    for (int j = blockIdx.y; j < n; j += gridDim.y) {
+        double xr = 0.0, xi = 0.0;
+        if (have_p) {
+            const double pr = Pr[i + (int64_t)j * m], pi = Pi[i + (int64_t)j * m];
+            xr = ar * pr - ai * pi;
+            xi = ar * pi + ai * pr;
+        }
+        double *cr = Cr + i + (int64_t)j * ldc, *ci = Ci + i + (int64_t)j * ldc;
+        if (use_c) {
+            const double c0 = *cr, c1 = *ci;
+            xr += br * c0 - bi * c1;
+            xi += br * c1 + bi * c0;
+        }
+        *cr = xr;
+        *ci = xi;
+    }
+}
+
+// Register-resident MFMA loop, no memory traffic: 16 independent accumulator
+// tiles per wave so that back-to-back issue never waits on a dependency.
+template <typename T> __global__ void __launch_bounds__(256) mfma_peak_kernel(T *sink, int iters) {
+    using M = Mfma<T>;
+    typename M::acc_t acc[16];
+#pragma unroll
+    for (int a = 0; a < 16; ++a)
+#pragma unroll
+        for (int r = 0; r < M::NR; ++r) acc[a][r] = T(0);
+    T x = T(threadIdx.x & 7) * T(0.125), y = T((threadIdx.x >> 3) & 7) * T(0.25);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 16; ++a) acc[a] = M::mma(x, y, acc[a]);
+    }
+    T s = T(0);
+#pragma unroll
+    for (int a = 0; a < 16; ++a)
+#pragma unroll
+        for (int r = 0; r < M::NR; ++r) s += acc[a][r];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// D = R * Cc with R(i, 0) = i, Cc(0, j) = 1 gives D(i, j) = i; with R(i, 0) = 1,
+// Cc(0, j) = j gives D(i, j) = j.  Only k = 0 carries data.
+template <typename T> __global__ void __launch_bounds__(64) mfma_layout_kernel(int *out) {
+    using M = Mfma<T>;
+    const int lane = threadIdx.x;
+    const bool k0 = (M::op_k(lane) == 0);
+    const T idx = T(M::op_idx(lane));
+    typename M::acc_t di, dj;
+#pragma unroll
+    for (int r = 0; r < M::NR; ++r) { di[r] = T(0); dj[r] = T(0); }
+    di = M::mma(k0 ? idx : T(0), k0 ? T(1) : T(0), di);
+    dj = M::mma(k0 ? T(1) : T(0), k0 ? idx : T(0), dj);
+#pragma unroll
+    for (int r = 0; r < M::NR; ++r) out[lane * M::NR + r] = 256 * (int)di[r] + (int)dj[r];
+}
+
+}  // namespace
+
+extern "C" {
+
+int xgemm_dgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double *A,
+                int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream) {
+    return gemm_impl<double>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
+                int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream) {
+    return gemm_impl<float>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+size_t xgemm_zgemm_worksize(int64_t m, int64_t n, const double alpha[2], const double beta[2]) {
+    if (!alpha || !beta || m <= 0 || n <= 0) return 0;
+    if (alpha[1] == 0.0 && beta[1] == 0.0) return 0;
+    return (size_t)2 * (size_t)m * (size_t)n;
+}
+
+int xgemm_zgemm_split(char transa, char transb, int64_t m, int64_t n, int64_t k, const double alpha[2],
+                      const double *Ar, const double *Ai, int64_t lda, const double *Br, const double *Bi,
+                      int64_t ldb, const double beta[2], double *Cr, double *Ci, int64_t ldc, double *work,
+                      int64_t lwork, void *stream) {
+    t_last_kernel = "none";
+    if (!is_n(transa) && !is_t(transa)) return -1;
+    if (!is_n(transb) && !is_t(transb)) return -2;
+    if (m < 0 || m > DIM_MAX) return -3;
+    if (n < 0 || n > DIM_MAX) return -4;
+    if (k < 0 || k > DIM_MAX) return -5;
+    if (!alpha) return -6;
+    if (!beta) return -13;
+    const double ar = alpha[0], ai = alpha[1], br = beta[0], bi = beta[1];
+    const bool ab_read = (ar != 0.0 || ai != 0.0) && m > 0 && n > 0 && k > 0;
+    const int64_t rows_a = is_n(transa) ? m : k, rows_b = is_n(transb) ? k : n;
+    if (ab_read && !Ar) return -7;
+    if (ab_read && !Ai) return -8;
+    if (lda < max64(1, rows_a)) return -9;
+    if (ab_read && !Br) return -10;
+    if (ab_read && !Bi) return -11;
+    if (ldb < max64(1, rows_b)) return -12;
+    if (m > 0 && n > 0 && !Cr) return -14;
+    if (m > 0 && n > 0 && !Ci) return -15;
+    if (ldc < max64(1, m)) return -16;
+    const int64_t need = (int64_t)xgemm_zgemm_worksize(m, n, alpha, beta);
+    if (need > 0 && !work) return -17;
+    if (lwork < need) return -18;
+    if (m == 0 || n == 0) return 0;
+    if (!ab_read && br == 1.0 && bi == 0.0) return 0;
+
+    // Im(op(X)) = sx * Xi : the conjugate only flips the sign of the imaginary plane.
+    const double sa = is_c(transa) ? -1.0 : 1.0, sb = is_c(transb) ? -1.0 : 1.0;
+    const char ta = is_n(transa) ? 'N' : 'T', tb = is_n(transb) ? 'N' : 'T';
+    int rc;
+    if (ai == 0.0 && bi == 0.0) {
+        // real scalars: accumulate straight into the planes of C
+        //   Cr = br Cr + ar Ar Br - ar sa sb Ai Bi ;  Ci = br Ci + ar sb Ar Bi + ar sa Ai Br
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, ar, Ar, lda, Br, ldb, br, Cr, ldc, stream))) return rc;
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, -ar * sa * sb, Ai, lda, Bi, ldb, 1.0, Cr, ldc, stream))) return rc;
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, ar * sb, Ar, lda, Bi, ldb, br, Ci, ldc, stream))) return rc;
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, ar * sa, Ai, lda, Br, ldb, 1.0, Ci, ldc, stream))) return rc;
+        return 0;
+    }
+    // complex scalars: P = op(A) op(B) into the workspace, then one combine pass
+    double *Pr = work, *Pi = work + (size_t)m * (size_t)n;
+    if (ab_read) {
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, 1.0, Ar, lda, Br, ldb, 0.0, Pr, m, stream))) return rc;
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, -sa * sb, Ai, lda, Bi, ldb, 1.0, Pr, m, stream))) return rc;
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, sb, Ar, lda, Bi, ldb, 0.0, Pi, m, stream))) return rc;
+        if ((rc = xgemm_dgemm(ta, tb, m, n, k, sa, Ai, lda, Br, ldb, 1.0, Pi, m, stream))) return rc;
+    }
+    const dim3 grid((unsigned)((m + 255) / 256), (unsigned)(n < 1024 ? n : 1024));
+    hipLaunchKernelGGL(zcombine_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), Cr, Ci, ldc, Pr, Pi,
+                       (int)m, (int)n, ar, ai, br, bi, ab_read ? 1 : 0);
+    return (int)hipGetLastError();
+}
+
+const char *xgemm_version(void) { return "xgemm 0.1 (gfx950)"; }
+
+const char *xgemm_last_kernel_name(void) { return t_last_kernel; }
+
+int xgemm_force_variant(int variant) {
+    int nd = 0, ns = 0;
+    d_variant_table(&nd);
+    s_variant_table(&ns);
+    if (variant < -1 || variant >= (nd > ns ? nd : ns)) return -1;
+    t_forced_variant = variant;
+    return 0;
+}
+
+const char *xgemm_variant_name(char prec, int variant) {
+    int nv = 0;
+    if (prec == 'd' || prec == 'D') {
+        const VariantEntry<double> *t = d_variant_table(&nv);
+        return (variant >= 0 && variant < nv) ? t[variant].name : nullptr;
+    }
+    if (prec == 's' || prec == 'S') {
+        const VariantEntry<float> *t = s_variant_table(&nv);
+        return (variant >= 0 && variant < nv) ? t[variant].name : nullptr;
+    }
+    return nullptr;
+}
+
+int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *stream) {
+    if (blocks <= 0 || iters < 0 || !sink) return (int)hipErrorInvalidValue;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (prec == 'd' || prec == 'D')
+        hipLaunchKernelGGL(mfma_peak_kernel<double>, dim3(blocks), dim3(256), 0, st, static_cast<double *>(sink), iters);
+    else if (prec == 's' || prec == 'S')
+        hipLaunchKernelGGL(mfma_peak_kernel<float>, dim3(blocks), dim3(256), 0, st, static_cast<float *>(sink), iters);
+    else
+        return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+int xgemm_mfma_layout_probe(char prec, int *out, void *stream) {
+    if (!out) return (int)hipErrorInvalidValue;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (prec == 'd' || prec == 'D')
+        hipLaunchKernelGGL(mfma_layout_kernel<double>, dim3(1), dim3(64), 0, st, out);
+    else if (prec == 's' || prec == 'S')
+        hipLaunchKernelGGL(mfma_layout_kernel<float>, dim3(1), dim3(64), 0, st, out);
+    else
+        return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+}  // extern "C"

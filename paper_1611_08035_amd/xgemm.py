@@ -1,0 +1,145 @@
+"""ctypes binding of libxgemm.so -- same names as the C ABI (include/xgemm.h).
+
+Matrix arguments may be torch tensors on the GPU (their ``data_ptr()`` is
+passed) or plain integer device addresses; ``None`` is a NULL pointer.  The
+stream defaults to torch's current stream on the current device.  Nothing is
+computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "libxgemm.so")
+
+EXPORTS = [
+    "xgemm_dgemm", "xgemm_sgemm", "xgemm_zgemm_split", "xgemm_zgemm_worksize", "xgemm_version",
+    "xgemm_last_kernel_name", "xgemm_force_variant", "xgemm_variant_name", "xgemm_mfma_peak_probe",
+    "xgemm_mfma_layout_probe",
+]
+
+
+class XgemmError(RuntimeError):
+    pass
+
+
+_lib = None
+_i64, _p, _c = ctypes.c_int64, ctypes.c_void_p, ctypes.c_char
+
+
+def library_path() -> str:
+    return _LIBPATH
+
+
+def lib():
+    """Load libxgemm.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIBPATH):
+        raise XgemmError(
+            f"{_LIBPATH} is missing: build it with `python -m paper_1611_08035_amd.build` "
+            "(there is no fallback path)")
+    # torch brings its own HIP runtime; load it first so that this library
+    # binds to the same runtime instance that owns the tensors' memory.
+    try:
+        import torch  # noqa: F401
+    except Exception:
+        pass
+    L = ctypes.CDLL(_LIBPATH)
+    for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
+        f = getattr(L, f"xgemm_{pre}gemm")
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _c, _i64, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p]
+    L.xgemm_zgemm_split.restype = ctypes.c_int
+    L.xgemm_zgemm_split.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
+                                    _p, _i64, _p]
+    L.xgemm_zgemm_worksize.restype = ctypes.c_size_t
+    L.xgemm_zgemm_worksize.argtypes = [_i64, _i64, _p, _p]
+    L.xgemm_version.restype = ctypes.c_char_p
+    L.xgemm_last_kernel_name.restype = ctypes.c_char_p
+    L.xgemm_force_variant.restype = ctypes.c_int
+    L.xgemm_force_variant.argtypes = [ctypes.c_int]
+    L.xgemm_variant_name.restype = ctypes.c_char_p
+    L.xgemm_variant_name.argtypes = [_c, ctypes.c_int]
+    L.xgemm_mfma_peak_probe.restype = ctypes.c_int
+    L.xgemm_mfma_peak_probe.argtypes = [_c, ctypes.c_int, ctypes.c_int, _p, _p]
+    L.xgemm_mfma_layout_probe.restype = ctypes.c_int
+    L.xgemm_mfma_layout_probe.argtypes = [_c, _p, _p]
+    _lib = L
+    return L
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()   # torch tensor
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ch(t):
+    return _c(t.encode("ascii") if isinstance(t, str) else t)
+
+
+def xgemm_dgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_dgemm(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                 _ptr(C), ldc, _stream(stream)))
+
+
+def xgemm_sgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_sgemm(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                 _ptr(C), ldc, _stream(stream)))
+
+
+def _pair(z):
+    if z is None:
+        return None
+    return (ctypes.c_double * 2)(float(z[0]), float(z[1]))
+
+
+def xgemm_zgemm_split(transa, transb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc,
+                      work=None, lwork=0, stream=None) -> int:
+    al, be = _pair(alpha), _pair(beta)
+    return int(lib().xgemm_zgemm_split(_ch(transa), _ch(transb), m, n, k, al, _ptr(Ar), _ptr(Ai), lda,
+                                       _ptr(Br), _ptr(Bi), ldb, be, _ptr(Cr), _ptr(Ci), ldc,
+                                       _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_zgemm_worksize(m, n, alpha, beta) -> int:
+    return int(lib().xgemm_zgemm_worksize(m, n, _pair(alpha), _pair(beta)))
+
+
+def xgemm_version() -> str:
+    return lib().xgemm_version().decode()
+
+
+def xgemm_last_kernel_name() -> str:
+    return lib().xgemm_last_kernel_name().decode()
+
+
+def xgemm_force_variant(variant: int) -> int:
+    return int(lib().xgemm_force_variant(int(variant)))
+
+
+def xgemm_variant_name(prec: str, variant: int):
+    r = lib().xgemm_variant_name(_ch(prec), int(variant))
+    return r.decode() if r else None
+
+
+def xgemm_mfma_peak_probe(prec, blocks, iters, sink, stream=None) -> int:
+    return int(lib().xgemm_mfma_peak_probe(_ch(prec), blocks, iters, _ptr(sink), _stream(stream)))
+
+
+def xgemm_mfma_layout_probe(prec, out, stream=None) -> int:
+    return int(lib().xgemm_mfma_layout_probe(_ch(prec), _ptr(out), _stream(stream)))

@@ -1,0 +1,91 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every
+symbol the header declares, and rejects illegal arguments before touching a
+device."""
+import os
+import re
+
+import pytest
+
+import paper_1611_08035_amd as xg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "xgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xgemm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = xg.lib()
+    names = declared_symbols()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(L, name), f"{name} declared in xgemm.h but not exported"
+    assert sorted(xg.EXPORTS) == names
+
+
+def test_version_and_variant_names():
+    assert "gfx950" in xg.xgemm_version()
+    assert xg.xgemm_variant_name("d", 0).startswith("d_")
+    assert xg.xgemm_variant_name("s", 0).startswith("s_")
+    assert xg.xgemm_variant_name("d", 1000) is None
+    assert xg.xgemm_force_variant(1000) == -1
+    assert xg.xgemm_force_variant(-1) == 0
+
+
+@pytest.mark.parametrize("fn", ["xgemm_dgemm", "xgemm_sgemm"])
+def test_illegal_arguments_are_rejected_on_the_host(fn):
+    f = getattr(xg, fn)
+    P = 4096   # any non-null address: nothing is launched on an error path
+    g = lambda *a: f(*a, stream=0)
+    assert g("X", "N", 2, 2, 2, 1.0, P, 2, P, 2, 0.0, P, 2) == -1
+    assert g("N", "Q", 2, 2, 2, 1.0, P, 2, P, 2, 0.0, P, 2) == -2
+    assert g("N", "N", -1, 2, 2, 1.0, P, 2, P, 2, 0.0, P, 2) == -3
+    assert g("N", "N", 2, -1, 2, 1.0, P, 2, P, 2, 0.0, P, 2) == -4
+    assert g("N", "N", 2, 2, -1, 1.0, P, 2, P, 2, 0.0, P, 2) == -5
+    assert g("N", "N", 2, 2, 2, 1.0, None, 2, P, 2, 0.0, P, 2) == -7
+    assert g("N", "N", 3, 2, 2, 1.0, P, 2, P, 2, 0.0, P, 3) == -8
+    assert g("T", "N", 3, 2, 4, 1.0, P, 3, P, 4, 0.0, P, 3) == -8
+    assert g("N", "N", 2, 2, 2, 1.0, P, 2, None, 2, 0.0, P, 2) == -9
+    assert g("N", "N", 2, 2, 3, 1.0, P, 2, P, 2, 0.0, P, 2) == -10
+    assert g("N", "T", 2, 3, 2, 1.0, P, 2, P, 2, 0.0, P, 2) == -10
+    assert g("N", "N", 2, 2, 2, 1.0, P, 2, P, 2, 0.0, None, 2) == -12
+    assert g("N", "N", 3, 2, 2, 1.0, P, 3, P, 2, 0.0, P, 2) == -13
+    assert g("N", "N", 0, 2, 2, 1.0, P, 0, P, 2, 0.0, P, 1) == -8
+    assert g("N", "N", 2 ** 31, 2, 2, 1.0, P, 2 ** 31, P, 2, 0.0, P, 2 ** 31) == -3
+    # quick returns launch nothing and succeed
+    assert g("N", "N", 0, 2, 2, 1.0, None, 1, None, 2, 0.0, None, 1) == 0
+    assert g("N", "N", 2, 0, 2, 1.0, None, 2, None, 2, 0.0, None, 2) == 0
+    assert g("N", "N", 2, 2, 0, 1.0, None, 2, None, 1, 1.0, P, 2) == 0
+    assert g("N", "N", 2, 2, 2, 0.0, None, 2, None, 2, 1.0, P, 2) == 0
+    assert xg.xgemm_last_kernel_name() == "none"
+
+
+def test_zgemm_illegal_arguments_and_worksize():
+    P = 4096
+    z = lambda *a, **kw: xg.xgemm_zgemm_split(*a, stream=0, **kw)
+    assert xg.xgemm_zgemm_worksize(5, 7, (1, 0), (0, 0)) == 0
+    assert xg.xgemm_zgemm_worksize(5, 7, (1, 2), (0, 0)) == 70
+    assert xg.xgemm_zgemm_worksize(5, 7, (1, 0), (0, 1)) == 70
+    assert z("X", "N", 2, 2, 2, (1, 0), P, P, 2, P, P, 2, (0, 0), P, P, 2) == -1
+    assert z("N", "N", 2, 2, 2, None, P, P, 2, P, P, 2, (0, 0), P, P, 2) == -6
+    assert z("N", "N", 2, 2, 2, (1, 0), P, None, 2, P, P, 2, (0, 0), P, P, 2) == -8
+    assert z("N", "N", 3, 2, 2, (1, 0), P, P, 2, P, P, 2, (0, 0), P, P, 3) == -9
+    assert z("N", "N", 2, 2, 2, (1, 0), P, P, 2, None, P, 2, (0, 0), P, P, 2) == -10
+    assert z("N", "N", 2, 2, 3, (1, 0), P, P, 2, P, P, 2, (0, 0), P, P, 2) == -12
+    assert z("N", "N", 2, 2, 2, (1, 0), P, P, 2, P, P, 2, None, P, P, 2) == -13
+    assert z("N", "N", 2, 2, 2, (1, 0), P, P, 2, P, P, 2, (0, 0), P, None, 2) == -15
+    assert z("N", "N", 3, 2, 2, (1, 0), P, P, 3, P, P, 2, (0, 0), P, P, 2) == -16
+    assert z("N", "N", 2, 2, 2, (1, 1), P, P, 2, P, P, 2, (0, 0), P, P, 2, work=None, lwork=8) == -17
+    assert z("N", "N", 2, 2, 2, (1, 1), P, P, 2, P, P, 2, (0, 0), P, P, 2, work=P, lwork=7) == -18
+    assert z("N", "N", 0, 2, 2, (1, 1), None, None, 1, None, None, 2, (0, 0), None, None, 1) == 0
+
+
+def test_missing_library_raises(monkeypatch):
+    import paper_1611_08035_amd.xgemm as mod
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "_LIBPATH", "/nonexistent/libxgemm.so")
+    with pytest.raises(mod.XgemmError):
+        mod.lib()

@@ -443,6 +443,21 @@ def test_zgemm_against_numpy_complex_and_real_special_case():
     assert np.array_equal(Rr, Cref) and np.array_equal(Gr, G) and not Ri.any()
 
 
+def test_zgemm_samples_match_full_reference():
+    rng = si.rng_for(90, 16)
+    m, n, k = 21, 19, 33
+    for ta, tb in [("N", "N"), ("C", "T"), ("T", "C")]:
+        (Ar, Ai, Br, Bi, Cr, Ci), lda, ldb, ldc = zoperands(rng, ta, tb, m, n, k, kind="uniform")
+        al, be = (1.5, -0.25), (0.5, 1.0)
+        _, Rr, Ri, Gr, Gi = oracle.zgemm_split_ext(ta, tb, m, n, k, al, Ar, Ai, lda, Br, Bi, ldb, be, Cr, Ci, ldc)
+        I, J = si.sample_indices(rng, m, n, 3, 3, 40)
+        info, rr, ri, gr, gi = oracle.zgemm_split_samples(ta, tb, m, n, k, al, Ar, Ai, lda, Br, Bi, ldb, be,
+                                                          Cr, Ci, ldc, I, J)
+        assert info == 0
+        assert np.array_equal(rr, Rr[J, I]) and np.array_equal(ri, Ri[J, I])
+        assert np.array_equal(gr, Gr[J, I]) and np.array_equal(gi, Gi[J, I])
+
+
 def test_zgemm_scalar_paths_and_errors():
     m, n, k = 5, 4, 3
     nan = np.full((8, 8), np.nan)
