@@ -107,11 +107,12 @@ const char *xgemm_variant_name(char prec, int variant);
 /*
  * MFMA-only micro-benchmark (confirms the matrix-core peak that percentages
  * are quoted against): launches `blocks` workgroups of 256 threads, each wave
- * issuing `iters` x 16 back-to-back register-resident MFMAs (FP64 16x16x4 for
- * prec 'd', FP32 32x32x2 for 's') with no memory traffic in the loop.  `sink`
- * is a device buffer of at least blocks*256 elements of that precision, written
- * once at the end.  Returns 0 or a hipError_t.  flops per launch =
- * blocks * 4 waves * iters * 16 * (2*16*16*4 for 'd', 2*32*32*2 for 's').
+ * issuing `iters` rounds of back-to-back register-resident MFMAs with no
+ * memory traffic in the loop: 16 FP64 16x16x4 per round for prec 'd', 8 FP32
+ * 32x32x2 per round for 's'.  `sink` is a device buffer of at least blocks*256
+ * elements of that precision, written once at the end.  Returns 0 or a
+ * hipError_t.  flops per launch = blocks * 4 waves * iters * 32768 for both
+ * precisions (16 * 2*16*16*4 = 8 * 2*32*32*2 = 32768).
  */
 int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *stream);
 

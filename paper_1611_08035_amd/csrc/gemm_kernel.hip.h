@@ -111,15 +111,28 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
         }
     }
 
-    // all of the slab is in bounds and 16-byte aligned
-    static __device__ __forceinline__ void load_fast(vec_t (&r)[NV], const T *base, int64_t ld, int tid) {
+    // Byte offset of every vector of this thread from the slab origin.  They do
+    // not change from slab to slab, so the steady-state loads are "uniform base
+    // pointer + per-lane 32-bit offset" and need no vector address arithmetic.
+    static __device__ __forceinline__ void offsets(uint32_t (&off)[NV], int64_t ld, int tid) {
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             int mn, p;
             pos(tid, q, mn, p);
-            const T *src = KCONTIG ? base + p + (int64_t)mn * ld : base + mn + (int64_t)p * ld;
-            r[q] = *reinterpret_cast<const vec_t *>(src);
+            off[q] = (uint32_t)((KCONTIG ? p + (int64_t)mn * ld : mn + (int64_t)p * ld) * (int64_t)sizeof(T));
         }
+    }
+
+    // All of the slab is in bounds and 16-byte aligned.  Buffer loads take the
+    // (wave-uniform) slab origin as a scalar resource and the per-lane offset as
+    // a 32-bit register, so no vector ALU work is spent on addresses.
+    static __device__ __forceinline__ void load_fast(vec_t (&r)[NV], const T *base, const uint32_t (&off)[NV]) {
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, -1, 0x00020000);
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            r[q] = __builtin_bit_cast(vec_t, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(rsrc, off[q], 0, 0));
     }
 
     // element-wise, zero-filled outside [0, mn_lim) x [0, k_lim); no alignment assumed
@@ -141,16 +154,25 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
         }
     }
 
-    static __device__ __forceinline__ void store(const vec_t (&r)[NV], T *s, int tid) {
+    // LDS position of vector 0 of this thread; vector q sits a compile-time
+    // constant further on (rows for MN-contiguous slabs, columns for K-contiguous).
+    static_assert(NT % (KCONTIG ? KT / V : MT / V) == 0, "vectors of one thread must differ by a constant");
+    static __device__ __forceinline__ int lds_origin(int tid) {
+        int mn, p;
+        pos(tid, 0, mn, p);
+        return p * S + mn;
+    }
+    static constexpr int lds_step = KCONTIG ? NT / (KT / V) : (NT / (MT / V)) * S;
+
+    // `s` already includes lds_origin(tid)
+    static __device__ __forceinline__ void store(const vec_t (&r)[NV], T *s) {
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
-            int mn, p;
-            pos(tid, q, mn, p);
             if (!KCONTIG) {
-                *reinterpret_cast<vec_t *>(s + p * S + mn) = r[q];
+                *reinterpret_cast<vec_t *>(s + q * lds_step) = r[q];
             } else {
 #pragma unroll
-                for (int e = 0; e < V; ++e) s[(p + e) * S + mn] = r[q][e];
+                for (int e = 0; e < V; ++e) s[e * S + q * lds_step] = r[q][e];
             }
         }
     }
@@ -190,18 +212,24 @@ template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC
     static constexpr int TM = WT_M / M::MI, TN = WT_N / M::MI;
     static_assert(WT_M % M::MI == 0 && WT_N % M::MI == 0, "wave tile must be whole MFMA tiles");
     static_assert(KT % M::KI == 0, "slab depth must be whole MFMA depths");
-    // LDS row strides.  Rows are read 16/32 consecutive elements at a time
-    // (conflict-free for any stride); the stride only has to keep 16-byte
-    // alignment for the vector writes of MN-contiguous slabs.
-    static constexpr int SA = MT_M, SB = MT_N;
-    static constexpr size_t LDS_BYTES = 2 * (size_t)KT * (SA + SB) * sizeof(T);
+    // LDS row strides.  A slab row is read 16 (fp64) / 32 (fp32) consecutive
+    // elements at a time, which touches every bank once for any stride.  The
+    // stride matters for the writes of K-contiguous slabs: the KT/V lanes that
+    // hold one row-vector mn write V rows apart, and with a power-of-two stride
+    // they would all hit the same banks.  With W = 128 B / sizeof(T) elements per
+    // LDS cycle, a stride of MT + W/KT makes the W lanes served in one cycle
+    // fall on W distinct banks.  MN-contiguous slabs keep stride MT (their
+    // 16-byte row writes are contiguous and need the alignment).
+    static constexpr int PADK = (128 / (int)sizeof(T)) / KT > 0 ? (128 / (int)sizeof(T)) / KT : 1;
+    static constexpr int stride(int mt, bool kcontig) { return kcontig ? mt + PADK : mt; }
+    static constexpr size_t LDS_BYTES = 2 * (size_t)KT * (MT_M + MT_N + 2 * PADK) * sizeof(T);
 };
 
 template <typename T, typename Cfg, bool AK, bool BK, bool FAST>
 __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<T> g) {
     using M = Mfma<T>;
     constexpr int MT_M = Cfg::MT_M, MT_N = Cfg::MT_N, KT = Cfg::KT, NT = Cfg::NT;
-    constexpr int SA = Cfg::SA, SB = Cfg::SB, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int SA = Cfg::stride(MT_M, AK), SB = Cfg::stride(MT_N, BK), TM = Cfg::TM, TN = Cfg::TN;
     using StA = Stager<T, MT_M, KT, SA, NT, AK>;
     using StB = Stager<T, MT_N, KT, SB, NT, BK>;
 
@@ -238,14 +266,17 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
 
     typename StA::vec_t ra[StA::NV];
     typename StB::vec_t rb[StB::NV];
+    uint32_t offa[StA::NV], offb[StB::NV];
+    StA::offsets(offa, g.lda, tid);
+    StB::offsets(offb, g.ldb, tid);
 
     const int nslab = (g.k + KT - 1) / KT;
 
     auto fetch = [&](int t) {
         const int k_lim = g.k - t * KT;
         if (interior && k_lim >= KT) {
-            StA::load_fast(ra, pa, g.lda, tid);
-            StB::load_fast(rb, pb, g.ldb, tid);
+            StA::load_fast(ra, pa, offa);
+            StB::load_fast(rb, pb, offb);
         } else {
             StA::load_guarded(ra, pa, g.lda, tid, m_lim, k_lim);
             StB::load_guarded(rb, pb, g.ldb, tid, n_lim, k_lim);
@@ -253,39 +284,70 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         pa += step_a;
         pb += step_b;
     };
+    T *const stash_a = lds + StA::lds_origin(tid);
+    T *const stash_b = lds + KT * SA + StB::lds_origin(tid);
     auto stash = [&](int buf) {
-        StA::store(ra, lds + buf * BUF, tid);
-        StB::store(rb, lds + buf * BUF + KT * SA, tid);
+        StA::store(ra, stash_a + buf * BUF);
+        StB::store(rb, stash_b + buf * BUF);
     };
 
-    // ramp-up: slab 0 into LDS buffer 0
+    // Operand fragments are double-buffered in registers: the LDS reads of
+    // MFMA group g+1 are issued before the MFMAs of group g, so a read has a whole
+    // group of MFMAs to land (the paper's rule of giving each permutation of b its
+    // own register so that loads never wait on the compute that still uses the
+    // old value, Sec. 5.2).
+    constexpr int NG = KT / M::KI;   // MFMA groups (rank-KI updates of the wave tile) per slab
+    static_assert(NG % 2 == 0, "fragment double buffering needs an even number of groups per slab");
+    const int kq = M::op_k(lane), iq = M::op_idx(lane);
+    const T *const frag_a = lds + kq * SA + wm0 + iq;
+    const T *const frag_b = lds + KT * SA + kq * SB + wn0 + iq;
+    T fa[2][TM], fb[2][TN];
+    // buf, grp and set are compile-time constants at every call site, so each
+    // read is "per-lane base register + immediate offset".
+    auto load_frags = [&](int buf, int grp, int set) {
+        const T *sa = frag_a + buf * BUF + grp * M::KI * SA;
+        const T *sb = frag_b + buf * BUF + grp * M::KI * SB;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[set][i] = sa[i * M::MI];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[set][j] = sb[j * M::MI];
+    };
+    auto mma_group = [&](int set) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) acc[j][i] = M::mma(fb[set][j], fa[set][i], acc[j][i]);
+    };
+
+    // ramp-up: slab 0 into LDS buffer 0, first fragments into registers
     fetch(0);
     stash(0);
     __syncthreads();
+    load_frags(0, 0, 0);
 
-    const int kq = M::op_k(lane), iq = M::op_idx(lane);
-
-    for (int t = 0; t < nslab; ++t) {
+    // steady state.  Per slab t (LDS buffer cur = t & 1): global loads of slab
+    // t+1 go out first; MFMA groups 0..NG-2 run with the next group's fragments
+    // in flight; then slab t+1 is written to the other LDS buffer and the
+    // workgroup synchronises; the last MFMA group of slab t is issued AFTER the
+    // barrier, together with the first fragment reads of slab t+1, so the
+    // post-barrier LDS latency is covered by a full group of MFMAs.
+    auto slab = [&](int t, int cur) {
         const bool more = (t + 1 < nslab);
-        if (more) fetch(t + 1);   // global loads in flight under the MFMAs below
-
-        const T *sa = lds + (t & 1) * BUF + kq * SA + wm0 + iq;
-        const T *sb = lds + (t & 1) * BUF + KT * SA + kq * SB + wn0 + iq;
+        if (more) fetch(t + 1);
 #pragma unroll
-        for (int kk = 0; kk < KT; kk += M::KI) {
-            T fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = sa[kk * SA + i * M::MI];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = sb[kk * SB + j * M::MI];
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i) acc[j][i] = M::mma(fb[j], fa[i], acc[j][i]);
+        for (int grp = 0; grp + 1 < NG; ++grp) {
+            load_frags(cur, grp + 1, (grp + 1) & 1);
+            mma_group(grp & 1);
         }
-
-        if (more) stash((t + 1) & 1);
+        if (more) stash(cur ^ 1);
         __syncthreads();
+        if (more) load_frags(cur ^ 1, 0, 0);
+        mma_group((NG - 1) & 1);
+    };
+    // two slabs per trip so that the LDS buffer index is a constant in the code
+    for (int t = 0; t < nslab; t += 2) {
+        slab(t, 0);
+        if (t + 1 < nslab) slab(t + 1, 1);
     }
 
     // flush: C = alpha*acc + beta*C on the part of the tile inside C

@@ -75,8 +75,11 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     g.m = (int)m; g.n = (int)n; g.k = (int)k;
     g.alpha = alpha; g.beta = beta;
     g.ntm = g.ntn = 0;
-    // 16-byte vector loads need aligned bases and column strides
-    const bool fast = aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0;
+    // The vector-load path needs 16-byte aligned bases and column strides, and
+    // per-lane byte offsets inside one slab (at most 256 columns) that fit 32 bits.
+    const int64_t ld_max = (int64_t(1) << 32) / (256 * (int64_t)sizeof(T)) - 1;
+    const bool fast = aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0 &&
+                      lda <= ld_max && ldb <= ld_max;
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
     return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
@@ -110,23 +113,25 @@ __global__ void __launch_bounds__(256) zcombine_kernel(double *Cr, double *Ci, i
     }
 }
 
-// Register-resident MFMA loop, no memory traffic: 16 independent accumulator
-// tiles per wave so that back-to-back issue never waits on a dependency.
-template <typename T> __global__ void __launch_bounds__(256) mfma_peak_kernel(T *sink, int iters) {
+// Register-resident MFMA loop, no memory traffic: NACC independent accumulator
+// tiles per wave (128 registers) so that back-to-back issue never waits on a
+// dependency.
+template <typename T> __global__ void __launch_bounds__(256, 2) mfma_peak_kernel(T *sink, int iters) {
     using M = Mfma<T>;
-    typename M::acc_t acc[16];
+    constexpr int NACC = 128 / (M::NR * (int)sizeof(T) / 4);
+    typename M::acc_t acc[NACC];
 #pragma unroll
-    for (int a = 0; a < 16; ++a)
+    for (int a = 0; a < NACC; ++a)
 #pragma unroll
         for (int r = 0; r < M::NR; ++r) acc[a][r] = T(0);
     T x = T(threadIdx.x & 7) * T(0.125), y = T((threadIdx.x >> 3) & 7) * T(0.25);
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int a = 0; a < 16; ++a) acc[a] = M::mma(x, y, acc[a]);
+        for (int a = 0; a < NACC; ++a) acc[a] = M::mma(x, y, acc[a]);
     }
     T s = T(0);
 #pragma unroll
-    for (int a = 0; a < 16; ++a)
+    for (int a = 0; a < NACC; ++a)
 #pragma unroll
         for (int r = 0; r < M::NR; ++r) s += acc[a][r];
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
