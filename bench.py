@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--variant", type=int, default=-1, help="force a tile variant (tuning)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep", action="store_true", help="also time the other shapes (stderr)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region, run one plain 1 GiB device-to-device copy kernel "
+                         "(a known-size reference for scaling HBM traffic counters under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -147,6 +150,14 @@ def main():
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)
+
+    if args.calib_copy:
+        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if args.sweep:
         del dA, dB, dC, host_ops

@@ -8,7 +8,6 @@ using D_128x128x16 = TileCfg<double, 128, 128, 16, 2, 2, 2>;
 using D_128x128x8 = TileCfg<double, 128, 128, 8, 2, 2, 2>;
 using D_256x128x8 = TileCfg<double, 256, 128, 8, 4, 2, 2>;
 using D_64x64x16 = TileCfg<double, 64, 64, 16, 2, 2, 2>;
-using D_128x128x32_o1 = TileCfg<double, 128, 128, 32, 2, 2, 1>;
 
 #define XG_ENTRY(T, CFG, NAME) {NAME, CFG::MT_M, CFG::MT_N, &launch_cfg<T, CFG>}
 
@@ -18,7 +17,6 @@ const VariantEntry<double> *d_variant_table(int *n) {
     XG_ENTRY(double, D_128x128x8, "d_128x128x8_w2x2"),
     XG_ENTRY(double, D_256x128x8, "d_256x128x8_w4x2"),
     XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2"),
-    XG_ENTRY(double, D_128x128x32_o1, "d_128x128x32_w2x2_o1"),
     };
     *n = (int)(sizeof(table) / sizeof(table[0]));
     return table;
