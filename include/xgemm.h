@@ -125,6 +125,17 @@ int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *st
  */
 int xgemm_mfma_layout_probe(char prec, int *out, void *stream);
 
+/*
+ * Placement probe: launches `blocks` workgroups of 256 threads, each asking for
+ * `lds_bytes` of LDS (0..163840) and staying resident for a fixed ~200k cycles,
+ * and writes 4 unsigned ints per wave to `out` (device, 16*blocks values):
+ * {HW_ID register, XCC_ID register, workgroup index, wave index in workgroup}.
+ * Shows which XCD, CU, SIMD and wave slot the hardware dispatcher gives to
+ * consecutive workgroups (the assumption behind the XCD-aware tile order).
+ * Returns 0 or a hipError_t.
+ */
+int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

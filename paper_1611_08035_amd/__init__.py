@@ -20,5 +20,6 @@ from .xgemm import (  # noqa: F401
     xgemm_variant_name,
     xgemm_mfma_peak_probe,
     xgemm_mfma_layout_probe,
+    xgemm_hwid_probe,
     EXPORTS,
 )

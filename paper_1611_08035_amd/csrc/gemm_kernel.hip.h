@@ -74,6 +74,27 @@ template <> struct Mfma<float> {
     static __device__ __forceinline__ int d_col(int lane) { return lane & 31; }
 };
 
+// N consecutive elements as one access (N = 1, 2 or 4); alignment of the
+// element type only is promised to the compiler.
+template <typename T, int N> struct Pack {
+    typedef T type __attribute__((ext_vector_type(N), aligned(sizeof(T))));
+    static __device__ __forceinline__ void load(const T *p, T (&out)[N]) {
+        const type v = *reinterpret_cast<const type *>(p);
+#pragma unroll
+        for (int t = 0; t < N; ++t) out[t] = v[t];
+    }
+    static __device__ __forceinline__ void store(T *p, const T (&in)[N]) {
+        type v;
+#pragma unroll
+        for (int t = 0; t < N; ++t) v[t] = in[t];
+        *reinterpret_cast<type *>(p) = v;
+    }
+};
+template <typename T> struct Pack<T, 1> {
+    static __device__ __forceinline__ void load(const T *p, T (&out)[1]) { out[0] = *p; }
+    static __device__ __forceinline__ void store(T *p, const T (&in)[1]) { *p = in[0]; }
+};
+
 template <typename T> struct GemmArgs {
     const T *A, *B;
     T *C;
@@ -123,19 +144,51 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
         }
     }
 
-    // All of the slab is in bounds and 16-byte aligned.  Buffer loads take the
-    // (wave-uniform) slab origin as a scalar resource and the per-lane offset as
-    // a 32-bit register, so no vector ALU work is spent on addresses.
+    // Buffer loads take the (wave-uniform) slab origin as a scalar resource and
+    // the per-lane offset as a 32-bit register, so no vector ALU work is spent
+    // on addresses.  The resource covers 2 GiB from the slab origin; an offset
+    // at or beyond that is out of range and the load returns zero.
+    static constexpr uint32_t RANGE = 0x80000000u;
+    static __device__ __forceinline__ __amdgpu_buffer_rsrc_t resource(const T *base) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, (int)RANGE, 0x00020000);
+    }
+
+    // the whole slab is in bounds: one 16-byte load per vector
     static __device__ __forceinline__ void load_fast(vec_t (&r)[NV], const T *base, const uint32_t (&off)[NV]) {
         typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, -1, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc = resource(base);
 #pragma unroll
         for (int q = 0; q < NV; ++q)
             r[q] = __builtin_bit_cast(vec_t, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(rsrc, off[q], 0, 0));
     }
 
-    // element-wise, zero-filled outside [0, mn_lim) x [0, k_lim); no alignment assumed
+    // Ragged slab (edge tile or K tail): one load per element, zero-filled
+    // outside [0, mn_lim) x [0, k_lim) by sending the out-of-range lanes' offsets
+    // past the end of the resource -- no branches, all loads in flight together.
+    static __device__ __forceinline__ void load_edge(vec_t (&r)[NV], const T *base, const uint32_t (&off)[NV],
+                                                     int tid, int mn_lim, int k_lim) {
+        const __amdgpu_buffer_rsrc_t rsrc = resource(base);
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            int mn, p;
+            pos(tid, q, mn, p);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int mne = KCONTIG ? mn : mn + e;
+                const int pe = KCONTIG ? p + e : p;
+                const uint32_t o = (mne < mn_lim && pe < k_lim) ? off[q] + e * (uint32_t)sizeof(T) : RANGE;
+                if constexpr (sizeof(T) == 8) {
+                    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                    r[q][e] = __builtin_bit_cast(T, (u32x2)__builtin_amdgcn_raw_buffer_load_b64(rsrc, o, 0, 0));
+                } else {
+                    r[q][e] = __builtin_bit_cast(T, (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, o, 0, 0));
+                }
+            }
+        }
+    }
+
+    // fallback without buffer addressing (leading dimensions too large for 32-bit
+    // offsets): element-wise, zero-filled outside [0, mn_lim) x [0, k_lim)
     static __device__ __forceinline__ void load_guarded(vec_t (&r)[NV], const T *base, int64_t ld, int tid,
                                                         int mn_lim, int k_lim) {
 #pragma unroll
@@ -218,10 +271,19 @@ template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC
     // hold one row-vector mn write V rows apart, and with a power-of-two stride
     // they would all hit the same banks.  With W = 128 B / sizeof(T) elements per
     // LDS cycle, a stride of MT + W/KT makes the W lanes served in one cycle
-    // fall on W distinct banks.  MN-contiguous slabs keep stride MT (their
-    // 16-byte row writes are contiguous and need the alignment).
-    static constexpr int PADK = (128 / (int)sizeof(T)) / KT > 0 ? (128 / (int)sizeof(T)) / KT : 1;
+    // fall on W distinct banks; it is rounded up to a multiple of 16 bytes so
+    // that vector reads of a row stay aligned (a 2-way conflict on those writes
+    // remains where the rounding applies).  MN-contiguous slabs keep stride MT.
+    static constexpr int VEC16 = 16 / (int)sizeof(T);
+    static constexpr int PAD0 = (128 / (int)sizeof(T)) / KT > 0 ? (128 / (int)sizeof(T)) / KT : 1;
+    static constexpr int PADK = ((PAD0 + VEC16 - 1) / VEC16) * VEC16;   // keeps rows 16-byte aligned
     static constexpr int stride(int mt, bool kcontig) { return kcontig ? mt + PADK : mt; }
+    // MFMA tiles of a wave are interleaved along m (and n): tile i = ib*VR + t
+    // covers rows  wm0 + ib*VR*MI + VR*idx + t  (idx = lane's operand index), so
+    // one LDS read of VR consecutive elements feeds VR tiles and the epilogue
+    // touches VR consecutive rows of C per lane (16-byte accesses).
+    static constexpr int vr(int tiles) { return tiles % VEC16 == 0 ? VEC16 : (tiles % 2 == 0 ? 2 : 1); }
+    static constexpr int VRM = vr(TM), VRN = vr(TN);
     static constexpr size_t LDS_BYTES = 2 * (size_t)KT * (MT_M + MT_N + 2 * PADK) * sizeof(T);
 };
 
@@ -256,6 +318,13 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     const int64_t step_a = AK ? (int64_t)KT : (int64_t)KT * g.lda;
     const int64_t step_b = BK ? (int64_t)KT : (int64_t)KT * g.ldb;
 
+    // Position of accumulator (tile j, tile i, register r) of this lane in C:
+    //   row m0 + c_m(i), column n0 + c_n(j, r)   (see the interleaving in TileCfg)
+    constexpr int VRM = Cfg::VRM, VRN = Cfg::VRN;
+    const int mc = wm0 + VRM * M::d_col(lane);
+    auto c_n = [&](int j, int r) { return wn0 + (j / VRN) * VRN * M::MI + VRN * M::d_row(lane, r) + (j % VRN); };
+    const bool full_tile = m_lim >= MT_M && n_lim >= MT_N;
+    const T alpha = g.alpha, beta = g.beta;
     typename M::acc_t acc[TN][TM];
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -277,6 +346,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         if (interior && k_lim >= KT) {
             StA::load_fast(ra, pa, offa);
             StB::load_fast(rb, pb, offb);
+        } else if (FAST) {
+            StA::load_edge(ra, pa, offa, tid, m_lim, k_lim);
+            StB::load_edge(rb, pb, offb, tid, n_lim, k_lim);
         } else {
             StA::load_guarded(ra, pa, g.lda, tid, m_lim, k_lim);
             StB::load_guarded(rb, pb, g.ldb, tid, n_lim, k_lim);
@@ -299,8 +371,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     constexpr int NG = KT / M::KI;   // MFMA groups (rank-KI updates of the wave tile) per slab
     static_assert(NG % 2 == 0, "fragment double buffering needs an even number of groups per slab");
     const int kq = M::op_k(lane), iq = M::op_idx(lane);
-    const T *const frag_a = lds + kq * SA + wm0 + iq;
-    const T *const frag_b = lds + KT * SA + kq * SB + wn0 + iq;
+    const T *const frag_a = lds + kq * SA + wm0 + VRM * iq;
+    const T *const frag_b = lds + KT * SA + kq * SB + wn0 + VRN * iq;
     T fa[2][TM], fb[2][TN];
     // buf, grp and set are compile-time constants at every call site, so each
     // read is "per-lane base register + immediate offset".
@@ -308,9 +380,19 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         const T *sa = frag_a + buf * BUF + grp * M::KI * SA;
         const T *sb = frag_b + buf * BUF + grp * M::KI * SB;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[set][i] = sa[i * M::MI];
+        for (int ib = 0; ib < TM / VRM; ++ib) {
+            T v[VRM];
+            Pack<T, VRM>::load(sa + ib * VRM * M::MI, v);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[set][j] = sb[j * M::MI];
+            for (int u = 0; u < VRM; ++u) fa[set][ib * VRM + u] = v[u];
+        }
+#pragma unroll
+        for (int jb = 0; jb < TN / VRN; ++jb) {
+            T v[VRN];
+            Pack<T, VRN>::load(sb + jb * VRN * M::MI, v);
+#pragma unroll
+            for (int u = 0; u < VRN; ++u) fb[set][jb * VRN + u] = v[u];
+        }
     };
     auto mma_group = [&](int set) {
 #pragma unroll
@@ -351,44 +433,62 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     }
 
     // flush: C = alpha*acc + beta*C on the part of the tile inside C
-    const T alpha = g.alpha, beta = g.beta;
     const bool use_c = (beta != T(0));
-    const int mc = wm0 + M::d_col(lane);
-    if (m_lim >= MT_M && n_lim >= MT_N) {
-        // whole tile inside C: no predicates; the loads of one accumulator
-        // row-block are all issued before the first dependent store
+    if (full_tile) {
+        // whole tile inside C: no predicates.  The reads of C are issued in
+        // batches of JB accumulator row-blocks (about 64 registers, the staging
+        // and fragment registers that are dead by now) ahead of the first
+        // dependent store, so each batch costs one memory round trip.
+        constexpr int REGS_PER_J = M::NR * TM * (int)sizeof(T) / 4;
+        constexpr int JB = 1;   // larger batches raised register pressure in the K loop and lost more than they gained
+        static_assert(TN % JB == 0, "row-block batches must divide the wave tile");
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            T *cp[M::NR];
-            T cold[M::NR][TM];
+        for (int j0 = 0; j0 < TN; j0 += JB) {
+            T *cp[JB][M::NR];
+            T cold[JB][M::NR][TM];
 #pragma unroll
-            for (int r = 0; r < M::NR; ++r)
-                cp[r] = g.C + (int64_t)(n0 + wn0 + j * M::MI + M::d_row(lane, r)) * g.ldc + m0 + mc;
+            for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+                for (int r = 0; r < M::NR; ++r)
+                    cp[jj][r] = g.C + (int64_t)(n0 + c_n(j0 + jj, r)) * g.ldc + m0 + mc;
             if (use_c) {
+#pragma unroll
+                for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+                    for (int r = 0; r < M::NR; ++r)
+#pragma unroll
+                        for (int ib = 0; ib < TM / VRM; ++ib) {
+                            T v[VRM];
+                            Pack<T, VRM>::load(cp[jj][r] + ib * VRM * M::MI, v);
+#pragma unroll
+                            for (int u = 0; u < VRM; ++u) cold[jj][r][ib * VRM + u] = v[u];
+                        }
+            }
+#pragma unroll
+            for (int jj = 0; jj < JB; ++jj)
 #pragma unroll
                 for (int r = 0; r < M::NR; ++r)
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) cold[r][i] = cp[r][i * M::MI];
-            }
+                    for (int ib = 0; ib < TM / VRM; ++ib) {
+                        T v[VRM];
 #pragma unroll
-            for (int r = 0; r < M::NR; ++r)
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    T v = alpha * acc[j][i][r];
-                    if (use_c) v += beta * cold[r][i];
-                    cp[r][i * M::MI] = v;
-                }
+                        for (int u = 0; u < VRM; ++u) {
+                            v[u] = alpha * acc[j0 + jj][ib * VRM + u][r];
+                            if (use_c) v[u] += beta * cold[jj][r][ib * VRM + u];
+                        }
+                        Pack<T, VRM>::store(cp[jj][r] + ib * VRM * M::MI, v);
+                    }
         }
     } else {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int r = 0; r < M::NR; ++r) {
-                const int nn = wn0 + j * M::MI + M::d_row(lane, r);
+                const int nn = c_n(j, r);
                 T *crow = g.C + (int64_t)(n0 + nn) * g.ldc + m0;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
-                    const int mm = mc + i * M::MI;
+                    const int mm = mc + (i / VRM) * VRM * M::MI + (i % VRM);
                     if (mm < m_lim && nn < n_lim) {
                         T v = alpha * acc[j][i][r];
                         if (use_c) v += beta * crow[mm];

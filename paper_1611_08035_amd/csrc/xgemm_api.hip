@@ -3,6 +3,7 @@
 #include "../../include/xgemm.h"
 #include "tables.h"
 
+#include <stdlib.h>
 #include <string.h>
 
 namespace {
@@ -11,6 +12,9 @@ using namespace xg;
 
 thread_local const char *t_last_kernel = "";
 thread_local int t_forced_variant = -1;
+// tuning knob (environment XGEMM_REQUIRE_ALIGNED=1): send operands that are not
+// 16-byte aligned to the element-wise fallback instead of the buffer-load path
+const bool t_require_aligned = getenv("XGEMM_REQUIRE_ALIGNED") != nullptr;
 
 inline bool is_n(char t) { return t == 'N' || t == 'n'; }
 inline bool is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; }
@@ -75,11 +79,14 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     g.m = (int)m; g.n = (int)n; g.k = (int)k;
     g.alpha = alpha; g.beta = beta;
     g.ntm = g.ntn = 0;
-    // The vector-load path needs 16-byte aligned bases and column strides, and
-    // per-lane byte offsets inside one slab (at most 256 columns) that fit 32 bits.
-    const int64_t ld_max = (int64_t(1) << 32) / (256 * (int64_t)sizeof(T)) - 1;
-    const bool fast = aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0 &&
-                      lda <= ld_max && ldb <= ld_max;
+    // The buffer-load path addresses one slab (at most 256 rows or columns of
+    // the stored operand) with 31-bit byte offsets; beyond that the element-wise
+    // fallback runs.  16-byte loads of 4- or 8-byte aligned data are legal for
+    // buffer instructions, so alignment of the bases or strides is not required.
+    const int64_t ld_max = (int64_t(1) << 31) / (257 * (int64_t)sizeof(T));
+    bool fast = lda <= ld_max && ldb <= ld_max;
+    if (t_require_aligned)
+        fast = fast && aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0;
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
     return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
@@ -151,6 +158,22 @@ template <typename T> __global__ void __launch_bounds__(64) mfma_layout_kernel(i
     dj = M::mma(k0 ? T(1) : T(0), k0 ? idx : T(0), dj);
 #pragma unroll
     for (int r = 0; r < M::NR; ++r) out[lane * M::NR + r] = 256 * (int)di[r] + (int)dj[r];
+}
+
+// One record per wave: {HW_ID, XCC_ID, blockIdx.x, wave in block}.  The block
+// asks for `lds_bytes` of LDS so that its CU residency matches a GEMM kernel's.
+__global__ void __launch_bounds__(256, 2) hwid_kernel(unsigned *out) {
+    extern __shared__ unsigned char lds_dummy[];
+    if (threadIdx.x == 0) lds_dummy[0] = 0;
+    if ((threadIdx.x & 63) == 0) {
+        const unsigned hw = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+        const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
+        unsigned *o = out + 4 * ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6));
+        o[0] = hw; o[1] = xcc; o[2] = blockIdx.x; o[3] = threadIdx.x >> 6;
+    }
+    // stay resident long enough that a full set of workgroups is live together
+    const long long t0 = __builtin_readcyclecounter();
+    while (__builtin_readcyclecounter() - t0 < 200000) {}
 }
 
 }  // namespace
@@ -265,6 +288,15 @@ int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *st
         hipLaunchKernelGGL(mfma_peak_kernel<float>, dim3(blocks), dim3(256), 0, st, static_cast<float *>(sink), iters);
     else
         return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream) {
+    if (blocks <= 0 || !out || lds_bytes < 0 || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(hwid_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return (int)attr;
+    hipLaunchKernelGGL(hwid_kernel, dim3(blocks), dim3(256), (size_t)lds_bytes, static_cast<hipStream_t>(stream), out);
     return (int)hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ _LIBPATH = os.path.join(_HERE, "libxgemm.so")
 EXPORTS = [
     "xgemm_dgemm", "xgemm_sgemm", "xgemm_zgemm_split", "xgemm_zgemm_worksize", "xgemm_version",
     "xgemm_last_kernel_name", "xgemm_force_variant", "xgemm_variant_name", "xgemm_mfma_peak_probe",
-    "xgemm_mfma_layout_probe",
+    "xgemm_mfma_layout_probe", "xgemm_hwid_probe",
 ]
 
 
@@ -67,6 +67,8 @@ def lib():
     L.xgemm_mfma_peak_probe.argtypes = [_c, ctypes.c_int, ctypes.c_int, _p, _p]
     L.xgemm_mfma_layout_probe.restype = ctypes.c_int
     L.xgemm_mfma_layout_probe.argtypes = [_c, _p, _p]
+    L.xgemm_hwid_probe.restype = ctypes.c_int
+    L.xgemm_hwid_probe.argtypes = [ctypes.c_int, ctypes.c_int, _p, _p]
     _lib = L
     return L
 
@@ -143,3 +145,7 @@ def xgemm_mfma_peak_probe(prec, blocks, iters, sink, stream=None) -> int:
 
 def xgemm_mfma_layout_probe(prec, out, stream=None) -> int:
     return int(lib().xgemm_mfma_layout_probe(_ch(prec), _ptr(out), _stream(stream)))
+
+
+def xgemm_hwid_probe(blocks, lds_bytes, out, stream=None) -> int:
+    return int(lib().xgemm_hwid_probe(blocks, lds_bytes, _ptr(out), _stream(stream)))
