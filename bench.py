@@ -191,8 +191,11 @@ def sweep(torch, np, xg, si, args):
                 raise RuntimeError(rc)
 
         flops = 2.0 * m * n * k
-        steps = max(5, min(50, int(2e12 / flops)))
-        wall, dev = time_calls(torch, step, steps, 3)
+        # the device clocks down while the host prepares the next operands:
+        # warm up for about 0.2 s of device time before timing a short kernel
+        est = max(flops / 60e12, 20e-6)
+        steps = max(5, min(200, int(0.1 / est)))
+        wall, dev = time_calls(torch, step, steps, max(3, min(400, int(0.2 / est))))
         peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
         bytes_alg = es * (m * k + k * n + m * n * (2 if beta != 0 else 1))
         bound = min(peak, flops / bytes_alg * HBM_TBPS * 1e12)
@@ -213,7 +216,7 @@ def sweep(torch, np, xg, si, args):
         if rc:
             raise RuntimeError(rc)
 
-    wall, dev = time_calls(torch, zstep, 10, 2)
+    wall, dev = time_calls(torch, zstep, 10, 5)
     flops = 8.0 * nsz ** 3
     print(json.dumps({"shape": f"zgemm(4m) NN {nsz}^3", "ms": round(dev * 1e3, 4),
                       "GFLOP/s": round(flops / dev / 1e9, 1),

@@ -28,15 +28,41 @@ template <> const VariantEntry<float> *table<float>(int *n) { return s_variant_t
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Pick a tile variant: the largest macro-tile that still gives every compute
-// unit work (256 CUs, two workgroups resident on each), else the smallest.
+// Number of compute units of the current device (256 on MI355X), read once.
+int num_cus() {
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
+    }();
+    return n;
+}
+
+// Pick a tile variant with a small analytical cost model, in the spirit of the
+// paper's model-driven kernel selection (Sec. 4): the tiles of a variant run in
+// rounds of (CUs x workgroups per CU); a full round costs
+// wgs * tile_area / eff, and the last, partly filled round costs
+// occ * tile_area / eff with occ workgroups per CU, derated when a CU holds a
+// single workgroup (one wave per SIMD has nobody to hide its stalls behind).
+// K is common to all variants and drops out.
 template <typename T> int choose_variant(int64_t m, int64_t n, const VariantEntry<T> *tab, int nv) {
     if (t_forced_variant >= 0 && t_forced_variant < nv) return t_forced_variant;
+    const int64_t cus = num_cus();
     int best = 0;
+    double best_cost = 0.0;
     for (int v = 0; v < nv; ++v) {
-        const int64_t tiles = ((m + tab[v].mt_m - 1) / tab[v].mt_m) * ((n + tab[v].mt_n - 1) / tab[v].mt_n);
-        if (tiles >= 256) return v;      // table is ordered by preference
-        best = v;
+        const VariantEntry<T> &e = tab[v];
+        const int64_t tiles = ((m + e.mt_m - 1) / e.mt_m) * ((n + e.mt_n - 1) / e.mt_n);
+        const int64_t slots = cus * e.wgs_per_cu;
+        const double area = (double)e.mt_m * (double)e.mt_n;
+        const int64_t full = tiles / slots, rem = tiles % slots;
+        double cost = (double)full * e.wgs_per_cu * area / e.eff;
+        if (rem > 0) {
+            const int64_t occ = (rem + cus - 1) / cus;
+            cost += (double)occ * area / (e.eff * (occ == 1 ? 0.8 : 1.0));
+        }
+        if (v == 0 || cost < best_cost) { best = v; best_cost = cost; }
     }
     return best;
 }

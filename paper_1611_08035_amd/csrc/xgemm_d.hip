@@ -8,15 +8,19 @@ using D_128x128x16 = TileCfg<double, 128, 128, 16, 2, 2, 2>;
 using D_128x128x8 = TileCfg<double, 128, 128, 8, 2, 2, 2>;
 using D_256x128x8 = TileCfg<double, 256, 128, 8, 4, 2, 2>;
 using D_64x64x16 = TileCfg<double, 64, 64, 16, 2, 2, 2>;
+using D_128x64x16 = TileCfg<double, 128, 64, 16, 2, 2, 2>;
+using D_64x128x16 = TileCfg<double, 64, 128, 16, 2, 2, 2>;
 
-#define XG_ENTRY(T, CFG, NAME) {NAME, CFG::MT_M, CFG::MT_N, &launch_cfg<T, CFG>}
+#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, WGS, EFF, &launch_cfg<T, CFG>}
 
 const VariantEntry<double> *d_variant_table(int *n) {
     static const VariantEntry<double> table[] = {
-    XG_ENTRY(double, D_128x128x16, "d_128x128x16_w2x2"),
-    XG_ENTRY(double, D_128x128x8, "d_128x128x8_w2x2"),
-    XG_ENTRY(double, D_256x128x8, "d_256x128x8_w4x2"),
-    XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2"),
+    XG_ENTRY(double, D_128x128x16, "d_128x128x16_w2x2", 2, 0.92f),
+    XG_ENTRY(double, D_128x128x8, "d_128x128x8_w2x2", 2, 0.88f),
+    XG_ENTRY(double, D_256x128x8, "d_256x128x8_w4x2", 1, 0.86f),
+    XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2", 4, 0.80f),
+    XG_ENTRY(double, D_128x64x16, "d_128x64x16_w2x2", 3, 0.86f),
+    XG_ENTRY(double, D_64x128x16, "d_64x128x16_w2x2", 3, 0.88f),
     };
     *n = (int)(sizeof(table) / sizeof(table[0]));
     return table;

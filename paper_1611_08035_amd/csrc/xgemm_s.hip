@@ -7,15 +7,17 @@ using S_128x128x16 = TileCfg<float, 128, 128, 16, 2, 2, 2>;
 using S_256x128x16 = TileCfg<float, 256, 128, 16, 2, 2, 2>;
 using S_64x64x16 = TileCfg<float, 64, 64, 16, 2, 2, 2>;
 using S_128x128x32 = TileCfg<float, 128, 128, 32, 2, 2, 2>;
+using S_128x64x16 = TileCfg<float, 128, 64, 16, 2, 2, 2>;
 
-#define XG_ENTRY(T, CFG, NAME) {NAME, CFG::MT_M, CFG::MT_N, &launch_cfg<T, CFG>}
+#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, WGS, EFF, &launch_cfg<T, CFG>}
 
 const VariantEntry<float> *s_variant_table(int *n) {
     static const VariantEntry<float> table[] = {
-    XG_ENTRY(float, S_128x128x16, "s_128x128x16_w2x2"),
-    XG_ENTRY(float, S_256x128x16, "s_256x128x16_w2x2"),
-    XG_ENTRY(float, S_64x64x16, "s_64x64x16_w2x2"),
-    XG_ENTRY(float, S_128x128x32, "s_128x128x32_w2x2"),
+    XG_ENTRY(float, S_128x128x16, "s_128x128x16_w2x2", 2, 0.91f),
+    XG_ENTRY(float, S_256x128x16, "s_256x128x16_w2x2", 2, 0.92f),
+    XG_ENTRY(float, S_64x64x16, "s_64x64x16_w2x2", 4, 0.75f),
+    XG_ENTRY(float, S_128x128x32, "s_128x128x32_w2x2", 2, 0.86f),
+    XG_ENTRY(float, S_128x64x16, "s_128x64x16_w2x2", 3, 0.88f),
     };
     *n = (int)(sizeof(table) / sizeof(table[0]));
     return table;
