@@ -231,6 +231,19 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
     }
 };
 
+// COUNT pairs of (one MFMA, one instruction of class MASK): a hint asking the
+// scheduler to issue every memory instruction in the shadow of an MFMA.  An
+// MFMA occupies the matrix pipe for 64 cycles during which this wave could not
+// issue another one anyway, so a lone LDS or global instruction placed there
+// is free, whereas a cluster of them stalls the pipe.
+template <int MASK, int COUNT> static __device__ __forceinline__ void interleave() {
+#pragma unroll
+    for (int c = 0; c < COUNT; ++c) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(MASK, 1, 0);
+    }
+}
+
 // blockIdx -> macro-tile.  Workgroups are dealt round-robin to the 8 XCDs, each
 // with its own L2: give every XCD one contiguous run of the tile order, and
 // walk that order in bands of GROUP_M tile-rows so that the tiles resident on
@@ -426,8 +439,56 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         if (more) load_frags(cur ^ 1, 0, 0);
         mma_group((NG - 1) & 1);
     };
-    // two slabs per trip so that the LDS buffer index is a constant in the code
-    for (int t = 0; t < nslab; t += 2) {
+    // The same step with nothing to decide: the tile is interior and the next
+    // slab is a full one, so the body is straight-line code (one scheduling
+    // region per pair of slabs).
+    // Instruction classes for the scheduler hints below.
+    constexpr int SG_MFMA = 0x008, SG_VMEM_RD = 0x020, SG_DS_RD = 0x100, SG_DS_WR = 0x200;
+    constexpr int N_MMA = TM * TN;                       // MFMAs per group
+    constexpr int N_FRAG = TM / VRM + TN / VRN;          // LDS reads per group
+    constexpr int N_LD = StA::NV + StB::NV;              // global loads per slab
+    constexpr int N_ST = (AK ? StA::NV * StA::V : StA::NV) + (BK ? StB::NV * StB::V : StB::NV);   // LDS writes (upper bound)
+    auto slab_hot = [&](int cur) {
+        StA::load_fast(ra, pa, offa);
+        StB::load_fast(rb, pb, offb);
+        pa += step_a;
+        pb += step_b;
+#pragma unroll
+        for (int grp = 0; grp + 1 < NG; ++grp) {
+            load_frags(cur, grp + 1, (grp + 1) & 1);
+            mma_group(grp & 1);
+        }
+        stash(cur ^ 1);
+        // schedule of the region that ends at the barrier: global loads under
+        // the first MFMAs, each group's fragment reads under its predecessor,
+        // LDS writes under the last MFMAs before the barrier
+        constexpr int PRE = (NG - 1) * N_MMA;                  // MFMAs before the barrier
+        constexpr int USED = N_LD + (NG - 1) * N_FRAG + N_ST;  // memory instructions to place
+        constexpr bool HINT = USED <= PRE && N_FRAG <= N_MMA;  // enough MFMA shadows to hide them in
+        if constexpr (HINT) {
+            interleave<SG_VMEM_RD, N_LD>();
+            interleave<SG_DS_RD, (NG - 1) * N_FRAG>();
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, PRE - USED, 0);
+            interleave<SG_DS_WR, N_ST>();
+        }
+        __syncthreads();
+        load_frags(cur ^ 1, 0, 0);
+        mma_group((NG - 1) & 1);
+        if constexpr (HINT) {
+            interleave<SG_DS_RD, N_FRAG>();
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, N_MMA - N_FRAG, 0);
+        }
+    };
+    // Two slabs per trip so that the LDS buffer index is a constant in the code.
+    int t = 0;
+    if (interior) {
+        const int nfull = g.k / KT;   // slabs 0..nfull-1 are full
+        for (; t + 2 < nfull; t += 2) {
+            slab_hot(0);
+            slab_hot(1);
+        }
+    }
+    for (; t < nslab; t += 2) {
         slab(t, 0);
         if (t + 1 < nslab) slab(t + 1, 1);
     }
