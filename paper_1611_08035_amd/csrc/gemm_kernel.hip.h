@@ -120,15 +120,30 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
     static_assert(KT % V == 0 && MT % V == 0, "vector width must divide the slab");
     typedef T vec_t __attribute__((ext_vector_type(V)));
 
-    // position of vector q of thread tid inside the slab: first element (mn, p)
+    // Position of vector q of thread tid inside the slab: first element (mn, p).
+    // MN-contiguous: consecutive threads walk along mn (coalesced 16-byte loads,
+    // contiguous 16-byte LDS writes).
+    // K-contiguous: a thread's vector holds V consecutive k of one mn and is
+    // written to LDS as V scalars in V different rows (the transposition).  The
+    // LDS serves W = 128 B / sizeof(T) lanes per cycle; with the row stride
+    // S = MT + PADK (PADK = 16 B / sizeof(T)) lane group g of W lanes is laid out
+    // as A = W / (PADK*V) k-chunks x B = W / A rows mn, whose bank offsets
+    // PADK*V*kc + mn cover 0..W-1 exactly once: conflict-free.  Each group of
+    // KP/A consecutive lane groups still covers whole rows of the slab, so the
+    // global loads use every byte of the lines they touch.
+    static constexpr int W = 128 / (int)sizeof(T);
+    static constexpr int KP = KT / V;
+    static constexpr int LA = (W / (V * V) < KP) ? W / (V * V) : KP;   // PADK == V (16 bytes)
+    static constexpr int LB = W / LA;
     static __device__ __forceinline__ void pos(int tid, int q, int &mn, int &p) {
         const int v = tid + q * NT;
         if (!KCONTIG) {
             mn = (v % (MT / V)) * V;
             p = v / (MT / V);
         } else {
-            p = (v % (KT / V)) * V;
-            mn = v / (KT / V);
+            const int kc = (v % LA) + LA * ((v / W) % (KP / LA));
+            p = kc * V;
+            mn = ((v / LA) % LB) + LB * (v / (W * (KP / LA)));
         }
     }
 
@@ -209,7 +224,8 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
 
     // LDS position of vector 0 of this thread; vector q sits a compile-time
     // constant further on (rows for MN-contiguous slabs, columns for K-contiguous).
-    static_assert(NT % (KCONTIG ? KT / V : MT / V) == 0, "vectors of one thread must differ by a constant");
+    static_assert(NT % (KCONTIG ? W * (KP / LA) : MT / V) == 0, "vectors of one thread must differ by a constant");
+    static_assert(!KCONTIG || (KP % LA == 0 && W / (V * V) <= KP), "K-contiguous lane layout needs KT >= W / V");
     static __device__ __forceinline__ int lds_origin(int tid) {
         int mn, p;
         pos(tid, 0, mn, p);
@@ -283,13 +299,11 @@ template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC
     // stride matters for the writes of K-contiguous slabs: the KT/V lanes that
     // hold one row-vector mn write V rows apart, and with a power-of-two stride
     // they would all hit the same banks.  With W = 128 B / sizeof(T) elements per
-    // LDS cycle, a stride of MT + W/KT makes the W lanes served in one cycle
-    // fall on W distinct banks; it is rounded up to a multiple of 16 bytes so
-    // that vector reads of a row stay aligned (a 2-way conflict on those writes
-    // remains where the rounding applies).  MN-contiguous slabs keep stride MT.
+    // LDS cycle, a stride of MT + 16 bytes makes the W lanes served in one cycle
+    // fall on W distinct banks once the lanes are dealt to (k-chunk, mn) pairs
+    // as Stager::pos does.  MN-contiguous slabs keep stride MT.
     static constexpr int VEC16 = 16 / (int)sizeof(T);
-    static constexpr int PAD0 = (128 / (int)sizeof(T)) / KT > 0 ? (128 / (int)sizeof(T)) / KT : 1;
-    static constexpr int PADK = ((PAD0 + VEC16 - 1) / VEC16) * VEC16;   // keeps rows 16-byte aligned
+    static constexpr int PADK = VEC16;   // 16 bytes: rows stay aligned for vector reads
     static constexpr int stride(int mt, bool kcontig) { return kcontig ? mt + PADK : mt; }
     // MFMA tiles of a wave are interleaved along m (and n): tile i = ib*VR + t
     // covers rows  wm0 + ib*VR*MI + VR*idx + t  (idx = lane's operand index), so
