@@ -247,17 +247,25 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
     }
 };
 
-// COUNT pairs of (one MFMA, one instruction of class MASK): a hint asking the
-// scheduler to issue every memory instruction in the shadow of an MFMA.  An
-// MFMA occupies the matrix pipe for 64 cycles during which this wave could not
-// issue another one anyway, so a lone LDS or global instruction placed there
-// is free, whereas a cluster of them stalls the pipe.
-template <int MASK, int COUNT> static __device__ __forceinline__ void interleave() {
-#pragma unroll
-    for (int c = 0; c < COUNT; ++c) {
+// COUNT instructions of class MASK dealt PER at a time behind one MFMA each: a
+// hint asking the scheduler to issue every memory instruction in the shadow of
+// an MFMA.  An MFMA occupies the matrix pipe for 64 cycles during which this
+// wave could not issue another one anyway, so one or two LDS or global
+// instructions placed there are free, whereas a cluster of them stalls the pipe.
+template <int MASK, int COUNT, int PER = 1> static __device__ __forceinline__ void interleave() {
+    if constexpr (COUNT > 0) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(MASK, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(MASK, COUNT < PER ? COUNT : PER, 0);
+        interleave<MASK, (COUNT > PER ? COUNT - PER : 0), PER>();
     }
+}
+constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+// smallest number of memory instructions per MFMA with which n_ld + n_rd + n_wr
+// of them fit behind n_mma MFMAs (0 if even 4 per MFMA do not)
+constexpr int shadow_quota(int n_mma, int n_ld, int n_rd, int n_wr) {
+    for (int q = 1; q <= 4; ++q)
+        if (ceil_div(n_ld, q) + ceil_div(n_rd, q) + ceil_div(n_wr, q) <= n_mma) return q;
+    return 0;
 }
 
 // blockIdx -> macro-tile.  Workgroups are dealt round-robin to the 8 XCDs, each
@@ -476,21 +484,25 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         // schedule of the region that ends at the barrier: global loads under
         // the first MFMAs, each group's fragment reads under its predecessor,
         // LDS writes under the last MFMAs before the barrier
-        constexpr int PRE = (NG - 1) * N_MMA;                  // MFMAs before the barrier
-        constexpr int USED = N_LD + (NG - 1) * N_FRAG + N_ST;  // memory instructions to place
-        constexpr bool HINT = USED <= PRE && N_FRAG <= N_MMA;  // enough MFMA shadows to hide them in
+        constexpr int PRE = (NG - 1) * N_MMA;        // MFMAs before the barrier
+        constexpr int N_RD = (NG - 1) * N_FRAG;      // fragment reads before the barrier
+        constexpr int Q = shadow_quota(PRE, N_LD, N_RD, N_ST);
+        constexpr int Q2 = shadow_quota(N_MMA, 0, N_FRAG, 0);
+        constexpr bool HINT = Q > 0 && Q2 > 0;
         if constexpr (HINT) {
-            interleave<SG_VMEM_RD, N_LD>();
-            interleave<SG_DS_RD, (NG - 1) * N_FRAG>();
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, PRE - USED, 0);
-            interleave<SG_DS_WR, N_ST>();
+            interleave<SG_VMEM_RD, N_LD, Q>();
+            interleave<SG_DS_RD, N_RD, Q>();
+            constexpr int REST = PRE - ceil_div(N_LD, Q) - ceil_div(N_RD, Q) - ceil_div(N_ST, Q);
+            if constexpr (REST > 0) __builtin_amdgcn_sched_group_barrier(SG_MFMA, REST, 0);
+            interleave<SG_DS_WR, N_ST, Q>();
         }
         __syncthreads();
         load_frags(cur ^ 1, 0, 0);
         mma_group((NG - 1) & 1);
         if constexpr (HINT) {
-            interleave<SG_DS_RD, N_FRAG>();
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, N_MMA - N_FRAG, 0);
+            interleave<SG_DS_RD, N_FRAG, Q2>();
+            constexpr int REST2 = N_MMA - ceil_div(N_FRAG, Q2);
+            if constexpr (REST2 > 0) __builtin_amdgcn_sched_group_barrier(SG_MFMA, REST2, 0);
         }
     };
     // Two slabs per trip so that the LDS buffer index is a constant in the code.
