@@ -15,12 +15,12 @@ using D_64x128x16 = TileCfg<double, 64, 128, 16, 2, 2, 2>;
 
 const VariantEntry<double> *d_variant_table(int *n) {
     static const VariantEntry<double> table[] = {
-    XG_ENTRY(double, D_128x128x16, "d_128x128x16_w2x2", 2, 0.92f),
-    XG_ENTRY(double, D_128x128x8, "d_128x128x8_w2x2", 2, 0.88f),
-    XG_ENTRY(double, D_256x128x8, "d_256x128x8_w4x2", 1, 0.86f),
-    XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2", 4, 0.80f),
-    XG_ENTRY(double, D_128x64x16, "d_128x64x16_w2x2", 3, 0.86f),
-    XG_ENTRY(double, D_64x128x16, "d_64x128x16_w2x2", 3, 0.88f),
+    XG_ENTRY(double, D_128x128x16, "d_128x128x16_w2x2", 2, 0.975f),
+    XG_ENTRY(double, D_128x128x8, "d_128x128x8_w2x2", 2, 0.93f),
+    XG_ENTRY(double, D_256x128x8, "d_256x128x8_w4x2", 1, 0.89f),
+    XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2", 4, 0.90f),
+    XG_ENTRY(double, D_128x64x16, "d_128x64x16_w2x2", 3, 0.95f),
+    XG_ENTRY(double, D_64x128x16, "d_64x128x16_w2x2", 3, 0.93f),
     };
     *n = (int)(sizeof(table) / sizeof(table[0]));
     return table;

@@ -13,11 +13,11 @@ using S_128x64x16 = TileCfg<float, 128, 64, 16, 2, 2, 2>;
 
 const VariantEntry<float> *s_variant_table(int *n) {
     static const VariantEntry<float> table[] = {
-    XG_ENTRY(float, S_128x128x16, "s_128x128x16_w2x2", 2, 0.91f),
-    XG_ENTRY(float, S_256x128x16, "s_256x128x16_w2x2", 2, 0.92f),
-    XG_ENTRY(float, S_64x64x16, "s_64x64x16_w2x2", 4, 0.75f),
-    XG_ENTRY(float, S_128x128x32, "s_128x128x32_w2x2", 2, 0.86f),
-    XG_ENTRY(float, S_128x64x16, "s_128x64x16_w2x2", 3, 0.88f),
+    XG_ENTRY(float, S_128x128x16, "s_128x128x16_w2x2", 2, 0.95f),
+    XG_ENTRY(float, S_256x128x16, "s_256x128x16_w2x2", 2, 0.975f),
+    XG_ENTRY(float, S_64x64x16, "s_64x64x16_w2x2", 4, 0.80f),
+    XG_ENTRY(float, S_128x128x32, "s_128x128x32_w2x2", 2, 0.88f),
+    XG_ENTRY(float, S_128x64x16, "s_128x64x16_w2x2", 3, 0.90f),
     };
     *n = (int)(sizeof(table) / sizeof(table[0]));
     return table;
