@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--size", type=int, default=8192, help="m = n = k of the headline dgemm")
+    ap.add_argument("--prec", choices=["d", "s"], default="d",
+                    help="d: the headline dgemm (default).  s: the sgemm square of the same size "
+                         "(alpha = beta = 1, minimal ld) for profiling; reported as its own metric")
     ap.add_argument("--variant", type=int, default=-1, help="force a tile variant (tuning)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep", action="store_true", help="also time the other shapes (stderr)")
@@ -110,14 +113,18 @@ def main():
     xg.xgemm_force_variant(args.variant)
 
     nsz = args.size
-    ld = si.padded_ld(nsz)
-    alpha, beta = 1.5, -0.5
-    host_ops, (dA, dB, dC) = device_operands(torch, np, si, np.float64, "N", "N", nsz, nsz, nsz, ld, ld, ld, 2)
+    single = args.prec == "s"
+    ld = nsz if single else si.padded_ld(nsz)
+    alpha, beta = (1.0, 1.0) if single else (1.5, -0.5)
+    dtype = np.float32 if single else np.float64
+    gemm = xg.xgemm_sgemm if single else xg.xgemm_dgemm
+    host_ops, (dA, dB, dC) = device_operands(torch, np, si, dtype, "N", "N", nsz, nsz, nsz, ld, ld, ld,
+                                             3 if single else 2)
 
     def step():
-        rc = xg.xgemm_dgemm("N", "N", nsz, nsz, nsz, alpha, dA, ld, dB, ld, beta, dC, ld)
+        rc = gemm("N", "N", nsz, nsz, nsz, alpha, dA, ld, dB, ld, beta, dC, ld)
         if rc:
-            raise RuntimeError(f"xgemm_dgemm returned {rc}")
+            raise RuntimeError(f"xgemm gemm returned {rc}")
 
     wall, dev = time_calls(torch, step, args.steps, args.warmup)
     kernel = xg.xgemm_last_kernel_name()
@@ -126,25 +133,29 @@ def main():
     achieved = flops / dev / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "dgemm_8192_hbm_traffic.json")
-    if nsz == 8192 and os.path.exists(tpath):
+    if nsz == 8192 and not single and os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
         except Exception:
             traffic = None
 
+    fkey = "f32" if single else "f64"
+    peak = PEAK_TFLOPS[fkey]
+    metric = METRIC if not single else f"sgemm GFLOP/s and % of FP32 MFMA peak at m=n=k={nsz} (1 GPU)"
     out = {
-        "metric": METRIC, "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1,
+        "metric": metric, "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": fkey,
         "data": "synthetic",
-        "config": {"workload": f"dgemm NN m=n=k={nsz} alpha=1.5 beta=-0.5 lda=ldb=ldc={ld} uniform[-1,1]",
+        "config": {"workload": f"{'s' if single else 'd'}gemm NN m=n=k={nsz} alpha={alpha} beta={beta} "
+                               f"lda=ldb=ldc={ld} uniform[-1,1]",
                    "kernel": kernel},
-        "pct_of_fp64_mfma_peak": round(100.0 * gflops / 1e3 / PEAK_TFLOPS["f64"], 2),
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS["f64"],
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["f64"], 4),
+        f"pct_of_fp{fkey[1:]}_mfma_peak": round(100.0 * gflops / 1e3 / peak, 2),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                      "traffic": traffic, "kernel": kernel, "avg_launch_ms": round(dev * 1e3, 4)},
     }
-    if not args.no_cpu:
+    if not args.no_cpu and not single:
         import oracle
         out["cpu_baseline"] = cpu_baseline(np, oracle, host_ops, nsz, nsz, ld, ld, ld, alpha, beta)
     else:
