@@ -126,6 +126,34 @@ int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *st
 int xgemm_mfma_layout_probe(char prec, int *out, void *stream);
 
 /*
+ * The paper's analytical kernel-selection model (host only, no device access).
+ *
+ * xgemm_model_outer_product_rate: Sec. 4.2.  Pipeline i retires rate[i]
+ *   instructions per cycle and receives count[i] instructions per outer
+ *   product; returns min_i rate[i] / count[i] over the pipelines with
+ *   count[i] > 0 (infinity if there is none), in outer products per cycle.
+ * xgemm_model_stalled_rate: Sec. 4.3.  A pipeline with L instructions of which
+ *   n_dependent expose a latency of `latency` cycles needs W = L + n*latency;
+ *   returns its instruction rate L / W (Little's law).
+ * xgemm_model_n_updates: Sec. 5.4, floor((r_total - m_r*n_r/v - r_a) / r_r);
+ *   r_a <= 0 means ceil(m_r / v).  Returns -1 on v <= 0 or r_r <= 0.
+ * xgemm_model_predict: the model instantiated for tile variant `variant` of
+ *   precision `prec` ('d' / 's') and the given transposes, per K slab:
+ *   out[0] MFMAs, out[1] global loads, out[2] LDS reads, out[3] LDS writes
+ *   (each per wave); out[4] matrix-pipe cycles per SIMD, out[5] LDS cycles per
+ *   CU, out[6] vector-memory cycles per CU; out[7] memory instructions that must
+ *   share one MFMA shadow (0: they do not fit); out[8] barrier stall in cycles;
+ *   out[9] predicted MFMA utilisation; out[10] vector registers per lane
+ *   (accumulators + staging + two fragment sets); out[11] waves per SIMD.
+ *   Returns 0; 1 if the register limit is violated; -1 bad prec, -2 bad variant,
+ *   -5 out == NULL.
+ */
+double xgemm_model_outer_product_rate(int n_pipes, const double *rate, const double *count);
+double xgemm_model_stalled_rate(double L, double n_dependent, double latency);
+int xgemm_model_n_updates(int r_total, int m_r, int n_r, int v, int r_a, int r_r);
+int xgemm_model_predict(char prec, int variant, char transa, char transb, double out[12]);
+
+/*
  * Placement probe: launches `blocks` workgroups of 256 threads, each asking for
  * `lds_bytes` of LDS (0..163840) and staying resident for a fixed ~200k cycles,
  * and writes 4 unsigned ints per wave to `out` (device, 16*blocks values):

@@ -8,6 +8,7 @@ namespace xg {
 template <typename T> struct VariantEntry {
     const char *name;
     int mt_m, mt_n;
+    int kt, wgm, wgn;   // slab depth, waves along m and n
     int wgs_per_cu;   // workgroups resident on one CU (register and LDS budget of the variant)
     float eff;        // fraction of the MFMA peak the variant sustains with its CU fully occupied (measured)
     // launch(transA is K-contiguous, transB is K-contiguous, fast path allowed, args, stream)

@@ -11,7 +11,7 @@ using D_64x64x16 = TileCfg<double, 64, 64, 16, 2, 2, 2>;
 using D_128x64x16 = TileCfg<double, 128, 64, 16, 2, 2, 2>;
 using D_64x128x16 = TileCfg<double, 64, 128, 16, 2, 2, 2>;
 
-#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, WGS, EFF, &launch_cfg<T, CFG>}
+#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, CFG::KT, CFG::WGM, CFG::WGN, WGS, EFF, &launch_cfg<T, CFG>}
 
 const VariantEntry<double> *d_variant_table(int *n) {
     static const VariantEntry<double> table[] = {

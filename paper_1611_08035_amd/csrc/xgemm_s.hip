@@ -9,7 +9,7 @@ using S_64x64x16 = TileCfg<float, 64, 64, 16, 2, 2, 2>;
 using S_128x128x32 = TileCfg<float, 128, 128, 32, 2, 2, 2>;
 using S_128x64x16 = TileCfg<float, 128, 64, 16, 2, 2, 2>;
 
-#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, WGS, EFF, &launch_cfg<T, CFG>}
+#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, CFG::KT, CFG::WGM, CFG::WGN, WGS, EFF, &launch_cfg<T, CFG>}
 
 const VariantEntry<float> *s_variant_table(int *n) {
     static const VariantEntry<float> table[] = {

@@ -16,7 +16,8 @@ _LIBPATH = os.path.join(_HERE, "libxgemm.so")
 EXPORTS = [
     "xgemm_dgemm", "xgemm_sgemm", "xgemm_zgemm_split", "xgemm_zgemm_worksize", "xgemm_version",
     "xgemm_last_kernel_name", "xgemm_force_variant", "xgemm_variant_name", "xgemm_mfma_peak_probe",
-    "xgemm_mfma_layout_probe", "xgemm_hwid_probe",
+    "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
+    "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict",
 ]
 
 
@@ -69,6 +70,14 @@ def lib():
     L.xgemm_mfma_layout_probe.argtypes = [_c, _p, _p]
     L.xgemm_hwid_probe.restype = ctypes.c_int
     L.xgemm_hwid_probe.argtypes = [ctypes.c_int, ctypes.c_int, _p, _p]
+    L.xgemm_model_outer_product_rate.restype = ctypes.c_double
+    L.xgemm_model_outer_product_rate.argtypes = [ctypes.c_int, _p, _p]
+    L.xgemm_model_stalled_rate.restype = ctypes.c_double
+    L.xgemm_model_stalled_rate.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double]
+    L.xgemm_model_n_updates.restype = ctypes.c_int
+    L.xgemm_model_n_updates.argtypes = [ctypes.c_int] * 6
+    L.xgemm_model_predict.restype = ctypes.c_int
+    L.xgemm_model_predict.argtypes = [_c, ctypes.c_int, _c, _c, _p]
     _lib = L
     return L
 
@@ -149,3 +158,25 @@ def xgemm_mfma_layout_probe(prec, out, stream=None) -> int:
 
 def xgemm_hwid_probe(blocks, lds_bytes, out, stream=None) -> int:
     return int(lib().xgemm_hwid_probe(blocks, lds_bytes, _ptr(out), _stream(stream)))
+
+
+def xgemm_model_outer_product_rate(rate, count) -> float:
+    n = len(rate)
+    r = (ctypes.c_double * n)(*[float(x) for x in rate])
+    c = (ctypes.c_double * n)(*[float(x) for x in count])
+    return float(lib().xgemm_model_outer_product_rate(n, r, c))
+
+
+def xgemm_model_stalled_rate(L, n_dependent, latency) -> float:
+    return float(lib().xgemm_model_stalled_rate(L, n_dependent, latency))
+
+
+def xgemm_model_n_updates(r_total, m_r, n_r, v, r_a, r_r) -> int:
+    return int(lib().xgemm_model_n_updates(r_total, m_r, n_r, v, r_a, r_r))
+
+
+def xgemm_model_predict(prec, variant, transa="N", transb="N"):
+    """Returns (status, list of 12 floats); see include/xgemm.h for the fields."""
+    out = (ctypes.c_double * 12)()
+    rc = int(lib().xgemm_model_predict(_ch(prec), int(variant), _ch(transa), _ch(transb), out))
+    return rc, list(out)
