@@ -513,6 +513,14 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
             slab_hot(0);
             slab_hot(1);
         }
+        if (t + 1 < nfull) {   // one more slab whose successor is full
+            slab_hot(0);
+            ++t;
+        }
+    }
+    if (t & 1) {
+        slab(t, 1);
+        ++t;
     }
     for (; t < nslab; t += 2) {
         slab(t, 0);
