@@ -57,6 +57,22 @@ int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k,
                 float beta, float *C, int64_t ldc, void *stream);
 
 /*
+ * Symmetric rank-k update on the real kernel (the paper's point that the level-3
+ * BLAS sit on GEMM, Abstract and Sec. 1):
+ *     C := alpha * A * A^T + beta * C   (trans = N, A is n x k)
+ *     C := alpha * A^T * A + beta * C   (trans = T or C, A is k x n)
+ * C is n x n; only its `uplo` triangle (L: i >= j, U: i <= j, diagonal included)
+ * is read and written, the other triangle is never touched.  Scalar semantics as
+ * for xgemm_dgemm (beta == 0: the triangle is write-only; alpha == 0 or k == 0:
+ * A is not read).  Illegal-argument numbering: uplo 1, trans 2, n 3, k 4,
+ * alpha 5, A 6, lda 7, beta 8, C 9, ldc 10.  flops: n (n + 1) k.
+ */
+int xgemm_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                double beta, double *C, int64_t ldc, void *stream);
+int xgemm_ssyrk(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+                float beta, float *C, int64_t ldc, void *stream);
+
+/*
  * Double-precision complex GEMM on split planes, built from the real kernel
  * (the paper's point that real GEMM carries complex GEMM, Abstract and Sec. 1;
  * the "4m" arrangement: four real products per complex product):
@@ -163,6 +179,19 @@ int xgemm_model_predict(char prec, int variant, char transa, char transb, double
  * Returns 0 or a hipError_t.
  */
 int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream);
+
+/*
+ * The workgroup -> macro-tile order the kernels use (host only, no device
+ * access), for tests and for reasoning about L2 reuse: for an m x n result cut
+ * into mt_m x mt_n tiles, uplo 0 (general), 1 (lower triangle) or 2 (upper
+ * triangle, m == n expected for 1 and 2), returns the number of workgroups a
+ * launch has and, when `out` is non-NULL, writes {tile row, tile column} of
+ * workgroup b to out[2b], out[2b+1] for b < min(count, cap).  Workgroup b runs
+ * on XCD b % 8.  Every tile that intersects the requested part of C appears
+ * exactly once; for a triangle a few tiles beside the diagonal that do not
+ * intersect it appear too and do nothing.  Returns -i for an illegal argument i.
+ */
+int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *out, int64_t cap);
 
 #ifdef __cplusplus
 }

@@ -71,6 +71,14 @@ def _declare(L):
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, sc, _p, _i64, _p, _i64,
                       sc, _p, _i64, _i64, _p, _p, _p, _p]
+    for name, sc in (("ref_dsyrk_work", ctypes.c_double), ("ref_ssyrk_work", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, sc, _p, _i64, sc, _p, _i64]
+    for name, sc in (("ref_dsyrk_ext", ctypes.c_double), ("ref_ssyrk_ext", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p, _p]
     L.ref_zgemm_split_ext.restype = ctypes.c_int
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
@@ -145,6 +153,29 @@ def gemm_samples(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, I, J):
     info = int(f(_ch(ta), _ch(tb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
                  ns, _ptr(I), _ptr(J), _ptr(cref), _ptr(g)))
     return info, cref, g
+
+
+def syrk_work(uplo, trans, n, k, alpha, A, lda, beta, C, ldc) -> int:
+    """In-place working-precision symmetric rank-k update of one triangle of C."""
+    pre, _ = _names(C.dtype if C is not None else np.float64)
+    f = getattr(lib(), f"ref_{pre}syrk_work")
+    return int(f(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc))
+
+
+def syrk_ext(uplo, trans, n, k, alpha, A, lda, beta, C, ldc):
+    """Extended-precision reference; returns (info, Cref, G), shape (n, n), zero outside the triangle."""
+    pre, wide = _names(C.dtype)
+    Cref = np.zeros((max(n, 0), max(n, 0)), dtype=wide)
+    G = np.zeros_like(Cref)
+    f = getattr(lib(), f"ref_{pre}syrk_ext")
+    info = int(f(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc, _ptr(Cref), _ptr(G)))
+    return info, Cref, G
+
+
+def triangle_mask(uplo, n):
+    """Boolean (n, n) mask in the (col, row) array layout: True where C(i, j) belongs to the triangle."""
+    j, i = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    return (i >= j) if uplo in "Ll" else (i <= j)
 
 
 def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc):

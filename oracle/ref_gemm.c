@@ -258,6 +258,101 @@ int NAME(char ta, char tb, i64 m, i64 n, i64 k, T alpha, const T *A, i64 lda,  \
 DEFINE_REF_GEMM_SAMPLES(ref_dgemm_samples, double, long double, fabsl)
 DEFINE_REF_GEMM_SAMPLES(ref_sgemm_samples, float, double, fabs)
 
+
+/* ------------------------------------------------------------------ */
+/* Symmetric rank-k update on one triangle (level-3 BLAS on top of the  */
+/* GEMM kernel, paper Abstract and Sec. 1):                             */
+/*   C := alpha * op(A) * op(A)^T + beta * C,  op(A) is n x k,          */
+/*   op(A)(i,p) = A[i + p*lda] (trans 'N') or A[p + i*lda] ('T'/'C').   */
+/* Only entries with i >= j (uplo 'L') or i <= j ('U') are read and     */
+/* written.  Same scalar rules as GEMM.  Errors: uplo 1, trans 2, n 3,  */
+/* k 4, alpha 5, A 6, lda 7, beta 8, C 9, ldc 10.                       */
+/* ------------------------------------------------------------------ */
+static int check_args_syrk(char uplo, char t, i64 n, i64 k, const void *A, i64 lda, const void *C, i64 ldc,
+                           int a_needed)
+{
+    if (uplo != 'L' && uplo != 'l' && uplo != 'U' && uplo != 'u') return -1;
+    if (!is_n(t) && !is_t(t)) return -2;
+    if (n < 0) return -3;
+    if (k < 0) return -4;
+    if (a_needed && n > 0 && k > 0 && A == NULL) return -6;
+    if (lda < max64(1, is_n(t) ? n : k)) return -7;
+    if (n > 0 && C == NULL) return -9;
+    if (ldc < max64(1, n)) return -10;
+    return 0;
+}
+
+#define OPS(i, p) (an ? A[(i) + (p) * lda] : A[(p) + (i) * lda])
+
+#define DEFINE_REF_SYRK_WORK(NAME, T)                                          \
+int NAME(char uplo, char t, i64 n, i64 k, T alpha, const T *A, i64 lda,        \
+         T beta, T *C, i64 ldc)                                                \
+{                                                                              \
+    int info = check_args_syrk(uplo, t, n, k, A, lda, C, ldc, alpha != (T)0);  \
+    if (info) return info;                                                     \
+    if (n == 0) return 0;                                                      \
+    if ((alpha == (T)0 || k == 0) && beta == (T)1) return 0;                   \
+    const int an = is_n(t), lower = (uplo == 'L' || uplo == 'l');              \
+    _Pragma("omp parallel for schedule(dynamic, 8)")                           \
+    for (i64 j = 0; j < n; ++j) {                                              \
+        const i64 i0 = lower ? j : 0, i1 = lower ? n : j + 1;                  \
+        for (i64 i = i0; i < i1; ++i) {                                        \
+            T acc = (T)0;                                                      \
+            if (alpha != (T)0)                                                 \
+                for (i64 p = 0; p < k; ++p) {                                  \
+                    T prod = OPS(i, p) * OPS(j, p);                            \
+                    acc = acc + prod;                                          \
+                }                                                              \
+            T r = alpha * acc;                                                 \
+            if (alpha == (T)0 || k == 0) r = (T)0;                             \
+            if (beta == (T)0) C[i + j * ldc] = r;                              \
+            else { T bc = beta * C[i + j * ldc]; C[i + j * ldc] = r + bc; }    \
+        }                                                                      \
+    }                                                                          \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_SYRK_WORK(ref_dsyrk_work, double)
+DEFINE_REF_SYRK_WORK(ref_ssyrk_work, float)
+
+/* Extended precision: Cref and G are dense n x n (ld = n); entries outside the
+ * triangle are set to 0 and carry no meaning. */
+#define DEFINE_REF_SYRK_EXT(NAME, T, W, WABS)                                  \
+int NAME(char uplo, char t, i64 n, i64 k, T alpha, const T *A, i64 lda,        \
+         T beta, const T *C, i64 ldc, W *Cref, W *G)                           \
+{                                                                              \
+    int info = check_args_syrk(uplo, t, n, k, A, lda, C, ldc, alpha != (T)0);  \
+    if (info) return info;                                                     \
+    const int an = is_n(t), lower = (uplo == 'L' || uplo == 'l');              \
+    const int use_a = (alpha != (T)0 && k > 0);                                \
+    _Pragma("omp parallel for schedule(dynamic, 8)")                           \
+    for (i64 j = 0; j < n; ++j) {                                              \
+        for (i64 i = 0; i < n; ++i) { Cref[i + j * n] = 0; G[i + j * n] = 0; } \
+        const i64 i0 = lower ? j : 0, i1 = lower ? n : j + 1;                  \
+        for (i64 i = i0; i < i1; ++i) {                                        \
+            W acc = 0, mag = 0;                                                \
+            if (use_a)                                                         \
+                for (i64 p = 0; p < k; ++p) {                                  \
+                    W prod = (W)OPS(i, p) * (W)OPS(j, p);                      \
+                    acc += prod;                                               \
+                    mag += WABS(prod);                                         \
+                }                                                              \
+            W r = (W)alpha * acc, g = WABS((W)alpha) * mag;                    \
+            if (beta != (T)0) {                                                \
+                W c = (W)C[i + j * ldc];                                       \
+                r += (W)beta * c;                                              \
+                g += WABS((W)beta) * WABS(c);                                  \
+            }                                                                  \
+            Cref[i + j * n] = r;                                               \
+            G[i + j * n] = g;                                                  \
+        }                                                                      \
+    }                                                                          \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_SYRK_EXT(ref_dsyrk_ext, double, long double, fabsl)
+DEFINE_REF_SYRK_EXT(ref_ssyrk_ext, float, double, fabs)
+
 /* ------------------------------------------------------------------ */
 /* Complex GEMM on split real/imaginary planes.                         */
 /*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/

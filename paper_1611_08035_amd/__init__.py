@@ -12,6 +12,9 @@ from .xgemm import (  # noqa: F401
     library_path,
     xgemm_dgemm,
     xgemm_sgemm,
+    xgemm_dsyrk,
+    xgemm_ssyrk,
+    xgemm_tile_map,
     xgemm_zgemm_split,
     xgemm_zgemm_worksize,
     xgemm_version,

@@ -102,6 +102,7 @@ template <typename T> struct GemmArgs {
     int m, n, k;
     T alpha, beta;
     int ntm, ntn;   // macro-tiles along m and n
+    int uplo;       // 0: all of C; 1: only the lower triangle (i >= j) is computed and written; 2: only the upper
 };
 
 // ---------------------------------------------------------------------------
@@ -275,20 +276,63 @@ constexpr int shadow_quota(int n_mma, int n_ld, int n_rd, int n_wr) {
 static constexpr int NUM_XCD = 8;
 static constexpr int GROUP_M = 8;
 
-static __device__ __forceinline__ void tile_of_block(int bid, int ntm, int ntn, int &tm, int &tn) {
-    const int nt = ntm * ntn;
+// Tile columns [c0, c1) a band of tile-rows [first, first + gsz) has to visit:
+// all of them for a general product; for a triangular result only those whose
+// tiles reach the triangle for at least one row of the band (the few tiles of
+// the band's corner that miss it leave at once in the kernel).
+struct BandCols { int c0, c1; };
+static __host__ __device__ __forceinline__ BandCols band_cols(int uplo, int first, int gsz, int ntn, int mt_m,
+                                                              int mt_n) {
+    BandCols b{0, ntn};
+    if (uplo == 1) {          // lower: first column of the tile <= last row of the band
+        const int64_t c = ((int64_t)(first + gsz) * mt_m - 1) / mt_n + 1;
+        if (c < ntn) b.c1 = (int)c;
+    } else if (uplo == 2) {   // upper: last column of the tile >= first row of the band
+        const int64_t c = ((int64_t)first * mt_m) / mt_n;
+        b.c0 = c < ntn ? (int)c : ntn;
+    }
+    return b;
+}
+
+// Number of workgroups to launch.
+static __host__ __device__ __forceinline__ int64_t tile_count(int uplo, int ntm, int ntn, int mt_m, int mt_n) {
+    if (uplo == 0) return (int64_t)ntm * ntn;
+    int64_t nt = 0;
+    for (int first = 0; first < ntm; first += GROUP_M) {
+        const int gsz = (ntm - first) < GROUP_M ? (ntm - first) : GROUP_M;
+        const BandCols b = band_cols(uplo, first, gsz, ntn, mt_m, mt_n);
+        nt += (int64_t)gsz * (b.c1 - b.c0);
+    }
+    return nt;
+}
+
+struct TilePos { int tm, tn; };
+static __host__ __device__ __forceinline__ TilePos tile_of_block(int bid, int nt, int ntm, int ntn, int uplo,
+                                                                 int mt_m, int mt_n) {
     const int per = (nt + NUM_XCD - 1) / NUM_XCD;
     int tall = nt % NUM_XCD;
     if (tall == 0) tall = NUM_XCD;
     const int xcd = bid % NUM_XCD, loc = bid / NUM_XCD;
-    const int lin = xcd < tall ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
-    const int width = GROUP_M * ntn;
-    const int grp = lin / width;
-    const int first = grp * GROUP_M;
+    int lin = xcd < tall ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
+    if (uplo == 0) {
+        const int width = GROUP_M * ntn;
+        const int grp = lin / width;
+        const int first = grp * GROUP_M;
+        const int gsz = (ntm - first) < GROUP_M ? (ntm - first) : GROUP_M;
+        const int in = lin - grp * width;
+        return TilePos{first + in % gsz, in / gsz};
+    }
+    // triangular: bands differ in width; walk them (uniform, a few scalar steps)
+    int first = 0;
+    for (; first + GROUP_M < ntm; first += GROUP_M) {
+        const BandCols b = band_cols(uplo, first, GROUP_M, ntn, mt_m, mt_n);
+        const int sz = GROUP_M * (b.c1 - b.c0);
+        if (lin < sz) break;
+        lin -= sz;
+    }
     const int gsz = (ntm - first) < GROUP_M ? (ntm - first) : GROUP_M;
-    const int in = lin - grp * width;
-    tm = first + in % gsz;
-    tn = in / gsz;
+    const BandCols b = band_cols(uplo, first, gsz, ntn, mt_m, mt_n);
+    return TilePos{first + lin % gsz, b.c0 + lin / gsz};
 }
 
 // ---------------------------------------------------------------------------
@@ -341,10 +385,22 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     const int wm0 = (wave % Cfg::WGM) * Cfg::WT_M;
     const int wn0 = (wave / Cfg::WGM) * Cfg::WT_N;
 
-    int tm, tn;
-    tile_of_block(blockIdx.x, g.ntm, g.ntn, tm, tn);
+    const TilePos tp = tile_of_block(blockIdx.x, (int)gridDim.x, g.ntm, g.ntn, g.uplo, MT_M, MT_N);
+    const int tm = tp.tm, tn = tp.tn;
+    if (tm >= g.ntm || tn >= g.ntn) return;   // cannot happen when the grid is tile_count() workgroups
     const int m0 = tm * MT_M, n0 = tn * MT_N;
     const int m_lim = g.m - m0, n_lim = g.n - n0;   // rows / cols of this tile inside C
+    // Triangular output (rank-k updates of a symmetric matrix): tiles wholly in
+    // the other triangle leave at once, tiles wholly inside run as usual, tiles
+    // the diagonal crosses take the predicated epilogue with the triangle test.
+    bool on_diagonal = false;
+    if (g.uplo == 1) {
+        if (m0 + MT_M - 1 < n0) return;
+        on_diagonal = m0 < n0 + MT_N - 1;
+    } else if (g.uplo == 2) {
+        if (n0 + MT_N - 1 < m0) return;
+        on_diagonal = n0 < m0 + MT_M - 1;
+    }
     const bool interior = FAST && m_lim >= MT_M && n_lim >= MT_N;
 
     // slab origins at depth 0
@@ -358,7 +414,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     constexpr int VRM = Cfg::VRM, VRN = Cfg::VRN;
     const int mc = wm0 + VRM * M::d_col(lane);
     auto c_n = [&](int j, int r) { return wn0 + (j / VRN) * VRN * M::MI + VRN * M::d_row(lane, r) + (j % VRN); };
-    const bool full_tile = m_lim >= MT_M && n_lim >= MT_N;
+    const bool full_tile = m_lim >= MT_M && n_lim >= MT_N && !on_diagonal;
     const T alpha = g.alpha, beta = g.beta;
     typename M::acc_t acc[TN][TM];
 #pragma unroll
@@ -584,7 +640,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     const int mm = mc + (i / VRM) * VRM * M::MI + (i % VRM);
-                    if (mm < m_lim && nn < n_lim) {
+                    // signed distance below the diagonal, flipped for the upper triangle
+                    const int below = (g.uplo == 2) ? (n0 - m0) + nn - mm : (m0 - n0) + mm - nn;
+                    if (mm < m_lim && nn < n_lim && (g.uplo == 0 || below >= 0)) {
                         T v = alpha * acc[j][i][r];
                         if (use_c) v += beta * crow[mm];
                         crow[mm] = v;
@@ -595,12 +653,14 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     }
 }
 
-// C := beta * C (beta == 0 stores zeros without reading), the alpha == 0 / k == 0 path.
+// C := beta * C (beta == 0 stores zeros without reading), the alpha == 0 / k == 0 path;
+// uplo as in GemmArgs.
 template <typename T>
-__global__ void __launch_bounds__(256) scale_kernel(T *C, int64_t ldc, int m, int n, T beta) {
+__global__ void __launch_bounds__(256) scale_kernel(T *C, int64_t ldc, int m, int n, T beta, int uplo) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= m) return;
     for (int j = blockIdx.y; j < n; j += gridDim.y) {
+        if ((uplo == 1 && i < j) || (uplo == 2 && i > j)) continue;
         T *p = C + i + (int64_t)j * ldc;
         *p = (beta == T(0)) ? T(0) : beta * *p;
     }

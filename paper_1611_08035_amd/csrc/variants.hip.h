@@ -25,27 +25,39 @@ static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
                                                        (int)Cfg::LDS_BYTES)
                                  : hipSuccess;
     if (attr != hipSuccess) return attr;
-    const dim3 grid((unsigned)(g.ntm * g.ntn)), block(Cfg::NT);
+    const int64_t nt = tile_count(g.uplo, g.ntm, g.ntn, Cfg::MT_M, Cfg::MT_N);
+    if (nt > 0x7fffffff) return hipErrorInvalidValue;   // beyond one grid dimension (and any device memory)
+    const dim3 grid((unsigned)nt), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, st, g);
     return hipGetLastError();
 }
 
+// The element-wise fallback (FAST == false: leading dimensions too large for
+// 32-bit slab offsets) is only built for the 64x64 tile; the host routes such
+// calls to that variant.
 template <typename T, typename Cfg>
 static hipError_t launch_cfg(bool ak, bool bk, bool fast, const GemmArgs<T> &g0, hipStream_t st) {
     GemmArgs<T> g = g0;
     g.ntm = (g.m + Cfg::MT_M - 1) / Cfg::MT_M;
     g.ntn = (g.n + Cfg::MT_N - 1) / Cfg::MT_N;
-    const int sel = (ak ? 4 : 0) | (bk ? 2 : 0) | (fast ? 1 : 0);
-    switch (sel) {
-        case 0: return launch_one<T, Cfg, false, false, false>(g, st);
-        case 1: return launch_one<T, Cfg, false, false, true>(g, st);
-        case 2: return launch_one<T, Cfg, false, true, false>(g, st);
-        case 3: return launch_one<T, Cfg, false, true, true>(g, st);
-        case 4: return launch_one<T, Cfg, true, false, false>(g, st);
-        case 5: return launch_one<T, Cfg, true, false, true>(g, st);
-        case 6: return launch_one<T, Cfg, true, true, false>(g, st);
-        default: return launch_one<T, Cfg, true, true, true>(g, st);
+    constexpr bool HAS_FALLBACK = (Cfg::MT_M == 64 && Cfg::MT_N == 64);
+    if (fast) {
+        switch ((ak ? 2 : 0) | (bk ? 1 : 0)) {
+            case 0: return launch_one<T, Cfg, false, false, true>(g, st);
+            case 1: return launch_one<T, Cfg, false, true, true>(g, st);
+            case 2: return launch_one<T, Cfg, true, false, true>(g, st);
+            default: return launch_one<T, Cfg, true, true, true>(g, st);
+        }
     }
+    if constexpr (HAS_FALLBACK) {
+        switch ((ak ? 2 : 0) | (bk ? 1 : 0)) {
+            case 0: return launch_one<T, Cfg, false, false, false>(g, st);
+            case 1: return launch_one<T, Cfg, false, true, false>(g, st);
+            case 2: return launch_one<T, Cfg, true, false, false>(g, st);
+            default: return launch_one<T, Cfg, true, true, false>(g, st);
+        }
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace xg

@@ -46,14 +46,15 @@ int num_cus() {
 // occ * tile_area / eff with occ workgroups per CU, derated when a CU holds a
 // single workgroup (one wave per SIMD has nobody to hide its stalls behind).
 // K is common to all variants and drops out.
-template <typename T> int choose_variant(int64_t m, int64_t n, const VariantEntry<T> *tab, int nv) {
+template <typename T> int choose_variant(int64_t m, int64_t n, int uplo, const VariantEntry<T> *tab, int nv) {
     if (t_forced_variant >= 0 && t_forced_variant < nv) return t_forced_variant;
     const int64_t cus = num_cus();
     int best = 0;
     double best_cost = 0.0;
     for (int v = 0; v < nv; ++v) {
         const VariantEntry<T> &e = tab[v];
-        const int64_t tiles = ((m + e.mt_m - 1) / e.mt_m) * ((n + e.mt_n - 1) / e.mt_n);
+        const int64_t tiles = tile_count(uplo, (int)((m + e.mt_m - 1) / e.mt_m), (int)((n + e.mt_n - 1) / e.mt_n),
+                                         e.mt_m, e.mt_n);
         const int64_t slots = cus * e.wgs_per_cu;
         const double area = (double)e.mt_m * (double)e.mt_n;
         const int64_t full = tiles / slots, rem = tiles % slots;
@@ -67,9 +68,10 @@ template <typename T> int choose_variant(int64_t m, int64_t n, const VariantEntr
     return best;
 }
 
+// uplo: 0 general, 1 lower, 2 upper (the caller has checked m == n for those).
 template <typename T>
 int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
-              const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream) {
+              const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream, int uplo = 0) {
     t_last_kernel = "none";
     if (!is_n(ta) && !is_t(ta)) return -1;
     if (!is_n(tb) && !is_t(tb)) return -2;
@@ -92,19 +94,20 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     if (!ab_read) {
         t_last_kernel = "scale";
         const dim3 grid((unsigned)((m + 255) / 256), (unsigned)(n < 1024 ? n : 1024));
-        hipLaunchKernelGGL(scale_kernel<T>, grid, dim3(256), 0, st, C, ldc, (int)m, (int)n, beta);
+        hipLaunchKernelGGL(scale_kernel<T>, grid, dim3(256), 0, st, C, ldc, (int)m, (int)n, beta, uplo);
         return (int)hipGetLastError();
     }
 
     int nv = 0;
     const VariantEntry<T> *tab = table<T>(&nv);
-    const int v = choose_variant<T>(m, n, tab, nv);
+    int v = choose_variant<T>(m, n, uplo, tab, nv);
     GemmArgs<T> g;
     g.A = A; g.B = B; g.C = C;
     g.lda = lda; g.ldb = ldb; g.ldc = ldc;
     g.m = (int)m; g.n = (int)n; g.k = (int)k;
     g.alpha = alpha; g.beta = beta;
     g.ntm = g.ntn = 0;
+    g.uplo = uplo;
     // The buffer-load path addresses one slab (at most 256 rows or columns of
     // the stored operand) with 31-bit byte offsets; beyond that the element-wise
     // fallback runs.  16-byte loads of 4- or 8-byte aligned data are legal for
@@ -113,9 +116,34 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     bool fast = lda <= ld_max && ldb <= ld_max;
     if (t_require_aligned)
         fast = fast && aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0;
+    if (!fast)   // the element-wise fallback exists for the 64x64 tile only
+        for (int i = 0; i < nv; ++i)
+            if (tab[i].mt_m == 64 && tab[i].mt_n == 64) v = i;
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
     return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
+}
+
+// C := alpha op(A) op(A)^T + beta C on one triangle: the GEMM kernel with B = A,
+// the opposite transpose, and the triangle mask.
+template <typename T>
+int syrk_impl(char uplo, char trans, int64_t n, int64_t k, T alpha, const T *A, int64_t lda, T beta, T *C,
+                     int64_t ldc, void *stream) {
+    t_last_kernel = "none";
+    const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
+    if (!lower && !upper) return -1;
+    if (!is_n(trans) && !is_t(trans)) return -2;
+    if (n < 0 || n > DIM_MAX) return -3;
+    if (k < 0 || k > DIM_MAX) return -4;
+    const bool a_read = (alpha != T(0)) && n > 0 && k > 0;
+    if (a_read && !A) return -6;
+    if (lda < max64(1, is_n(trans) ? n : k)) return -7;
+    if (n > 0 && !C) return -9;
+    if (ldc < max64(1, n)) return -10;
+    // op(A) op(A)^T: second operand is the same matrix with the opposite transpose
+    const int rc = gemm_impl<T>(is_n(trans) ? 'N' : 'T', is_n(trans) ? 'T' : 'N', n, n, k, alpha, A, lda, A, lda, beta,
+                                C, ldc, stream, lower ? 1 : 2);
+    return rc;   // the argument checks above cover every error gemm_impl could report
 }
 
 // Elementwise combine for the complex path with complex scalars:
@@ -214,6 +242,34 @@ int xgemm_dgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, doubl
 int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
                 int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream) {
     return gemm_impl<float>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+int xgemm_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda, double beta,
+                double *C, int64_t ldc, void *stream) {
+    return syrk_impl<double>(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream);
+}
+
+int xgemm_ssyrk(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda, float beta,
+                float *C, int64_t ldc, void *stream) {
+    return syrk_impl<float>(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream);
+}
+
+int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *out, int64_t cap) {
+    if (uplo < 0 || uplo > 2) return -1;
+    if (m <= 0 || m > DIM_MAX) return -2;
+    if (n <= 0 || n > DIM_MAX) return -3;
+    if (mt_m <= 0) return -4;
+    if (mt_n <= 0) return -5;
+    const int ntm = (int)((m + mt_m - 1) / mt_m), ntn = (int)((n + mt_n - 1) / mt_n);
+    const int64_t nt = tile_count(uplo, ntm, ntn, mt_m, mt_n);
+    if (nt > DIM_MAX) return -2;
+    if (out)
+        for (int64_t b = 0; b < nt && b < cap; ++b) {
+            const TilePos t = tile_of_block((int)b, (int)nt, ntm, ntn, uplo, mt_m, mt_n);
+            out[2 * b] = t.tm;
+            out[2 * b + 1] = t.tn;
+        }
+    return nt;
 }
 
 size_t xgemm_zgemm_worksize(int64_t m, int64_t n, const double alpha[2], const double beta[2]) {

@@ -14,10 +14,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "libxgemm.so")
 
 EXPORTS = [
-    "xgemm_dgemm", "xgemm_sgemm", "xgemm_zgemm_split", "xgemm_zgemm_worksize", "xgemm_version",
+    "xgemm_dgemm", "xgemm_sgemm", "xgemm_dsyrk", "xgemm_ssyrk", "xgemm_zgemm_split", "xgemm_zgemm_worksize", "xgemm_version",
     "xgemm_last_kernel_name", "xgemm_force_variant", "xgemm_variant_name", "xgemm_mfma_peak_probe",
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
-    "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict",
+    "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
 ]
 
 
@@ -53,11 +53,17 @@ def lib():
         f = getattr(L, f"xgemm_{pre}gemm")
         f.restype = ctypes.c_int
         f.argtypes = [_c, _c, _i64, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p]
+    for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
+        f = getattr(L, f"xgemm_{pre}syrk")
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _c, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p]
     L.xgemm_zgemm_split.restype = ctypes.c_int
     L.xgemm_zgemm_split.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
                                     _p, _i64, _p]
     L.xgemm_zgemm_worksize.restype = ctypes.c_size_t
     L.xgemm_zgemm_worksize.argtypes = [_i64, _i64, _p, _p]
+    L.xgemm_tile_map.restype = _i64
+    L.xgemm_tile_map.argtypes = [ctypes.c_int, _i64, _i64, ctypes.c_int, ctypes.c_int, _p, _i64]
     L.xgemm_version.restype = ctypes.c_char_p
     L.xgemm_last_kernel_name.restype = ctypes.c_char_p
     L.xgemm_force_variant.restype = ctypes.c_int
@@ -111,6 +117,16 @@ def xgemm_dgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, st
 def xgemm_sgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream=None) -> int:
     return int(lib().xgemm_sgemm(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                  _ptr(C), ldc, _stream(stream)))
+
+
+def xgemm_dsyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_dsyrk(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
+                                 _stream(stream)))
+
+
+def xgemm_ssyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_ssyrk(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
+                                 _stream(stream)))
 
 
 def _pair(z):
@@ -180,3 +196,13 @@ def xgemm_model_predict(prec, variant, transa="N", transb="N"):
     out = (ctypes.c_double * 12)()
     rc = int(lib().xgemm_model_predict(_ch(prec), int(variant), _ch(transa), _ch(transb), out))
     return rc, list(out)
+
+
+def xgemm_tile_map(uplo, m, n, mt_m, mt_n, want_tiles=True):
+    """Returns (count, tiles): tiles is a list of (tile row, tile column) per workgroup, or None."""
+    cnt = int(lib().xgemm_tile_map(int(uplo), m, n, int(mt_m), int(mt_n), None, 0))
+    if cnt <= 0 or not want_tiles:
+        return cnt, None
+    buf = (ctypes.c_int * (2 * cnt))()
+    lib().xgemm_tile_map(int(uplo), m, n, int(mt_m), int(mt_n), buf, cnt)
+    return cnt, [(buf[2 * b], buf[2 * b + 1]) for b in range(cnt)]

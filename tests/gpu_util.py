@@ -64,3 +64,41 @@ def check_samples(out, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, I, 
     nviol, ratio = oracle.bound_violations(out[J, I], cref, g, k, unit_roundoff(C.dtype), factor)
     assert nviol == 0, f"{nviol} sampled elements outside the bound (max ratio {ratio})"
     return ratio
+
+
+def run_syrk(xg, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, expect=0):
+    """Run xgemm_{d,s}syrk on copies of the numpy operands; return C after the call."""
+    torch = torch_mod()
+    f = xg.xgemm_dsyrk if C.dtype == np.float64 else xg.xgemm_ssyrk
+    dA, dC = to_dev(A), to_dev(C)
+    rc = f(uplo, trans, n, k, alpha, dA, lda, beta, dC, ldc)
+    torch.cuda.synchronize()
+    assert rc == expect, f"return code {rc}, expected {expect}"
+    return dC.cpu().numpy()
+
+
+def make_syrk_operands(rng, trans, n, k, pad=(0, 0), dtype=np.float64, kind="uniform", R=8):
+    ra, ca = (n, k) if trans == "N" else (k, n)
+    lda, ldc = max(ra, 1) + pad[0], max(n, 1) + pad[1]
+    if kind == "uniform":
+        gen = lambda r, c, ld: si.uniform(rng, r, c, ld, dtype)
+    else:
+        gen = lambda r, c, ld: si.integers(rng, r, c, ld, dtype, R=R)
+    return gen(ra, ca, lda), lda, gen(n, n, ldc), ldc
+
+
+def check_syrk_full(xg, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, factor=4.0):
+    """GPU triangle against the extended-precision oracle on every element of the
+    triangle; everything else in the buffer (other triangle, padding rows) must be
+    bit-identical to the input.  Returns the largest err/bound ratio."""
+    out = run_syrk(xg, uplo, trans, n, k, alpha, A, lda, beta, C, ldc)
+    info, Cref, G = oracle.syrk_ext(uplo, trans, n, k, alpha, A, lda, beta, C, ldc)
+    assert info == 0
+    mask = oracle.triangle_mask(uplo, n)
+    got = np.where(mask, out[:, :n], 0).astype(out.dtype)
+    nviol, ratio = oracle.bound_violations(got, Cref, G, k, unit_roundoff(C.dtype), factor)
+    assert nviol == 0, f"{nviol} elements outside the bound (max ratio {ratio}) for {uplo}{trans} {n}x{k}"
+    keep = np.ones(C.shape, dtype=bool)
+    keep[:, :n] = ~mask
+    assert np.array_equal(out[keep], C[keep], equal_nan=True), "elements outside the triangle were written"
+    return ratio

@@ -63,6 +63,27 @@ def test_illegal_arguments_are_rejected_on_the_host(fn):
     assert xg.xgemm_last_kernel_name() == "none"
 
 
+@pytest.mark.parametrize("fn", ["xgemm_dsyrk", "xgemm_ssyrk"])
+def test_syrk_illegal_arguments_and_quick_returns(fn):
+    f = getattr(xg, fn)
+    P = 4096
+    g = lambda *a: f(*a, stream=0)
+    assert g("X", "N", 2, 2, 1.0, P, 2, 0.0, P, 2) == -1
+    assert g("L", "Q", 2, 2, 1.0, P, 2, 0.0, P, 2) == -2
+    assert g("L", "N", -1, 2, 1.0, P, 2, 0.0, P, 2) == -3
+    assert g("L", "N", 2 ** 31, 2, 1.0, P, 2 ** 31, 0.0, P, 2 ** 31) == -3
+    assert g("U", "N", 2, -1, 1.0, P, 2, 0.0, P, 2) == -4
+    assert g("U", "N", 2, 2, 1.0, None, 2, 0.0, P, 2) == -6
+    assert g("L", "N", 3, 2, 1.0, P, 2, 0.0, P, 3) == -7
+    assert g("L", "T", 2, 3, 1.0, P, 2, 0.0, P, 2) == -7
+    assert g("L", "N", 2, 2, 1.0, P, 2, 0.0, None, 2) == -9
+    assert g("L", "N", 3, 2, 1.0, P, 3, 0.0, P, 2) == -10
+    assert g("L", "N", 0, 2, 1.0, None, 1, 0.0, None, 1) == 0
+    assert g("U", "T", 2, 0, 1.0, None, 1, 1.0, P, 2) == 0
+    assert g("U", "C", 2, 2, 0.0, None, 2, 1.0, P, 2) == 0
+    assert xg.xgemm_last_kernel_name() == "none"
+
+
 def test_zgemm_illegal_arguments_and_worksize():
     P = 4096
     z = lambda *a, **kw: xg.xgemm_zgemm_split(*a, stream=0, **kw)
@@ -81,6 +102,39 @@ def test_zgemm_illegal_arguments_and_worksize():
     assert z("N", "N", 2, 2, 2, (1, 1), P, P, 2, P, P, 2, (0, 0), P, P, 2, work=None, lwork=8) == -17
     assert z("N", "N", 2, 2, 2, (1, 1), P, P, 2, P, P, 2, (0, 0), P, P, 2, work=P, lwork=7) == -18
     assert z("N", "N", 0, 2, 2, (1, 1), None, None, 1, None, None, 2, (0, 0), None, None, 1) == 0
+
+
+@pytest.mark.parametrize("mt_m,mt_n", [(128, 128), (256, 128), (64, 64), (128, 64), (64, 128)])
+@pytest.mark.parametrize("uplo", [0, 1, 2])
+def test_tile_order_covers_every_needed_tile_exactly_once(uplo, mt_m, mt_n):
+    for m, n in [(1, 1), (100, 100), (1000, 1000), (8192, 8192), (4097, 4097), (3001, 3001)] + \
+            ([(4097, 3001), (130, 9000), (9000, 130)] if uplo == 0 else []):
+        cnt, tiles = xg.xgemm_tile_map(uplo, m, n, mt_m, mt_n)
+        ntm, ntn = -(-m // mt_m), -(-n // mt_n)
+        assert cnt == len(tiles) and len(set(tiles)) == cnt, "a tile is visited twice"
+        assert all(0 <= tm < ntm and 0 <= tn < ntn for tm, tn in tiles)
+        def needed(tm, tn):
+            r0, r1 = tm * mt_m, min(m, (tm + 1) * mt_m) - 1
+            c0, c1 = tn * mt_n, min(n, (tn + 1) * mt_n) - 1
+            return True if uplo == 0 else (r1 >= c0 if uplo == 1 else c1 >= r0)
+        need = {(tm, tn) for tm in range(ntm) for tn in range(ntn) if needed(tm, tn)}
+        assert need <= set(tiles), "a tile of the result is never computed"
+        # the idle tiles of a triangular launch are confined to band corners
+        assert cnt - len(need) <= ntm * 8
+        if uplo == 0:
+            assert cnt == ntm * ntn
+
+
+def test_tile_order_xcd_runs_are_contiguous():
+    # workgroup b runs on XCD b % 8; each XCD must own one contiguous run of the band order
+    cnt, tiles = xg.xgemm_tile_map(0, 8192, 8192, 128, 128)
+    order = {t: i for i, t in enumerate(
+        (first + r, c) for first in range(0, 64, 8) for c in range(64) for r in range(8))}
+    for x in range(8):
+        pos = [order[tiles[b]] for b in range(x, cnt, 8)]
+        assert pos == list(range(pos[0], pos[0] + len(pos)))
+    assert xg.xgemm_tile_map(3, 8, 8, 8, 8)[0] == -1 and xg.xgemm_tile_map(0, 0, 8, 8, 8)[0] == -2
+    assert xg.xgemm_tile_map(0, 8, 8, 0, 8)[0] == -4
 
 
 def test_missing_library_raises(monkeypatch):

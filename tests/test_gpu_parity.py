@@ -129,6 +129,20 @@ def test_every_variant_integer_bit_exact(dtype, prec, variant):
             assert np.array_equal(out, want, equal_nan=True)
 
 
+def test_element_wise_fallback_kernels():
+    """The fallback for leading dimensions beyond the 32-bit slab offsets cannot be
+    reached with matrices that fit a test; a tuning switch read at load time sends
+    unaligned operands there, so it is exercised in a child process."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    env = dict(os.environ, XGEMM_REQUIRE_ALIGNED="1")
+    r = subprocess.run([sys.executable, "-u", os.path.join(here, "fallback_case.py")], env=env, capture_output=True,
+                       text=True, timeout=300)
+    assert r.returncode == 0 and "fallback ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 # --------------------------------------------------------------------------
 # closed forms and scalar paths (automatic variant choice)
 # --------------------------------------------------------------------------

@@ -53,7 +53,7 @@ def kernel_metadata():
 
 def test_gemm_kernels_never_spill():
     ks = [k for k in kernel_metadata() if k["name"] and "gemm_kernel" in k["name"]]
-    assert len(ks) >= 40, "expected every tile variant x transpose pair x load path"
+    assert len(ks) >= 40, "expected every tile variant x transpose pair (+ the fallback path)"
     for k in ks:
         assert int(k["vgpr_spill_count"]) == 0, k
         assert int(k["sgpr_spill_count"] or 0) == 0, k
