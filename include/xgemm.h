@@ -73,6 +73,40 @@ int xgemm_ssyrk(char uplo, char trans, int64_t n, int64_t k, float alpha, const 
                 float beta, float *C, int64_t ldc, void *stream);
 
 /*
+ * The same four routines with a caller-owned workspace, which lets the library
+ * cut the tiles of the last, partly filled round of workgroups along K (the k_c
+ * loop of Fig. 1 moved across workgroups for those tiles only): each piece
+ * leaves its partial sums in the workspace, the piece that finishes last adds
+ * them in a fixed order and writes C, so results do not depend on timing and
+ * satisfy the same error bound.  Whether and how far to split is decided by the
+ * cost model from the shape; shapes that fill their rounds run exactly as in
+ * the plain routines.
+ *   work : device buffer, 16-byte aligned, lwork bytes; xgemm_workspace_bytes()
+ *          is the size that never limits the split (8 KiB of counters + 64 MiB).
+ *          Smaller buffers split less; NULL or lwork <= 8 KiB: never split.
+ *          Before its first use the first 8 KiB must be zero
+ *          (xgemm_workspace_init); every call leaves them zero again.  Calls
+ *          that share a workspace must be ordered on one stream (or otherwise
+ *          not overlap); its other contents are undefined after a call.
+ * Illegal-argument numbering as in the plain routines, then work (14 for gemm,
+ * 11 for syrk; reported when it is not 16-byte aligned).
+ */
+size_t xgemm_workspace_bytes(void);
+/* Clears the counters at the start of `work` on `stream` (a kernel launch).
+ * Returns 0, -1 (work NULL or misaligned), -2 (lwork < 8 KiB) or a hipError_t. */
+int xgemm_workspace_init(void *work, size_t lwork, void *stream);
+int xgemm_dgemm_ws(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                   double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
+                   double beta, double *C, int64_t ldc, void *work, size_t lwork, void *stream);
+int xgemm_sgemm_ws(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                   float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                   float beta, float *C, int64_t ldc, void *work, size_t lwork, void *stream);
+int xgemm_dsyrk_ws(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                   double beta, double *C, int64_t ldc, void *work, size_t lwork, void *stream);
+int xgemm_ssyrk_ws(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+                   float beta, float *C, int64_t ldc, void *work, size_t lwork, void *stream);
+
+/*
  * Double-precision complex GEMM on split planes, built from the real kernel
  * (the paper's point that real GEMM carries complex GEMM, Abstract and Sec. 1;
  * the "4m" arrangement: four real products per complex product):
@@ -115,6 +149,14 @@ const char *xgemm_last_kernel_name(void);
  * Returns 0, or -1 if the index is out of range.
  */
 int xgemm_force_variant(int variant);
+
+/* Benchmark/tuning control for the *_ws routines on the calling thread: -1 lets
+ * the cost model decide (default), 0 never splits, 2..32 splits the tail tiles
+ * into that many pieces wherever the shape and workspace allow.  Returns 0, or
+ * -1 for any other value.  xgemm_last_split(): pieces per tail tile used by the
+ * last call on this thread (1: nothing was split). */
+int xgemm_force_split(int pieces);
+int xgemm_last_split(void);
 
 /* Name of tile variant `variant` for precision `prec` ('d' or 's'), or NULL
  * past the end of the list. */

@@ -15,6 +15,14 @@ from .xgemm import (  # noqa: F401
     xgemm_dsyrk,
     xgemm_ssyrk,
     xgemm_tile_map,
+    xgemm_workspace_bytes,
+    xgemm_workspace_init,
+    xgemm_dgemm_ws,
+    xgemm_sgemm_ws,
+    xgemm_dsyrk_ws,
+    xgemm_ssyrk_ws,
+    xgemm_force_split,
+    xgemm_last_split,
     xgemm_zgemm_split,
     xgemm_zgemm_worksize,
     xgemm_version,

@@ -103,6 +103,16 @@ template <typename T> struct GemmArgs {
     T alpha, beta;
     int ntm, ntn;   // macro-tiles along m and n
     int uplo;       // 0: all of C; 1: only the lower triangle (i >= j) is computed and written; 2: only the upper
+    // Split tail (kernels built with SPLIT only).  The first `ndp` tiles of the
+    // tile order are computed whole, one workgroup each; every later tile is cut
+    // along K into `nsplit` pieces, one workgroup each, which leave their partial
+    // sums in `part` (piece s of split tile q at part[(q*nsplit + s) * MT_M*MT_N])
+    // and count themselves in cnt[q]; the piece that arrives last adds the
+    // partial sums in the order s = 0, 1, ... and writes C.  cnt[] is zero before
+    // the launch and zero again after it.  nsplit <= 1: nothing is split.
+    int ndp, nsplit;
+    T *part;
+    unsigned *cnt;
 };
 
 // ---------------------------------------------------------------------------
@@ -306,14 +316,21 @@ static __host__ __device__ __forceinline__ int64_t tile_count(int uplo, int ntm,
     return nt;
 }
 
-struct TilePos { int tm, tn; };
-static __host__ __device__ __forceinline__ TilePos tile_of_block(int bid, int nt, int ntm, int ntn, int uplo,
-                                                                 int mt_m, int mt_n) {
+// Position of workgroup `bid` of `nt` in the tile order: XCD x = bid % 8 owns
+// one contiguous run of the order.
+static __host__ __device__ __forceinline__ int lin_of_block(int bid, int nt) {
     const int per = (nt + NUM_XCD - 1) / NUM_XCD;
     int tall = nt % NUM_XCD;
     if (tall == 0) tall = NUM_XCD;
     const int xcd = bid % NUM_XCD, loc = bid / NUM_XCD;
-    int lin = xcd < tall ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
+    return xcd < tall ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
+}
+
+// Tile at position `lin` of the tile order (bands of GROUP_M tile-rows, walked
+// column by column).
+struct TilePos { int tm, tn; };
+static __host__ __device__ __forceinline__ TilePos tile_of_lin(int lin, int ntm, int ntn, int uplo, int mt_m,
+                                                               int mt_n) {
     if (uplo == 0) {
         const int width = GROUP_M * ntn;
         const int grp = lin / width;
@@ -366,7 +383,7 @@ template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC
     static constexpr size_t LDS_BYTES = 2 * (size_t)KT * (MT_M + MT_N + 2 * PADK) * sizeof(T);
 };
 
-template <typename T, typename Cfg, bool AK, bool BK, bool FAST>
+template <typename T, typename Cfg, bool AK, bool BK, bool FAST, bool SPLIT = false>
 __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<T> g) {
     using M = Mfma<T>;
     constexpr int MT_M = Cfg::MT_M, MT_N = Cfg::MT_N, KT = Cfg::KT, NT = Cfg::NT;
@@ -385,7 +402,21 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     const int wm0 = (wave % Cfg::WGM) * Cfg::WT_M;
     const int wn0 = (wave / Cfg::WGM) * Cfg::WT_N;
 
-    const TilePos tp = tile_of_block(blockIdx.x, (int)gridDim.x, g.ntm, g.ntn, g.uplo, MT_M, MT_N);
+    // which tile, and (SPLIT) which piece of its K range
+    int lin, piece = 0, npieces = 1;
+    if constexpr (SPLIT) {
+        const int bid = blockIdx.x;
+        if (bid < g.ndp) {
+            lin = lin_of_block(bid, g.ndp);
+        } else {
+            npieces = g.nsplit;
+            lin = g.ndp + (bid - g.ndp) / npieces;
+            piece = (bid - g.ndp) % npieces;
+        }
+    } else {
+        lin = lin_of_block(blockIdx.x, (int)gridDim.x);
+    }
+    const TilePos tp = tile_of_lin(lin, g.ntm, g.ntn, g.uplo, MT_M, MT_N);
     const int tm = tp.tm, tn = tp.tn;
     if (tm >= g.ntm || tn >= g.ntn) return;   // cannot happen when the grid is tile_count() workgroups
     const int m0 = tm * MT_M, n0 = tn * MT_N;
@@ -403,9 +434,21 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     }
     const bool interior = FAST && m_lim >= MT_M && n_lim >= MT_N;
 
-    // slab origins at depth 0
-    const T *pa = AK ? g.A + (int64_t)m0 * g.lda : g.A + m0;
-    const T *pb = BK ? g.B + (int64_t)n0 * g.ldb : g.B + (int64_t)n0;
+    // K range of this workgroup: all of it, or piece `piece` of `npieces` in whole slabs
+    int k_begin = 0, k_len = g.k;
+    if constexpr (SPLIT) {
+        if (npieces > 1) {
+            const int nsl = (g.k + KT - 1) / KT, base = nsl / npieces, extra = nsl % npieces;
+            const int s0 = piece * base + (piece < extra ? piece : extra);
+            const int cnt = base + (piece < extra ? 1 : 0);
+            k_begin = s0 * KT;
+            k_len = (g.k - k_begin) < cnt * KT ? (g.k - k_begin) : cnt * KT;
+        }
+    }
+
+    // slab origins at depth k_begin
+    const T *pa = AK ? g.A + (int64_t)m0 * g.lda + k_begin : g.A + m0 + (int64_t)k_begin * g.lda;
+    const T *pb = BK ? g.B + (int64_t)n0 * g.ldb + k_begin : g.B + (int64_t)n0 + (int64_t)k_begin * g.ldb;
     const int64_t step_a = AK ? (int64_t)KT : (int64_t)KT * g.lda;
     const int64_t step_b = BK ? (int64_t)KT : (int64_t)KT * g.ldb;
 
@@ -430,10 +473,10 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     StA::offsets(offa, g.lda, tid);
     StB::offsets(offb, g.ldb, tid);
 
-    const int nslab = (g.k + KT - 1) / KT;
+    const int nslab = (k_len + KT - 1) / KT;
 
     auto fetch = [&](int t) {
-        const int k_lim = g.k - t * KT;
+        const int k_lim = k_len - t * KT;
         if (interior && k_lim >= KT) {
             StA::load_fast(ra, pa, offa);
             StB::load_fast(rb, pb, offb);
@@ -564,7 +607,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     // Two slabs per trip so that the LDS buffer index is a constant in the code.
     int t = 0;
     if (interior) {
-        const int nfull = g.k / KT;   // slabs 0..nfull-1 are full
+        const int nfull = k_len / KT;   // slabs 0..nfull-1 are full
         for (; t + 2 < nfull; t += 2) {
             slab_hot(0);
             slab_hot(1);
@@ -581,6 +624,59 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     for (; t < nslab; t += 2) {
         slab(t, 0);
         if (t + 1 < nslab) slab(t + 1, 1);
+    }
+
+    // Split tile: leave the partial sums in the workspace (in register order, so
+    // every store covers NT consecutive vectors); the piece that arrives last
+    // adds all of them in a fixed order, which makes the result independent of
+    // the order of arrival, and goes on to the flush.  Nobody waits for anybody.
+    if constexpr (SPLIT) {
+        if (npieces > 1) {
+            constexpr int PV = Cfg::VEC16;                         // registers per 16-byte access
+            static_assert(M::NR % PV == 0, "accumulator registers must pack into 16-byte vectors");
+            constexpr int64_t TILE = (int64_t)MT_M * MT_N;
+            const int q = lin - g.ndp;                             // index of the split tile
+            T *const mine = g.part + ((int64_t)q * npieces + piece) * TILE + (int64_t)tid * PV;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < M::NR; r += PV) {
+                        T v[PV];
+#pragma unroll
+                        for (int u = 0; u < PV; ++u) v[u] = acc[j][i][r + u];
+                        Pack<T, PV>::store(mine + (int64_t)(((j * TM + i) * M::NR + r) / PV) * (NT * PV), v);
+                    }
+            __threadfence();      // partial sums visible device-wide before the arrival is counted
+            __syncthreads();
+            unsigned *const flag = reinterpret_cast<unsigned *>(lds_raw);
+            if (tid == 0) *flag = atomicAdd(g.cnt + q, 1u);
+            __syncthreads();
+            if (*flag != (unsigned)(npieces - 1)) return;
+            __threadfence();      // the other pieces' partial sums are visible from here on
+            if (tid == 0) atomicExch(g.cnt + q, 0u);   // leave the counter as it was found
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < M::NR; ++r) acc[j][i][r] = T(0);
+            for (int sp = 0; sp < npieces; ++sp) {
+                const T *const src = g.part + ((int64_t)q * npieces + sp) * TILE + (int64_t)tid * PV;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < M::NR; r += PV) {
+                            T v[PV];
+                            Pack<T, PV>::load(src + (int64_t)(((j * TM + i) * M::NR + r) / PV) * (NT * PV), v);
+#pragma unroll
+                            for (int u = 0; u < PV; ++u) acc[j][i][r + u] += v[u];
+                        }
+            }
+        }
     }
 
     // flush: C = alpha*acc + beta*C on the part of the tile inside C

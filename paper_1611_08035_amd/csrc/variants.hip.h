@@ -11,13 +11,14 @@ template <typename T> struct VariantEntry {
     int kt, wgm, wgn;   // slab depth, waves along m and n
     int wgs_per_cu;   // workgroups resident on one CU (register and LDS budget of the variant)
     float eff;        // fraction of the MFMA peak the variant sustains with its CU fully occupied (measured)
+    bool has_split;   // kernels with the split tail (GemmArgs::nsplit > 1) are built for this variant
     // launch(transA is K-contiguous, transB is K-contiguous, fast path allowed, args, stream)
     hipError_t (*launch)(bool ak, bool bk, bool fast, const GemmArgs<T> &g, hipStream_t st);
 };
 
-template <typename T, typename Cfg, bool AK, bool BK, bool FAST>
+template <typename T, typename Cfg, bool AK, bool BK, bool FAST, bool SPLIT = false>
 static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
-    auto kern = gemm_kernel<T, Cfg, AK, BK, FAST>;
+    auto kern = gemm_kernel<T, Cfg, AK, BK, FAST, SPLIT>;
     // LDS beyond 64 KiB has to be requested explicitly; done once per kernel.
     static hipError_t attr = (Cfg::LDS_BYTES > 65536)
                                  ? hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -25,7 +26,11 @@ static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
                                                        (int)Cfg::LDS_BYTES)
                                  : hipSuccess;
     if (attr != hipSuccess) return attr;
-    const int64_t nt = tile_count(g.uplo, g.ntm, g.ntn, Cfg::MT_M, Cfg::MT_N);
+    int64_t nt = tile_count(g.uplo, g.ntm, g.ntn, Cfg::MT_M, Cfg::MT_N);
+    if constexpr (SPLIT) {
+        if (g.ndp < 0 || g.ndp > nt || g.nsplit < 1 || !g.part || !g.cnt) return hipErrorInvalidValue;
+        nt = g.ndp + (nt - g.ndp) * g.nsplit;
+    }
     if (nt > 0x7fffffff) return hipErrorInvalidValue;   // beyond one grid dimension (and any device memory)
     const dim3 grid((unsigned)nt), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::LDS_BYTES, st, g);
@@ -35,12 +40,24 @@ static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
 // The element-wise fallback (FAST == false: leading dimensions too large for
 // 32-bit slab offsets) is only built for the 64x64 tile; the host routes such
 // calls to that variant.
-template <typename T, typename Cfg>
+template <typename T, typename Cfg, bool WITH_SPLIT = false>
 static hipError_t launch_cfg(bool ak, bool bk, bool fast, const GemmArgs<T> &g0, hipStream_t st) {
     GemmArgs<T> g = g0;
     g.ntm = (g.m + Cfg::MT_M - 1) / Cfg::MT_M;
     g.ntn = (g.n + Cfg::MT_N - 1) / Cfg::MT_N;
     constexpr bool HAS_FALLBACK = (Cfg::MT_M == 64 && Cfg::MT_N == 64);
+    if (g.nsplit > 1) {
+        if constexpr (WITH_SPLIT) {
+            if (!fast) return hipErrorInvalidValue;
+            switch ((ak ? 2 : 0) | (bk ? 1 : 0)) {
+                case 0: return launch_one<T, Cfg, false, false, true, true>(g, st);
+                case 1: return launch_one<T, Cfg, false, true, true, true>(g, st);
+                case 2: return launch_one<T, Cfg, true, false, true, true>(g, st);
+                default: return launch_one<T, Cfg, true, true, true, true>(g, st);
+            }
+        }
+        return hipErrorInvalidValue;
+    }
     if (fast) {
         switch ((ak ? 2 : 0) | (bk ? 1 : 0)) {
             case 0: return launch_one<T, Cfg, false, false, true>(g, st);

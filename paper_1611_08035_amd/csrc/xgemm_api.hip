@@ -12,6 +12,8 @@ using namespace xg;
 
 thread_local const char *t_last_kernel = "";
 thread_local int t_forced_variant = -1;
+thread_local int t_forced_split = -1;   // -1: the model decides; 0: never split; S >= 2: split into S pieces where feasible
+thread_local int t_last_split = 1;
 // tuning knob (environment XGEMM_REQUIRE_ALIGNED=1): send operands that are not
 // 16-byte aligned to the element-wise fallback instead of the buffer-load path
 const bool t_require_aligned = getenv("XGEMM_REQUIRE_ALIGNED") != nullptr;
@@ -39,31 +41,74 @@ int num_cus() {
     return n;
 }
 
-// Pick a tile variant with a small analytical cost model, in the spirit of the
-// paper's model-driven kernel selection (Sec. 4): the tiles of a variant run in
-// rounds of (CUs x workgroups per CU); a full round costs
-// wgs * tile_area / eff, and the last, partly filled round costs
-// occ * tile_area / eff with occ workgroups per CU, derated when a CU holds a
-// single workgroup (one wave per SIMD has nobody to hide its stalls behind).
-// K is common to all variants and drops out.
-template <typename T> int choose_variant(int64_t m, int64_t n, int uplo, const VariantEntry<T> *tab, int nv) {
-    if (t_forced_variant >= 0 && t_forced_variant < nv) return t_forced_variant;
+// Workspace of the *_ws entry points: arrival counters, then partial tiles.
+constexpr size_t WS_CNT_BYTES = 8192;                       // 2048 counters
+constexpr size_t WS_PART_BYTES = size_t(64) << 20;          // 512 tiles of 128 KiB
+constexpr int SPLIT_MAX = 32;                               // pieces per tile
+constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece must keep
+// Cost of one piece beyond its MFMA work (ramp-up, partial-sum round trip,
+// arrival), as a K depth, and of reading one partial tile in the reduction.
+constexpr double SPLIT_PIECE_K = 96.0, SPLIT_REDUCE_K = 12.0;
+
+struct Plan {
+    int v;          // tile variant
+    int nsplit;     // pieces per split tile (1: nothing is split)
+    int64_t ndp;    // tiles computed whole
+};
+
+// Pick a tile variant, and whether to split the last partial round along K, with
+// a small analytical cost model in the spirit of the paper's model-driven kernel
+// selection (Sec. 4): the tiles of a variant run in rounds of (CUs x workgroups
+// per CU); a full round costs wgs * tile_area * k / eff, and the last, partly
+// filled round costs occ * tile_area * k / eff with occ workgroups per CU,
+// derated when a CU holds a single workgroup (one wave per SIMD has nobody to
+// hide its stalls behind).  With a workspace the rem tiles of the last round may
+// instead be cut into S = floor(slots / rem) pieces of depth k / S each, at the
+// price of a fixed overhead per piece and of re-reading S partial tiles.
+template <typename T>
+Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> *tab, int nv, bool fast,
+               size_t lwork) {
     const int64_t cus = num_cus();
-    int best = 0;
+    Plan best{0, 1, 0};
     double best_cost = 0.0;
-    for (int v = 0; v < nv; ++v) {
+    const int v_lo = (t_forced_variant >= 0 && t_forced_variant < nv) ? t_forced_variant : 0;
+    const int v_hi = (t_forced_variant >= 0 && t_forced_variant < nv) ? t_forced_variant + 1 : nv;
+    for (int v = v_lo; v < v_hi; ++v) {
         const VariantEntry<T> &e = tab[v];
         const int64_t tiles = tile_count(uplo, (int)((m + e.mt_m - 1) / e.mt_m), (int)((n + e.mt_n - 1) / e.mt_n),
                                          e.mt_m, e.mt_n);
         const int64_t slots = cus * e.wgs_per_cu;
         const double area = (double)e.mt_m * (double)e.mt_n;
         const int64_t full = tiles / slots, rem = tiles % slots;
-        double cost = (double)full * e.wgs_per_cu * area / e.eff;
-        if (rem > 0) {
-            const int64_t occ = (rem + cus - 1) / cus;
-            cost += (double)occ * area / (e.eff * (occ == 1 ? 0.8 : 1.0));
+        const double rounds = (double)full * e.wgs_per_cu * area * (double)k / e.eff;
+        auto tail = [&](int64_t units, double depth) {
+            const int64_t occ = (units + cus - 1) / cus;
+            return (double)occ * area * depth / (e.eff * (occ == 1 ? 0.8 : 1.0));
+        };
+        Plan p{v, 1, tiles};
+        double cost = rounds + (rem > 0 ? tail(rem, (double)k) : 0.0);
+        if (rem > 0 && e.has_split && fast && lwork > WS_CNT_BYTES && t_forced_split != 0 &&
+            rem <= (int64_t)(WS_CNT_BYTES / sizeof(unsigned))) {
+            const int64_t nslab = (k + e.kt - 1) / e.kt;
+            const int64_t by_ws = (int64_t)((lwork - WS_CNT_BYTES) / ((size_t)rem * (size_t)area * sizeof(T)));
+            int64_t smax = slots / rem;
+            if (smax > nslab / SPLIT_MIN_SLABS) smax = nslab / SPLIT_MIN_SLABS;
+            if (smax > SPLIT_MAX) smax = SPLIT_MAX;
+            if (smax > by_ws) smax = by_ws;
+            if (t_forced_split > 1 && smax >= 2) {       // tuning: take the forced count if it is feasible
+                const int64_t S = t_forced_split < smax ? t_forced_split : smax;
+                p.nsplit = (int)S;
+                p.ndp = full * slots;
+                cost = rounds + tail(rem * S, (double)k / (double)S + SPLIT_PIECE_K) + area * (double)S * SPLIT_REDUCE_K;
+            } else if (t_forced_split < 0) {
+                for (int64_t S = 2; S <= smax; ++S) {
+                    const double c = rounds + tail(rem * S, (double)k / (double)S + SPLIT_PIECE_K) +
+                                     area * (double)S * SPLIT_REDUCE_K / e.eff;
+                    if (c < cost) { cost = c; p.nsplit = (int)S; p.ndp = full * slots; }
+                }
+            }
         }
-        if (v == 0 || cost < best_cost) { best = v; best_cost = cost; }
+        if (v == v_lo || cost < best_cost) { best = p; best_cost = cost; }
     }
     return best;
 }
@@ -71,8 +116,10 @@ template <typename T> int choose_variant(int64_t m, int64_t n, int uplo, const V
 // uplo: 0 general, 1 lower, 2 upper (the caller has checked m == n for those).
 template <typename T>
 int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
-              const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream, int uplo = 0) {
+              const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream, int uplo = 0, void *work = nullptr,
+              size_t lwork = 0) {
     t_last_kernel = "none";
+    t_last_split = 1;
     if (!is_n(ta) && !is_t(ta)) return -1;
     if (!is_n(tb) && !is_t(tb)) return -2;
     if (m < 0 || m > DIM_MAX) return -3;
@@ -100,7 +147,6 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
 
     int nv = 0;
     const VariantEntry<T> *tab = table<T>(&nv);
-    int v = choose_variant<T>(m, n, uplo, tab, nv);
     GemmArgs<T> g;
     g.A = A; g.B = B; g.C = C;
     g.lda = lda; g.ldb = ldb; g.ldc = ldc;
@@ -116,9 +162,23 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     bool fast = lda <= ld_max && ldb <= ld_max;
     if (t_require_aligned)
         fast = fast && aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0;
+    if (!work || (reinterpret_cast<uintptr_t>(work) & 15u)) lwork = 0;
+    const Plan plan = make_plan<T>(m, n, k, uplo, tab, nv, fast, lwork);
+    int v = plan.v;
     if (!fast)   // the element-wise fallback exists for the 64x64 tile only
         for (int i = 0; i < nv; ++i)
             if (tab[i].mt_m == 64 && tab[i].mt_n == 64) v = i;
+    g.ndp = 0;
+    g.nsplit = 1;
+    g.part = nullptr;
+    g.cnt = nullptr;
+    if (fast && plan.nsplit > 1) {
+        g.ndp = (int)plan.ndp;
+        g.nsplit = plan.nsplit;
+        g.cnt = static_cast<unsigned *>(work);
+        g.part = reinterpret_cast<T *>(static_cast<unsigned char *>(work) + WS_CNT_BYTES);
+        t_last_split = plan.nsplit;
+    }
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
     return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
@@ -128,7 +188,7 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
 // the opposite transpose, and the triangle mask.
 template <typename T>
 int syrk_impl(char uplo, char trans, int64_t n, int64_t k, T alpha, const T *A, int64_t lda, T beta, T *C,
-                     int64_t ldc, void *stream) {
+              int64_t ldc, void *stream, void *work = nullptr, size_t lwork = 0) {
     t_last_kernel = "none";
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
     if (!lower && !upper) return -1;
@@ -142,8 +202,15 @@ int syrk_impl(char uplo, char trans, int64_t n, int64_t k, T alpha, const T *A, 
     if (ldc < max64(1, n)) return -10;
     // op(A) op(A)^T: second operand is the same matrix with the opposite transpose
     const int rc = gemm_impl<T>(is_n(trans) ? 'N' : 'T', is_n(trans) ? 'T' : 'N', n, n, k, alpha, A, lda, A, lda, beta,
-                                C, ldc, stream, lower ? 1 : 2);
+                                C, ldc, stream, lower ? 1 : 2, work, lwork);
     return rc;   // the argument checks above cover every error gemm_impl could report
+}
+
+// Clears the arrival counters of a workspace (a kernel, not a memset, so that a
+// caller may capture it in a graph).
+__global__ void __launch_bounds__(256) zero_words_kernel(unsigned *p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
 }
 
 // Elementwise combine for the complex path with complex scalars:
@@ -244,6 +311,51 @@ int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, float
     return gemm_impl<float>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
 }
 
+size_t xgemm_workspace_bytes(void) { return WS_CNT_BYTES + WS_PART_BYTES; }
+
+int xgemm_workspace_init(void *work, size_t lwork, void *stream) {
+    if (!work || (reinterpret_cast<uintptr_t>(work) & 15u)) return -1;
+    if (lwork < WS_CNT_BYTES) return -2;
+    constexpr int N = (int)(WS_CNT_BYTES / sizeof(unsigned));
+    hipLaunchKernelGGL(zero_words_kernel, dim3(N / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<unsigned *>(work), N);
+    return (int)hipGetLastError();
+}
+
+int xgemm_dgemm_ws(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double *A,
+                   int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *work,
+                   size_t lwork, void *stream) {
+    if (work && (reinterpret_cast<uintptr_t>(work) & 15u)) return -14;
+    return gemm_impl<double>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 0, work, lwork);
+}
+
+int xgemm_sgemm_ws(char transa, char transb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
+                   int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *work,
+                   size_t lwork, void *stream) {
+    if (work && (reinterpret_cast<uintptr_t>(work) & 15u)) return -14;
+    return gemm_impl<float>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 0, work, lwork);
+}
+
+int xgemm_dsyrk_ws(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                   double beta, double *C, int64_t ldc, void *work, size_t lwork, void *stream) {
+    if (work && (reinterpret_cast<uintptr_t>(work) & 15u)) return -11;
+    return syrk_impl<double>(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream, work, lwork);
+}
+
+int xgemm_ssyrk_ws(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda, float beta,
+                   float *C, int64_t ldc, void *work, size_t lwork, void *stream) {
+    if (work && (reinterpret_cast<uintptr_t>(work) & 15u)) return -11;
+    return syrk_impl<float>(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream, work, lwork);
+}
+
+int xgemm_force_split(int pieces) {
+    if (pieces < -1 || pieces == 1 || pieces > SPLIT_MAX) return -1;
+    t_forced_split = pieces;
+    return 0;
+}
+
+int xgemm_last_split(void) { return t_last_split; }
+
 int xgemm_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda, double beta,
                 double *C, int64_t ldc, void *stream) {
     return syrk_impl<double>(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream);
@@ -265,7 +377,7 @@ int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *
     if (nt > DIM_MAX) return -2;
     if (out)
         for (int64_t b = 0; b < nt && b < cap; ++b) {
-            const TilePos t = tile_of_block((int)b, (int)nt, ntm, ntn, uplo, mt_m, mt_n);
+            const TilePos t = tile_of_lin(lin_of_block((int)b, (int)nt), ntm, ntn, uplo, mt_m, mt_n);
             out[2 * b] = t.tm;
             out[2 * b + 1] = t.tn;
         }

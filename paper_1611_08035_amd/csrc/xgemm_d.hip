@@ -11,11 +11,13 @@ using D_64x64x16 = TileCfg<double, 64, 64, 16, 2, 2, 2>;
 using D_128x64x16 = TileCfg<double, 128, 64, 16, 2, 2, 2>;
 using D_64x128x16 = TileCfg<double, 64, 128, 16, 2, 2, 2>;
 
-#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, CFG::KT, CFG::WGM, CFG::WGN, WGS, EFF, &launch_cfg<T, CFG>}
+#define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, CFG::KT, CFG::WGM, CFG::WGN, WGS, EFF, false, &launch_cfg<T, CFG, false>}
+// the same with the split-tail kernels built as well
+#define XG_ENTRY_SPLIT(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, CFG::KT, CFG::WGM, CFG::WGN, WGS, EFF, true, &launch_cfg<T, CFG, true>}
 
 const VariantEntry<double> *d_variant_table(int *n) {
     static const VariantEntry<double> table[] = {
-    XG_ENTRY(double, D_128x128x16, "d_128x128x16_w2x2", 2, 0.975f),
+    XG_ENTRY_SPLIT(double, D_128x128x16, "d_128x128x16_w2x2", 2, 0.975f),
     XG_ENTRY(double, D_128x128x8, "d_128x128x8_w2x2", 2, 0.93f),
     XG_ENTRY(double, D_256x128x8, "d_256x128x8_w4x2", 1, 0.89f),
     XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2", 4, 0.90f),

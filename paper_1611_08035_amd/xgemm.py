@@ -18,6 +18,8 @@ EXPORTS = [
     "xgemm_last_kernel_name", "xgemm_force_variant", "xgemm_variant_name", "xgemm_mfma_peak_probe",
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
+    "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split",
 ]
 
 
@@ -57,6 +59,20 @@ def lib():
         f = getattr(L, f"xgemm_{pre}syrk")
         f.restype = ctypes.c_int
         f.argtypes = [_c, _c, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p]
+    for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
+        f = getattr(L, f"xgemm_{pre}gemm_ws")
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _c, _i64, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p, ctypes.c_size_t, _p]
+        f = getattr(L, f"xgemm_{pre}syrk_ws")
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _c, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p, ctypes.c_size_t, _p]
+    L.xgemm_workspace_bytes.restype = ctypes.c_size_t
+    L.xgemm_workspace_bytes.argtypes = []
+    L.xgemm_workspace_init.restype = ctypes.c_int
+    L.xgemm_workspace_init.argtypes = [_p, ctypes.c_size_t, _p]
+    L.xgemm_force_split.restype = ctypes.c_int
+    L.xgemm_force_split.argtypes = [ctypes.c_int]
+    L.xgemm_last_split.restype = ctypes.c_int
     L.xgemm_zgemm_split.restype = ctypes.c_int
     L.xgemm_zgemm_split.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
                                     _p, _i64, _p]
@@ -127,6 +143,42 @@ def xgemm_dsyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream=None) -> 
 def xgemm_ssyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream=None) -> int:
     return int(lib().xgemm_ssyrk(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
                                  _stream(stream)))
+
+
+def xgemm_workspace_bytes() -> int:
+    return int(lib().xgemm_workspace_bytes())
+
+
+def xgemm_workspace_init(work, lwork, stream=None) -> int:
+    return int(lib().xgemm_workspace_init(_ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_dgemm_ws(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, work, lwork, stream=None) -> int:
+    return int(lib().xgemm_dgemm_ws(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                    _ptr(C), ldc, _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_sgemm_ws(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, work, lwork, stream=None) -> int:
+    return int(lib().xgemm_sgemm_ws(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                    _ptr(C), ldc, _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_dsyrk_ws(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, work, lwork, stream=None) -> int:
+    return int(lib().xgemm_dsyrk_ws(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
+                                    _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_ssyrk_ws(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, work, lwork, stream=None) -> int:
+    return int(lib().xgemm_ssyrk_ws(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
+                                    _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_force_split(pieces) -> int:
+    return int(lib().xgemm_force_split(int(pieces)))
+
+
+def xgemm_last_split() -> int:
+    return int(lib().xgemm_last_split())
 
 
 def _pair(z):

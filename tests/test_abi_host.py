@@ -104,6 +104,27 @@ def test_zgemm_illegal_arguments_and_worksize():
     assert z("N", "N", 0, 2, 2, (1, 1), None, None, 1, None, None, 2, (0, 0), None, None, 1) == 0
 
 
+def test_workspace_routines_host_side():
+    P = 4096
+    assert xg.xgemm_workspace_bytes() == 8192 + (64 << 20)
+    assert xg.xgemm_workspace_init(None, 1 << 20, stream=0) == -1
+    assert xg.xgemm_workspace_init(P + 4, 1 << 20, stream=0) == -1
+    assert xg.xgemm_workspace_init(P, 100, stream=0) == -2
+    for f in (xg.xgemm_dgemm_ws, xg.xgemm_sgemm_ws):
+        assert f("X", "N", 2, 2, 2, 1.0, P, 2, P, 2, 0.0, P, 2, P, 1 << 20, stream=0) == -1
+        assert f("N", "N", 3, 2, 2, 1.0, P, 3, P, 2, 0.0, P, 2, P, 1 << 20, stream=0) == -13
+        assert f("N", "N", 2, 2, 2, 1.0, P, 2, P, 2, 0.0, P, 2, P + 8, 1 << 20, stream=0) == -14
+        assert f("N", "N", 0, 2, 2, 1.0, None, 1, None, 2, 0.0, None, 1, None, 0, stream=0) == 0
+    for f in (xg.xgemm_dsyrk_ws, xg.xgemm_ssyrk_ws):
+        assert f("X", "N", 2, 2, 1.0, P, 2, 0.0, P, 2, P, 1 << 20, stream=0) == -1
+        assert f("L", "N", 3, 2, 1.0, P, 3, 0.0, P, 2, P, 1 << 20, stream=0) == -10
+        assert f("L", "N", 2, 2, 1.0, P, 2, 0.0, P, 2, P + 4, 1 << 20, stream=0) == -11
+        assert f("L", "N", 0, 2, 1.0, None, 1, 0.0, None, 1, None, 0, stream=0) == 0
+    assert xg.xgemm_force_split(1) == -1 and xg.xgemm_force_split(33) == -1 and xg.xgemm_force_split(-2) == -1
+    assert xg.xgemm_force_split(4) == 0 and xg.xgemm_force_split(0) == 0 and xg.xgemm_force_split(-1) == 0
+    assert xg.xgemm_last_split() == 1
+
+
 @pytest.mark.parametrize("mt_m,mt_n", [(128, 128), (256, 128), (64, 64), (128, 64), (64, 128)])
 @pytest.mark.parametrize("uplo", [0, 1, 2])
 def test_tile_order_covers_every_needed_tile_exactly_once(uplo, mt_m, mt_n):
