@@ -158,6 +158,16 @@ int xgemm_force_variant(int variant);
 int xgemm_force_split(int pieces);
 int xgemm_last_split(void);
 
+/*
+ * What the library would launch for a product of this shape (host only; uses
+ * the CU count of the current device, 256 if there is none): out[0] tile
+ * variant, out[1] pieces per split tail tile (1: none), out[2] number of tiles
+ * computed whole.  prec 'd' / 's'; uplo 0 general, 1 / 2 triangular (syrk,
+ * m == n); lwork: size of the workspace the call would be given (0: none).
+ * Honours xgemm_force_variant / xgemm_force_split.  Returns 0 or -i.
+ */
+int xgemm_plan(char prec, int uplo, int64_t m, int64_t n, int64_t k, size_t lwork, int out[3]);
+
 /* Name of tile variant `variant` for precision `prec` ('d' or 's'), or NULL
  * past the end of the list. */
 const char *xgemm_variant_name(char prec, int variant);
@@ -229,9 +239,8 @@ int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream);
  * triangle, m == n expected for 1 and 2), returns the number of workgroups a
  * launch has and, when `out` is non-NULL, writes {tile row, tile column} of
  * workgroup b to out[2b], out[2b+1] for b < min(count, cap).  Workgroup b runs
- * on XCD b % 8.  Every tile that intersects the requested part of C appears
- * exactly once; for a triangle a few tiles beside the diagonal that do not
- * intersect it appear too and do nothing.  Returns -i for an illegal argument i.
+ * on XCD b % 8.  Exactly the tiles that intersect the requested part of C
+ * appear, each once.  Returns -i for an illegal argument i.
  */
 int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *out, int64_t cap);
 

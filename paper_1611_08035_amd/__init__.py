@@ -23,6 +23,7 @@ from .xgemm import (  # noqa: F401
     xgemm_ssyrk_ws,
     xgemm_force_split,
     xgemm_last_split,
+    xgemm_plan,
     xgemm_zgemm_split,
     xgemm_zgemm_worksize,
     xgemm_version,

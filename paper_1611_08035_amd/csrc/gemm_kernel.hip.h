@@ -286,32 +286,56 @@ constexpr int shadow_quota(int n_mma, int n_ld, int n_rd, int n_wr) {
 static constexpr int NUM_XCD = 8;
 static constexpr int GROUP_M = 8;
 
-// Tile columns [c0, c1) a band of tile-rows [first, first + gsz) has to visit:
-// all of them for a general product; for a triangular result only those whose
-// tiles reach the triangle for at least one row of the band (the few tiles of
-// the band's corner that miss it leave at once in the kernel).
-struct BandCols { int c0, c1; };
-static __host__ __device__ __forceinline__ BandCols band_cols(int uplo, int first, int gsz, int ntn, int mt_m,
-                                                              int mt_n) {
-    BandCols b{0, ntn};
-    if (uplo == 1) {          // lower: first column of the tile <= last row of the band
-        const int64_t c = ((int64_t)(first + gsz) * mt_m - 1) / mt_n + 1;
-        if (c < ntn) b.c1 = (int)c;
-    } else if (uplo == 2) {   // upper: last column of the tile >= first row of the band
-        const int64_t c = ((int64_t)first * mt_m) / mt_n;
-        b.c0 = c < ntn ? (int)c : ntn;
+// Triangular results (uplo 1: lower, 2: upper): inside a band of tile-rows
+// [first, first + gsz) only the tiles that reach the triangle are in the order.
+// The columns of the band fall into a run whose tiles are all needed ("whole"
+// columns [w0, w1)) and a short run beside the diagonal with fewer rows each
+// ("cut" columns [p0, p1), at most gsz * mt_m / mt_n + 1 of them); the cut run
+// follows the whole run for the lower triangle and precedes it for the upper.
+struct Band { int w0, w1, p0, p1; };
+static __host__ __device__ __forceinline__ int min_i(int64_t a, int64_t b) { return (int)(a < b ? a : b); }
+static __host__ __device__ __forceinline__ Band band_of(int uplo, int first, int gsz, int ntn, int mt_m, int mt_n) {
+    Band b;
+    if (uplo == 1) {
+        // column tn is needed from row floor(tn*mt_n / mt_m) on
+        b.w0 = 0;
+        b.w1 = min_i(ntn, ((int64_t)(first + 1) * mt_m - 1) / mt_n + 1);
+        b.p0 = b.w1;
+        b.p1 = min_i(ntn, ((int64_t)(first + gsz) * mt_m - 1) / mt_n + 1);
+    } else {
+        // column tn is needed up to row floor(((tn+1)*mt_n - 1) / mt_m)
+        b.p0 = min_i(ntn, ((int64_t)first * mt_m) / mt_n);
+        b.p1 = min_i(ntn, ((int64_t)(first + gsz - 1) * mt_m) / mt_n);
+        b.w0 = b.p1;
+        b.w1 = ntn;
     }
     return b;
 }
+// rows [r0, r0 + cnt) of the band that column tn needs
+struct ColRows { int r0, cnt; };
+static __host__ __device__ __forceinline__ ColRows col_rows(int uplo, int first, int gsz, int tn, int mt_m, int mt_n) {
+    if (uplo == 1) {
+        const int lo = (int)(((int64_t)tn * mt_n) / mt_m);
+        const int r0 = lo > first ? lo : first;
+        return ColRows{r0, first + gsz - r0};
+    }
+    const int hi = (int)((((int64_t)tn + 1) * mt_n - 1) / mt_m) + 1;
+    return ColRows{first, (hi < first + gsz ? hi : first + gsz) - first};
+}
+static __host__ __device__ __forceinline__ int band_size(int uplo, int first, int gsz, int ntn, int mt_m, int mt_n) {
+    const Band b = band_of(uplo, first, gsz, ntn, mt_m, mt_n);
+    int sz = gsz * (b.w1 - b.w0);
+    for (int tn = b.p0; tn < b.p1; ++tn) sz += col_rows(uplo, first, gsz, tn, mt_m, mt_n).cnt;
+    return sz;
+}
 
-// Number of workgroups to launch.
+// Number of workgroups to launch (without split tiles).
 static __host__ __device__ __forceinline__ int64_t tile_count(int uplo, int ntm, int ntn, int mt_m, int mt_n) {
     if (uplo == 0) return (int64_t)ntm * ntn;
     int64_t nt = 0;
     for (int first = 0; first < ntm; first += GROUP_M) {
         const int gsz = (ntm - first) < GROUP_M ? (ntm - first) : GROUP_M;
-        const BandCols b = band_cols(uplo, first, gsz, ntn, mt_m, mt_n);
-        nt += (int64_t)gsz * (b.c1 - b.c0);
+        nt += band_size(uplo, first, gsz, ntn, mt_m, mt_n);
     }
     return nt;
 }
@@ -339,17 +363,27 @@ static __host__ __device__ __forceinline__ TilePos tile_of_lin(int lin, int ntm,
         const int in = lin - grp * width;
         return TilePos{first + in % gsz, in / gsz};
     }
-    // triangular: bands differ in width; walk them (uniform, a few scalar steps)
+    // triangular: bands differ in size; walk them (uniform, scalar work)
     int first = 0;
     for (; first + GROUP_M < ntm; first += GROUP_M) {
-        const BandCols b = band_cols(uplo, first, GROUP_M, ntn, mt_m, mt_n);
-        const int sz = GROUP_M * (b.c1 - b.c0);
+        const int sz = band_size(uplo, first, GROUP_M, ntn, mt_m, mt_n);
         if (lin < sz) break;
         lin -= sz;
     }
     const int gsz = (ntm - first) < GROUP_M ? (ntm - first) : GROUP_M;
-    const BandCols b = band_cols(uplo, first, gsz, ntn, mt_m, mt_n);
-    return TilePos{first + lin % gsz, b.c0 + lin / gsz};
+    const Band b = band_of(uplo, first, gsz, ntn, mt_m, mt_n);
+    const int whole = gsz * (b.w1 - b.w0);
+    if (uplo == 1) {
+        if (lin < whole) return TilePos{first + lin % gsz, b.w0 + lin / gsz};
+        lin -= whole;
+    }
+    for (int tn = b.p0; tn < b.p1; ++tn) {
+        const ColRows c = col_rows(uplo, first, gsz, tn, mt_m, mt_n);
+        if (lin < c.cnt) return TilePos{c.r0 + lin, tn};
+        lin -= c.cnt;
+    }
+    if (uplo == 2 && lin < whole) return TilePos{first + lin % gsz, b.w0 + lin / gsz};
+    return TilePos{ntm, ntn};   // past the end of the order: no tile
 }
 
 // ---------------------------------------------------------------------------
@@ -626,126 +660,146 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         if (t + 1 < nslab) slab(t + 1, 1);
     }
 
+    // flush of one accumulator row-block j (the MFMA tiles (j, 0..TM-1) of this
+    // wave): C = alpha*acc + beta*C on the part of the tile inside C
+    const bool use_c = (beta != T(0));
+    // whole tile inside C: no predicates, 16-byte accesses.  The reads of C of a
+    // row-block are issued together ahead of the first dependent store, so each
+    // row-block costs one memory round trip.
+    auto flush_full = [&](int j, const typename M::acc_t (&a)[TM]) {
+        T *cp[M::NR];
+        T cold[M::NR][TM];
+#pragma unroll
+        for (int r = 0; r < M::NR; ++r) cp[r] = g.C + (int64_t)(n0 + c_n(j, r)) * g.ldc + m0 + mc;
+        if (use_c) {
+#pragma unroll
+            for (int r = 0; r < M::NR; ++r)
+#pragma unroll
+                for (int ib = 0; ib < TM / VRM; ++ib) {
+                    T v[VRM];
+                    Pack<T, VRM>::load(cp[r] + ib * VRM * M::MI, v);
+#pragma unroll
+                    for (int u = 0; u < VRM; ++u) cold[r][ib * VRM + u] = v[u];
+                }
+        }
+#pragma unroll
+        for (int r = 0; r < M::NR; ++r)
+#pragma unroll
+            for (int ib = 0; ib < TM / VRM; ++ib) {
+                T v[VRM];
+#pragma unroll
+                for (int u = 0; u < VRM; ++u) {
+                    v[u] = alpha * a[ib * VRM + u][r];
+                    if (use_c) v[u] += beta * cold[r][ib * VRM + u];
+                }
+                Pack<T, VRM>::store(cp[r] + ib * VRM * M::MI, v);
+            }
+    };
+    // edge or diagonal tile: element by element under the bounds and triangle tests
+    auto flush_edge = [&](int j, const typename M::acc_t (&a)[TM]) {
+#pragma unroll
+        for (int r = 0; r < M::NR; ++r) {
+            const int nn = c_n(j, r);
+            T *crow = g.C + (int64_t)(n0 + nn) * g.ldc + m0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int mm = mc + (i / VRM) * VRM * M::MI + (i % VRM);
+                // signed distance below the diagonal, flipped for the upper triangle
+                const int below = (g.uplo == 2) ? (n0 - m0) + nn - mm : (m0 - n0) + mm - nn;
+                if (mm < m_lim && nn < n_lim && (g.uplo == 0 || below >= 0)) {
+                    T v = alpha * a[i][r];
+                    if (use_c) v += beta * crow[mm];
+                    crow[mm] = v;
+                }
+            }
+        }
+    };
+
     // Split tile: leave the partial sums in the workspace (in register order, so
     // every store covers NT consecutive vectors); the piece that arrives last
     // adds all of them in a fixed order, which makes the result independent of
-    // the order of arrival, and goes on to the flush.  Nobody waits for anybody.
+    // the order of arrival, and flushes.  Nobody waits for anybody.
+    // The partial sums travel between compute units that may sit on different
+    // XCDs, whose L2 caches are not coherent with each other: they are written
+    // through to memory and read around the caches (system-scope accesses), so
+    // that no cache has to be flushed or invalidated as a whole; the arrival
+    // counter is a device-scope atomic issued after this workgroup's stores have
+    // been acknowledged.
     if constexpr (SPLIT) {
         if (npieces > 1) {
+            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+            typedef typename StA::vec_t vec_t;
             constexpr int PV = Cfg::VEC16;                         // registers per 16-byte access
+            constexpr int THROUGH = 17;                            // cache policy bits sc0 | sc1
             static_assert(M::NR % PV == 0, "accumulator registers must pack into 16-byte vectors");
             constexpr int64_t TILE = (int64_t)MT_M * MT_N;
+            constexpr int NVJ = TM * M::NR / PV;                   // 16-byte vectors of one row-block
             const int q = lin - g.ndp;                             // index of the split tile
-            T *const mine = g.part + ((int64_t)q * npieces + piece) * TILE + (int64_t)tid * PV;
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int r = 0; r < M::NR; r += PV) {
-                        T v[PV];
-#pragma unroll
-                        for (int u = 0; u < PV; ++u) v[u] = acc[j][i][r + u];
-                        Pack<T, PV>::store(mine + (int64_t)(((j * TM + i) * M::NR + r) / PV) * (NT * PV), v);
-                    }
-            __threadfence();      // partial sums visible device-wide before the arrival is counted
-            __syncthreads();
-            unsigned *const flag = reinterpret_cast<unsigned *>(lds_raw);
-            if (tid == 0) *flag = atomicAdd(g.cnt + q, 1u);
-            __syncthreads();
-            if (*flag != (unsigned)(npieces - 1)) return;
-            __threadfence();      // the other pieces' partial sums are visible from here on
-            if (tid == 0) atomicExch(g.cnt + q, 0u);   // leave the counter as it was found
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int r = 0; r < M::NR; ++r) acc[j][i][r] = T(0);
-            for (int sp = 0; sp < npieces; ++sp) {
-                const T *const src = g.part + ((int64_t)q * npieces + sp) * TILE + (int64_t)tid * PV;
+            const uint32_t lane_off = (uint32_t)tid * 16u;
+            {
+                const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
+                    g.part + ((int64_t)q * npieces + piece) * TILE, 0, (int)(TILE * sizeof(T)), 0x00020000);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
                         for (int r = 0; r < M::NR; r += PV) {
-                            T v[PV];
-                            Pack<T, PV>::load(src + (int64_t)(((j * TM + i) * M::NR + r) / PV) * (NT * PV), v);
+                            vec_t v;
 #pragma unroll
-                            for (int u = 0; u < PV; ++u) acc[j][i][r + u] += v[u];
+                            for (int u = 0; u < PV; ++u) v[u] = acc[j][i][r + u];
+                            const int vi = j * NVJ + (i * M::NR + r) / PV;
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), mine,
+                                                                   lane_off + (uint32_t)vi * (NT * 16u), 0, THROUGH);
                         }
             }
+            // every store of this wave acknowledged (vmcnt(0); the other counters stay as they are)
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            unsigned *const flag = reinterpret_cast<unsigned *>(lds_raw);
+            if (tid == 0) *flag = __hip_atomic_fetch_add(g.cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (*flag != (unsigned)(npieces - 1)) return;
+            // leave the counter as it was found
+            if (tid == 0) __hip_atomic_store(g.cnt + q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // row-block by row-block: sum of the pieces in the order 0, 1, ..., then flush
+            const T *const tile0 = g.part + (int64_t)q * npieces * TILE;
+#pragma unroll 1
+            for (int j = 0; j < TN; ++j) {
+                typename M::acc_t sum[TM];
+#pragma unroll 1
+                for (int sp = 0; sp < npieces; ++sp) {
+                    const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(
+                        const_cast<T *>(tile0 + (int64_t)sp * TILE), 0, (int)(TILE * sizeof(T)), 0x00020000);
+                    vec_t v[NVJ];
+#pragma unroll
+                    for (int vi = 0; vi < NVJ; ++vi)
+                        v[vi] = __builtin_bit_cast(vec_t, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(
+                                                              src, lane_off + (uint32_t)(j * NVJ + vi) * (NT * 16u), 0,
+                                                              THROUGH));
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < M::NR; r += PV)
+#pragma unroll
+                            for (int u = 0; u < PV; ++u) {
+                                const T x = v[(i * M::NR + r) / PV][u];
+                                sum[i][r + u] = (sp == 0) ? x : sum[i][r + u] + x;
+                            }
+                }
+                if (full_tile) flush_full(j, sum);
+                else flush_edge(j, sum);
+            }
+            return;
         }
     }
 
-    // flush: C = alpha*acc + beta*C on the part of the tile inside C
-    const bool use_c = (beta != T(0));
     if (full_tile) {
-        // whole tile inside C: no predicates.  The reads of C are issued in
-        // batches of JB accumulator row-blocks (about 64 registers, the staging
-        // and fragment registers that are dead by now) ahead of the first
-        // dependent store, so each batch costs one memory round trip.
-        constexpr int REGS_PER_J = M::NR * TM * (int)sizeof(T) / 4;
-        constexpr int JB = 1;   // larger batches raised register pressure in the K loop and lost more than they gained
-        static_assert(TN % JB == 0, "row-block batches must divide the wave tile");
 #pragma unroll
-        for (int j0 = 0; j0 < TN; j0 += JB) {
-            T *cp[JB][M::NR];
-            T cold[JB][M::NR][TM];
-#pragma unroll
-            for (int jj = 0; jj < JB; ++jj)
-#pragma unroll
-                for (int r = 0; r < M::NR; ++r)
-                    cp[jj][r] = g.C + (int64_t)(n0 + c_n(j0 + jj, r)) * g.ldc + m0 + mc;
-            if (use_c) {
-#pragma unroll
-                for (int jj = 0; jj < JB; ++jj)
-#pragma unroll
-                    for (int r = 0; r < M::NR; ++r)
-#pragma unroll
-                        for (int ib = 0; ib < TM / VRM; ++ib) {
-                            T v[VRM];
-                            Pack<T, VRM>::load(cp[jj][r] + ib * VRM * M::MI, v);
-#pragma unroll
-                            for (int u = 0; u < VRM; ++u) cold[jj][r][ib * VRM + u] = v[u];
-                        }
-            }
-#pragma unroll
-            for (int jj = 0; jj < JB; ++jj)
-#pragma unroll
-                for (int r = 0; r < M::NR; ++r)
-#pragma unroll
-                    for (int ib = 0; ib < TM / VRM; ++ib) {
-                        T v[VRM];
-#pragma unroll
-                        for (int u = 0; u < VRM; ++u) {
-                            v[u] = alpha * acc[j0 + jj][ib * VRM + u][r];
-                            if (use_c) v[u] += beta * cold[jj][r][ib * VRM + u];
-                        }
-                        Pack<T, VRM>::store(cp[jj][r] + ib * VRM * M::MI, v);
-                    }
-        }
+        for (int j = 0; j < TN; ++j) flush_full(j, acc[j]);
     } else {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int r = 0; r < M::NR; ++r) {
-                const int nn = c_n(j, r);
-                T *crow = g.C + (int64_t)(n0 + nn) * g.ldc + m0;
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const int mm = mc + (i / VRM) * VRM * M::MI + (i % VRM);
-                    // signed distance below the diagonal, flipped for the upper triangle
-                    const int below = (g.uplo == 2) ? (n0 - m0) + nn - mm : (m0 - n0) + mm - nn;
-                    if (mm < m_lim && nn < n_lim && (g.uplo == 0 || below >= 0)) {
-                        T v = alpha * acc[j][i][r];
-                        if (use_c) v += beta * crow[mm];
-                        crow[mm] = v;
-                    }
-                }
-            }
-        }
+        for (int j = 0; j < TN; ++j) flush_edge(j, acc[j]);
     }
 }
 

@@ -46,9 +46,14 @@ constexpr size_t WS_CNT_BYTES = 8192;                       // 2048 counters
 constexpr size_t WS_PART_BYTES = size_t(64) << 20;          // 512 tiles of 128 KiB
 constexpr int SPLIT_MAX = 32;                               // pieces per tile
 constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece must keep
-// Cost of one piece beyond its MFMA work (ramp-up, partial-sum round trip,
-// arrival), as a K depth, and of reading one partial tile in the reduction.
-constexpr double SPLIT_PIECE_K = 96.0, SPLIT_REDUCE_K = 12.0;
+
+// Constants of the cost model below, measured on MI355X (times in microseconds).
+constexpr double CLOCK_GHZ = 2.4;
+constexpr double T_ROUND0 = 10.0;        // ramp-up and flush of a workgroup that nothing else hides
+constexpr double LONE_EFF = 0.95;        // a CU holding one workgroup, relative to a full one
+constexpr double REDUCE_GBS = 80.0;      // rate at which one workgroup reads partial tiles back
+constexpr double PART_TBS = 6.0;         // rate at which all partial tiles are written and read
+constexpr double T_SPLIT0 = 2.0;         // arrival counting
 
 struct Plan {
     int v;          // tile variant
@@ -58,52 +63,62 @@ struct Plan {
 
 // Pick a tile variant, and whether to split the last partial round along K, with
 // a small analytical cost model in the spirit of the paper's model-driven kernel
-// selection (Sec. 4): the tiles of a variant run in rounds of (CUs x workgroups
-// per CU); a full round costs wgs * tile_area * k / eff, and the last, partly
-// filled round costs occ * tile_area * k / eff with occ workgroups per CU,
-// derated when a CU holds a single workgroup (one wave per SIMD has nobody to
-// hide its stalls behind).  With a workspace the rem tiles of the last round may
-// instead be cut into S = floor(slots / rem) pieces of depth k / S each, at the
-// price of a fixed overhead per piece and of re-reading S partial tiles.
+// selection (Sec. 4).  A CU works through a tile of depth k in
+//   t(k) = 2 * tile_area * k / (CU peak * eff)
+// whether it holds one tile or shares its matrix pipes between several.  The
+// tiles of a variant run in rounds of (CUs x workgroups per CU); a full round
+// costs wgs * t(k); the last, partly filled round costs occ * t(k) with occ
+// workgroups per CU (a lone workgroup has nobody to hide its stalls behind:
+// LONE_EFF) plus its unhidden ramp-up and flush.  With a workspace the rem
+// tiles of that round may instead be cut into S <= slots / rem pieces of depth
+// k / S each; that adds the write and read of rem * S partial tiles and the
+// serial read of S partial tiles by the workgroup that finishes each tile.
 template <typename T>
 Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> *tab, int nv, bool fast,
                size_t lwork) {
     const int64_t cus = num_cus();
+    const double cu_flops_per_us = (sizeof(T) == 8 ? 32.0 : 64.0) * 4.0 * CLOCK_GHZ * 1e3;   // flop / us
     Plan best{0, 1, 0};
     double best_cost = 0.0;
-    const int v_lo = (t_forced_variant >= 0 && t_forced_variant < nv) ? t_forced_variant : 0;
-    const int v_hi = (t_forced_variant >= 0 && t_forced_variant < nv) ? t_forced_variant + 1 : nv;
+    const bool forced_v = t_forced_variant >= 0 && t_forced_variant < nv;
+    const int v_lo = forced_v ? t_forced_variant : 0, v_hi = forced_v ? t_forced_variant + 1 : nv;
     for (int v = v_lo; v < v_hi; ++v) {
         const VariantEntry<T> &e = tab[v];
         const int64_t tiles = tile_count(uplo, (int)((m + e.mt_m - 1) / e.mt_m), (int)((n + e.mt_n - 1) / e.mt_n),
                                          e.mt_m, e.mt_n);
         const int64_t slots = cus * e.wgs_per_cu;
         const double area = (double)e.mt_m * (double)e.mt_n;
+        const double tile_bytes = area * sizeof(T);
         const int64_t full = tiles / slots, rem = tiles % slots;
-        const double rounds = (double)full * e.wgs_per_cu * area * (double)k / e.eff;
-        auto tail = [&](int64_t units, double depth) {
+        auto t_tile = [&](double depth) { return 2.0 * area * depth / (cu_flops_per_us * e.eff); };
+        auto t_tail = [&](int64_t units, double depth) {
             const int64_t occ = (units + cus - 1) / cus;
-            return (double)occ * area * depth / (e.eff * (occ == 1 ? 0.8 : 1.0));
+            return T_ROUND0 + (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : 1.0);
         };
+        const double rounds = (double)full * e.wgs_per_cu * t_tile((double)k);
         Plan p{v, 1, tiles};
-        double cost = rounds + (rem > 0 ? tail(rem, (double)k) : 0.0);
+        double cost = rounds + (rem > 0 ? t_tail(rem, (double)k) : 0.0);
         if (rem > 0 && e.has_split && fast && lwork > WS_CNT_BYTES && t_forced_split != 0 &&
             rem <= (int64_t)(WS_CNT_BYTES / sizeof(unsigned))) {
             const int64_t nslab = (k + e.kt - 1) / e.kt;
-            const int64_t by_ws = (int64_t)((lwork - WS_CNT_BYTES) / ((size_t)rem * (size_t)area * sizeof(T)));
+            const int64_t by_ws = (int64_t)((lwork - WS_CNT_BYTES) / ((size_t)rem * (size_t)tile_bytes));
             int64_t smax = slots / rem;
             if (smax > nslab / SPLIT_MIN_SLABS) smax = nslab / SPLIT_MIN_SLABS;
             if (smax > SPLIT_MAX) smax = SPLIT_MAX;
             if (smax > by_ws) smax = by_ws;
+            auto t_split = [&](int64_t S) {
+                return rounds + t_tail(rem * S, (double)k / (double)S) + T_SPLIT0 +
+                       (double)S * tile_bytes / (REDUCE_GBS * 1e3) +
+                       2.0 * (double)(rem * S) * tile_bytes / (PART_TBS * 1e6);
+            };
             if (t_forced_split > 1 && smax >= 2) {       // tuning: take the forced count if it is feasible
                 const int64_t S = t_forced_split < smax ? t_forced_split : smax;
                 p.nsplit = (int)S;
                 p.ndp = full * slots;
-                cost = rounds + tail(rem * S, (double)k / (double)S + SPLIT_PIECE_K) + area * (double)S * SPLIT_REDUCE_K;
+                cost = t_split(S);
             } else if (t_forced_split < 0) {
                 for (int64_t S = 2; S <= smax; ++S) {
-                    const double c = rounds + tail(rem * S, (double)k / (double)S + SPLIT_PIECE_K) +
-                                     area * (double)S * SPLIT_REDUCE_K / e.eff;
+                    const double c = t_split(S);
                     if (c < cost) { cost = c; p.nsplit = (int)S; p.ndp = full * slots; }
                 }
             }
@@ -346,6 +361,29 @@ int xgemm_ssyrk_ws(char uplo, char trans, int64_t n, int64_t k, float alpha, con
                    float *C, int64_t ldc, void *work, size_t lwork, void *stream) {
     if (work && (reinterpret_cast<uintptr_t>(work) & 15u)) return -11;
     return syrk_impl<float>(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream, work, lwork);
+}
+
+int xgemm_plan(char prec, int uplo, int64_t m, int64_t n, int64_t k, size_t lwork, int out[3]) {
+    if (uplo < 0 || uplo > 2) return -2;
+    if (m <= 0 || m > DIM_MAX) return -3;
+    if (n <= 0 || n > DIM_MAX) return -4;
+    if (k <= 0 || k > DIM_MAX) return -5;
+    if (!out) return -7;
+    int nv = 0;
+    Plan p;
+    if (prec == 'd' || prec == 'D') {
+        const VariantEntry<double> *t = d_variant_table(&nv);
+        p = make_plan<double>(m, n, k, uplo, t, nv, true, lwork);
+    } else if (prec == 's' || prec == 'S') {
+        const VariantEntry<float> *t = s_variant_table(&nv);
+        p = make_plan<float>(m, n, k, uplo, t, nv, true, lwork);
+    } else {
+        return -1;
+    }
+    out[0] = p.v;
+    out[1] = p.nsplit;
+    out[2] = (int)p.ndp;
+    return 0;
 }
 
 int xgemm_force_split(int pieces) {

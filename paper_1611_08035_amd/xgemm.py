@@ -19,7 +19,7 @@ EXPORTS = [
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
-    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan",
 ]
 
 
@@ -73,6 +73,8 @@ def lib():
     L.xgemm_force_split.restype = ctypes.c_int
     L.xgemm_force_split.argtypes = [ctypes.c_int]
     L.xgemm_last_split.restype = ctypes.c_int
+    L.xgemm_plan.restype = ctypes.c_int
+    L.xgemm_plan.argtypes = [_c, ctypes.c_int, _i64, _i64, _i64, ctypes.c_size_t, _p]
     L.xgemm_zgemm_split.restype = ctypes.c_int
     L.xgemm_zgemm_split.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
                                     _p, _i64, _p]
@@ -179,6 +181,13 @@ def xgemm_force_split(pieces) -> int:
 
 def xgemm_last_split() -> int:
     return int(lib().xgemm_last_split())
+
+
+def xgemm_plan(prec, uplo, m, n, k, lwork=0):
+    """Returns (variant, pieces per split tile, tiles computed whole) or a negative error code."""
+    out = (ctypes.c_int * 3)()
+    rc = int(lib().xgemm_plan(_ch(prec), int(uplo), m, n, k, lwork, out))
+    return (out[0], out[1], out[2]) if rc == 0 else rc
 
 
 def _pair(z):
