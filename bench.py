@@ -216,6 +216,42 @@ def sweep(torch, np, xg, si, args):
                           "frac_of_min_mfma_hbm_bound": round(flops / dev / bound, 4),
                           "GB/s_algorithmic": round(bytes_alg / dev / 1e9, 1)}), file=sys.stderr, flush=True)
         del dA, dB, dC
+    # beyond the configurations: symmetric rank-k updates (n (n + 1) k flops) and
+    # shapes whose last round of tiles is nearly empty, plain and with a workspace
+    lw = xg.xgemm_workspace_bytes()
+    work = torch.zeros(lw, dtype=torch.uint8, device="cuda")
+    extra = [("syrk", "d", 8192, 8192, 8192), ("syrk", "d", 16384, 16384, 16384), ("syrk", "d", 4096, 4096, 4096),
+             ("syrk", "s", 8192, 8192, 8192), ("syrk", "s", 16384, 16384, 16384),
+             ("gemm", "d", 3328, 2560, 2048), ("gemm", "d", 3072, 3072, 3072), ("gemm", "d", 512, 512, 8192),
+             ("gemm", "s", 3328, 2560, 2048)]
+    for op, prec, m, n, k in extra:
+        dtype = np.float64 if prec == "d" else np.float32
+        ld = si.padded_ld(m)
+        _, (dA, dB, dC) = device_operands(torch, np, si, dtype, "N", "T", m, n, k, ld, si.padded_ld(n), ld, 6)
+        flops = float(m) * (m + 1) * k if op == "syrk" else 2.0 * m * n * k
+        peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
+        for use_ws in (False, True):
+            if op == "syrk":
+                f = getattr(xg, f"xgemm_{prec}syrk_ws")
+                call = lambda: f("L", "N", m, k, 1.5, dA, ld, -0.5, dC, ld, work if use_ws else None, lw if use_ws else 0)
+            else:
+                f = getattr(xg, f"xgemm_{prec}gemm_ws")
+                call = lambda: f("N", "T", m, n, k, 1.5, dA, ld, dB, si.padded_ld(n), -0.5, dC, ld,
+                                 work if use_ws else None, lw if use_ws else 0)
+
+            def step():
+                rc = call()
+                if rc:
+                    raise RuntimeError(rc)
+
+            est = max(flops / 60e12, 20e-6)
+            steps = max(5, min(200, int(0.1 / est)))
+            wall, dev = time_calls(torch, step, steps, max(3, min(400, int(0.2 / est))))
+            print(json.dumps({"shape": f"{prec}{op}{'_ws' if use_ws else ''} {m}x{n}x{k}",
+                              "kernel": xg.xgemm_last_kernel_name(), "pieces": xg.xgemm_last_split(),
+                              "ms": round(dev * 1e3, 4), "GFLOP/s": round(flops / dev / 1e9, 1),
+                              "frac_of_mfma_peak": round(flops / dev / peak, 4)}), file=sys.stderr, flush=True)
+        del dA, dB, dC
     # zgemm 4096^3 on split planes: four real launches, 8 m n k flops
     nsz = 4096
     rng = si.rng_for(5, nsz)
