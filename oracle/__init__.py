@@ -79,6 +79,14 @@ def _declare(L):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p, _p]
+    for name, sc in (("ref_dtrsm_work", ctypes.c_double), ("ref_strsm_work", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64]
+    for name, sc in (("ref_dtrsm_resid", ctypes.c_double), ("ref_strsm_resid", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64, _p, _i64, _p, _p]
     L.ref_zgemm_split_ext.restype = ctypes.c_int
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
@@ -176,6 +184,24 @@ def triangle_mask(uplo, n):
     """Boolean (n, n) mask in the (col, row) array layout: True where C(i, j) belongs to the triangle."""
     j, i = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
     return (i >= j) if uplo in "Ll" else (i <= j)
+
+
+def trsm_work(side, uplo, trans, diag, m, n, alpha, A, lda, B, ldb) -> int:
+    """In-place working-precision triangular solve: B <- X with op(T) X = alpha B (L) or X op(T) = alpha B (R)."""
+    pre, _ = _names(B.dtype if B is not None else np.float64)
+    f = getattr(lib(), f"ref_{pre}trsm_work")
+    return int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb))
+
+
+def trsm_resid(side, uplo, trans, diag, m, n, alpha, A, lda, B0, ldb, X, ldx):
+    """Extended-precision residual of a candidate X; returns (info, R, G), each of shape (n, m)."""
+    pre, wide = _names(B0.dtype)
+    R = np.zeros((max(n, 0), max(m, 0)), dtype=wide)
+    G = np.zeros_like(R)
+    f = getattr(lib(), f"ref_{pre}trsm_resid")
+    info = int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B0), ldb,
+                 _ptr(X), ldx, _ptr(R), _ptr(G)))
+    return info, R, G
 
 
 def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc):

@@ -353,6 +353,119 @@ int NAME(char uplo, char t, i64 n, i64 k, T alpha, const T *A, i64 lda,        \
 DEFINE_REF_SYRK_EXT(ref_dsyrk_ext, double, long double, fabsl)
 DEFINE_REF_SYRK_EXT(ref_ssyrk_ext, float, double, fabs)
 
+
+/* ------------------------------------------------------------------ */
+/* Triangular solve with many right-hand sides (level-3 BLAS on top of  */
+/* the GEMM kernel, paper Abstract and Sec. 1):                         */
+/*   side 'L':  op(T) X = alpha B,   T is m x m                         */
+/*   side 'R':  X op(T) = alpha B,   T is n x n                         */
+/* B (m x n) is overwritten by X.  Only the `uplo` triangle of the      */
+/* stored T is read; diag 'U' takes a unit diagonal and does not read   */
+/* the stored one.  alpha == 0 gives X = 0 without reading T or B.      */
+/* Plain substitution, one right-hand side at a time: with E = op(T)    */
+/* (side L) or op(T)^T (side R), row r of the solve is                  */
+/*   x_r = (alpha b_r - sum_{c before r} E(r,c) x_c) / E(r,r).          */
+/* Errors: side 1, uplo 2, trans 3, diag 4, m 5, n 6, alpha 7, A 8,     */
+/* lda 9, B 10, ldb 11.                                                 */
+/* ------------------------------------------------------------------ */
+static int check_args_trsm(char side, char uplo, char t, char diag, i64 m, i64 n, int a_needed, const void *A,
+                           i64 lda, const void *B, i64 ldb)
+{
+    const int left = (side == 'L' || side == 'l'), right = (side == 'R' || side == 'r');
+    if (!left && !right) return -1;
+    if (uplo != 'L' && uplo != 'l' && uplo != 'U' && uplo != 'u') return -2;
+    if (!is_n(t) && !is_t(t)) return -3;
+    if (diag != 'U' && diag != 'u' && diag != 'N' && diag != 'n') return -4;
+    if (m < 0) return -5;
+    if (n < 0) return -6;
+    if (a_needed && m > 0 && n > 0 && A == NULL) return -8;
+    if (lda < max64(1, left ? m : n)) return -9;
+    if (m > 0 && n > 0 && B == NULL) return -10;
+    if (ldb < max64(1, m)) return -11;
+    return 0;
+}
+
+/* E(r,c) for the solve "E x = rhs": element (r,c) of op(T) for side L, of op(T)^T for side R */
+#define TRI_E(r, c) (etrans ? A[(c) + (r) * lda] : A[(r) + (c) * lda])
+
+#define DEFINE_REF_TRSM_WORK(NAME, T)                                          \
+int NAME(char side, char uplo, char t, char diag, i64 m, i64 n, T alpha,       \
+         const T *A, i64 lda, T *B, i64 ldb)                                   \
+{                                                                              \
+    int info = check_args_trsm(side, uplo, t, diag, m, n, alpha != (T)0, A, lda, B, ldb); \
+    if (info) return info;                                                     \
+    if (m == 0 || n == 0) return 0;                                            \
+    const int left = (side == 'L' || side == 'l');                             \
+    if (alpha == (T)0) {                                                       \
+        for (i64 j = 0; j < n; ++j) for (i64 i = 0; i < m; ++i) B[i + j * ldb] = (T)0; \
+        return 0;                                                              \
+    }                                                                          \
+    const int etrans = (is_t(t) ? 1 : 0) ^ (left ? 0 : 1);                     \
+    const int lower = ((uplo == 'L' || uplo == 'l') ? 1 : 0) ^ etrans;         \
+    const int unit = (diag == 'U' || diag == 'u');                             \
+    const i64 dim = left ? m : n, nrhs = left ? n : m;                         \
+    const i64 xs = left ? 1 : ldb, rs = left ? ldb : 1; /* strides inside / between right-hand sides */ \
+    _Pragma("omp parallel for schedule(static)")                               \
+    for (i64 q = 0; q < nrhs; ++q) {                                           \
+        T *x = B + q * rs;                                                     \
+        for (i64 step = 0; step < dim; ++step) {                               \
+            const i64 r = lower ? step : dim - 1 - step;                       \
+            T acc = alpha * x[r * xs];                                         \
+            for (i64 s2 = 0; s2 < step; ++s2) {                                \
+                const i64 c = lower ? s2 : dim - 1 - s2;                       \
+                T prod = TRI_E(r, c) * x[c * xs];                              \
+                acc = acc - prod;                                              \
+            }                                                                  \
+            x[r * xs] = unit ? acc : acc / TRI_E(r, r);                        \
+        }                                                                      \
+    }                                                                          \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_TRSM_WORK(ref_dtrsm_work, double)
+DEFINE_REF_TRSM_WORK(ref_strsm_work, float)
+
+/* Residual of a candidate solution X (m x n, leading dimension ldx) in extended
+ * precision:  R = alpha B0 - op(T) X  (side L)  or  alpha B0 - X op(T)  (side R),
+ * G = |alpha||B0| + |op(T)||X|  (resp. |X||op(T)|); R and G dense m x n, ld = m.
+ * B0 is the right-hand side before the solve. */
+#define DEFINE_REF_TRSM_RESID(NAME, T, W, WABS)                                \
+int NAME(char side, char uplo, char t, char diag, i64 m, i64 n, T alpha,       \
+         const T *A, i64 lda, const T *B0, i64 ldb, const T *X, i64 ldx,       \
+         W *R, W *G)                                                           \
+{                                                                              \
+    int info = check_args_trsm(side, uplo, t, diag, m, n, 1, A, lda, B0, ldb); \
+    if (info) return info;                                                     \
+    if (m > 0 && n > 0 && X == NULL) return -12;                               \
+    if (ldx < max64(1, m)) return -13;                                         \
+    const int left = (side == 'L' || side == 'l');                             \
+    const int etrans = (is_t(t) ? 1 : 0) ^ (left ? 0 : 1);                     \
+    const int lower = ((uplo == 'L' || uplo == 'l') ? 1 : 0) ^ etrans;         \
+    const int unit = (diag == 'U' || diag == 'u');                             \
+    const i64 dim = left ? m : n;                                              \
+    _Pragma("omp parallel for schedule(static)")                               \
+    for (i64 j = 0; j < n; ++j)                                                \
+        for (i64 i = 0; i < m; ++i) {                                          \
+            /* the solve's row index r and right-hand side: (i, column j) or (j, row i) */ \
+            const i64 r = left ? i : j;                                        \
+            W acc = (W)alpha * (W)B0[i + j * ldb];                             \
+            W mag = WABS(acc);                                                 \
+            const i64 c0 = lower ? 0 : r, c1 = lower ? r + 1 : dim;            \
+            for (i64 c = c0; c < c1; ++c) {                                    \
+                W e = (c == r && unit) ? (W)1 : (W)TRI_E(r, c);                \
+                W x = left ? (W)X[c + j * ldx] : (W)X[i + c * ldx];            \
+                acc -= e * x;                                                  \
+                mag += WABS(e * x);                                            \
+            }                                                                  \
+            R[i + j * m] = acc;                                                \
+            G[i + j * m] = mag;                                                \
+        }                                                                      \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_TRSM_RESID(ref_dtrsm_resid, double, long double, fabsl)
+DEFINE_REF_TRSM_RESID(ref_strsm_resid, float, double, fabs)
+
 /* ------------------------------------------------------------------ */
 /* Complex GEMM on split real/imaginary planes.                         */
 /*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/

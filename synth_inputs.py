@@ -70,6 +70,40 @@ def identity(nrows, ld=None, dtype=np.float64, sentinel=np.nan):
     return X
 
 
+def _mask_triangle(X, n, uplo, unit_diag, sentinel):
+    """Overwrite everything the triangular routines must not read with the sentinel."""
+    j, i = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    outside = (i < j) if uplo in "Ll" else (i > j)
+    if unit_diag:
+        outside |= (i == j)
+    X[:, :n][outside] = sentinel
+    return X
+
+
+def triangular(rng, n, ld=None, dtype=np.float64, uplo="L", unit_diag=False, sentinel=np.nan):
+    """Well-conditioned triangular factor of the kind a pivoted LU or a Cholesky
+    factorisation leaves behind: off-diagonal entries uniform in [-1, 1] / n,
+    diagonal uniform in [1, 2] (or implicit ones).  The other triangle, the
+    diagonal of a unit-diagonal matrix and the padding hold the sentinel."""
+    ld = n if ld is None else ld
+    X = _alloc(n, n, ld, dtype, sentinel)
+    X[:, :n] = (rng.uniform(-1.0, 1.0, size=(n, n)) / max(n, 1)).astype(dtype)
+    d = rng.uniform(1.0, 2.0, size=n).astype(dtype)
+    X[np.arange(n), np.arange(n)] = d
+    return _mask_triangle(X, n, uplo, unit_diag, sentinel)
+
+
+def int_triangular(rng, n, ld=None, dtype=np.float64, uplo="L", unit_diag=False, R=4, sentinel=np.nan):
+    """Integer off-diagonal entries in [-R, R] and a diagonal of signed powers of
+    two (1, 2 or 4): every quotient by a diagonal entry is exact."""
+    ld = n if ld is None else ld
+    X = _alloc(n, n, ld, dtype, sentinel)
+    X[:, :n] = rng.integers(-R, R + 1, size=(n, n)).astype(dtype)
+    d = (2.0 ** rng.integers(0, 3, size=n)) * rng.choice([-1.0, 1.0], size=n)
+    X[np.arange(n), np.arange(n)] = d.astype(dtype)
+    return _mask_triangle(X, n, uplo, unit_diag, sentinel)
+
+
 def rng_for(config: int, index: int = 0):
     return np.random.Generator(np.random.PCG64(seed_for(config, index)))
 
