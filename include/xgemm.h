@@ -73,7 +73,30 @@ int xgemm_ssyrk(char uplo, char trans, int64_t n, int64_t k, float alpha, const 
                 float beta, float *C, int64_t ldc, void *stream);
 
 /*
- * The same four routines with a caller-owned workspace, which lets the library
+ * Triangular solve with many right-hand sides on the real kernel (level-3 BLAS
+ * above GEMM, Abstract and Sec. 1):
+ *     side L:  op(T) X = alpha B,   T is m x m
+ *     side R:  X op(T) = alpha B,   T is n x n
+ * B (m x n) is overwritten by X.  T is triangular: only its `uplo` triangle is
+ * read (the other one may hold anything); diag U takes a unit diagonal and does
+ * not read the stored one.  alpha == 0 gives X = 0 without reading T or B.
+ * T is halved recursively; the halves are coupled by GEMMs with the
+ * off-diagonal block (alpha -1, beta 1), diagonal blocks of order <= 64 are
+ * solved by substitution, so every element of X comes out of a sum of at most
+ * dim products plus one division (multiplication by the reciprocal of the
+ * diagonal entry) and satisfies the componentwise residual bound
+ *     |alpha B - op(T) X| <= 4 dim u (|alpha B| + |op(T)| |X|),  dim = m or n.
+ * T must not overlap B.  No singularity check.  Illegal-argument numbering:
+ * side 1, uplo 2, transa 3, diag 4, m 5, n 6, alpha 7, A 8, lda 9, B 10, ldb 11.
+ * flops: m^2 n (side L) or m n^2 (side R).
+ */
+int xgemm_dtrsm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha,
+                const double *A, int64_t lda, double *B, int64_t ldb, void *stream);
+int xgemm_strsm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, float alpha,
+                const float *A, int64_t lda, float *B, int64_t ldb, void *stream);
+
+/*
+ * GEMM and SYRK with a caller-owned workspace, which lets the library
  * cut the tiles of the last, partly filled round of workgroups along K (the k_c
  * loop of Fig. 1 moved across workgroups for those tiles only): each piece
  * leaves its partial sums in the workspace, the piece that finishes last adds

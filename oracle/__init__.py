@@ -87,6 +87,10 @@ def _declare(L):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64, _p, _i64, _p, _p]
+    for name, sc in (("ref_dtrsm_resid_samples", ctypes.c_double), ("ref_strsm_resid_samples", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64, _p, _i64, _i64, _p, _p, _p, _p]
     L.ref_zgemm_split_ext.restype = ctypes.c_int
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
@@ -201,6 +205,19 @@ def trsm_resid(side, uplo, trans, diag, m, n, alpha, A, lda, B0, ldb, X, ldx):
     f = getattr(lib(), f"ref_{pre}trsm_resid")
     info = int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B0), ldb,
                  _ptr(X), ldx, _ptr(R), _ptr(G)))
+    return info, R, G
+
+
+def trsm_resid_samples(side, uplo, trans, diag, m, n, alpha, A, lda, B0, ldb, X, ldx, I, J):
+    """The residual at the entries (I[s], J[s]) only; returns (info, R, G) as 1-d arrays."""
+    pre, wide = _names(B0.dtype)
+    I = np.ascontiguousarray(I, dtype=np.int64)
+    J = np.ascontiguousarray(J, dtype=np.int64)
+    R = np.zeros(I.size, dtype=wide)
+    G = np.zeros(I.size, dtype=wide)
+    f = getattr(lib(), f"ref_{pre}trsm_resid_samples")
+    info = int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B0), ldb,
+                 _ptr(X), ldx, I.size, _ptr(I), _ptr(J), _ptr(R), _ptr(G)))
     return info, R, G
 
 

@@ -466,6 +466,46 @@ int NAME(char side, char uplo, char t, char diag, i64 m, i64 n, T alpha,       \
 DEFINE_REF_TRSM_RESID(ref_dtrsm_resid, double, long double, fabsl)
 DEFINE_REF_TRSM_RESID(ref_strsm_resid, float, double, fabs)
 
+
+/* The same residual at sampled entries only: R[s], G[s] for element (I[s], J[s]). */
+#define DEFINE_REF_TRSM_RESID_SAMPLES(NAME, T, W, WABS)                        \
+int NAME(char side, char uplo, char t, char diag, i64 m, i64 n, T alpha,       \
+         const T *A, i64 lda, const T *B0, i64 ldb, const T *X, i64 ldx,       \
+         i64 ns, const i64 *I, const i64 *J, W *R, W *G)                       \
+{                                                                              \
+    int info = check_args_trsm(side, uplo, t, diag, m, n, 1, A, lda, B0, ldb); \
+    if (info) return info;                                                     \
+    if (m > 0 && n > 0 && X == NULL) return -12;                               \
+    if (ldx < max64(1, m)) return -13;                                         \
+    for (i64 s = 0; s < ns; ++s)                                               \
+        if (I[s] < 0 || I[s] >= m || J[s] < 0 || J[s] >= n) return -15;        \
+    const int left = (side == 'L' || side == 'l');                             \
+    const int etrans = (is_t(t) ? 1 : 0) ^ (left ? 0 : 1);                     \
+    const int lower = ((uplo == 'L' || uplo == 'l') ? 1 : 0) ^ etrans;         \
+    const int unit = (diag == 'U' || diag == 'u');                             \
+    const i64 dim = left ? m : n;                                              \
+    _Pragma("omp parallel for schedule(static)")                               \
+    for (i64 s = 0; s < ns; ++s) {                                             \
+        const i64 i = I[s], j = J[s];                                          \
+        const i64 r = left ? i : j;                                            \
+        W acc = (W)alpha * (W)B0[i + j * ldb];                                 \
+        W mag = WABS(acc);                                                     \
+        const i64 c0 = lower ? 0 : r, c1 = lower ? r + 1 : dim;                \
+        for (i64 c = c0; c < c1; ++c) {                                        \
+            W e = (c == r && unit) ? (W)1 : (W)TRI_E(r, c);                    \
+            W x = left ? (W)X[c + j * ldx] : (W)X[i + c * ldx];                \
+            acc -= e * x;                                                      \
+            mag += WABS(e * x);                                                \
+        }                                                                      \
+        R[s] = acc;                                                            \
+        G[s] = mag;                                                            \
+    }                                                                          \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_TRSM_RESID_SAMPLES(ref_dtrsm_resid_samples, double, long double, fabsl)
+DEFINE_REF_TRSM_RESID_SAMPLES(ref_strsm_resid_samples, float, double, fabs)
+
 /* ------------------------------------------------------------------ */
 /* Complex GEMM on split real/imaginary planes.                         */
 /*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/

@@ -14,6 +14,8 @@ from .xgemm import (  # noqa: F401
     xgemm_sgemm,
     xgemm_dsyrk,
     xgemm_ssyrk,
+    xgemm_dtrsm,
+    xgemm_strsm,
     xgemm_tile_map,
     xgemm_workspace_bytes,
     xgemm_workspace_init,

@@ -19,7 +19,7 @@ EXPORTS = [
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
-    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm",
 ]
 
 
@@ -66,6 +66,10 @@ def lib():
         f = getattr(L, f"xgemm_{pre}syrk_ws")
         f.restype = ctypes.c_int
         f.argtypes = [_c, _c, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p, ctypes.c_size_t, _p]
+    for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
+        f = getattr(L, f"xgemm_{pre}trsm")
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _c, _c, _c, _i64, _i64, sc, _p, _i64, _p, _i64, _p]
     L.xgemm_workspace_bytes.restype = ctypes.c_size_t
     L.xgemm_workspace_bytes.argtypes = []
     L.xgemm_workspace_init.restype = ctypes.c_int
@@ -144,6 +148,16 @@ def xgemm_dsyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream=None) -> 
 
 def xgemm_ssyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream=None) -> int:
     return int(lib().xgemm_ssyrk(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
+                                 _stream(stream)))
+
+
+def xgemm_dtrsm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=None) -> int:
+    return int(lib().xgemm_dtrsm(_ch(side), _ch(uplo), _ch(transa), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
+                                 _stream(stream)))
+
+
+def xgemm_strsm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=None) -> int:
+    return int(lib().xgemm_strsm(_ch(side), _ch(uplo), _ch(transa), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
                                  _stream(stream)))
 
 

@@ -104,6 +104,26 @@ def test_zgemm_illegal_arguments_and_worksize():
     assert z("N", "N", 0, 2, 2, (1, 1), None, None, 1, None, None, 2, (0, 0), None, None, 1) == 0
 
 
+@pytest.mark.parametrize("fn", ["xgemm_dtrsm", "xgemm_strsm"])
+def test_trsm_illegal_arguments_and_quick_returns(fn):
+    f = getattr(xg, fn)
+    P = 4096
+    g = lambda *a: f(*a, stream=0)
+    assert g("X", "L", "N", "N", 4, 3, 1.0, P, 4, P, 4) == -1
+    assert g("L", "X", "N", "N", 4, 3, 1.0, P, 4, P, 4) == -2
+    assert g("L", "L", "X", "N", 4, 3, 1.0, P, 4, P, 4) == -3
+    assert g("L", "L", "N", "X", 4, 3, 1.0, P, 4, P, 4) == -4
+    assert g("L", "L", "N", "N", -1, 3, 1.0, P, 4, P, 4) == -5
+    assert g("L", "L", "N", "N", 4, 2 ** 31, 1.0, P, 4, P, 4) == -6
+    assert g("L", "L", "N", "N", 4, 3, 1.0, None, 4, P, 4) == -8
+    assert g("L", "L", "N", "N", 4, 3, 1.0, P, 3, P, 4) == -9
+    assert g("R", "L", "N", "N", 4, 3, 1.0, P, 2, P, 4) == -9
+    assert g("L", "L", "N", "N", 4, 3, 1.0, P, 4, None, 4) == -10
+    assert g("L", "L", "N", "N", 4, 3, 1.0, P, 4, P, 3) == -11
+    assert g("L", "L", "N", "N", 0, 3, 1.0, None, 1, None, 1) == 0
+    assert g("R", "U", "T", "U", 4, 0, 1.0, None, 1, None, 4) == 0
+
+
 def test_workspace_routines_host_side():
     P = 4096
     assert xg.xgemm_workspace_bytes() == 8192 + (64 << 20)

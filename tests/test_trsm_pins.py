@@ -155,6 +155,10 @@ def test_residual_routine(side, uplo, trans, diag):
     dense = np.longdouble(1.5) * Bd - (T @ Xd if side == "L" else Xd @ T)
     denseG = np.abs(np.longdouble(1.5) * Bd) + (np.abs(T) @ np.abs(Xd) if side == "L" else np.abs(Xd) @ np.abs(T))
     assert np.allclose(R.T, dense, rtol=0, atol=1e-17) and np.allclose(G.T, denseG, rtol=1e-15)
+    I, J = si.sample_indices(rng, m, n, 3, 3, 200)
+    info, Rs, Gs = oracle.trsm_resid_samples(side, uplo, trans, diag, m, n, 1.5, A, lda, B, ldb, X, ldb, I, J)
+    assert info == 0 and np.array_equal(Rs, R[J, I]) and np.array_equal(Gs, G[J, I])
+    assert oracle.trsm_resid_samples(side, uplo, trans, diag, m, n, 1.5, A, lda, B, ldb, X, ldb, [m], [0])[0] == -15
     Xbad = X.copy()
     Xbad[n // 2, m // 2] *= 1 + 1e-9
     _, R2, G2 = oracle.trsm_resid(side, uplo, trans, diag, m, n, 1.5, A, lda, B, ldb, Xbad, ldb)
