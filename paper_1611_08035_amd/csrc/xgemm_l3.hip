@@ -14,7 +14,6 @@
 namespace {
 
 constexpr int NB = 64;        // order of the diagonal blocks solved by substitution
-constexpr int LDE = NB + 2;   // LDS column stride of the block (keeps 16-byte alignment, spreads banks)
 
 inline bool is_n(char t) { return t == 'N' || t == 'n'; }
 inline bool is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; }
@@ -34,63 +33,97 @@ template <typename T> struct BlockArgs {
     int unit;        // implicit unit diagonal
 };
 
-// One wave solves E x = b for 64 right-hand sides, one per lane, the unsolved
-// part of x in registers.  E is brought to lower-triangular form in LDS (an
-// upper-triangular E is reversed in both indices, and the right-hand sides with
-// it), stored by columns with the reciprocals of the diagonal kept apart.
-// Step c takes the pivot from register 0, stores it, and eliminates it from
-// the rows below while shifting them down one register:
-//   x_c = reg[0] / E_cc;   reg[i] = reg[i+1] - E(c+1+i, c) x_c,  i = 0..NB-2
-// so the registers are indexed statically inside a loop over c that stays a
-// loop.  Registers whose row lies beyond the block pick up whatever LDS holds
-// past the column and are never used as pivots.  All lanes read the same
-// element of E at the same time (LDS broadcast).
-template <typename T> __global__ void __launch_bounds__(64) trsm_block_kernel(const BlockArgs<T> a) {
-    __shared__ T e_cols[(NB + 1) * LDE];   // one spare column: reads below the last row stay inside the array
-    __shared__ T d_inv[NB];
-    const int t = threadIdx.x;
+// Diagonal-block solve E x = b by substitution, E of order nbk <= NB = 64.
+// A workgroup of 4 waves brings E to unit lower-triangular form in LDS once:
+// an upper-triangular E is reversed in both indices (and the right-hand sides
+// with it), and every column is divided by its diagonal entry, E = E' D, so that
+// E' y = b with y = D x has a unit diagonal and x = D^-1 y.  Each wave then
+// solves RHS_PER_WAVE right-hand sides at once with the rows of the system
+// spread over its 64 lanes: lane r holds y_r of every right-hand side in
+// registers.  Step c reads column c of E' (one LDS element per lane, zero on
+// and above the diagonal), takes the pivot y_c of each right-hand side from
+// lane c into scalar registers, and updates all rows below in one FMA per
+// right-hand side:  y_r -= E'(r, c) y_c.
+constexpr int RHS_PER_WAVE = 16;
+constexpr int WAVES = 4;
+
+template <typename T> static __device__ __forceinline__ T lane_value(T v, int lane) {
+    if constexpr (sizeof(T) == 8) {
+        typedef int i32x2 __attribute__((ext_vector_type(2)));
+        i32x2 p = __builtin_bit_cast(i32x2, v);
+        p[0] = __builtin_amdgcn_readlane(p[0], lane);
+        p[1] = __builtin_amdgcn_readlane(p[1], lane);
+        return __builtin_bit_cast(T, p);
+    } else {
+        return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+    }
+}
+
+template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_kernel(const BlockArgs<T> a) {
+    constexpr int DUMP = NB * NB;            // takes the writes of threads that hold nothing
+    __shared__ T e_cols[DUMP + 1];           // E'(r, c) at [c * NB + r]
+    __shared__ T d_inv[NB + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nbk = a.nbk;
     const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
+    const int lowr = a.stored_lower ? 1 : 0;
 
-    for (int i = t; i < (NB + 1) * LDE; i += 64) e_cols[i] = T(0);
-    d_inv[t] = T(1);
+    for (int i = tid; i < DUMP + 1; i += 64 * WAVES) e_cols[i] = T(0);
+    if (tid < NB + 1) d_inv[tid] = T(1);
     __syncthreads();
-    // stored column s, stored row t: only the referenced triangle is read
-    for (int s = 0; s < nbk; ++s) {
-        const bool inside = t < nbk && (a.stored_lower ? t >= s : t <= s) && !(a.unit && t == s);
-        if (inside) {
-            const T v = a.A[t + (int64_t)s * a.lda];
-            int r = a.etrans ? s : t, c = a.etrans ? t : s;
+    // reciprocal of the diagonal, at the position its row takes after the reversal
+    if (tid < nbk && !a.unit) d_inv[e_lower ? tid : nbk - 1 - tid] = T(1) / a.A[tid + (int64_t)tid * a.lda];
+    __syncthreads();
+    // Thread (wave w, lane t) takes stored row t and the stored columns s = w, w + 4, ...; only
+    // the referenced triangle is read.  Loads first, LDS writes after; positions outside the
+    // triangle re-read element (0, 0) and go to the spare slot, so there is no branch.
+    {
+        constexpr int PER = NB / WAVES;
+        T row[PER];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int s = wave + u * WAVES;
+            const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane > s)) | ((lowr ^ 1) & (int)(lane < s)));
+            row[u] = a.A[(inside ? lane : 0) + (int64_t)(inside ? s : 0) * a.lda];
+        }
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int s = wave + u * WAVES;
+            const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane > s)) | ((lowr ^ 1) & (int)(lane < s)));
+            int r = a.etrans ? s : lane, c = a.etrans ? lane : s;
             if (!e_lower) { r = nbk - 1 - r; c = nbk - 1 - c; }
-            if (r == c) d_inv[r] = T(1) / v;
-            else e_cols[c * LDE + r] = v;
+            const int cc = inside ? c : NB;
+            e_cols[inside ? c * NB + r : DUMP] = row[u] * d_inv[cc];   // column c scaled by 1 / E(c, c)
         }
     }
     __syncthreads();
 
-    const int q = blockIdx.x * 64 + t;
-    const bool active = q < a.nrhs;
-    // lanes past the last right-hand side work on a copy of the last one and store nothing;
-    // positions past the block's order re-read its first element and are replaced by zero:
-    // every load is in bounds and none is conditional
-    const int qq = active ? q : a.nrhs - 1;
-    const int64_t xs = a.left ? 1 : a.ldb;                       // stride inside a right-hand side
-    T *const xp = a.B + (a.left ? (int64_t)qq * a.ldb : (int64_t)qq);
-    const int64_t first = e_lower ? 0 : (int64_t)(nbk - 1) * xs, step = e_lower ? xs : -xs;
-    T x[NB];
+    // right-hand sides q0 .. q0 + RHS_PER_WAVE - 1 of this wave; element `lane` of each
+    const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
+    if (q0 >= a.nrhs) return;                                    // wave-uniform, after the last barrier
+    const int pos = lane < nbk ? (e_lower ? lane : nbk - 1 - lane) : 0;   // lanes past the order re-read element 0
+    const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;       // strides between / inside right-hand sides
+    T *const xp = a.B + (int64_t)pos * xs;
+    T y[RHS_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        const T v = xp[first + (i < nbk ? i : 0) * step];
-        x[i] = i < nbk ? v : T(0);
+    for (int j = 0; j < RHS_PER_WAVE; ++j) {
+        const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;     // past the last one: a copy that is not stored
+        const T v = xp[(int64_t)q * qs];
+        y[j] = lane < nbk ? v : T(0);
     }
+    T e = e_cols[lane];                                          // column 0
 #pragma unroll 1
     for (int c = 0; c < nbk; ++c) {
-        const T xc = x[0] * d_inv[c];
-        if (active) xp[first + c * step] = xc;
-        const T *const col = e_cols + c * LDE + c + 1;
+        const T e_next = e_cols[(c + 1 < NB ? c + 1 : c) * NB + lane];
 #pragma unroll
-        for (int i = 0; i + 1 < NB; ++i) x[i] = x[i + 1] - col[i] * xc;
-        x[NB - 1] = T(0);
+        for (int j = 0; j < RHS_PER_WAVE; ++j) y[j] -= e * lane_value(y[j], c);
+        e = e_next;
+    }
+    const T d = d_inv[lane < nbk ? lane : NB];
+    if (lane < nbk) {
+#pragma unroll
+        for (int j = 0; j < RHS_PER_WAVE; ++j)
+            if (q0 + j < a.nrhs) xp[(int64_t)(q0 + j) * qs] = y[j] * d;
     }
 }
 
@@ -141,7 +174,8 @@ template <typename T> struct Solve {
         a.etrans = etrans() ? 1 : 0;
         a.stored_lower = stored_lower ? 1 : 0;
         a.unit = unit ? 1 : 0;
-        hipLaunchKernelGGL(trsm_block_kernel<T>, dim3((unsigned)((a.nrhs + 63) / 64)), dim3(64), 0,
+        constexpr int PER_WG = RHS_PER_WAVE * WAVES;
+        hipLaunchKernelGGL(trsm_block_kernel<T>, dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(64 * WAVES), 0,
                            static_cast<hipStream_t>(stream), a);
         return (int)hipGetLastError();
     }
