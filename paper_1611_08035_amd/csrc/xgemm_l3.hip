@@ -60,47 +60,18 @@ template <typename T> static __device__ __forceinline__ T lane_value(T v, int la
 }
 
 template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_kernel(const BlockArgs<T> a) {
-    constexpr int DUMP = NB * NB;            // takes the writes of threads that hold nothing
-    __shared__ T e_cols[DUMP + 1];           // E'(r, c) at [c * NB + r]
-    __shared__ T d_inv[NB + 1];
+    __shared__ T e_cols[NB * NB];            // E(r, c) at [c * NB + r], zero on and above the diagonal
+    __shared__ T d_inv[NB];                  // 1 / E(c, c)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nbk = a.nbk;
     const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
     const int lowr = a.stored_lower ? 1 : 0;
+    constexpr int PER = NB / WAVES;
 
-    for (int i = tid; i < DUMP + 1; i += 64 * WAVES) e_cols[i] = T(0);
-    if (tid < NB + 1) d_inv[tid] = T(1);
-    __syncthreads();
-    // reciprocal of the diagonal, at the position its row takes after the reversal
-    if (tid < nbk && !a.unit) d_inv[e_lower ? tid : nbk - 1 - tid] = T(1) / a.A[tid + (int64_t)tid * a.lda];
-    __syncthreads();
-    // Thread (wave w, lane t) takes stored row t and the stored columns s = w, w + 4, ...; only
-    // the referenced triangle is read.  Loads first, LDS writes after; positions outside the
-    // triangle re-read element (0, 0) and go to the spare slot, so there is no branch.
-    {
-        constexpr int PER = NB / WAVES;
-        T row[PER];
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int s = wave + u * WAVES;
-            const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane > s)) | ((lowr ^ 1) & (int)(lane < s)));
-            row[u] = a.A[(inside ? lane : 0) + (int64_t)(inside ? s : 0) * a.lda];
-        }
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int s = wave + u * WAVES;
-            const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane > s)) | ((lowr ^ 1) & (int)(lane < s)));
-            int r = a.etrans ? s : lane, c = a.etrans ? lane : s;
-            if (!e_lower) { r = nbk - 1 - r; c = nbk - 1 - c; }
-            const int cc = inside ? c : NB;
-            e_cols[inside ? c * NB + r : DUMP] = row[u] * d_inv[cc];   // column c scaled by 1 / E(c, c)
-        }
-    }
-    __syncthreads();
-
-    // right-hand sides q0 .. q0 + RHS_PER_WAVE - 1 of this wave; element `lane` of each
+    // Every global load of the kernel is issued before the first wait: the
+    // right-hand sides of this wave, this thread's share of the block, the diagonal.
+    // right-hand sides q0 .. q0 + RHS_PER_WAVE - 1; lane holds element `pos` of each
     const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
-    if (q0 >= a.nrhs) return;                                    // wave-uniform, after the last barrier
     const int pos = lane < nbk ? (e_lower ? lane : nbk - 1 - lane) : 0;   // lanes past the order re-read element 0
     const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;       // strides between / inside right-hand sides
     T *const xp = a.B + (int64_t)pos * xs;
@@ -108,18 +79,48 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_k
 #pragma unroll
     for (int j = 0; j < RHS_PER_WAVE; ++j) {
         const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;     // past the last one: a copy that is not stored
-        const T v = xp[(int64_t)q * qs];
-        y[j] = lane < nbk ? v : T(0);
+        y[j] = xp[(int64_t)q * qs];
     }
-    T e = e_cols[lane];                                          // column 0
+    // Thread (wave w, lane t) takes stored row t and the stored columns s = w, w + 4, ...; only the
+    // referenced triangle is read, positions outside it re-read element (0, 0) and count as zero.
+    T row[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int s = wave + u * WAVES;
+        const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane > s)) | ((lowr ^ 1) & (int)(lane < s)));
+        const T v = a.A[(inside ? lane : 0) + (int64_t)(inside ? s : 0) * a.lda];
+        row[u] = inside ? v : T(0);
+    }
+    const bool has_diag = tid < nbk && !a.unit;
+    const T dv = a.A[has_diag ? tid + (int64_t)tid * a.lda : 0];
+
+    // (stored row, stored column) -> (r, c) of E is one-to-one on the NB x NB square (positions
+    // outside the block map to themselves), so every LDS element is written exactly once
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int s = wave + u * WAVES;
+        const bool in_blk = lane < nbk && s < nbk;
+        int r = a.etrans ? s : lane, c = a.etrans ? lane : s;
+        if (in_blk && !e_lower) { r = nbk - 1 - r; c = nbk - 1 - c; }
+        e_cols[c * NB + r] = row[u];
+    }
+    if (tid < NB) d_inv[tid < nbk ? (e_lower ? tid : nbk - 1 - tid) : tid] = has_diag ? T(1) / dv : T(1);
+    __syncthreads();
+    if (q0 >= a.nrhs) return;                                    // wave-uniform, after the last barrier
+
+    // E = E' D with E' unit lower triangular: solve E' y = b, then x = D^-1 y
+#pragma unroll
+    for (int j = 0; j < RHS_PER_WAVE; ++j) y[j] = lane < nbk ? y[j] : T(0);
+    T e = e_cols[lane] * d_inv[0];                               // column 0 of E'
 #pragma unroll 1
     for (int c = 0; c < nbk; ++c) {
-        const T e_next = e_cols[(c + 1 < NB ? c + 1 : c) * NB + lane];
+        const int cn = c + 1 < NB ? c + 1 : c;
+        const T e_next = e_cols[cn * NB + lane] * d_inv[cn];
 #pragma unroll
         for (int j = 0; j < RHS_PER_WAVE; ++j) y[j] -= e * lane_value(y[j], c);
         e = e_next;
     }
-    const T d = d_inv[lane < nbk ? lane : NB];
+    const T d = d_inv[lane];
     if (lane < nbk) {
 #pragma unroll
         for (int j = 0; j < RHS_PER_WAVE; ++j)
