@@ -91,6 +91,11 @@ def _declare(L):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64, _p, _i64, _i64, _p, _p, _p, _p]
+    for name, sc in (("ref_dtrmm_ext", ctypes.c_double), ("ref_strmm_ext", ctypes.c_float),
+                     ("ref_dtrmm_wp", ctypes.c_double), ("ref_strmm_wp", ctypes.c_float)):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64, _p, _p]
     L.ref_zgemm_split_ext.restype = ctypes.c_int
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
@@ -219,6 +224,33 @@ def trsm_resid_samples(side, uplo, trans, diag, m, n, alpha, A, lda, B0, ldb, X,
     info = int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B0), ldb,
                  _ptr(X), ldx, I.size, _ptr(I), _ptr(J), _ptr(R), _ptr(G)))
     return info, R, G
+
+
+def trmm_ext(side, uplo, trans, diag, m, n, alpha, A, lda, B, ldb):
+    """alpha op(T) B (side L) or alpha B op(T) (side R) in extended precision; returns (info, Out, G), shape (n, m)."""
+    pre, wide = _names(B.dtype)
+    Out = np.zeros((max(n, 0), max(m, 0)), dtype=wide)
+    G = np.zeros_like(Out)
+    f = getattr(lib(), f"ref_{pre}trmm_ext")
+    info = int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
+                 _ptr(Out), _ptr(G)))
+    return info, Out, G
+
+
+def trmm_work(side, uplo, trans, diag, m, n, alpha, A, lda, B, ldb) -> int:
+    """Working-precision triangular product, B overwritten (through a dense temporary)."""
+    if B is None:
+        f = lib().ref_dtrmm_wp
+        return int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, None, ldb, None, None))
+    pre, _ = _names(B.dtype)
+    Out = np.zeros((max(n, 0), max(m, 0)), dtype=B.dtype)
+    G = np.zeros_like(Out)
+    f = getattr(lib(), f"ref_{pre}trmm_wp")
+    info = int(f(_ch(side), _ch(uplo), _ch(trans), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
+                 _ptr(Out), _ptr(G)))
+    if info == 0 and m > 0 and n > 0:
+        B[:, :m] = Out
+    return info
 
 
 def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc):

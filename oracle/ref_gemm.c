@@ -506,6 +506,57 @@ int NAME(char side, char uplo, char t, char diag, i64 m, i64 n, T alpha,       \
 DEFINE_REF_TRSM_RESID_SAMPLES(ref_dtrsm_resid_samples, double, long double, fabsl)
 DEFINE_REF_TRSM_RESID_SAMPLES(ref_strsm_resid_samples, float, double, fabs)
 
+
+/* ------------------------------------------------------------------ */
+/* Triangular matrix product (level-3 BLAS on top of the GEMM kernel):  */
+/*   side 'L':  B := alpha op(T) B,   T is m x m                        */
+/*   side 'R':  B := alpha B op(T),   T is n x n                        */
+/* Same conventions as the triangular solve (only the `uplo` triangle   */
+/* of T is read, diag 'U' implies ones; alpha == 0 gives B = 0 without  */
+/* reading T or B).  Argument numbering as for the solve.  The result   */
+/* is the definition: each element is the sum over the triangle in      */
+/* increasing index order, times alpha.                                 */
+/* ------------------------------------------------------------------ */
+#define DEFINE_REF_TRMM(NAME, T, W, WABS)                                      \
+/* Out (m x n, ld = m) = alpha op(T) B (or B op(T)) in precision W; G = |alpha| |op(T)| |B| */ \
+int NAME(char side, char uplo, char t, char diag, i64 m, i64 n, T alpha,       \
+         const T *A, i64 lda, const T *B, i64 ldb, W *Out, W *G)               \
+{                                                                              \
+    int info = check_args_trsm(side, uplo, t, diag, m, n, alpha != (T)0, A, lda, B, ldb); \
+    if (info) return info;                                                     \
+    const int left = (side == 'L' || side == 'l');                             \
+    const int etrans = (is_t(t) ? 1 : 0) ^ (left ? 0 : 1);                     \
+    const int lower = ((uplo == 'L' || uplo == 'l') ? 1 : 0) ^ etrans;         \
+    const int unit = (diag == 'U' || diag == 'u');                             \
+    const i64 dim = left ? m : n;                                              \
+    _Pragma("omp parallel for schedule(static)")                               \
+    for (i64 j = 0; j < n; ++j)                                                \
+        for (i64 i = 0; i < m; ++i) {                                          \
+            /* with E = op(T) (side L) or op(T)^T (side R): out = sum_c E(r, c) x_c */ \
+            const i64 r = left ? i : j;                                        \
+            W acc = 0, mag = 0;                                                \
+            if (alpha != (T)0) {                                               \
+                const i64 c0 = lower ? 0 : r, c1 = lower ? r + 1 : dim;        \
+                for (i64 c = c0; c < c1; ++c) {                                \
+                    W e = (c == r && unit) ? (W)1 : (W)TRI_E(r, c);            \
+                    W x = left ? (W)B[c + j * ldb] : (W)B[i + c * ldb];        \
+                    W prod = e * x;                                            \
+                    acc = acc + prod;                                          \
+                    mag += WABS(prod);                                         \
+                }                                                              \
+            }                                                                  \
+            Out[i + j * m] = (alpha == (T)0) ? (W)0 : (W)alpha * acc;          \
+            G[i + j * m] = WABS((W)alpha) * mag;                               \
+        }                                                                      \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_TRMM(ref_dtrmm_ext, double, long double, fabsl)
+DEFINE_REF_TRMM(ref_strmm_ext, float, double, fabs)
+/* working precision (W = T): the bit-exact reference for integer data */
+DEFINE_REF_TRMM(ref_dtrmm_wp, double, double, fabs)
+DEFINE_REF_TRMM(ref_strmm_wp, float, float, fabsf)
+
 /* ------------------------------------------------------------------ */
 /* Complex GEMM on split real/imaginary planes.                         */
 /*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/
