@@ -96,6 +96,23 @@ int xgemm_strsm(char side, char uplo, char transa, char diag, int64_t m, int64_t
                 const float *A, int64_t lda, float *B, int64_t ldb, void *stream);
 
 /*
+ * Triangular matrix product on the real kernel, in place:
+ *     side L:  B := alpha op(T) B,   T is m x m
+ *     side R:  B := alpha B op(T),   T is n x n
+ * Conventions, argument numbering and flop count as for xgemm_dtrsm (only the
+ * `uplo` triangle of T is read, diag U implies ones, alpha == 0 gives B = 0
+ * without reading T or B, T must not overlap B).  Same recursive organisation:
+ * the halves of T are coupled by GEMMs with the off-diagonal block, diagonal
+ * blocks of order <= 64 are multiplied by a small kernel.  Every element is a
+ * sum of at most dim products in some order, so it satisfies the product bound
+ *     |B_out - alpha op(T) B| <= 4 dim u |alpha| |op(T)| |B|.
+ */
+int xgemm_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha,
+                const double *A, int64_t lda, double *B, int64_t ldb, void *stream);
+int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, float alpha,
+                const float *A, int64_t lda, float *B, int64_t ldb, void *stream);
+
+/*
  * GEMM and SYRK with a caller-owned workspace, which lets the library
  * cut the tiles of the last, partly filled round of workgroups along K (the k_c
  * loop of Fig. 1 moved across workgroups for those tiles only): each piece

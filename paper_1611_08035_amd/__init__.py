@@ -16,6 +16,8 @@ from .xgemm import (  # noqa: F401
     xgemm_ssyrk,
     xgemm_dtrsm,
     xgemm_strsm,
+    xgemm_dtrmm,
+    xgemm_strmm,
     xgemm_tile_map,
     xgemm_workspace_bytes,
     xgemm_workspace_init,

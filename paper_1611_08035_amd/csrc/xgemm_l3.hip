@@ -1,11 +1,11 @@
 // xgemm_l3.hip -- level-3 routines on top of the GEMM entry points: the
-// triangular solve with many right-hand sides.
+// triangular solve with many right-hand sides and the triangular product.
 //
-// The solve is organised so that almost all of its arithmetic is GEMM: the
-// triangular matrix is halved recursively, each half is solved in turn, and
+// Both are organised so that almost all of their arithmetic is GEMM: the
+// triangular matrix is halved recursively, each half is handled in turn, and
 // the coupling between the halves is one product with the off-diagonal block
 // (depth = half the order, so the products are large).  Diagonal blocks of
-// order <= NB are solved by substitution in a small kernel of their own.
+// order <= NB are solved (multiplied) in a small kernel of their own.
 #include "../../include/xgemm.h"
 
 #include <hip/hip_runtime.h>
@@ -31,6 +31,7 @@ template <typename T> struct BlockArgs {
     int etrans;      // the solve's matrix E has E(r,c) = A[c + r*lda] if set, A[r + c*lda] otherwise
     int stored_lower;   // which triangle of the stored matrix is referenced
     int unit;        // implicit unit diagonal
+    T alpha;         // triangular product only: scalar applied to the result
 };
 
 // Diagonal-block solve E x = b by substitution, E of order nbk <= NB = 64.
@@ -128,6 +129,70 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_k
     }
 }
 
+// Diagonal-block product x := alpha E x with the same organisation: E (lower
+// after the index maps, diagonal included) in LDS, the rows of the result across
+// the lanes of a wave, 16 right-hand sides per wave; step c adds column c of E
+// times element c of each right-hand side, taken from lane c.
+template <typename T> __global__ void __launch_bounds__(64 * WAVES) trmm_block_kernel(const BlockArgs<T> a) {
+    __shared__ T e_cols[NB * NB];            // E(r, c) at [c * NB + r], zero above the diagonal
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nbk = a.nbk;
+    const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
+    const int lowr = a.stored_lower ? 1 : 0, unit = a.unit ? 1 : 0;
+    constexpr int PER = NB / WAVES;
+
+    const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
+    const int pos = lane < nbk ? (e_lower ? lane : nbk - 1 - lane) : 0;
+    const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;
+    T *const xp = a.B + (int64_t)pos * xs;
+    T x[RHS_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < RHS_PER_WAVE; ++j) {
+        const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;
+        x[j] = xp[(int64_t)q * qs];
+    }
+    T row[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int s = wave + u * WAVES;
+        // the referenced triangle, with the diagonal unless it is implicit
+        const int tri = (lowr & (int)(lane > s)) | ((lowr ^ 1) & (int)(lane < s)) | ((unit ^ 1) & (int)(lane == s));
+        const int inside = (int)(lane < nbk) & (int)(s < nbk) & tri;
+        const T v = a.A[(inside ? lane : 0) + (int64_t)(inside ? s : 0) * a.lda];
+        row[u] = inside ? v : ((unit & (int)(lane == s) & (int)(lane < nbk)) ? T(1) : T(0));
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int s = wave + u * WAVES;
+        const bool in_blk = lane < nbk && s < nbk;
+        int r = a.etrans ? s : lane, c = a.etrans ? lane : s;
+        if (in_blk && !e_lower) { r = nbk - 1 - r; c = nbk - 1 - c; }
+        e_cols[c * NB + r] = row[u];
+    }
+    __syncthreads();
+    if (q0 >= a.nrhs) return;
+
+    T acc[RHS_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < RHS_PER_WAVE; ++j) {
+        x[j] = lane < nbk ? x[j] : T(0);
+        acc[j] = T(0);
+    }
+    T e = e_cols[lane];
+#pragma unroll 1
+    for (int c = 0; c < nbk; ++c) {
+        const T e_next = e_cols[(c + 1 < NB ? c + 1 : c) * NB + lane];
+#pragma unroll
+        for (int j = 0; j < RHS_PER_WAVE; ++j) acc[j] += e * lane_value(x[j], c);
+        e = e_next;
+    }
+    if (lane < nbk) {
+#pragma unroll
+        for (int j = 0; j < RHS_PER_WAVE; ++j)
+            if (q0 + j < a.nrhs) xp[(int64_t)(q0 + j) * qs] = a.alpha * acc[j];
+    }
+}
+
 // B := alpha * B (alpha == 0 stores zeros without reading)
 template <typename T> __global__ void __launch_bounds__(256) scale_b_kernel(T *B, int64_t ldb, int m, int n, T alpha) {
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -151,17 +216,19 @@ template <> int real_gemm<float>(char ta, char tb, int64_t m, int64_t n, int64_t
     return xgemm_sgemm(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
 }
 
-template <typename T> struct Solve {
+template <typename T> struct Tri {
     bool left, stored_lower, trans, unit;
     const T *A;
     int64_t lda;
     T *B;
     int64_t ldb, m, n;
     void *stream;
+    bool product;   // false: solve; true: B := alpha op(T) B
+    T alpha;        // product only
 
-    // E = op(T) for side L, op(T)^T for side R; the solve runs first-block-first when E is lower
+    // E = op(T) for side L, op(T)^T for side R
     bool etrans() const { return trans != !left; }
-    bool forward() const { return stored_lower != etrans(); }
+    bool e_lower() const { return stored_lower != etrans(); }
 
     int block(int64_t off, int64_t dim) const {
         BlockArgs<T> a;
@@ -175,44 +242,52 @@ template <typename T> struct Solve {
         a.etrans = etrans() ? 1 : 0;
         a.stored_lower = stored_lower ? 1 : 0;
         a.unit = unit ? 1 : 0;
+        a.alpha = alpha;
         constexpr int PER_WG = RHS_PER_WAVE * WAVES;
-        hipLaunchKernelGGL(trsm_block_kernel<T>, dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(64 * WAVES), 0,
-                           static_cast<hipStream_t>(stream), a);
+        const dim3 grid((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), blk(64 * WAVES);
+        if (product) hipLaunchKernelGGL(trmm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
+        else hipLaunchKernelGGL(trsm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
         return (int)hipGetLastError();
+    }
+
+    // part `to` of B += coef * (off-diagonal block of op(T)) applied to part `from`; parts are the
+    // rows (side L) or columns (side R) [off, off + n1) = 0 and [off + n1, off + n1 + n2) = 1
+    int couple(int64_t off, int64_t n1, int64_t n2, int from, T coef) const {
+        // the off-diagonal block of the stored triangle: T21 (n2 x n1) or T12 (n1 x n2)
+        const T *blk = stored_lower ? A + (off + n1) + off * lda : A + off + (off + n1) * lda;
+        const char tc = trans ? 'T' : 'N';
+        const int64_t o[2] = {off, off + n1}, len[2] = {n1, n2};
+        const int to = 1 - from;
+        if (left)
+            return real_gemm<T>(tc, 'N', len[to], n, len[from], coef, blk, lda, B + o[from], ldb, T(1), B + o[to], ldb,
+                                stream);
+        return real_gemm<T>('N', tc, m, len[to], len[from], coef, B + o[from] * ldb, ldb, blk, lda, T(1),
+                            B + o[to] * ldb, ldb, stream);
     }
 
     // rows/columns [off, off + dim) of the triangular matrix against the matching part of B
     int run(int64_t off, int64_t dim) const {
         if (dim <= NB) return block(off, dim);
         const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1;
-        // the off-diagonal block of the stored triangle: T21 (n2 x n1) or T12 (n1 x n2)
-        const T *blk = stored_lower ? A + (off + n1) + off * lda : A + off + (off + n1) * lda;
-        const char tc = trans ? 'T' : 'N';
         int rc;
-        if (forward()) {
-            if ((rc = run(off, n1))) return rc;
-            if (left)   // B2 -= op(T)21 X1
-                rc = real_gemm<T>(tc, 'N', n2, n, n1, T(-1), blk, lda, B + off, ldb, T(1), B + off + n1, ldb, stream);
-            else        // B2 -= X1 op(T)12
-                rc = real_gemm<T>('N', tc, m, n2, n1, T(-1), B + off * ldb, ldb, blk, lda, T(1), B + (off + n1) * ldb,
-                                  ldb, stream);
-            if (rc) return rc;
-            return run(off + n1, n2);
+        if (!product) {
+            // E lower: x1 = E11^-1 b1;  b2 -= E21 x1;  x2 = E22^-1 b2.   E upper: the other way round.
+            const int head = e_lower() ? 0 : 1;
+            if ((rc = head == 0 ? run(off, n1) : run(off + n1, n2))) return rc;
+            if ((rc = couple(off, n1, n2, head, T(-1)))) return rc;
+            return head == 0 ? run(off + n1, n2) : run(off, n1);
         }
-        if ((rc = run(off + n1, n2))) return rc;
-        if (left)       // B1 -= op(T)12 X2
-            rc = real_gemm<T>(tc, 'N', n1, n, n2, T(-1), blk, lda, B + off + n1, ldb, T(1), B + off, ldb, stream);
-        else            // B1 -= X2 op(T)21
-            rc = real_gemm<T>('N', tc, m, n1, n2, T(-1), B + (off + n1) * ldb, ldb, blk, lda, T(1), B + off * ldb, ldb,
-                              stream);
-        if (rc) return rc;
-        return run(off, n1);
+        // E lower: b2 := a E22 b2;  b2 += a E21 b1 (b1 still the input);  b1 := a E11 b1.   E upper: the other way round.
+        const int head = e_lower() ? 1 : 0;
+        if ((rc = head == 0 ? run(off, n1) : run(off + n1, n2))) return rc;
+        if ((rc = couple(off, n1, n2, 1 - head, alpha))) return rc;
+        return head == 0 ? run(off + n1, n2) : run(off, n1);
     }
 };
 
 template <typename T>
-int trsm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n, T alpha, const T *A, int64_t lda,
-              T *B, int64_t ldb, void *stream) {
+int check_tri_args(char side, char uplo, char transa, char diag, int64_t m, int64_t n, T alpha, const T *A, int64_t lda,
+                   const T *B, int64_t ldb) {
     const bool left = (side == 'L' || side == 'l'), right = (side == 'R' || side == 'r');
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
     const bool unit = (diag == 'U' || diag == 'u'), nonunit = (diag == 'N' || diag == 'n');
@@ -227,21 +302,57 @@ int trsm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n
     if (lda < max64(1, left ? m : n)) return -9;
     if (m > 0 && n > 0 && !B) return -10;
     if (ldb < max64(1, m)) return -11;
+    return 0;
+}
+
+template <typename T> int scale_b(T *B, int64_t ldb, int64_t m, int64_t n, T alpha, void *stream) {
+    const dim3 grid((unsigned)((m + 255) / 256), (unsigned)(n < 1024 ? n : 1024));
+    hipLaunchKernelGGL(scale_b_kernel<T>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), B, ldb, (int)m, (int)n, alpha);
+    return (int)hipGetLastError();
+}
+
+template <typename T>
+int trsm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n, T alpha, const T *A, int64_t lda,
+              T *B, int64_t ldb, void *stream) {
+    const int info = check_tri_args<T>(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb);
+    if (info) return info;
     if (m == 0 || n == 0) return 0;
     if (alpha != T(1)) {
-        const dim3 grid((unsigned)((m + 255) / 256), (unsigned)(n < 1024 ? n : 1024));
-        hipLaunchKernelGGL(scale_b_kernel<T>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), B, ldb, (int)m, (int)n,
-                           alpha);
-        const int rc = (int)hipGetLastError();
+        const int rc = scale_b<T>(B, ldb, m, n, alpha, stream);
         if (rc || alpha == T(0)) return rc;
     }
-    Solve<T> s{left, lower, is_t(transa), unit, A, lda, B, ldb, m, n, stream};
+    const bool left = (side == 'L' || side == 'l');
+    Tri<T> s{left, uplo == 'L' || uplo == 'l', is_t(transa), diag == 'U' || diag == 'u', A, lda, B, ldb, m, n, stream,
+             false, T(1)};
+    return s.run(0, left ? m : n);
+}
+
+template <typename T>
+int trmm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n, T alpha, const T *A, int64_t lda,
+              T *B, int64_t ldb, void *stream) {
+    const int info = check_tri_args<T>(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb);
+    if (info) return info;
+    if (m == 0 || n == 0) return 0;
+    if (alpha == T(0)) return scale_b<T>(B, ldb, m, n, alpha, stream);
+    const bool left = (side == 'L' || side == 'l');
+    Tri<T> s{left, uplo == 'L' || uplo == 'l', is_t(transa), diag == 'U' || diag == 'u', A, lda, B, ldb, m, n, stream,
+             true, alpha};
     return s.run(0, left ? m : n);
 }
 
 }  // namespace
 
 extern "C" {
+
+int xgemm_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha, const double *A,
+                int64_t lda, double *B, int64_t ldb, void *stream) {
+    return trmm_impl<double>(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream);
+}
+
+int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, float alpha, const float *A,
+                int64_t lda, float *B, int64_t ldb, void *stream) {
+    return trmm_impl<float>(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream);
+}
 
 int xgemm_dtrsm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha, const double *A,
                 int64_t lda, double *B, int64_t ldb, void *stream) {

@@ -19,7 +19,7 @@ EXPORTS = [
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
-    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm",
 ]
 
 
@@ -67,9 +67,10 @@ def lib():
         f.restype = ctypes.c_int
         f.argtypes = [_c, _c, _i64, _i64, sc, _p, _i64, sc, _p, _i64, _p, ctypes.c_size_t, _p]
     for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
-        f = getattr(L, f"xgemm_{pre}trsm")
-        f.restype = ctypes.c_int
-        f.argtypes = [_c, _c, _c, _c, _i64, _i64, sc, _p, _i64, _p, _i64, _p]
+        for op in ("trsm", "trmm"):
+            f = getattr(L, f"xgemm_{pre}{op}")
+            f.restype = ctypes.c_int
+            f.argtypes = [_c, _c, _c, _c, _i64, _i64, sc, _p, _i64, _p, _i64, _p]
     L.xgemm_workspace_bytes.restype = ctypes.c_size_t
     L.xgemm_workspace_bytes.argtypes = []
     L.xgemm_workspace_init.restype = ctypes.c_int
@@ -158,6 +159,16 @@ def xgemm_dtrsm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=No
 
 def xgemm_strsm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=None) -> int:
     return int(lib().xgemm_strsm(_ch(side), _ch(uplo), _ch(transa), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
+                                 _stream(stream)))
+
+
+def xgemm_dtrmm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=None) -> int:
+    return int(lib().xgemm_dtrmm(_ch(side), _ch(uplo), _ch(transa), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
+                                 _stream(stream)))
+
+
+def xgemm_strmm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=None) -> int:
+    return int(lib().xgemm_strmm(_ch(side), _ch(uplo), _ch(transa), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
                                  _stream(stream)))
 
 

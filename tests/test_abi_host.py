@@ -104,7 +104,7 @@ def test_zgemm_illegal_arguments_and_worksize():
     assert z("N", "N", 0, 2, 2, (1, 1), None, None, 1, None, None, 2, (0, 0), None, None, 1) == 0
 
 
-@pytest.mark.parametrize("fn", ["xgemm_dtrsm", "xgemm_strsm"])
+@pytest.mark.parametrize("fn", ["xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm"])
 def test_trsm_illegal_arguments_and_quick_returns(fn):
     f = getattr(xg, fn)
     P = 4096
