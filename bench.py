@@ -298,6 +298,26 @@ def sweep(torch, np, xg, si, args):
                       "GFLOP/s": round(flops / dev / 1e9, 1),
                       "frac_of_mfma_peak": round(flops / dev / (PEAK_TFLOPS['f64'] * 1e12), 4)}),
           file=sys.stderr, flush=True)
+    del planes
+    # the same product on interleaved storage (split into planes, real GEMMs, merge), 4m and 3m;
+    # both counted as 8 m n k flops
+    zs = [torch.from_numpy(si.uniform(rng, 2 * nsz, nsz)).cuda() for _ in range(3)]
+    for method, name in ((0, "4m"), (1, "3m")):
+        lw = xg.xgemm_zgemm_workbytes(nsz, nsz, nsz, method)
+        zwork = torch.empty(lw, dtype=torch.uint8, device="cuda")
+
+        def zistep():
+            rc = xg.xgemm_zgemm("N", "N", nsz, nsz, nsz, (1.0, 0.0), zs[0], nsz, zs[1], nsz, (0.0, 0.0), zs[2], nsz,
+                                method, zwork, lw)
+            if rc:
+                raise RuntimeError(rc)
+
+        wall, dev = time_calls(torch, zistep, 10, 5)
+        print(json.dumps({"shape": f"zgemm interleaved ({name}) NN {nsz}^3", "ms": round(dev * 1e3, 4),
+                          "GFLOP/s(8mnk)": round(flops / dev / 1e9, 1),
+                          "frac_of_mfma_peak(8mnk)": round(flops / dev / (PEAK_TFLOPS['f64'] * 1e12), 4)}),
+              file=sys.stderr, flush=True)
+        del zwork
 
 
 if __name__ == "__main__":

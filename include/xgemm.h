@@ -174,6 +174,33 @@ int xgemm_zgemm_split(char transa, char transb, int64_t m, int64_t n, int64_t k,
  * beta are real, else 2*m*n).  Host-only; touches no device. */
 size_t xgemm_zgemm_worksize(int64_t m, int64_t n, const double alpha[2], const double beta[2]);
 
+/*
+ * Double-precision complex GEMM on interleaved storage (the BLAS layout: element
+ * (i, j) of X is the pair X[2*(i + j*ldx)], X[2*(i + j*ldx) + 1]; leading
+ * dimensions count complex elements; A, B, C 16-byte aligned), built from the
+ * real kernel:
+ *     C := alpha op(A) op(B) + beta C,   op(X) = X, X^T or X^H (trans N, T, C).
+ * The operands are taken apart into real planes in `work`, real GEMMs produce
+ * the planes of the product, and one pass merges alpha * product + beta * C
+ * into C.
+ *   method 0 ("4m"): four real products, Pr = Ar Br - Ai Bi, Pi = Ar Bi + Ai Br;
+ *            each plane within 8 k u of its own sum of magnitudes.
+ *   method 1 ("3m"): three real products, T1 = Ar Br, T2 = Ai Bi,
+ *            T3 = (Ar + Ai)(Br + Bi), Pr = T1 - T2, Pi = T3 - T1 - T2: a quarter
+ *            fewer flops, but the imaginary part is only accurate relative to
+ *            (|Ar| + |Ai|)(|Br| + |Bi|), i.e. to the magnitudes of both planes.
+ * work: device buffer, 16-byte aligned, lwork >= xgemm_zgemm_workbytes(m, n, k,
+ * method) bytes (2 or 3 planes each of A, B and the product); contents undefined
+ * afterwards; not needed when alpha == 0 or k == 0.  alpha, beta: host {re, im}.
+ * Illegal-argument numbering: transa 1, transb 2, m 3, n 4, k 5, alpha 6, A 7,
+ * lda 8, B 9, ldb 10, beta 11, C 12, ldc 13, method 14, work 15, lwork 16.
+ * flops counted as 8 m n k for both methods.
+ */
+int xgemm_zgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, const double alpha[2],
+                const double *A, int64_t lda, const double *B, int64_t ldb, const double beta[2],
+                double *C, int64_t ldc, int method, void *work, size_t lwork, void *stream);
+size_t xgemm_zgemm_workbytes(int64_t m, int64_t n, int64_t k, int method);
+
 /* Library version string (static storage). */
 const char *xgemm_version(void);
 

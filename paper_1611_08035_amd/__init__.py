@@ -29,6 +29,8 @@ from .xgemm import (  # noqa: F401
     xgemm_last_split,
     xgemm_plan,
     xgemm_zgemm_split,
+    xgemm_zgemm,
+    xgemm_zgemm_workbytes,
     xgemm_zgemm_worksize,
     xgemm_version,
     xgemm_last_kernel_name,

@@ -19,7 +19,7 @@ EXPORTS = [
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
-    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_zgemm", "xgemm_zgemm_workbytes",
 ]
 
 
@@ -71,6 +71,11 @@ def lib():
             f = getattr(L, f"xgemm_{pre}{op}")
             f.restype = ctypes.c_int
             f.argtypes = [_c, _c, _c, _c, _i64, _i64, sc, _p, _i64, _p, _i64, _p]
+    L.xgemm_zgemm.restype = ctypes.c_int
+    L.xgemm_zgemm.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _i64, _p, _i64, _p, _p, _i64, ctypes.c_int, _p,
+                              ctypes.c_size_t, _p]
+    L.xgemm_zgemm_workbytes.restype = ctypes.c_size_t
+    L.xgemm_zgemm_workbytes.argtypes = [_i64, _i64, _i64, ctypes.c_int]
     L.xgemm_workspace_bytes.restype = ctypes.c_size_t
     L.xgemm_workspace_bytes.argtypes = []
     L.xgemm_workspace_init.restype = ctypes.c_int
@@ -227,6 +232,17 @@ def xgemm_zgemm_split(transa, transb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, 
     return int(lib().xgemm_zgemm_split(_ch(transa), _ch(transb), m, n, k, al, _ptr(Ar), _ptr(Ai), lda,
                                        _ptr(Br), _ptr(Bi), ldb, be, _ptr(Cr), _ptr(Ci), ldc,
                                        _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_zgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, method=0, work=None, lwork=0,
+                stream=None) -> int:
+    al, be = _pair(alpha), _pair(beta)
+    return int(lib().xgemm_zgemm(_ch(transa), _ch(transb), m, n, k, al, _ptr(A), lda, _ptr(B), ldb, be, _ptr(C), ldc,
+                                 int(method), _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_zgemm_workbytes(m, n, k, method=0) -> int:
+    return int(lib().xgemm_zgemm_workbytes(m, n, k, int(method)))
 
 
 def xgemm_zgemm_worksize(m, n, alpha, beta) -> int:

@@ -174,6 +174,35 @@ def test_tile_order_xcd_runs_are_contiguous():
     assert xg.xgemm_tile_map(0, 8, 8, 0, 8)[0] == -4
 
 
+def test_interleaved_zgemm_illegal_arguments_and_work_size():
+    P = 4096
+    z = lambda *a, **kw: xg.xgemm_zgemm(*a, stream=0, **kw)
+    assert xg.xgemm_zgemm_workbytes(5, 7, 3, 0) == 8 * 2 * (15 + 21 + 35)
+    assert xg.xgemm_zgemm_workbytes(5, 7, 3, 1) == 8 * 3 * (15 + 21 + 35)
+    assert xg.xgemm_zgemm_workbytes(0, 7, 3, 0) == 0
+    big = 1 << 20
+    ok = dict(work=P, lwork=big)
+    assert z("X", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, **ok) == -1
+    assert z("N", "X", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, **ok) == -2
+    assert z("N", "N", -1, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, **ok) == -3
+    assert z("N", "N", 2, -1, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, **ok) == -4
+    assert z("N", "N", 2, 2, -1, (1, 0), P, 2, P, 2, (0, 0), P, 2, **ok) == -5
+    assert z("N", "N", 2, 2, 2, None, P, 2, P, 2, (0, 0), P, 2, **ok) == -6
+    assert z("N", "N", 2, 2, 2, (1, 0), None, 2, P, 2, (0, 0), P, 2, **ok) == -7
+    assert z("N", "N", 2, 2, 2, (1, 0), P + 8, 2, P, 2, (0, 0), P, 2, **ok) == -7
+    assert z("C", "N", 2, 2, 3, (1, 0), P, 2, P, 3, (0, 0), P, 2, **ok) == -8
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, None, 2, (0, 0), P, 2, **ok) == -9
+    assert z("N", "T", 2, 3, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, **ok) == -10
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, None, P, 2, **ok) == -11
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), None, 2, **ok) == -12
+    assert z("N", "N", 3, 2, 2, (1, 0), P, 3, P, 2, (0, 0), P, 2, **ok) == -13
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, method=2, **ok) == -14
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, work=None, lwork=big) == -15
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, work=P, lwork=8 * 2 * 12 - 1) == -16
+    assert z("N", "N", 0, 2, 2, (1, 0), None, 1, None, 2, (0, 0), None, 1) == 0
+    assert z("N", "N", 2, 2, 0, (1, 0), None, 2, None, 1, (1, 0), P, 2) == 0
+
+
 def test_missing_library_raises(monkeypatch):
     import paper_1611_08035_amd.xgemm as mod
     monkeypatch.setattr(mod, "_lib", None)
