@@ -96,6 +96,14 @@ def _declare(L):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char] * 4 + [_i64, _i64, sc, _p, _i64, _p, _i64, _p, _p]
+    for name in ("ref_dpotrf", "ref_spotrf"):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, _i64, _p, _i64]
+    for name in ("ref_dpotrf_resid", "ref_spotrf_resid"):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.c_char, _i64, _p, _i64, _p, _i64, _i64, _p, _p, _p, _p]
     L.ref_zgemm_split_ext.restype = ctypes.c_int
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
@@ -251,6 +259,30 @@ def trmm_work(side, uplo, trans, diag, m, n, alpha, A, lda, B, ldb) -> int:
     if info == 0 and m > 0 and n > 0:
         B[:, :m] = Out
     return info
+
+
+def potrf(uplo, n, A, lda) -> int:
+    """In-place working-precision Cholesky factorisation of the `uplo` triangle; returns LAPACK's info."""
+    pre, _ = _names(A.dtype if A is not None else np.float64)
+    return int(getattr(lib(), f"ref_{pre}potrf")(_ch(uplo), n, _ptr(A), lda))
+
+
+def potrf_resid(uplo, n, A0, lda, F, ldf, I=None, J=None):
+    """Extended-precision residual A0 - L L^T and magnitude |L||L|^T of a candidate factor on the
+    triangle: dense (n, n) arrays in the (col, row) layout, or 1-d arrays at the entries (I, J)."""
+    pre, wide = _names(A0.dtype)
+    f = getattr(lib(), f"ref_{pre}potrf_resid")
+    if I is None:
+        R = np.zeros((max(n, 0), max(n, 0)), dtype=wide)
+        G = np.zeros_like(R)
+        info = int(f(_ch(uplo), n, _ptr(A0), lda, _ptr(F), ldf, -1, None, None, _ptr(R), _ptr(G)))
+        return info, R, G
+    I = np.ascontiguousarray(I, dtype=np.int64)
+    J = np.ascontiguousarray(J, dtype=np.int64)
+    R = np.zeros(I.size, dtype=wide)
+    G = np.zeros(I.size, dtype=wide)
+    info = int(f(_ch(uplo), n, _ptr(A0), lda, _ptr(F), ldf, I.size, _ptr(I), _ptr(J), _ptr(R), _ptr(G)))
+    return info, R, G
 
 
 def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc):

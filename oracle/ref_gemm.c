@@ -557,6 +557,92 @@ DEFINE_REF_TRMM(ref_strmm_ext, float, double, fabs)
 DEFINE_REF_TRMM(ref_dtrmm_wp, double, double, fabs)
 DEFINE_REF_TRMM(ref_strmm_wp, float, float, fabsf)
 
+
+/* ------------------------------------------------------------------ */
+/* Cholesky factorisation (a LAPACK-level driver on top of the level-3  */
+/* routines; the paper's motivation for a fast GEMM, Sec. 1):           */
+/*   uplo 'L':  A = L L^T,  L lower triangular, overwrites the lower    */
+/*   uplo 'U':  A = U^T U,  U upper triangular, overwrites the upper    */
+/* triangle of the symmetric positive definite A; the other triangle is */
+/* neither read nor written.  Column by column in the natural order:    */
+/*   l_jj = sqrt(a_jj - sum_{p<j} l_jp^2),                              */
+/*   l_ij = (a_ij - sum_{p<j} l_ip l_jp) / l_jj   (i > j).              */
+/* Returns 0, -i for an illegal argument (uplo 1, n 2, A 3, lda 4), or  */
+/* j > 0 if the leading minor of order j is not positive definite (the  */
+/* factorisation stops there, as in LAPACK).                            */
+/* ------------------------------------------------------------------ */
+#define CH(i, j) (A[lower ? (i) + (j) * lda : (j) + (i) * lda])   /* element (i,j), i >= j, of L = U^T */
+
+#define DEFINE_REF_POTRF(NAME, T, SQRT)                                        \
+int NAME(char uplo, i64 n, T *A, i64 lda)                                      \
+{                                                                              \
+    const int lower = (uplo == 'L' || uplo == 'l');                            \
+    if (!lower && uplo != 'U' && uplo != 'u') return -1;                       \
+    if (n < 0) return -2;                                                      \
+    if (n > 0 && A == NULL) return -3;                                         \
+    if (lda < max64(1, n)) return -4;                                          \
+    for (i64 j = 0; j < n; ++j) {                                              \
+        T d = CH(j, j);                                                        \
+        for (i64 p = 0; p < j; ++p) { T sq = CH(j, p) * CH(j, p); d = d - sq; }\
+        if (!(d > (T)0)) return (int)(j + 1);                                  \
+        d = SQRT(d);                                                           \
+        CH(j, j) = d;                                                          \
+        _Pragma("omp parallel for schedule(static) if (n - j > 256)")          \
+        for (i64 i = j + 1; i < n; ++i) {                                      \
+            T acc = CH(i, j);                                                  \
+            for (i64 p = 0; p < j; ++p) { T prod = CH(i, p) * CH(j, p); acc = acc - prod; } \
+            CH(i, j) = acc / d;                                                \
+        }                                                                      \
+    }                                                                          \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_POTRF(ref_dpotrf, double, sqrt)
+DEFINE_REF_POTRF(ref_spotrf, float, sqrtf)
+
+/* Residual of a candidate factor F against the original A0, on the `uplo`
+ * triangle, in extended precision: R = A0 - L L^T, G = |L| |L|^T with L the
+ * lower-triangular factor (F itself, or F^T for uplo 'U').  Either dense n x n
+ * (ns < 0; entries outside the triangle are zero) or at ns sampled entries
+ * (I[s], J[s]) of the triangle. */
+#define FCH(i, j) (F[lower ? (i) + (j) * ldf : (j) + (i) * ldf])
+
+#define DEFINE_REF_POTRF_RESID(NAME, T, W, WABS)                               \
+int NAME(char uplo, i64 n, const T *A0, i64 lda, const T *F, i64 ldf,          \
+         i64 ns, const i64 *I, const i64 *J, W *R, W *G)                       \
+{                                                                              \
+    const int lower = (uplo == 'L' || uplo == 'l');                            \
+    if (!lower && uplo != 'U' && uplo != 'u') return -1;                       \
+    if (n < 0) return -2;                                                      \
+    if (n > 0 && A0 == NULL) return -3;                                        \
+    if (lda < max64(1, n)) return -4;                                          \
+    if (n > 0 && F == NULL) return -5;                                         \
+    if (ldf < max64(1, n)) return -6;                                          \
+    const i64 cnt = ns < 0 ? n * n : ns;                                       \
+    for (i64 s = 0; s < (ns < 0 ? 0 : ns); ++s) {                              \
+        if (I[s] < 0 || I[s] >= n || J[s] < 0 || J[s] >= n) return -8;         \
+        if (lower ? I[s] < J[s] : I[s] > J[s]) return -8;                      \
+    }                                                                          \
+    _Pragma("omp parallel for schedule(dynamic, 64)")                          \
+    for (i64 s = 0; s < cnt; ++s) {                                            \
+        const i64 i = ns < 0 ? s % n : I[s], j = ns < 0 ? s / n : J[s];        \
+        if (lower ? i < j : i > j) { R[s] = 0; G[s] = 0; continue; }           \
+        const i64 hi = i > j ? i : j, lo = i > j ? j : i;   /* (L L^T)(hi, lo) = sum_{p <= lo} */ \
+        W acc = (W)A0[i + j * lda], mag = 0;                                   \
+        for (i64 p = 0; p <= lo; ++p) {                                        \
+            W prod = (W)FCH(hi, p) * (W)FCH(lo, p);                            \
+            acc -= prod;                                                       \
+            mag += WABS(prod);                                                 \
+        }                                                                      \
+        R[s] = acc;                                                            \
+        G[s] = mag;                                                            \
+    }                                                                          \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_POTRF_RESID(ref_dpotrf_resid, double, long double, fabsl)
+DEFINE_REF_POTRF_RESID(ref_spotrf_resid, float, double, fabs)
+
 /* ------------------------------------------------------------------ */
 /* Complex GEMM on split real/imaginary planes.                         */
 /*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/

@@ -104,6 +104,18 @@ def int_triangular(rng, n, ld=None, dtype=np.float64, uplo="L", unit_diag=False,
     return _mask_triangle(X, n, uplo, unit_diag, sentinel)
 
 
+def spd(rng, n, ld=None, dtype=np.float64, uplo="L", sentinel=np.nan):
+    """Symmetric positive definite matrix given by one triangle: off-diagonal
+    entries uniform in [-1, 1], diagonal n + uniform[0, 1] (strictly diagonally
+    dominant, hence positive definite; condition number of order one).  The other
+    triangle and the padding hold the sentinel."""
+    ld = n if ld is None else ld
+    X = _alloc(n, n, ld, dtype, sentinel)
+    X[:, :n] = rng.uniform(-1.0, 1.0, size=(n, n)).astype(dtype)
+    X[np.arange(n), np.arange(n)] = (n + rng.uniform(0.0, 1.0, size=n)).astype(dtype)
+    return _mask_triangle(X, n, uplo, False, sentinel)
+
+
 def rng_for(config: int, index: int = 0):
     return np.random.Generator(np.random.PCG64(seed_for(config, index)))
 
