@@ -113,6 +113,25 @@ int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t
                 const float *A, int64_t lda, float *B, int64_t ldb, void *stream);
 
 /*
+ * Cholesky factorisation on the level-3 routines (a LAPACK-level driver of the
+ * kind the paper names as the reason for a fast GEMM, Sec. 1):
+ *     uplo L:  A = L L^T, the lower triangle of A is overwritten by L
+ *     uplo U:  A = U^T U, the upper triangle of A is overwritten by U
+ * A is n x n symmetric positive definite, given by its `uplo` triangle; the
+ * other triangle is neither read nor written.  Recursive: factor the leading
+ * half, solve for the off-diagonal block (xgemm_*trsm), update the trailing
+ * half (xgemm_*syrk), factor it; diagonal blocks of order <= 64 are factored by
+ * one workgroup.  `info` is a DEVICE int written on the stream: 0 on success,
+ * j > 0 if the leading minor of order j is not positive definite (the factor is
+ * then undefined from column j on, and only the first failure is recorded).
+ * The computed factor satisfies |A - L L^T| <= 4 n u |L| |L|^T on the triangle.
+ * Returns 0, -i for an illegal argument (uplo 1, n 2, A 3, lda 4, info 5) or a
+ * hipError_t.  flops: n^3 / 3.
+ */
+int xgemm_dpotrf(char uplo, int64_t n, double *A, int64_t lda, int *info, void *stream);
+int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *stream);
+
+/*
  * GEMM and SYRK with a caller-owned workspace, which lets the library
  * cut the tiles of the last, partly filled round of workgroups along K (the k_c
  * loop of Fig. 1 moved across workgroups for those tiles only): each piece

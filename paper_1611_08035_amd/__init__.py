@@ -18,6 +18,8 @@ from .xgemm import (  # noqa: F401
     xgemm_strsm,
     xgemm_dtrmm,
     xgemm_strmm,
+    xgemm_dpotrf,
+    xgemm_spotrf,
     xgemm_tile_map,
     xgemm_workspace_bytes,
     xgemm_workspace_init,

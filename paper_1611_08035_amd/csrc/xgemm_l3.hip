@@ -340,9 +340,109 @@ int trmm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n
     return s.run(0, left ? m : n);
 }
 
+// Cholesky factorisation of a diagonal block of order nbk <= NB, in LDS, one
+// workgroup: column by column,  l_cc = sqrt(a_cc),  l_rc = a_rc / l_cc,
+// a_rj -= l_rc l_jc for the columns j > c still to come.  An upper-stored block
+// (A = U^T U) is the lower problem on the transposed block.  A pivot that is
+// not positive stops the block and is reported: *info receives base + c + 1
+// unless an earlier failure is already recorded there.
+template <typename T>
+__global__ void __launch_bounds__(256) potf2_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
+    __shared__ T a[NB][NB + 1];            // a[r][c], r >= c
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        const int r = idx % NB, c = idx / NB;          // consecutive threads: consecutive stored rows
+        // stored element (r, c) of the referenced triangle goes to a[max][min]
+        const bool inside = r < nbk && c < nbk && (lower ? r >= c : r <= c);
+        if (inside) {
+            const T v = A[r + (int64_t)c * lda];
+            if (lower) a[r][c] = v; else a[c][r] = v;
+        }
+    }
+    __syncthreads();
+    for (int c = 0; c < nbk; ++c) {
+        const T d = a[c][c];
+        if (!(d > T(0))) {                              // the same value in every thread: uniform exit
+            if (tid == 0 && *info == 0) *info = base + c + 1;
+            break;
+        }
+        const T s = sqrt(d);
+        __syncthreads();                                // everybody has read the pivot
+        if (tid == c) a[c][c] = s;
+        if (tid > c && tid < nbk) a[tid][c] = a[tid][c] / s;
+        __syncthreads();
+        for (int idx = tid; idx < NB * NB; idx += 256) {
+            const int r = idx % NB, j = idx / NB;
+            if (j > c && r >= j && r < nbk) a[r][j] -= a[r][c] * a[j][c];
+        }
+        __syncthreads();
+    }
+    for (int idx = tid; idx < NB * NB; idx += 256) {
+        const int r = idx % NB, c = idx / NB;
+        const bool inside = r < nbk && c < nbk && (lower ? r >= c : r <= c);
+        if (inside) A[r + (int64_t)c * lda] = lower ? a[r][c] : a[c][r];
+    }
+}
+
+__global__ void clear_info_kernel(int *info) { *info = 0; }
+
+int syrk_call(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda, double beta,
+              double *C, int64_t ldc, void *stream) {
+    return xgemm_dsyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream);
+}
+int syrk_call(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda, float beta,
+              float *C, int64_t ldc, void *stream) {
+    return xgemm_ssyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, stream);
+}
+
+// A11 = L11 L11^T;  A21 := A21 L11^-T;  A22 -= A21 A21^T;  then the same on A22
+// (upper:  A11 = U11^T U11;  A12 := U11^-T A12;  A22 -= A12^T A12).
+template <typename T> int potrf_run(bool lower, int64_t off, int64_t dim, T *A, int64_t lda, int *info, void *stream) {
+    T *D = A + off + off * lda;
+    if (dim <= NB) {
+        hipLaunchKernelGGL(potf2_kernel<T>, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), D, lda, (int)dim,
+                           lower ? 1 : 0, info, (int)off);
+        return (int)hipGetLastError();
+    }
+    const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1;
+    int rc;
+    if ((rc = potrf_run<T>(lower, off, n1, A, lda, info, stream))) return rc;
+    T *P = lower ? D + n1 : D + n1 * lda;        // A21 (n2 x n1) or A12 (n1 x n2)
+    T *D2 = D + n1 + n1 * lda;
+    if (lower) {
+        if ((rc = trsm_impl<T>('R', 'L', 'T', 'N', n2, n1, T(1), D, lda, P, lda, stream))) return rc;
+        if ((rc = syrk_call('L', 'N', n2, n1, T(-1), P, lda, T(1), D2, lda, stream))) return rc;
+    } else {
+        if ((rc = trsm_impl<T>('L', 'U', 'T', 'N', n1, n2, T(1), D, lda, P, lda, stream))) return rc;
+        if ((rc = syrk_call('U', 'T', n2, n1, T(-1), P, lda, T(1), D2, lda, stream))) return rc;
+    }
+    return potrf_run<T>(lower, off + n1, n2, A, lda, info, stream);
+}
+
+template <typename T> int potrf_impl(char uplo, int64_t n, T *A, int64_t lda, int *info, void *stream) {
+    const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
+    if (!lower && !upper) return -1;
+    if (n < 0 || n > DIM_MAX) return -2;
+    if (n > 0 && !A) return -3;
+    if (lda < max64(1, n)) return -4;
+    if (!info) return -5;
+    hipLaunchKernelGGL(clear_info_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), info);
+    const int rc = (int)hipGetLastError();
+    if (rc || n == 0) return rc;
+    return potrf_run<T>(lower, 0, n, A, lda, info, stream);
+}
+
 }  // namespace
 
 extern "C" {
+
+int xgemm_dpotrf(char uplo, int64_t n, double *A, int64_t lda, int *info, void *stream) {
+    return potrf_impl<double>(uplo, n, A, lda, info, stream);
+}
+
+int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *stream) {
+    return potrf_impl<float>(uplo, n, A, lda, info, stream);
+}
 
 int xgemm_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha, const double *A,
                 int64_t lda, double *B, int64_t ldb, void *stream) {

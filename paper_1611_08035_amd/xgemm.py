@@ -19,7 +19,7 @@ EXPORTS = [
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
-    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_zgemm", "xgemm_zgemm_workbytes",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf",
 ]
 
 
@@ -71,6 +71,10 @@ def lib():
             f = getattr(L, f"xgemm_{pre}{op}")
             f.restype = ctypes.c_int
             f.argtypes = [_c, _c, _c, _c, _i64, _i64, sc, _p, _i64, _p, _i64, _p]
+    for pre in "ds":
+        f = getattr(L, f"xgemm_{pre}potrf")
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _i64, _p, _i64, _p, _p]
     L.xgemm_zgemm.restype = ctypes.c_int
     L.xgemm_zgemm.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _i64, _p, _i64, _p, _p, _i64, ctypes.c_int, _p,
                               ctypes.c_size_t, _p]
@@ -175,6 +179,14 @@ def xgemm_dtrmm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=No
 def xgemm_strmm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, stream=None) -> int:
     return int(lib().xgemm_strmm(_ch(side), _ch(uplo), _ch(transa), _ch(diag), m, n, alpha, _ptr(A), lda, _ptr(B), ldb,
                                  _stream(stream)))
+
+
+def xgemm_dpotrf(uplo, n, A, lda, info, stream=None) -> int:
+    return int(lib().xgemm_dpotrf(_ch(uplo), n, _ptr(A), lda, _ptr(info), _stream(stream)))
+
+
+def xgemm_spotrf(uplo, n, A, lda, info, stream=None) -> int:
+    return int(lib().xgemm_spotrf(_ch(uplo), n, _ptr(A), lda, _ptr(info), _stream(stream)))
 
 
 def xgemm_workspace_bytes() -> int:

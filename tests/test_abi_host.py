@@ -124,6 +124,18 @@ def test_trsm_illegal_arguments_and_quick_returns(fn):
     assert g("R", "U", "T", "U", 4, 0, 1.0, None, 1, None, 4) == 0
 
 
+@pytest.mark.parametrize("fn", ["xgemm_dpotrf", "xgemm_spotrf"])
+def test_potrf_illegal_arguments(fn):
+    f = getattr(xg, fn)
+    P = 4096
+    assert f("X", 4, P, 4, P, stream=0) == -1
+    assert f("L", -1, P, 4, P, stream=0) == -2
+    assert f("L", 2 ** 31, P, 2 ** 31, P, stream=0) == -2
+    assert f("U", 4, None, 4, P, stream=0) == -3
+    assert f("U", 4, P, 3, P, stream=0) == -4
+    assert f("L", 4, P, 4, None, stream=0) == -5
+
+
 def test_workspace_routines_host_side():
     P = 4096
     assert xg.xgemm_workspace_bytes() == 8192 + (64 << 20)
