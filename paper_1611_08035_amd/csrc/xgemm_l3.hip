@@ -340,47 +340,67 @@ int trmm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n
     return s.run(0, left ? m : n);
 }
 
-// Cholesky factorisation of a diagonal block of order nbk <= NB, in LDS, one
-// workgroup: column by column,  l_cc = sqrt(a_cc),  l_rc = a_rc / l_cc,
-// a_rj -= l_rc l_jc for the columns j > c still to come.  An upper-stored block
-// (A = U^T U) is the lower problem on the transposed block.  A pivot that is
-// not positive stops the block and is reported: *info receives base + c + 1
-// unless an earlier failure is already recorded there.
+// Cholesky factorisation of a diagonal block of order nbk <= NB by one wave:
+// lane r holds row r of the not yet factored columns in registers, column c in
+// register 0.  Step c:  l_cc = sqrt(a_cc)  (lane c's value, broadcast),
+// l_rc = a_rc / l_cc, stored straight to memory; then every later column j gets
+// a_rj -= l_rc l_jc, with l_jc read back from LDS, while moving one register down
+// (reg[i] <- reg[i+1] - ...), so that registers are indexed statically inside a
+// loop over c that stays a loop.  Entries above the diagonal take part with
+// whatever they hold and are never stored.  An upper-stored block (A = U^T U) is
+// the lower problem on the transposed block.  A pivot that is not positive stops
+// the block and is reported: *info receives base + c + 1 unless an earlier
+// failure is already recorded there.
 template <typename T>
-__global__ void __launch_bounds__(256) potf2_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
-    __shared__ T a[NB][NB + 1];            // a[r][c], r >= c
-    const int tid = threadIdx.x;
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int r = idx % NB, c = idx / NB;          // consecutive threads: consecutive stored rows
-        // stored element (r, c) of the referenced triangle goes to a[max][min]
-        const bool inside = r < nbk && c < nbk && (lower ? r >= c : r <= c);
-        if (inside) {
-            const T v = A[r + (int64_t)c * lda];
-            if (lower) a[r][c] = v; else a[c][r] = v;
-        }
+__global__ void __launch_bounds__(64) potf2_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
+    const int lane = threadIdx.x;
+    // element (r, c), r >= c, of the lower problem sits at A[r + c*lda] (lower) or A[c + r*lda] (upper);
+    // lanes and columns outside the triangle re-read the block's first element and hold zero
+    const int64_t rs = lower ? 1 : lda, cs = lower ? lda : 1;
+    T a[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        const bool inside = lane < nbk && c <= lane;
+        const T v = A[inside ? lane * rs + c * cs : 0];
+        a[c] = inside ? v : T(0);
     }
-    __syncthreads();
+    // column c of L goes through LDS so that every lane can read l_jc for all j > c
+    // with one broadcast read each (constant offsets from a per-column base)
+    __shared__ T lcol[2 * NB];
+    lcol[NB + lane] = T(0);                              // read when c + 1 + i runs past the block
+#pragma unroll 1
     for (int c = 0; c < nbk; ++c) {
-        const T d = a[c][c];
-        if (!(d > T(0))) {                              // the same value in every thread: uniform exit
-            if (tid == 0 && *info == 0) *info = base + c + 1;
+        const T d = lane_value(a[0], c);
+        if (!(d > T(0))) {                               // wave-uniform
+            if (lane == 0 && *info == 0) *info = base + c + 1;
             break;
         }
         const T s = sqrt(d);
-        __syncthreads();                                // everybody has read the pivot
-        if (tid == c) a[c][c] = s;
-        if (tid > c && tid < nbk) a[tid][c] = a[tid][c] / s;
-        __syncthreads();
-        for (int idx = tid; idx < NB * NB; idx += 256) {
-            const int r = idx % NB, j = idx / NB;
-            if (j > c && r >= j && r < nbk) a[r][j] -= a[r][c] * a[j][c];
+        const T l = lane == c ? s : a[0] / s;
+        if (lane >= c && lane < nbk) A[lane * rs + c * cs] = l;
+        lcol[lane] = l;
+        __builtin_amdgcn_wave_barrier();                 // one wave: program order suffices, keep the compiler from reordering
+        const T *const lj = lcol + c + 1;
+        // the wave is alone on its SIMD: reads of one chunk of l_jc are in flight while the previous chunk is used
+        constexpr int CH = 16;
+        T buf[2][CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) buf[0][u] = lj[u];
+#pragma unroll
+        for (int i0 = 0; i0 < NB; i0 += CH) {
+            const int cur = (i0 / CH) & 1;
+            if (i0 + CH < NB) {
+#pragma unroll
+                for (int u = 0; u < CH; ++u) buf[cur ^ 1][u] = lj[i0 + CH + u];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < CH; ++u)
+                if (i0 + u + 1 < NB) a[i0 + u] = a[i0 + u + 1] - l * buf[cur][u];
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
-    }
-    for (int idx = tid; idx < NB * NB; idx += 256) {
-        const int r = idx % NB, c = idx / NB;
-        const bool inside = r < nbk && c < nbk && (lower ? r >= c : r <= c);
-        if (inside) A[r + (int64_t)c * lda] = lower ? a[r][c] : a[c][r];
+        a[NB - 1] = T(0);
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -400,7 +420,7 @@ int syrk_call(char uplo, char trans, int64_t n, int64_t k, float alpha, const fl
 template <typename T> int potrf_run(bool lower, int64_t off, int64_t dim, T *A, int64_t lda, int *info, void *stream) {
     T *D = A + off + off * lda;
     if (dim <= NB) {
-        hipLaunchKernelGGL(potf2_kernel<T>, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), D, lda, (int)dim,
+        hipLaunchKernelGGL(potf2_kernel<T>, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), D, lda, (int)dim,
                            lower ? 1 : 0, info, (int)off);
         return (int)hipGetLastError();
     }
