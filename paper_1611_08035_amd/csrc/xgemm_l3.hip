@@ -11,6 +11,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace {
 
 constexpr int NB = 64;        // order of the diagonal blocks solved by substitution
@@ -129,6 +131,132 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_k
     }
 }
 
+// The same solve for diagonal blocks of order up to WIDE = 64 * GROUPS: lane l of a
+// wave holds rows l, l + 64, ... of the 8 systems of its wave (GROUPS values per
+// system), and E' passes through LDS in panels of PANEL columns: the loads of
+// panel p + 1 are issued before panel p is used and written to LDS after it.
+// One kernel of this kind replaces the four block solves and three coupling
+// products that recursion down to order 64 would spend on a block of order 256.
+constexpr int GROUPS = 4, WIDE = 64 * GROUPS, PANEL = 16;
+constexpr int WIDE_RHS = 8;   // right-hand sides per wave: GROUPS * WIDE_RHS values per lane stay in plain vector registers
+
+template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_kernel(const BlockArgs<T> a) {
+    static_assert(64 * WAVES == WIDE && 64 % PANEL == 0, "one thread per row of a panel; panels do not straddle groups");
+    __shared__ T e_pan[PANEL * WIDE];        // E'(r, c0 + k) at [k * WIDE + r], zero on and above the diagonal
+    __shared__ T d_inv[WIDE];                // 1 / E(c, c)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int dim = a.nbk;
+    const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
+    const int lowr = a.stored_lower ? 1 : 0;
+
+    // right-hand sides q0 .. q0 + WIDE_RHS - 1 of this wave; lane holds elements lane + 64 g of each
+    const int q0 = (blockIdx.x * WAVES + wave) * WIDE_RHS;
+    const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;
+    T y[GROUPS][WIDE_RHS];
+    int64_t xoff[GROUPS];
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int idx = lane + 64 * g;
+        const int pos = idx < dim ? (e_lower ? idx : dim - 1 - idx) : 0;    // rows past the order re-read element 0
+        xoff[g] = (int64_t)pos * xs;
+#pragma unroll
+        for (int j = 0; j < WIDE_RHS; ++j) {
+            const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;           // past the last one: a copy that is not stored
+            y[g][j] = a.B[xoff[g] + (int64_t)q * qs];
+        }
+    }
+    // diagonal: thread t takes entry t of the stored diagonal
+    {
+        const bool has_diag = tid < dim && !a.unit;
+        const T dv = a.A[has_diag ? tid + (int64_t)tid * a.lda : 0];
+        d_inv[tid < dim ? (e_lower ? tid : dim - 1 - tid) : tid] = has_diag ? T(1) / dv : T(1);
+    }
+    // Panel p holds columns c0 = p * PANEL .. of E.  Thread -> (row r, column k of the panel), chosen
+    // so that consecutive threads read consecutive memory: rows of E are contiguous unless E is a
+    // transpose of the stored block, in which case its columns are.
+    T stage[PANEL];
+    auto fetch = [&](int p) {
+#pragma unroll
+        for (int u = 0; u < PANEL; ++u) {
+            const int r = a.etrans ? (tid / PANEL) + (WIDE / PANEL) * u : tid;
+            const int c = p * PANEL + (a.etrans ? tid % PANEL : u);
+            const int inside = (int)(r < dim) & (int)(c < dim) & (int)(r > c);          // strictly lower part of E
+            const int rr = e_lower ? r : dim - 1 - r, cc = e_lower ? c : dim - 1 - c;   // position before the reversal
+            const int64_t off = a.etrans ? cc + (int64_t)rr * a.lda : rr + (int64_t)cc * a.lda;
+            const T v = a.A[inside ? off : 0];
+            stage[u] = inside ? v : T(0);
+        }
+    };
+    auto stash = [&](int p) {
+#pragma unroll
+        for (int u = 0; u < PANEL; ++u) {
+            const int r = a.etrans ? (tid / PANEL) + (WIDE / PANEL) * u : tid;
+            const int k = a.etrans ? tid % PANEL : u;
+            const int c = p * PANEL + k;
+            e_pan[k * WIDE + r] = stage[u] * d_inv[c < WIDE ? c : 0];     // column c scaled by 1 / E(c, c)
+        }
+    };
+    const int npan = (dim + PANEL - 1) / PANEL;
+    fetch(0);
+    __syncthreads();                 // d_inv complete
+    stash(0);
+    __syncthreads();
+    const bool live = q0 < a.nrhs;   // a wave without right-hand sides still serves the panels
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+        for (int j = 0; j < WIDE_RHS; ++j) y[g][j] = lane + 64 * g < dim ? y[g][j] : T(0);
+
+    // columns of group gc (compile-time), panel by panel
+    auto group = [&](auto gc_tag) {
+        constexpr int gc = decltype(gc_tag)::value;
+#pragma unroll 1
+        for (int p = gc * (64 / PANEL); p < (gc + 1) * (64 / PANEL) && p < npan; ++p) {
+            if (p + 1 < npan) fetch(p + 1);
+            if (live) {
+                // the multipliers of column k + 1 are read while column k is applied
+                T e[GROUPS], e_next[GROUPS];
+#pragma unroll
+                for (int g = gc; g < GROUPS; ++g) e[g] = e_pan[lane + 64 * g];
+#pragma unroll 2
+                for (int k = 0; k < PANEL; ++k) {
+                    const int lc = (p * PANEL + k) & 63;                  // lane that holds the pivots
+                    const int kn = k + 1 < PANEL ? k + 1 : k;
+#pragma unroll
+                    for (int g = gc; g < GROUPS; ++g) e_next[g] = e_pan[kn * WIDE + lane + 64 * g];
+#pragma unroll
+                    for (int j = 0; j < WIDE_RHS; ++j) {
+                        const T piv = lane_value(y[gc][j], lc);
+#pragma unroll
+                        for (int g = gc; g < GROUPS; ++g) y[g][j] -= e[g] * piv;
+                    }
+#pragma unroll
+                    for (int g = gc; g < GROUPS; ++g) e[g] = e_next[g];
+                }
+            }
+            __syncthreads();         // everybody is done with this panel
+            if (p + 1 < npan) stash(p + 1);
+            __syncthreads();
+        }
+    };
+    group(std::integral_constant<int, 0>{});
+    group(std::integral_constant<int, 1>{});
+    group(std::integral_constant<int, 2>{});
+    group(std::integral_constant<int, 3>{});
+
+    if (!live) return;
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int idx = lane + 64 * g;
+        if (idx < dim) {
+            const T d = d_inv[idx];
+#pragma unroll
+            for (int j = 0; j < WIDE_RHS; ++j)
+                if (q0 + j < a.nrhs) a.B[xoff[g] + (int64_t)(q0 + j) * qs] = y[g][j] * d;
+        }
+    }
+}
+
 // Diagonal-block product x := alpha E x with the same organisation: E (lower
 // after the index maps, diagonal included) in LDS, the rows of the result across
 // the lanes of a wave, 16 right-hand sides per wave; step c adds column c of E
@@ -243,10 +371,11 @@ template <typename T> struct Tri {
         a.stored_lower = stored_lower ? 1 : 0;
         a.unit = unit ? 1 : 0;
         a.alpha = alpha;
-        constexpr int PER_WG = RHS_PER_WAVE * WAVES;
-        const dim3 grid((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), blk(64 * WAVES);
+        const int per_wg = ((!product && dim > NB) ? WIDE_RHS : RHS_PER_WAVE) * WAVES;
+        const dim3 grid((unsigned)((a.nrhs + per_wg - 1) / per_wg)), blk(64 * WAVES);
         if (product) hipLaunchKernelGGL(trmm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
-        else hipLaunchKernelGGL(trsm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
+        else if (dim <= NB) hipLaunchKernelGGL(trsm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
+        else hipLaunchKernelGGL(trsm_wide_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
         return (int)hipGetLastError();
     }
 
@@ -267,7 +396,7 @@ template <typename T> struct Tri {
 
     // rows/columns [off, off + dim) of the triangular matrix against the matching part of B
     int run(int64_t off, int64_t dim) const {
-        if (dim <= NB) return block(off, dim);
+        if (dim <= (product ? NB : WIDE)) return block(off, dim);
         const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1;
         int rc;
         if (!product) {
