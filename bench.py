@@ -252,35 +252,57 @@ def sweep(torch, np, xg, si, args):
                               "ms": round(dev * 1e3, 4), "GFLOP/s": round(flops / dev / 1e9, 1),
                               "frac_of_mfma_peak": round(flops / dev / peak, 4)}), file=sys.stderr, flush=True)
         del dA, dB, dC
-    # triangular solves (m^2 n flops for side L): B is restored before every timed call
-    for prec, side, uplo, trans, msz in (("d", "L", "L", "N", 8192), ("d", "R", "U", "T", 8192), ("d", "L", "L", "N", 16384),
-                                         ("d", "L", "L", "N", 4096), ("s", "L", "L", "N", 8192)):
+    # triangular solves and products (m^2 n flops for side L) and Cholesky factorisations (n^3 / 3):
+    # the matrix that is overwritten is restored before every timed call
+    def timed_in_place(restore, call, reps=8, skip=3):
+        times = []
+        for it in range(reps):
+            restore()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rc = call()
+            e1.record()
+            torch.cuda.synchronize()
+            if rc:
+                raise RuntimeError(rc)
+            if it >= skip:
+                times.append(e0.elapsed_time(e1) * 1e-3)
+        return sum(times) / len(times)
+
+    for op, prec, side, uplo, trans, msz in (("trsm", "d", "L", "L", "N", 8192), ("trsm", "d", "R", "U", "T", 8192),
+                                             ("trsm", "d", "L", "L", "N", 16384), ("trsm", "d", "L", "L", "N", 4096),
+                                             ("trsm", "s", "L", "L", "N", 8192), ("trmm", "d", "L", "L", "N", 8192),
+                                             ("trmm", "d", "L", "L", "N", 16384)):
         dtype = np.float64 if prec == "d" else np.float32
         ld = si.padded_ld(msz)
         rng = si.rng_for(7, msz)
         dT = torch.from_numpy(si.triangular(rng, msz, ld, dtype, uplo, False, sentinel=0.0)).cuda()
         dB0 = torch.from_numpy(si.uniform(rng, msz, msz, ld, dtype, sentinel=0.0)).cuda()
         dB = dB0.clone()
-        f = getattr(xg, f"xgemm_{prec}trsm")
+        f = getattr(xg, f"xgemm_{prec}{op}")
+        dev = timed_in_place(lambda: dB.copy_(dB0), lambda: f(side, uplo, trans, "N", msz, msz, 1.0, dT, ld, dB, ld))
         flops = float(msz) ** 3
         peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
-        times = []
-        for it in range(8):
-            dB.copy_(dB0)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            rc = f(side, uplo, trans, "N", msz, msz, 1.0, dT, ld, dB, ld)
-            e1.record()
-            torch.cuda.synchronize()
-            if rc:
-                raise RuntimeError(rc)
-            if it >= 3:
-                times.append(e0.elapsed_time(e1) * 1e-3)
-        dev = sum(times) / len(times)
-        print(json.dumps({"shape": f"{prec}trsm {side}{uplo}{trans}N {msz}x{msz}", "ms": round(dev * 1e3, 4),
+        print(json.dumps({"shape": f"{prec}{op} {side}{uplo}{trans}N {msz}x{msz}", "ms": round(dev * 1e3, 4),
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dT, dB0, dB
+    for prec, uplo, nsz in (("d", "L", 8192), ("d", "L", 16384), ("d", "L", 32768), ("s", "L", 16384)):
+        dtype = np.float64 if prec == "d" else np.float32
+        ld = si.padded_ld(nsz)
+        dA0 = torch.from_numpy(si.spd(si.rng_for(8, nsz), nsz, ld, dtype, uplo, sentinel=0.0)).cuda()
+        dA = dA0.clone()
+        dinfo = torch.zeros(1, dtype=torch.int32, device="cuda")
+        f = getattr(xg, f"xgemm_{prec}potrf")
+        dev = timed_in_place(lambda: dA.copy_(dA0), lambda: f(uplo, nsz, dA, ld, dinfo), reps=5, skip=2)
+        if int(dinfo.item()) != 0:
+            raise RuntimeError("potrf info %d" % int(dinfo.item()))
+        flops = float(nsz) ** 3 / 3.0
+        peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
+        print(json.dumps({"shape": f"{prec}potrf {uplo} {nsz}", "ms": round(dev * 1e3, 4),
+                          "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
+              file=sys.stderr, flush=True)
+        del dA0, dA
     # zgemm 4096^3 on split planes: four real launches, 8 m n k flops
     nsz = 4096
     rng = si.rng_for(5, nsz)

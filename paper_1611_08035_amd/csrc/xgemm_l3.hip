@@ -396,6 +396,7 @@ template <typename T> struct Tri {
 
     // rows/columns [off, off + dim) of the triangular matrix against the matching part of B
     int run(int64_t off, int64_t dim) const {
+        // the product measured faster with order-64 blocks and GEMMs in between than with a wide block kernel
         if (dim <= (product ? NB : WIDE)) return block(off, dim);
         const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1;
         int rc;
