@@ -93,6 +93,7 @@ def main():
     ap.add_argument("--variant", type=int, default=-1, help="force a tile variant (tuning)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep", action="store_true", help="also time the other shapes (stderr)")
+    ap.add_argument("--only", default=None, help="with --sweep: only the rows whose name contains this text")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device-to-device copy kernel "
                          "(a known-size reference for scaling HBM traffic counters under rocprofv3)")
@@ -190,7 +191,10 @@ def sweep(torch, np, xg, si, args):
         for k in (64, 128, 256):
             rows.append(("d", "N", "N", mn, mn, k, mn, k, mn, -1.0, 1.0, 4, "normal"))
     rows.append(("d", "N", "N", 4097, 3001, 257, 4097, 257, 4097, -1.0, 1.0, 4, "normal"))
+    want = lambda name: args.only is None or args.only in name
     for prec, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, cfg, kind in rows:
+        if not want(f"{prec}gemm {ta}{tb} {m}x{n}x{k}"):
+            continue
         dtype = np.float64 if prec == "d" else np.float32
         es = 8 if prec == "d" else 4
         _, (dA, dB, dC) = device_operands(torch, np, si, dtype, ta, tb, m, n, k, lda, ldb, ldc, cfg, kind)
@@ -225,12 +229,16 @@ def sweep(torch, np, xg, si, args):
              ("gemm", "d", 3328, 2560, 2048), ("gemm", "d", 3072, 3072, 3072), ("gemm", "d", 512, 512, 8192),
              ("gemm", "s", 3328, 2560, 2048)]
     for op, prec, m, n, k in extra:
+        if not (want(f"{prec}{op} {m}x{n}x{k}") or want(f"{prec}{op}_ws {m}x{n}x{k}")):
+            continue
         dtype = np.float64 if prec == "d" else np.float32
         ld = si.padded_ld(m)
         _, (dA, dB, dC) = device_operands(torch, np, si, dtype, "N", "T", m, n, k, ld, si.padded_ld(n), ld, 6)
         flops = float(m) * (m + 1) * k if op == "syrk" else 2.0 * m * n * k
         peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
         for use_ws in (False, True):
+            if not want(f"{prec}{op}{'_ws' if use_ws else ''} {m}x{n}x{k}"):
+                continue
             if op == "syrk":
                 f = getattr(xg, f"xgemm_{prec}syrk_ws")
                 call = lambda: f("L", "N", m, k, 1.5, dA, ld, -0.5, dC, ld, work if use_ws else None, lw if use_ws else 0)
@@ -273,6 +281,8 @@ def sweep(torch, np, xg, si, args):
                                              ("trsm", "d", "L", "L", "N", 16384), ("trsm", "d", "L", "L", "N", 4096),
                                              ("trsm", "s", "L", "L", "N", 8192), ("trmm", "d", "L", "L", "N", 8192),
                                              ("trmm", "d", "L", "L", "N", 16384)):
+        if not want(f"{prec}{op} {side}{uplo}{trans}N {msz}x{msz}"):
+            continue
         dtype = np.float64 if prec == "d" else np.float32
         ld = si.padded_ld(msz)
         rng = si.rng_for(7, msz)
@@ -288,6 +298,8 @@ def sweep(torch, np, xg, si, args):
               file=sys.stderr, flush=True)
         del dT, dB0, dB
     for prec, uplo, nsz in (("d", "L", 8192), ("d", "L", 16384), ("d", "L", 32768), ("s", "L", 16384)):
+        if not want(f"{prec}potrf {uplo} {nsz}"):
+            continue
         dtype = np.float64 if prec == "d" else np.float32
         ld = si.padded_ld(nsz)
         dA0 = torch.from_numpy(si.spd(si.rng_for(8, nsz), nsz, ld, dtype, uplo, sentinel=0.0)).cuda()
@@ -303,6 +315,8 @@ def sweep(torch, np, xg, si, args):
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dA0, dA
+    if not want("zgemm"):
+        return
     # zgemm 4096^3 on split planes: four real launches, 8 m n k flops
     nsz = 4096
     rng = si.rng_for(5, nsz)
