@@ -1,0 +1,70 @@
+"""Host-side checks of the launch plan (tile variant, split of the last round):
+no GPU needed, the planner falls back to 256 CUs when there is no device."""
+import pytest
+
+import paper_1611_08035_amd as xg
+
+WS = None
+
+
+def name(prec, v):
+    return xg.xgemm_variant_name(prec, v)
+
+
+@pytest.fixture(autouse=True)
+def _auto():
+    xg.xgemm_force_variant(-1)
+    xg.xgemm_force_split(-1)
+    yield
+    xg.xgemm_force_variant(-1)
+    xg.xgemm_force_split(-1)
+
+
+def test_benchmark_configurations_fill_their_rounds_and_are_never_split():
+    ws = xg.xgemm_workspace_bytes()
+    for prec, shape, want in [("d", (8192, 8192, 8192), "d_128x128x16_w2x2"), ("d", (4096, 4096, 4096), "d_128x128x16_w2x2"),
+                              ("s", (8192, 8192, 8192), "s_256x128x16_w2x2"), ("s", (16384, 16384, 16384), "s_256x128x16_w2x2"),
+                              ("d", (16384, 16384, 64), "d_128x128x16_w2x2"), ("d", (16384, 16384, 256), "d_128x128x16_w2x2")]:
+        for lwork in (0, ws):
+            v, pieces, whole = xg.xgemm_plan(prec, 0, *shape, lwork)
+            assert name(prec, v) == want and pieces == 1, (prec, shape, lwork)
+            mt = [int(x) for x in want.split("_")[1].split("x")[:2]]
+            assert whole == -(-shape[0] // mt[0]) * -(-shape[1] // mt[1])
+
+
+def test_small_problems_take_small_tiles():
+    for prec in "ds":
+        v, pieces, whole = xg.xgemm_plan(prec, 0, 512, 512, 512, 0)
+        assert name(prec, v).startswith(f"{prec}_64x64") and pieces == 1 and whole == 64
+
+
+def test_tail_round_is_split_only_with_a_workspace_and_only_the_tail():
+    ws = xg.xgemm_workspace_bytes()
+    # 26 x 20 = 520 tiles of 128 x 128 on 512 slots
+    v, pieces, whole = xg.xgemm_plan("d", 0, 3328, 2560, 2048, ws)
+    assert name("d", v) == "d_128x128x16_w2x2" and pieces > 1 and whole == 512
+    assert xg.xgemm_plan("d", 0, 3328, 2560, 2048, 0)[1] == 1
+    assert xg.xgemm_plan("d", 0, 3328, 2560, 2048, 8192)[1] == 1            # counters only: no room for partial tiles
+    # depth limits the pieces: at least 4 slabs of 16 each
+    assert xg.xgemm_plan("d", 0, 3328, 2560, 128, ws)[1] <= 2
+    # a tall-K product with few tiles is split from the first tile on
+    v, pieces, whole = xg.xgemm_plan("d", 0, 512, 512, 8192, ws)
+    assert name("d", v) == "d_128x128x16_w2x2" and pieces >= 8 and whole == 0
+    # the triangular update counts the tiles of the triangle only
+    v, pieces, whole = xg.xgemm_plan("d", 1, 8192, 8192, 8192, ws)
+    assert name("d", v) == "d_128x128x16_w2x2" and whole == 2048 and pieces == 8      # 2080 tiles: 32 in the tail
+
+
+def test_forcing_and_errors():
+    ws = xg.xgemm_workspace_bytes()
+    xg.xgemm_force_variant(3)
+    assert xg.xgemm_plan("d", 0, 8192, 8192, 8192, ws)[0] == 3
+    xg.xgemm_force_variant(0)
+    xg.xgemm_force_split(0)
+    assert xg.xgemm_plan("d", 0, 3328, 2560, 2048, ws)[1] == 1
+    xg.xgemm_force_split(4)
+    assert xg.xgemm_plan("d", 0, 3328, 2560, 2048, ws)[1] == 4
+    assert xg.xgemm_plan("x", 0, 8, 8, 8, 0) == -1
+    assert xg.xgemm_plan("d", 3, 8, 8, 8, 0) == -2
+    assert xg.xgemm_plan("d", 0, 0, 8, 8, 0) == -3
+    assert xg.xgemm_plan("d", 0, 8, 8, 0, 0) == -5
