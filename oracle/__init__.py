@@ -104,6 +104,14 @@ def _declare(L):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char, _i64, _p, _i64, _p, _i64, _i64, _p, _p, _p, _p]
+    for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
+        for suf in ("ext", "wp"):
+            f = getattr(L, f"ref_{pre}syr2k_{suf}")
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p, _p]
+            f = getattr(L, f"ref_{pre}symm_{suf}")
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p, _p]
     L.ref_zgemm_split_ext.restype = ctypes.c_int
     L.ref_zgemm_split_ext.argtypes = [ctypes.c_char, ctypes.c_char, _i64, _i64, _i64, _p,
                                       _p, _p, _i64, _p, _p, _i64, _p, _p, _p, _i64,
@@ -283,6 +291,54 @@ def potrf_resid(uplo, n, A0, lda, F, ldf, I=None, J=None):
     G = np.zeros(I.size, dtype=wide)
     info = int(f(_ch(uplo), n, _ptr(A0), lda, _ptr(F), ldf, I.size, _ptr(I), _ptr(J), _ptr(R), _ptr(G)))
     return info, R, G
+
+
+def _dense_pair(fname, dtype, rows, cols, args):
+    Out = np.zeros((max(cols, 0), max(rows, 0)), dtype=dtype)
+    G = np.zeros_like(Out)
+    info = int(getattr(lib(), fname)(*args, _ptr(Out), _ptr(G)))
+    return info, Out, G
+
+
+def syr2k_ext(uplo, trans, n, k, alpha, A, lda, B, ldb, beta, C, ldc):
+    """Extended-precision rank-2k update of one triangle; (info, Cref, G), shape (n, n), zero outside the triangle."""
+    pre, wide = _names(C.dtype)
+    return _dense_pair(f"ref_{pre}syr2k_ext", wide, n, n,
+                       (_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc))
+
+
+def syr2k_work(uplo, trans, n, k, alpha, A, lda, B, ldb, beta, C, ldc) -> int:
+    """Working-precision rank-2k update; the triangle of C is overwritten."""
+    if C is None:
+        return int(lib().ref_dsyr2k_wp(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, None, ldc,
+                                       None, None))
+    pre, _ = _names(C.dtype)
+    info, Out, _g = _dense_pair(f"ref_{pre}syr2k_wp", C.dtype, n, n,
+                                (_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc))
+    if info == 0 and n > 0:
+        mask = triangle_mask(uplo, n)
+        C[:, :n][mask] = Out[mask]
+    return info
+
+
+def symm_ext(side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc):
+    """Extended-precision symmetric product; (info, Cref, G), shape (n, m)."""
+    pre, wide = _names(C.dtype)
+    return _dense_pair(f"ref_{pre}symm_ext", wide, m, n,
+                       (_ch(side), _ch(uplo), m, n, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc))
+
+
+def symm_work(side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc) -> int:
+    """Working-precision symmetric product; C is overwritten."""
+    if C is None:
+        return int(lib().ref_dsymm_wp(_ch(side), _ch(uplo), m, n, alpha, _ptr(A), lda, _ptr(B), ldb, beta, None, ldc,
+                                      None, None))
+    pre, _ = _names(C.dtype)
+    info, Out, _g = _dense_pair(f"ref_{pre}symm_wp", C.dtype, m, n,
+                                (_ch(side), _ch(uplo), m, n, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc))
+    if info == 0 and m > 0 and n > 0:
+        C[:, :m] = Out
+    return info
 
 
 def zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc):

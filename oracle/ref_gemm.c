@@ -643,6 +643,125 @@ int NAME(char uplo, i64 n, const T *A0, i64 lda, const T *F, i64 ldf,          \
 DEFINE_REF_POTRF_RESID(ref_dpotrf_resid, double, long double, fabsl)
 DEFINE_REF_POTRF_RESID(ref_spotrf_resid, float, double, fabs)
 
+
+/* ------------------------------------------------------------------ */
+/* The two remaining real level-3 routines on top of the GEMM kernel.   */
+/*                                                                      */
+/* Symmetric rank-2k update on one triangle:                            */
+/*   C := alpha op(A) op(B)^T + alpha op(B) op(A)^T + beta C,           */
+/*   op(X) n x k:  X(i,p) (trans 'N') or X(p,i) ('T'/'C').              */
+/* Errors: uplo 1, trans 2, n 3, k 4, alpha 5, A 6, lda 7, B 8, ldb 9,  */
+/* beta 10, C 11, ldc 12.  Out / G dense n x n (ld n), zero outside the  */
+/* triangle; G = |alpha| (|op(A)||op(B)|^T + |op(B)||op(A)|^T) + |beta||C|. */
+/*                                                                      */
+/* Symmetric matrix product:                                            */
+/*   side 'L':  C := alpha A B + beta C,  A m x m symmetric             */
+/*   side 'R':  C := alpha B A + beta C,  A n x n symmetric             */
+/* A is given by its `uplo` triangle; the other triangle is not read.   */
+/* Errors: side 1, uplo 2, m 3, n 4, alpha 5, A 6, lda 7, B 8, ldb 9,   */
+/* beta 10, C 11, ldc 12.  Out / G dense m x n (ld m).                  */
+/* Sums run in increasing index order.                                  */
+/* ------------------------------------------------------------------ */
+#define OPX(X, ldx, i, p) (an ? X[(i) + (p) * (ldx)] : X[(p) + (i) * (ldx)])
+
+#define DEFINE_REF_SYR2K(NAME, T, W, WABS)                                     \
+int NAME(char uplo, char t, i64 n, i64 k, T alpha, const T *A, i64 lda,        \
+         const T *B, i64 ldb, T beta, const T *C, i64 ldc, W *Out, W *G)       \
+{                                                                              \
+    const int lower = (uplo == 'L' || uplo == 'l');                            \
+    if (!lower && uplo != 'U' && uplo != 'u') return -1;                       \
+    if (!is_n(t) && !is_t(t)) return -2;                                       \
+    if (n < 0) return -3;                                                      \
+    if (k < 0) return -4;                                                      \
+    const int an = is_n(t);                                                    \
+    const int use_ab = (alpha != (T)0 && k > 0 && n > 0);                      \
+    if (use_ab && A == NULL) return -6;                                        \
+    if (lda < max64(1, an ? n : k)) return -7;                                 \
+    if (use_ab && B == NULL) return -8;                                        \
+    if (ldb < max64(1, an ? n : k)) return -9;                                 \
+    if (n > 0 && C == NULL) return -11;                                        \
+    if (ldc < max64(1, n)) return -12;                                         \
+    _Pragma("omp parallel for schedule(dynamic, 8)")                           \
+    for (i64 j = 0; j < n; ++j)                                                \
+        for (i64 i = 0; i < n; ++i) {                                          \
+            W acc = 0, mag = 0;                                                \
+            if ((lower ? i >= j : i <= j)) {                                   \
+                if (use_ab)                                                    \
+                    for (i64 p = 0; p < k; ++p) {                              \
+                        W p1 = (W)OPX(A, lda, i, p) * (W)OPX(B, ldb, j, p);    \
+                        W p2 = (W)OPX(B, ldb, i, p) * (W)OPX(A, lda, j, p);    \
+                        acc += p1; acc += p2;                                  \
+                        mag += WABS(p1) + WABS(p2);                            \
+                    }                                                          \
+                acc = (W)alpha * acc;                                          \
+                mag = WABS((W)alpha) * mag;                                    \
+                if (beta != (T)0) {                                            \
+                    W c = (W)C[i + j * ldc];                                   \
+                    acc += (W)beta * c;                                        \
+                    mag += WABS((W)beta) * WABS(c);                            \
+                }                                                              \
+            }                                                                  \
+            Out[i + j * n] = acc;                                              \
+            G[i + j * n] = mag;                                                \
+        }                                                                      \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_SYR2K(ref_dsyr2k_ext, double, long double, fabsl)
+DEFINE_REF_SYR2K(ref_ssyr2k_ext, float, double, fabs)
+DEFINE_REF_SYR2K(ref_dsyr2k_wp, double, double, fabs)
+DEFINE_REF_SYR2K(ref_ssyr2k_wp, float, float, fabsf)
+
+/* element (r, c) of the symmetric A from its stored triangle */
+#define SYM(r, c) ((lower ? (r) >= (c) : (r) <= (c)) ? A[(r) + (c) * lda] : A[(c) + (r) * lda])
+
+#define DEFINE_REF_SYMM(NAME, T, W, WABS)                                      \
+int NAME(char side, char uplo, i64 m, i64 n, T alpha, const T *A, i64 lda,     \
+         const T *B, i64 ldb, T beta, const T *C, i64 ldc, W *Out, W *G)       \
+{                                                                              \
+    const int left = (side == 'L' || side == 'l');                             \
+    const int lower = (uplo == 'L' || uplo == 'l');                            \
+    if (!left && side != 'R' && side != 'r') return -1;                        \
+    if (!lower && uplo != 'U' && uplo != 'u') return -2;                       \
+    if (m < 0) return -3;                                                      \
+    if (n < 0) return -4;                                                      \
+    const int use_ab = (alpha != (T)0 && m > 0 && n > 0);                      \
+    if (use_ab && A == NULL) return -6;                                        \
+    if (lda < max64(1, left ? m : n)) return -7;                               \
+    if (use_ab && B == NULL) return -8;                                        \
+    if (ldb < max64(1, m)) return -9;                                          \
+    if (m > 0 && n > 0 && C == NULL) return -11;                               \
+    if (ldc < max64(1, m)) return -12;                                         \
+    const i64 dim = left ? m : n;                                              \
+    _Pragma("omp parallel for schedule(static)")                               \
+    for (i64 j = 0; j < n; ++j)                                                \
+        for (i64 i = 0; i < m; ++i) {                                          \
+            W acc = 0, mag = 0;                                                \
+            if (use_ab)                                                        \
+                for (i64 c = 0; c < dim; ++c) {                                \
+                    W prod = left ? (W)SYM(i, c) * (W)B[c + j * ldb]           \
+                                  : (W)B[i + c * ldb] * (W)SYM(c, j);          \
+                    acc += prod;                                               \
+                    mag += WABS(prod);                                         \
+                }                                                              \
+            acc = (W)alpha * acc;                                              \
+            mag = WABS((W)alpha) * mag;                                        \
+            if (beta != (T)0) {                                                \
+                W c = (W)C[i + j * ldc];                                       \
+                acc += (W)beta * c;                                            \
+                mag += WABS((W)beta) * WABS(c);                                \
+            }                                                                  \
+            Out[i + j * m] = acc;                                              \
+            G[i + j * m] = mag;                                                \
+        }                                                                      \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_SYMM(ref_dsymm_ext, double, long double, fabsl)
+DEFINE_REF_SYMM(ref_ssymm_ext, float, double, fabs)
+DEFINE_REF_SYMM(ref_dsymm_wp, double, double, fabs)
+DEFINE_REF_SYMM(ref_ssymm_wp, float, float, fabsf)
+
 /* ------------------------------------------------------------------ */
 /* Complex GEMM on split real/imaginary planes.                         */
 /*   C := alpha * op(A) * op(B) + beta * C,  op in {N, T, C(onj-transp)}*/
