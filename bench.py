@@ -297,6 +297,33 @@ def sweep(torch, np, xg, si, args):
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dT, dB0, dB
+    # the two remaining real level-3 routines: symmetric product (2 m^2 n flops) and rank-2k update (2 n (n + 1) k)
+    for op, prec, nsz in (("symm", "d", 8192), ("symm", "d", 16384), ("syr2k", "d", 8192), ("symm", "s", 8192),
+                          ("syr2k", "s", 8192)):
+        if not want(f"{prec}{op} {nsz}"):
+            continue
+        dtype = np.float64 if prec == "d" else np.float32
+        ld = si.padded_ld(nsz)
+        rng = si.rng_for(9, nsz)
+        dX, dY, dZ = (torch.from_numpy(si.uniform(rng, nsz, nsz, ld, dtype, sentinel=0.0)).cuda() for _ in range(3))
+        f = getattr(xg, f"xgemm_{prec}{op}")
+        if op == "symm":
+            call = lambda: f("L", "L", nsz, nsz, 1.5, dX, ld, dY, ld, -0.5, dZ, ld)
+            flops = 2.0 * float(nsz) ** 3
+        else:
+            call = lambda: f("L", "N", nsz, nsz, 1.5, dX, ld, dY, ld, -0.5, dZ, ld)
+            flops = 2.0 * float(nsz) * (nsz + 1) * nsz
+
+        def step():
+            rc = call()
+            if rc:
+                raise RuntimeError(rc)
+
+        wall, dev = time_calls(torch, step, 5, 3)
+        peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
+        print(json.dumps({"shape": f"{prec}{op} {nsz}", "ms": round(dev * 1e3, 4), "GFLOP/s": round(flops / dev / 1e9, 1),
+                          "frac_of_mfma_peak": round(flops / dev / peak, 4)}), file=sys.stderr, flush=True)
+        del dX, dY, dZ
     for prec, uplo, nsz in (("d", "L", 8192), ("d", "L", 16384), ("d", "L", 32768), ("s", "L", 16384)):
         if not want(f"{prec}potrf {uplo} {nsz}"):
             continue

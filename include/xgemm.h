@@ -73,6 +73,38 @@ int xgemm_ssyrk(char uplo, char trans, int64_t n, int64_t k, float alpha, const 
                 float beta, float *C, int64_t ldc, void *stream);
 
 /*
+ * Symmetric rank-2k update on the real kernel (two launches of the GEMM kernel in
+ * triangle mode, the second accumulating onto the first):
+ *     C := alpha op(A) op(B)^T + alpha op(B) op(A)^T + beta C,
+ * op(X) is n x k (trans N: X; T or C: X^T, X stored k x n); only the `uplo`
+ * triangle of the n x n C is read and written.  Scalar rules as for xgemm_dsyrk.
+ * Illegal-argument numbering: uplo 1, trans 2, n 3, k 4, alpha 5, A 6, lda 7,
+ * B 8, ldb 9, beta 10, C 11, ldc 12.  flops: 2 n (n + 1) k.
+ */
+int xgemm_dsyr2k(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                 const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream);
+int xgemm_ssyr2k(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+                 const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream);
+
+/*
+ * Symmetric matrix product on the real kernel:
+ *     side L:  C := alpha A B + beta C,   A is m x m
+ *     side R:  C := alpha B A + beta C,   A is n x n
+ * A is symmetric and given by its `uplo` triangle; the other triangle is not
+ * read.  B and C are m x n; A and B must not overlap C.  C is scaled by beta
+ * first (beta == 0: written without being read), then A is halved recursively:
+ * the stored off-diagonal block enters two GEMMs (as it is and transposed),
+ * diagonal blocks of order <= 64 are mirrored into full blocks by a small
+ * kernel.  Every element satisfies the product bound with k = m (L) or n (R).
+ * Illegal-argument numbering: side 1, uplo 2, m 3, n 4, alpha 5, A 6, lda 7,
+ * B 8, ldb 9, beta 10, C 11, ldc 12.  flops: 2 m^2 n (L) or 2 m n^2 (R).
+ */
+int xgemm_dsymm(char side, char uplo, int64_t m, int64_t n, double alpha, const double *A, int64_t lda,
+                const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream);
+int xgemm_ssymm(char side, char uplo, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
+                const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream);
+
+/*
  * Triangular solve with many right-hand sides on the real kernel (level-3 BLAS
  * above GEMM, Abstract and Sec. 1):
  *     side L:  op(T) X = alpha B,   T is m x m

@@ -18,6 +18,10 @@ from .xgemm import (  # noqa: F401
     xgemm_strsm,
     xgemm_dtrmm,
     xgemm_strmm,
+    xgemm_dsyr2k,
+    xgemm_ssyr2k,
+    xgemm_dsymm,
+    xgemm_ssymm,
     xgemm_dpotrf,
     xgemm_spotrf,
     xgemm_tile_map,

@@ -228,6 +228,32 @@ __global__ void __launch_bounds__(256) zero_words_kernel(unsigned *p, int n) {
     if (i < n) p[i] = 0u;
 }
 
+// C := alpha op(A) op(B)^T + alpha op(B) op(A)^T + beta C on one triangle: two launches of the GEMM
+// kernel in triangle mode, the second accumulating onto the first.
+template <typename T>
+int syr2k_impl(char uplo, char trans, int64_t n, int64_t k, T alpha, const T *A, int64_t lda, const T *B, int64_t ldb,
+               T beta, T *C, int64_t ldc, void *stream) {
+    t_last_kernel = "none";
+    const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
+    if (!lower && !upper) return -1;
+    if (!is_n(trans) && !is_t(trans)) return -2;
+    if (n < 0 || n > DIM_MAX) return -3;
+    if (k < 0 || k > DIM_MAX) return -4;
+    const bool ab_read = (alpha != T(0)) && n > 0 && k > 0;
+    if (ab_read && !A) return -6;
+    if (lda < max64(1, is_n(trans) ? n : k)) return -7;
+    if (ab_read && !B) return -8;
+    if (ldb < max64(1, is_n(trans) ? n : k)) return -9;
+    if (n > 0 && !C) return -11;
+    if (ldc < max64(1, n)) return -12;
+    const char t1 = is_n(trans) ? 'N' : 'T', t2 = is_n(trans) ? 'T' : 'N';
+    const int ul = lower ? 1 : 2;
+    // without a product term this is the scaling (or nothing) that the first call does by itself
+    const int rc = gemm_impl<T>(t1, t2, n, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, ul);
+    if (rc || !ab_read) return rc;
+    return gemm_impl<T>(t1, t2, n, n, k, alpha, B, ldb, A, lda, T(1), C, ldc, stream, ul);
+}
+
 // Elementwise combine for the complex path with complex scalars:
 //   Cr = ar Pr - ai Pi + br Cr - bi Ci,   Ci = ar Pi + ai Pr + br Ci + bi Cr
 // have_p == 0: the product term is absent (alpha == 0 or k == 0), P is not read.
@@ -324,6 +350,16 @@ int xgemm_dgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, doubl
 int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
                 int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream) {
     return gemm_impl<float>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+int xgemm_dsyr2k(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                 const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream) {
+    return syr2k_impl<double>(uplo, trans, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+int xgemm_ssyr2k(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+                 const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream) {
+    return syr2k_impl<float>(uplo, trans, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
 }
 
 size_t xgemm_workspace_bytes(void) { return WS_CNT_BYTES + WS_PART_BYTES; }

@@ -582,9 +582,179 @@ template <typename T> int potrf_impl(char uplo, int64_t n, T *A, int64_t lda, in
     return potrf_run<T>(lower, 0, n, A, lda, info, stream);
 }
 
+// ---------------------------------------------------------------------------
+// Symmetric matrix product  C := alpha A B + beta C  (side L)  or  alpha B A + beta C  (side R),
+// A symmetric, given by one triangle.  C is scaled by beta first; then A is halved recursively:
+// the stored off-diagonal block couples the halves through two GEMMs (once as it is, once
+// transposed), the diagonal blocks recurse, and diagonal blocks of order <= NB go to the kernel
+// below, which mirrors the stored triangle into a full block in LDS and accumulates with the rows
+// of the result across the lanes of a wave, like the triangular kernels.
+// ---------------------------------------------------------------------------
+template <typename T> struct SymmBlockArgs {
+    const T *A;      // top-left element of the diagonal block
+    int64_t lda;
+    const T *B;      // the block's rows (side L) or columns (side R) of B
+    int64_t ldb;
+    T *C;            // the same part of C
+    int64_t ldc;
+    int nbk, nrhs, left, stored_lower;
+    T alpha;
+};
+
+template <typename T> __global__ void __launch_bounds__(64 * WAVES) symm_block_kernel(const SymmBlockArgs<T> a) {
+    __shared__ T e_cols[NB * NB];            // the full symmetric block, element (r, c) at [c * NB + r]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nbk = a.nbk;
+    const int lowr = a.stored_lower ? 1 : 0;
+    constexpr int PER = NB / WAVES;
+
+    const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
+    const int pos = lane < nbk ? lane : 0;
+    const int64_t bq = a.left ? a.ldb : 1, bx = a.left ? 1 : a.ldb;      // strides between / inside right-hand sides
+    const int64_t cq = a.left ? a.ldc : 1, cx = a.left ? 1 : a.ldc;
+    T x[RHS_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < RHS_PER_WAVE; ++j) {
+        const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;
+        x[j] = a.B[(int64_t)pos * bx + (int64_t)q * bq];
+    }
+    // thread (wave w, lane t): stored row t, stored columns s = w, w + 4, ...; the referenced triangle
+    // with its diagonal; everything else counts as zero here and is supplied by the mirror image
+    T row[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int s = wave + u * WAVES;
+        const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane >= s)) | ((lowr ^ 1) & (int)(lane <= s)));
+        const T v = a.A[(inside ? lane : 0) + (int64_t)(inside ? s : 0) * a.lda];
+        row[u] = inside ? v : T(0);
+    }
+    for (int i = tid; i < NB * NB; i += 64 * WAVES) e_cols[i] = T(0);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int s = wave + u * WAVES;
+        const int inside = (int)(lane < nbk) & (int)(s < nbk) & ((lowr & (int)(lane >= s)) | ((lowr ^ 1) & (int)(lane <= s)));
+        if (inside) {
+            e_cols[s * NB + lane] = row[u];
+            e_cols[lane * NB + s] = row[u];
+        }
+    }
+    __syncthreads();
+    if (q0 >= a.nrhs) return;
+
+    T acc[RHS_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < RHS_PER_WAVE; ++j) {
+        x[j] = lane < nbk ? x[j] : T(0);
+        acc[j] = T(0);
+    }
+    T e = e_cols[lane];
+#pragma unroll 1
+    for (int c = 0; c < nbk; ++c) {
+        const T e_next = e_cols[(c + 1 < NB ? c + 1 : c) * NB + lane];
+#pragma unroll
+        for (int j = 0; j < RHS_PER_WAVE; ++j) acc[j] += e * lane_value(x[j], c);
+        e = e_next;
+    }
+    if (lane < nbk) {
+#pragma unroll
+        for (int j = 0; j < RHS_PER_WAVE; ++j)
+            if (q0 + j < a.nrhs) {
+                T *c = a.C + (int64_t)lane * cx + (int64_t)(q0 + j) * cq;
+                *c += a.alpha * acc[j];
+            }
+    }
+}
+
+template <typename T> struct Symm {
+    bool left, lower;
+    const T *A;
+    int64_t lda;
+    const T *B;
+    int64_t ldb;
+    T *C;
+    int64_t ldc, m, n;
+    T alpha;
+    void *stream;
+
+    int run(int64_t off, int64_t dim) const {
+        if (dim <= NB) {
+            SymmBlockArgs<T> a;
+            a.A = A + off + off * lda;
+            a.lda = lda;
+            a.B = left ? B + off : B + off * ldb;
+            a.ldb = ldb;
+            a.C = left ? C + off : C + off * ldc;
+            a.ldc = ldc;
+            a.nbk = (int)dim;
+            a.nrhs = (int)(left ? n : m);
+            a.left = left ? 1 : 0;
+            a.stored_lower = lower ? 1 : 0;
+            a.alpha = alpha;
+            constexpr int PER_WG = RHS_PER_WAVE * WAVES;
+            hipLaunchKernelGGL(symm_block_kernel<T>, dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(64 * WAVES), 0,
+                               static_cast<hipStream_t>(stream), a);
+            return (int)hipGetLastError();
+        }
+        const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1, o2 = off + n1;
+        // stored off-diagonal block: A21 (n2 x n1) of a lower, A12 (n1 x n2) of an upper triangle
+        const T *S = lower ? A + o2 + off * lda : A + off + o2 * lda;
+        const char as12 = lower ? 'T' : 'N', as21 = lower ? 'N' : 'T';   // how S gives A12 and A21
+        int rc;
+        if (left) {
+            if ((rc = real_gemm<T>(as12, 'N', n1, n, n2, alpha, S, lda, B + o2, ldb, T(1), C + off, ldc, stream))) return rc;
+            if ((rc = real_gemm<T>(as21, 'N', n2, n, n1, alpha, S, lda, B + off, ldb, T(1), C + o2, ldc, stream))) return rc;
+        } else {
+            if ((rc = real_gemm<T>('N', as21, m, n1, n2, alpha, B + o2 * ldb, ldb, S, lda, T(1), C + off * ldc, ldc, stream)))
+                return rc;
+            if ((rc = real_gemm<T>('N', as12, m, n2, n1, alpha, B + off * ldb, ldb, S, lda, T(1), C + o2 * ldc, ldc, stream)))
+                return rc;
+        }
+        if ((rc = run(off, n1))) return rc;
+        return run(o2, n2);
+    }
+};
+
+template <typename T>
+int symm_impl(char side, char uplo, int64_t m, int64_t n, T alpha, const T *A, int64_t lda, const T *B, int64_t ldb,
+              T beta, T *C, int64_t ldc, void *stream) {
+    const bool left = (side == 'L' || side == 'l'), right = (side == 'R' || side == 'r');
+    const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
+    if (!left && !right) return -1;
+    if (!lower && !upper) return -2;
+    if (m < 0 || m > DIM_MAX) return -3;
+    if (n < 0 || n > DIM_MAX) return -4;
+    const bool ab_read = alpha != T(0) && m > 0 && n > 0;
+    if (ab_read && !A) return -6;
+    if (lda < max64(1, left ? m : n)) return -7;
+    if (ab_read && !B) return -8;
+    if (ldb < max64(1, m)) return -9;
+    if (m > 0 && n > 0 && !C) return -11;
+    if (ldc < max64(1, m)) return -12;
+    if (m == 0 || n == 0) return 0;
+    if (!ab_read && beta == T(1)) return 0;
+    if (beta != T(1)) {
+        const int rc = scale_b<T>(C, ldc, m, n, beta, stream);
+        if (rc) return rc;
+    }
+    if (!ab_read) return 0;
+    Symm<T> s{left, lower, A, lda, B, ldb, C, ldc, m, n, alpha, stream};
+    return s.run(0, left ? m : n);
+}
+
 }  // namespace
 
 extern "C" {
+
+int xgemm_dsymm(char side, char uplo, int64_t m, int64_t n, double alpha, const double *A, int64_t lda, const double *B,
+                int64_t ldb, double beta, double *C, int64_t ldc, void *stream) {
+    return symm_impl<double>(side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+int xgemm_ssymm(char side, char uplo, int64_t m, int64_t n, float alpha, const float *A, int64_t lda, const float *B,
+                int64_t ldb, float beta, float *C, int64_t ldc, void *stream) {
+    return symm_impl<float>(side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
 
 int xgemm_dpotrf(char uplo, int64_t n, double *A, int64_t lda, int *info, void *stream) {
     return potrf_impl<double>(uplo, n, A, lda, info, stream);

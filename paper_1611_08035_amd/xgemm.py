@@ -19,7 +19,8 @@ EXPORTS = [
     "xgemm_mfma_layout_probe", "xgemm_hwid_probe", "xgemm_model_outer_product_rate",
     "xgemm_model_stalled_rate", "xgemm_model_n_updates", "xgemm_model_predict", "xgemm_tile_map",
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
-    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf",
+    "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
+    "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf",
 ]
 
 
@@ -75,6 +76,11 @@ def lib():
         f = getattr(L, f"xgemm_{pre}potrf")
         f.restype = ctypes.c_int
         f.argtypes = [_c, _i64, _p, _i64, _p, _p]
+    for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
+        for op in ("syr2k", "symm"):
+            f = getattr(L, f"xgemm_{pre}{op}")
+            f.restype = ctypes.c_int
+            f.argtypes = [_c, _c, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p]
     L.xgemm_zgemm.restype = ctypes.c_int
     L.xgemm_zgemm.argtypes = [_c, _c, _i64, _i64, _i64, _p, _p, _i64, _p, _i64, _p, _p, _i64, ctypes.c_int, _p,
                               ctypes.c_size_t, _p]
@@ -187,6 +193,20 @@ def xgemm_dpotrf(uplo, n, A, lda, info, stream=None) -> int:
 
 def xgemm_spotrf(uplo, n, A, lda, info, stream=None) -> int:
     return int(lib().xgemm_spotrf(_ch(uplo), n, _ptr(A), lda, _ptr(info), _stream(stream)))
+
+
+def _two_flag_op(name):
+    def call(f1, f2, d1, d2, alpha, A, lda, B, ldb, beta, C, ldc, stream=None) -> int:
+        return int(getattr(lib(), name)(_ch(f1), _ch(f2), d1, d2, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                                        _stream(stream)))
+    call.__name__ = name
+    return call
+
+
+xgemm_dsyr2k = _two_flag_op("xgemm_dsyr2k")   # (uplo, trans, n, k, alpha, A, lda, B, ldb, beta, C, ldc)
+xgemm_ssyr2k = _two_flag_op("xgemm_ssyr2k")
+xgemm_dsymm = _two_flag_op("xgemm_dsymm")     # (side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc)
+xgemm_ssymm = _two_flag_op("xgemm_ssymm")
 
 
 def xgemm_workspace_bytes() -> int:

@@ -136,6 +136,40 @@ def test_potrf_illegal_arguments(fn):
     assert f("L", 4, P, 4, None, stream=0) == -5
 
 
+@pytest.mark.parametrize("pre", "ds")
+def test_syr2k_and_symm_illegal_arguments(pre):
+    P = 4096
+    f = getattr(xg, f"xgemm_{pre}syr2k")
+    g = lambda *a: f(*a, stream=0)
+    assert g("X", "N", 4, 3, 1.0, P, 4, P, 4, 0.0, P, 4) == -1
+    assert g("L", "X", 4, 3, 1.0, P, 4, P, 4, 0.0, P, 4) == -2
+    assert g("L", "N", -1, 3, 1.0, P, 4, P, 4, 0.0, P, 4) == -3
+    assert g("L", "N", 4, -1, 1.0, P, 4, P, 4, 0.0, P, 4) == -4
+    assert g("L", "N", 4, 3, 1.0, None, 4, P, 4, 0.0, P, 4) == -6
+    assert g("L", "N", 4, 3, 1.0, P, 3, P, 4, 0.0, P, 4) == -7
+    assert g("L", "N", 4, 3, 1.0, P, 4, None, 4, 0.0, P, 4) == -8
+    assert g("L", "T", 4, 3, 1.0, P, 3, P, 2, 0.0, P, 4) == -9
+    assert g("L", "N", 4, 3, 1.0, P, 4, P, 4, 0.0, None, 4) == -11
+    assert g("L", "N", 4, 3, 1.0, P, 4, P, 4, 0.0, P, 3) == -12
+    assert g("U", "T", 0, 3, 1.0, None, 3, None, 3, 0.0, None, 1) == 0
+    assert g("U", "N", 4, 0, 1.0, None, 4, None, 4, 1.0, P, 4) == 0
+    f = getattr(xg, f"xgemm_{pre}symm")
+    g = lambda *a: f(*a, stream=0)
+    assert g("X", "L", 4, 3, 1.0, P, 4, P, 4, 0.0, P, 4) == -1
+    assert g("L", "X", 4, 3, 1.0, P, 4, P, 4, 0.0, P, 4) == -2
+    assert g("L", "L", -1, 3, 1.0, P, 4, P, 4, 0.0, P, 4) == -3
+    assert g("L", "L", 4, -1, 1.0, P, 4, P, 4, 0.0, P, 4) == -4
+    assert g("L", "L", 4, 3, 1.0, None, 4, P, 4, 0.0, P, 4) == -6
+    assert g("L", "L", 4, 3, 1.0, P, 3, P, 4, 0.0, P, 4) == -7
+    assert g("R", "L", 4, 3, 1.0, P, 2, P, 4, 0.0, P, 4) == -7
+    assert g("L", "L", 4, 3, 1.0, P, 4, None, 4, 0.0, P, 4) == -8
+    assert g("L", "L", 4, 3, 1.0, P, 4, P, 3, 0.0, P, 4) == -9
+    assert g("L", "L", 4, 3, 1.0, P, 4, P, 4, 0.0, None, 4) == -11
+    assert g("L", "L", 4, 3, 1.0, P, 4, P, 4, 0.0, P, 3) == -12
+    assert g("L", "L", 0, 3, 1.0, None, 1, None, 1, 0.0, None, 1) == 0
+    assert g("R", "U", 4, 3, 0.0, None, 3, None, 4, 1.0, P, 4) == 0
+
+
 def test_workspace_routines_host_side():
     P = 4096
     assert xg.xgemm_workspace_bytes() == 8192 + (64 << 20)
