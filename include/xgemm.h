@@ -357,7 +357,7 @@ int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream);
  * triangle, m == n expected for 1 and 2), returns the number of workgroups a
  * launch has and, when `out` is non-NULL, writes {tile row, tile column} of
  * workgroup b to out[2b], out[2b+1] for b < min(count, cap).  Workgroup b runs
- * on XCD b % 8.  Exactly the tiles that intersect the requested part of C
+ * on the same XCD as every workgroup b' = b (mod 8).  Exactly the tiles that intersect the requested part of C
  * appear, each once.  Returns -i for an illegal argument i.
  */
 int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *out, int64_t cap);

@@ -340,7 +340,7 @@ static __host__ __device__ __forceinline__ int64_t tile_count(int uplo, int ntm,
     return nt;
 }
 
-// Position of workgroup `bid` of `nt` in the tile order: XCD x = bid % 8 owns
+// Position of workgroup `bid` of `nt` in the tile order: the XCD that gets the workgroups bid = x (mod 8) owns
 // one contiguous run of the order.
 static __host__ __device__ __forceinline__ int lin_of_block(int bid, int nt) {
     const int per = (nt + NUM_XCD - 1) / NUM_XCD;

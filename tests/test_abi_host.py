@@ -209,7 +209,7 @@ def test_tile_order_covers_every_needed_tile_exactly_once(uplo, mt_m, mt_n):
 
 
 def test_tile_order_xcd_runs_are_contiguous():
-    # workgroup b runs on XCD b % 8; each XCD must own one contiguous run of the band order
+    # workgroups b = x (mod 8) share an XCD; each XCD must own one contiguous run of the band order
     cnt, tiles = xg.xgemm_tile_map(0, 8192, 8192, 128, 128)
     order = {t: i for i, t in enumerate(
         (first + r, c) for first in range(0, 64, 8) for c in range(64) for r in range(8))}

@@ -57,8 +57,9 @@ def test_mfma_accumulator_layout(prec):
 
 
 def test_workgroups_are_dealt_round_robin_to_xcds():
-    """The tile order assumes workgroup b runs on XCD b % 8 and that a CU holds
-    two 4-wave workgroups of the 128x128 fp64 kernel (66 048 B of LDS each)."""
+    """The tile order assumes that workgroups are dealt round-robin to the 8 XCDs (b and b' share an
+    XCD exactly when b = b' mod 8; which XCD workgroup 0 gets depends on what was launched before)
+    and that a CU holds two 4-wave workgroups of the 128x128 fp64 kernel (66 048 B of LDS each)."""
     torch = torch_mod()
     blocks = 1024
     out = torch.zeros(16 * blocks, dtype=torch.int32, device="cuda")
@@ -67,7 +68,7 @@ def test_workgroups_are_dealt_round_robin_to_xcds():
     rec = out.cpu().numpy().astype(np.uint32).reshape(blocks, 4, 4)
     assert np.array_equal(rec[:, 0, 2], np.arange(blocks))          # workgroup index as written
     xcc = rec[:, 0, 1] & 0xF
-    assert np.array_equal(xcc, np.arange(blocks) % 8)
+    assert np.array_equal(xcc, (np.arange(blocks) + int(xcc[0])) % 8)
     hw = rec[:512, 0, 0]
     cu_key = (xcc[:512].astype(np.int64) << 16) | (((hw >> 13) & 7) << 8) | (((hw >> 12) & 1) << 4) | ((hw >> 8) & 0xF)
     _, counts = np.unique(cu_key, return_counts=True)
