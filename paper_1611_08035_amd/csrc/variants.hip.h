@@ -1,6 +1,8 @@
 // variants.hip.h -- table of tile variants and the launcher shared by the
 // per-precision translation units.  Included once per precision with T fixed.
 #pragma once
+#include <atomic>
+
 #include "gemm_kernel.hip.h"
 
 namespace xg {
@@ -19,13 +21,19 @@ template <typename T> struct VariantEntry {
 template <typename T, typename Cfg, bool AK, bool BK, bool FAST, bool SPLIT = false>
 static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
     auto kern = gemm_kernel<T, Cfg, AK, BK, FAST, SPLIT>;
-    // LDS beyond 64 KiB has to be requested explicitly; done once per kernel.
-    static hipError_t attr = (Cfg::LDS_BYTES > 65536)
-                                 ? hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       (int)Cfg::LDS_BYTES)
-                                 : hipSuccess;
-    if (attr != hipSuccess) return attr;
+    // LDS beyond 64 KiB has to be requested explicitly: once per kernel and device.
+    if constexpr (Cfg::LDS_BYTES > 65536) {
+        constexpr int MAX_DEV = 64;
+        static std::atomic<int> done[MAX_DEV];          // 0: not yet, 1: granted
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+        if (done[dev].load(std::memory_order_acquire) == 0) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::LDS_BYTES);
+            if (e != hipSuccess) return e;
+            done[dev].store(1, std::memory_order_release);
+        }
+    }
     int64_t nt = tile_count(g.uplo, g.ntm, g.ntn, Cfg::MT_M, Cfg::MT_N);
     if constexpr (SPLIT) {
         if (g.ndp < 0 || g.ndp > nt || g.nsplit < 1 || !g.part || !g.cnt) return hipErrorInvalidValue;

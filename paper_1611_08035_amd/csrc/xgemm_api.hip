@@ -3,6 +3,7 @@
 #include "../../include/xgemm.h"
 #include "tables.h"
 
+#include <atomic>
 #include <stdlib.h>
 #include <string.h>
 
@@ -30,15 +31,16 @@ template <> const VariantEntry<float> *table<float>(int *n) { return s_variant_t
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Number of compute units of the current device (256 on MI355X), read once.
+// Number of compute units of the current device (256 on MI355X), read once per device.
 int num_cus() {
-    static const int n = [] {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
-        return cus;
-    }();
-    return n;
+    constexpr int MAX_DEV = 64;
+    static std::atomic<int> cached[MAX_DEV];          // 0: not read yet
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return 256;
+    if ((cus = cached[dev].load(std::memory_order_relaxed)) > 0) return cus;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+    cached[dev].store(cus, std::memory_order_relaxed);
+    return cus;
 }
 
 // Workspace of the *_ws entry points: arrival counters, then partial tiles.

@@ -41,13 +41,13 @@ template <typename T> struct BlockArgs {
 // an upper-triangular E is reversed in both indices (and the right-hand sides
 // with it), and every column is divided by its diagonal entry, E = E' D, so that
 // E' y = b with y = D x has a unit diagonal and x = D^-1 y.  Each wave then
-// solves RHS_PER_WAVE right-hand sides at once with the rows of the system
+// solves RPW right-hand sides (4, 8 or 16, chosen by the host) at once with the rows of the system
 // spread over its 64 lanes: lane r holds y_r of every right-hand side in
 // registers.  Step c reads column c of E' (one LDS element per lane, zero on
 // and above the diagonal), takes the pivot y_c of each right-hand side from
 // lane c into scalar registers, and updates all rows below in one FMA per
 // right-hand side:  y_r -= E'(r, c) y_c.
-constexpr int RHS_PER_WAVE = 16;
+constexpr int RHS_PER_WAVE = 16;     // the product kernels; the solves choose 2 .. 16 by the number of right-hand sides
 constexpr int WAVES = 4;
 
 template <typename T> static __device__ __forceinline__ T lane_value(T v, int lane) {
@@ -62,7 +62,7 @@ template <typename T> static __device__ __forceinline__ T lane_value(T v, int la
     }
 }
 
-template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_kernel(const BlockArgs<T> a) {
+template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trsm_block_kernel(const BlockArgs<T> a) {
     __shared__ T e_cols[NB * NB];            // E(r, c) at [c * NB + r], zero on and above the diagonal
     __shared__ T d_inv[NB];                  // 1 / E(c, c)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -73,14 +73,14 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_k
 
     // Every global load of the kernel is issued before the first wait: the
     // right-hand sides of this wave, this thread's share of the block, the diagonal.
-    // right-hand sides q0 .. q0 + RHS_PER_WAVE - 1; lane holds element `pos` of each
-    const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
+    // right-hand sides q0 .. q0 + RPW - 1; lane holds element `pos` of each
+    const int q0 = (blockIdx.x * WAVES + wave) * RPW;
     const int pos = lane < nbk ? (e_lower ? lane : nbk - 1 - lane) : 0;   // lanes past the order re-read element 0
     const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;       // strides between / inside right-hand sides
     T *const xp = a.B + (int64_t)pos * xs;
-    T y[RHS_PER_WAVE];
+    T y[RPW];
 #pragma unroll
-    for (int j = 0; j < RHS_PER_WAVE; ++j) {
+    for (int j = 0; j < RPW; ++j) {
         const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;     // past the last one: a copy that is not stored
         y[j] = xp[(int64_t)q * qs];
     }
@@ -113,34 +113,33 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_block_k
 
     // E = E' D with E' unit lower triangular: solve E' y = b, then x = D^-1 y
 #pragma unroll
-    for (int j = 0; j < RHS_PER_WAVE; ++j) y[j] = lane < nbk ? y[j] : T(0);
+    for (int j = 0; j < RPW; ++j) y[j] = lane < nbk ? y[j] : T(0);
     T e = e_cols[lane] * d_inv[0];                               // column 0 of E'
 #pragma unroll 1
     for (int c = 0; c < nbk; ++c) {
         const int cn = c + 1 < NB ? c + 1 : c;
         const T e_next = e_cols[cn * NB + lane] * d_inv[cn];
 #pragma unroll
-        for (int j = 0; j < RHS_PER_WAVE; ++j) y[j] -= e * lane_value(y[j], c);
+        for (int j = 0; j < RPW; ++j) y[j] -= e * lane_value(y[j], c);
         e = e_next;
     }
     const T d = d_inv[lane];
     if (lane < nbk) {
 #pragma unroll
-        for (int j = 0; j < RHS_PER_WAVE; ++j)
+        for (int j = 0; j < RPW; ++j)
             if (q0 + j < a.nrhs) xp[(int64_t)(q0 + j) * qs] = y[j] * d;
     }
 }
 
 // The same solve for diagonal blocks of order up to WIDE = 64 * GROUPS: lane l of a
-// wave holds rows l, l + 64, ... of the 8 systems of its wave (GROUPS values per
-// system), and E' passes through LDS in panels of PANEL columns: the loads of
+// wave holds rows l, l + 64, ... of the RPW (2, 4 or 8) systems of its wave (GROUPS
+// values per system), and E' passes through LDS in panels of PANEL columns: the loads of
 // panel p + 1 are issued before panel p is used and written to LDS after it.
 // One kernel of this kind replaces the four block solves and three coupling
 // products that recursion down to order 64 would spend on a block of order 256.
 constexpr int GROUPS = 4, WIDE = 64 * GROUPS, PANEL = 16;
-constexpr int WIDE_RHS = 8;   // right-hand sides per wave: GROUPS * WIDE_RHS values per lane stay in plain vector registers
 
-template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_kernel(const BlockArgs<T> a) {
+template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_kernel(const BlockArgs<T> a) {
     static_assert(64 * WAVES == WIDE && 64 % PANEL == 0, "one thread per row of a panel; panels do not straddle groups");
     __shared__ T e_pan[PANEL * WIDE];        // E'(r, c0 + k) at [k * WIDE + r], zero on and above the diagonal
     __shared__ T d_inv[WIDE];                // 1 / E(c, c)
@@ -149,10 +148,10 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_ke
     const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
     const int lowr = a.stored_lower ? 1 : 0;
 
-    // right-hand sides q0 .. q0 + WIDE_RHS - 1 of this wave; lane holds elements lane + 64 g of each
-    const int q0 = (blockIdx.x * WAVES + wave) * WIDE_RHS;
+    // right-hand sides q0 .. q0 + RPW - 1 of this wave; lane holds elements lane + 64 g of each
+    const int q0 = (blockIdx.x * WAVES + wave) * RPW;
     const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;
-    T y[GROUPS][WIDE_RHS];
+    T y[GROUPS][RPW];
     int64_t xoff[GROUPS];
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g) {
@@ -160,7 +159,7 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_ke
         const int pos = idx < dim ? (e_lower ? idx : dim - 1 - idx) : 0;    // rows past the order re-read element 0
         xoff[g] = (int64_t)pos * xs;
 #pragma unroll
-        for (int j = 0; j < WIDE_RHS; ++j) {
+        for (int j = 0; j < RPW; ++j) {
             const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;           // past the last one: a copy that is not stored
             y[g][j] = a.B[xoff[g] + (int64_t)q * qs];
         }
@@ -205,7 +204,7 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_ke
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g)
 #pragma unroll
-        for (int j = 0; j < WIDE_RHS; ++j) y[g][j] = lane + 64 * g < dim ? y[g][j] : T(0);
+        for (int j = 0; j < RPW; ++j) y[g][j] = lane + 64 * g < dim ? y[g][j] : T(0);
 
     // columns of group gc (compile-time), panel by panel
     auto group = [&](auto gc_tag) {
@@ -225,7 +224,7 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_ke
 #pragma unroll
                     for (int g = gc; g < GROUPS; ++g) e_next[g] = e_pan[kn * WIDE + lane + 64 * g];
 #pragma unroll
-                    for (int j = 0; j < WIDE_RHS; ++j) {
+                    for (int j = 0; j < RPW; ++j) {
                         const T piv = lane_value(y[gc][j], lc);
 #pragma unroll
                         for (int g = gc; g < GROUPS; ++g) y[g][j] -= e[g] * piv;
@@ -251,7 +250,7 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_ke
         if (idx < dim) {
             const T d = d_inv[idx];
 #pragma unroll
-            for (int j = 0; j < WIDE_RHS; ++j)
+            for (int j = 0; j < RPW; ++j)
                 if (q0 + j < a.nrhs) a.B[xoff[g] + (int64_t)(q0 + j) * qs] = y[g][j] * d;
         }
     }
@@ -371,11 +370,30 @@ template <typename T> struct Tri {
         a.stored_lower = stored_lower ? 1 : 0;
         a.unit = unit ? 1 : 0;
         a.alpha = alpha;
-        const int per_wg = ((!product && dim > NB) ? WIDE_RHS : RHS_PER_WAVE) * WAVES;
-        const dim3 grid((unsigned)((a.nrhs + per_wg - 1) / per_wg)), blk(64 * WAVES);
-        if (product) hipLaunchKernelGGL(trmm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
-        else if (dim <= NB) hipLaunchKernelGGL(trsm_block_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
-        else hipLaunchKernelGGL(trsm_wide_kernel<T>, grid, blk, 0, static_cast<hipStream_t>(stream), a);
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const dim3 blk(64 * WAVES);
+        auto grid = [&](int rpw) { return dim3((unsigned)((a.nrhs + rpw * WAVES - 1) / (rpw * WAVES))); };
+        if (product) {
+            hipLaunchKernelGGL(trmm_block_kernel<T>, grid(RHS_PER_WAVE), blk, 0, st, a);
+        } else {
+            // Right-hand sides per wave: a solve is a chain of dependent steps whose length in time
+            // grows with the right-hand sides a wave carries, so few right-hand sides are spread
+            // thinly over many waves, and only a count that fills the device is packed densely.
+            // (Measured: in double precision 2 per wave win up to about 2048 waves; in single
+            // precision, where a pivot costs one lane read instead of two, 4 per wave win throughout.)
+            constexpr bool DBL = sizeof(T) == 8;
+            constexpr int64_t SOLVE_WAVES = DBL ? 2048 : 4096;
+            auto fits = [&](int rpw) { return (a.nrhs + rpw - 1) / rpw <= SOLVE_WAVES; };
+            if (dim <= NB) {
+                if (fits(4)) hipLaunchKernelGGL((trsm_block_kernel<T, 4>), grid(4), blk, 0, st, a);
+                else if (fits(8)) hipLaunchKernelGGL((trsm_block_kernel<T, 8>), grid(8), blk, 0, st, a);
+                else hipLaunchKernelGGL((trsm_block_kernel<T, 16>), grid(16), blk, 0, st, a);
+            } else {
+                if (DBL && fits(2)) hipLaunchKernelGGL((trsm_wide_kernel<T, 2>), grid(2), blk, 0, st, a);
+                else if (fits(4)) hipLaunchKernelGGL((trsm_wide_kernel<T, 4>), grid(4), blk, 0, st, a);
+                else hipLaunchKernelGGL((trsm_wide_kernel<T, 8>), grid(8), blk, 0, st, a);
+            }
+        }
         return (int)hipGetLastError();
     }
 
@@ -470,67 +488,207 @@ int trmm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n
     return s.run(0, left ? m : n);
 }
 
-// Cholesky factorisation of a diagonal block of order nbk <= NB by one wave:
-// lane r holds row r of the not yet factored columns in registers, column c in
-// register 0.  Step c:  l_cc = sqrt(a_cc)  (lane c's value, broadcast),
-// l_rc = a_rc / l_cc, stored straight to memory; then every later column j gets
-// a_rj -= l_rc l_jc, with l_jc read back from LDS, while moving one register down
-// (reg[i] <- reg[i+1] - ...), so that registers are indexed statically inside a
-// loop over c that stays a loop.  Entries above the diagonal take part with
-// whatever they hold and are never stored.  An upper-stored block (A = U^T U) is
-// the lower problem on the transposed block.  A pivot that is not positive stops
-// the block and is reported: *info receives base + c + 1 unless an earlier
-// failure is already recorded there.
+// 16x16x4 matrix instruction of each precision as used by the block Cholesky:
+// lane l supplies element (l & 15, l >> 4) of the 16x4 row operand and element
+// (l >> 4, l & 15) of the 4x16 column operand; register r of lane l holds element
+// (drow(l, r), l & 15) of the 16x16 result.
+template <typename T> struct Mma16;
+template <> struct Mma16<double> {
+    typedef double acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t mma(double row_op, double col_op, acc_t c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(row_op, col_op, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int drow(int lane, int r) { return (lane >> 4) + 4 * r; }
+    static __device__ __forceinline__ double rsq(double x) { return __builtin_amdgcn_rsq(x); }
+    static constexpr double TINY = 0x1p-767, BIG = 0x1p1000;   // pivots the fast route accepts
+};
+template <> struct Mma16<float> {
+    typedef float acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t mma(float row_op, float col_op, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(row_op, col_op, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int drow(int lane, int r) { return 4 * (lane >> 4) + r; }
+    static __device__ __forceinline__ float rsq(float x) { return __builtin_amdgcn_rsqf(x); }
+    static constexpr float TINY = 0x1p-96f, BIG = 0x1p100f;
+};
+
+// ~ 1 / sqrt(d), good to about an ulp for TINY <= d <= BIG, from the hardware's
+// estimate y (good to about 2^-23):  h = y / 2 is refined once against g = d y with
+// the residual 1/2 - h g (error squared, about 2^-45), then once more against d
+// itself with 1/4 - (d h) h.  Seven dependent operations after the estimate, no
+// branch, instead of the several dozen of a correctly rounded square root followed
+// by a division.  Outside that range (and for zero, negative or non-numeric d) the
+// result is not to be used.
+template <typename T> static __device__ __forceinline__ T inverse_root(T d) {
+    const T y = Mma16<T>::rsq(d);
+    const T g = d * y, h = T(0.5) * y;
+    const T h1 = __builtin_fma(h, __builtin_fma(-h, g, T(0.5)), h);
+    const T e = __builtin_fma(-(d * h1), h1, T(0.25));
+    return __builtin_fma(T(4) * h1, e, h1 + h1);
+}
+
+// Cholesky factorisation of a diagonal block of order nbk <= NB = 64 by one wave.
+//
+// The block lives in the registers of the wave as 16x16 tiles in the result layout
+// of the matrix instruction (tile rows >= tile columns only), so that the update of
+// everything to the right of a finished panel of four columns is one instruction
+// per tile,  tile(I, J) -= L(I, panel) L(J, panel)^T,  whose two operands have the
+// same register format.  Per panel:
+//   1. the four columns leave the tiles through LDS and arrive one row per lane;
+//   2. they are factored there: the 4x4 block on the diagonal in every lane alike,
+//      from values read out of the lanes that own it, and each lane's own row with
+//      the reciprocal pivot roots and the block's entries of L that this yields;
+//      no step of it branches.  Pivots outside the range that the reciprocal square
+//      root estimate serves, and a ragged last panel, take a column-by-column route
+//      with the library's square root and a division instead.  Finished columns go
+//      straight to memory;
+//   3. the panel returns through LDS in operand format and the tiles are updated.
+// After four panels the first tile column is finished and the tiles move up and to
+// the left by one, which keeps every register index static while the loops over
+// tile columns and panels stay loops (the code stays small: it runs once per
+// launch, from a cold instruction cache).  Entries above the diagonal and rows
+// above a panel take part with whatever they hold; they only reach entries that
+// are finished or never stored.  An upper-stored block (A = U^T U) is the lower
+// problem on the transposed block.  A pivot that is not positive stops the block
+// and is reported: *info receives base + c + 1 unless an earlier failure is already
+// recorded there.
 template <typename T>
 __global__ void __launch_bounds__(64) potf2_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
-    const int lane = threadIdx.x;
-    // element (r, c), r >= c, of the lower problem sits at A[r + c*lda] (lower) or A[c + r*lda] (upper);
-    // lanes and columns outside the triangle re-read the block's first element and hold zero
+    using M = Mma16<T>;
+    using acc_t = typename M::acc_t;
+    constexpr int TI = NB / 16;                           // tiles per side
+    const int lane = threadIdx.x, lc = lane & 15;
+    // element (r, c), r >= c, of the lower problem sits at A[r + c*lda] (lower) or A[c + r*lda] (upper)
     const int64_t rs = lower ? 1 : lda, cs = lower ? lda : 1;
-    T a[NB];
+    __shared__ T pan[4 * NB];                             // a panel: column k of it at [k * NB + row]
+
+    acc_t acc[TI][TI];
 #pragma unroll
-    for (int c = 0; c < NB; ++c) {
-        const bool inside = lane < nbk && c <= lane;
-        const T v = A[inside ? lane * rs + c * cs : 0];
-        a[c] = inside ? v : T(0);
-    }
-    // column c of L goes through LDS so that every lane can read l_jc for all j > c
-    // with one broadcast read each (constant offsets from a per-column base)
-    __shared__ T lcol[2 * NB];
-    lcol[NB + lane] = T(0);                              // read when c + 1 + i runs past the block
-#pragma unroll 1
-    for (int c = 0; c < nbk; ++c) {
-        const T d = lane_value(a[0], c);
-        if (!(d > T(0))) {                               // wave-uniform
-            if (lane == 0 && *info == 0) *info = base + c + 1;
-            break;
-        }
-        const T s = sqrt(d);
-        const T l = lane == c ? s : a[0] / s;
-        if (lane >= c && lane < nbk) A[lane * rs + c * cs] = l;
-        lcol[lane] = l;
-        __builtin_amdgcn_wave_barrier();                 // one wave: program order suffices, keep the compiler from reordering
-        const T *const lj = lcol + c + 1;
-        // the wave is alone on its SIMD: reads of one chunk of l_jc are in flight while the previous chunk is used
-        constexpr int CH = 16;
-        T buf[2][CH];
+    for (int J = 0; J < TI; ++J)
 #pragma unroll
-        for (int u = 0; u < CH; ++u) buf[0][u] = lj[u];
+        for (int I = J; I < TI; ++I)
 #pragma unroll
-        for (int i0 = 0; i0 < NB; i0 += CH) {
-            const int cur = (i0 / CH) & 1;
-            if (i0 + CH < NB) {
-#pragma unroll
-                for (int u = 0; u < CH; ++u) buf[cur ^ 1][u] = lj[i0 + CH + u];
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * I + M::drow(lane, r), col = 16 * J + lc;
+                const bool inside = row < nbk && col <= row;
+                const T v = A[inside ? row * rs + col * cs : 0];
+                acc[I][J][r] = inside ? v : T(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll 1
+    for (int J = 0; J < TI; ++J) {
+        const int row0 = 16 * J;                          // first row and column of the block that tile (0, 0) holds now
+        const int grow = row0 + lane;                     // this lane's row of the block in the one-row-per-lane layout
+#pragma unroll 1
+        for (int jj = 0; jj < 16; jj += 4) {
+            const int c0 = row0 + jj;
+            if (c0 >= nbk) return;
+            // 1. columns jj .. jj+3 of tile column 0 -> one row per lane
+            const int kk = lc - jj;
+            if (kk >= 0 && kk < 4) {
 #pragma unroll
-            for (int u = 0; u < CH; ++u)
-                if (i0 + u + 1 < NB) a[i0 + u] = a[i0 + u + 1] - l * buf[cur][u];
-            __builtin_amdgcn_sched_barrier(0);
+                for (int I = 0; I < TI; ++I)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) pan[kk * NB + 16 * I + M::drow(lane, r)] = acc[I][0][r];
+            }
+            __builtin_amdgcn_wave_barrier();              // one wave: LDS operations complete in program order
+            T pk[4], l[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pk[k] = pan[k * NB + lane];
+            __builtin_amdgcn_wave_barrier();
+            // 2. factor the panel.  Fast route, free of branches: the panel's 4x4 diagonal block
+            // is read from the lanes that own it and factored in every lane alike (d[k], the
+            // pivots; ri[k] ~ 1 / sqrt(d[k]); lik, the block's entries of L), while each lane
+            // applies the same operations in the same order to its own row, so that the rows
+            // of the diagonal block come out bit for bit as the values used for the others.
+            bool fast;
+            {
+                const T a00 = lane_value(pk[0], jj), a10 = lane_value(pk[0], jj + 1), a20 = lane_value(pk[0], jj + 2),
+                        a30 = lane_value(pk[0], jj + 3), a11 = lane_value(pk[1], jj + 1), a21 = lane_value(pk[1], jj + 2),
+                        a31 = lane_value(pk[1], jj + 3), a22 = lane_value(pk[2], jj + 2), a32 = lane_value(pk[2], jj + 3),
+                        a33 = lane_value(pk[3], jj + 3);
+                T d[4], ri[4], q[4];
+                d[0] = a00;
+                ri[0] = inverse_root<T>(d[0]);
+                const T l10 = a10 * ri[0], l20 = a20 * ri[0], l30 = a30 * ri[0];
+                d[1] = __builtin_fma(-l10, l10, a11);
+                ri[1] = inverse_root<T>(d[1]);
+                const T l21 = __builtin_fma(-l20, l10, a21) * ri[1], l31 = __builtin_fma(-l30, l10, a31) * ri[1];
+                d[2] = __builtin_fma(-l21, l21, __builtin_fma(-l20, l20, a22));
+                ri[2] = inverse_root<T>(d[2]);
+                const T l32 = __builtin_fma(-l31, l21, __builtin_fma(-l30, l20, a32)) * ri[2];
+                d[3] = __builtin_fma(-l32, l32, __builtin_fma(-l31, l31, __builtin_fma(-l30, l30, a33)));
+                ri[3] = inverse_root<T>(d[3]);
+                q[0] = pk[0] * ri[0];
+                q[1] = __builtin_fma(-q[0], l10, pk[1]) * ri[1];
+                q[2] = __builtin_fma(-q[1], l21, __builtin_fma(-q[0], l20, pk[2])) * ri[2];
+                q[3] = __builtin_fma(-q[2], l32, __builtin_fma(-q[1], l31, __builtin_fma(-q[0], l30, pk[3]))) * ri[3];
+                // valid if all four columns exist and every pivot is in the range the estimate serves
+                // (a pivot that is zero, negative or not a number fails the first comparison)
+                int valid = (int)(c0 + 4 <= nbk);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) valid &= (int)(d[k] >= M::TINY) & (int)(d[k] <= M::BIG);
+                fast = valid != 0;
+                if (fast) {                               // wave-uniform
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const T g = d[k] * ri[k];         // the diagonal entry: one correction step on d ri
+                        const T s = __builtin_fma(__builtin_fma(-g, g, d[k]), T(0.5) * ri[k], g);
+                        l[k] = q[k];
+                        if (lane >= jj + k && grow < nbk) A[grow * rs + (c0 + k) * cs] = lane == jj + k ? s : q[k];
+                    }
+                }
+            }
+            // Careful route, column by column: the block's last panel when the order is not a
+            // multiple of four, pivots that are tiny, huge or not positive.
+            if (!fast) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int piv = jj + k;               // lane that holds the pivot row
+                    l[k] = T(0);
+                    if (c0 + k < nbk) {                   // wave-uniform
+                        const T d = lane_value(pk[k], piv);
+                        if (!(d > T(0))) {
+                            if (lane == 0 && *info == 0) *info = base + c0 + k + 1;
+                            return;
+                        }
+                        const T s = sqrt(d);
+                        l[k] = lane == piv ? s : pk[k] / s;
+                        if (lane >= piv && grow < nbk) A[grow * rs + (c0 + k) * cs] = l[k];
+#pragma unroll
+                        for (int k2 = k + 1; k2 < 4; ++k2) pk[k2] -= l[k] * lane_value(l[k], jj + k2);
+                    }
+                }
+            }
+            // 3. the panel in operand format: lane t gets L(16 I + (t & 15), c0 + (t >> 4))
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pan[k * NB + lane] = l[k];
+            __builtin_amdgcn_wave_barrier();
+            T op[TI], nop[TI];
+#pragma unroll
+            for (int I = 0; I < TI; ++I) {
+                op[I] = pan[(lane >> 4) * NB + 16 * I + lc];
+                nop[I] = -op[I];
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int live = TI - J;                      // tile rows and columns that still hold part of the block
+#pragma unroll
+            for (int J2 = 0; J2 < TI; ++J2) {
+                if (J2 < live && (J2 > 0 || jj < 12)) {   // wave-uniform; the first tile column is finished after its last panel
+#pragma unroll
+                    for (int I = J2; I < TI; ++I) acc[I][J2] = M::mma(nop[I], op[J2], acc[I][J2]);
+                }
+            }
         }
-        a[NB - 1] = T(0);
-        __builtin_amdgcn_wave_barrier();
+        // the first tile row and column are finished: everything moves up and to the left by one tile
+#pragma unroll
+        for (int J2 = 0; J2 + 1 < TI; ++J2)
+#pragma unroll
+            for (int I = J2; I + 1 < TI; ++I) acc[I][J2] = acc[I + 1][J2 + 1];
+#pragma unroll
+        for (int J2 = 0; J2 < TI; ++J2)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[TI - 1][J2][r] = T(0);
     }
 }
 

@@ -44,6 +44,26 @@ def test_sizes_from_one_block_to_several_levels(dtype, uplo):
         assert np.allclose(F[:, :n][mask], want[:, :n][mask], rtol=tol, atol=tol)
 
 
+@pytest.mark.parametrize("dtype,shift", [(np.float64, -780), (np.float32, -110), (np.float64, 900), (np.float32, 100)])
+def test_pivots_far_from_one(dtype, shift):
+    """Pivots near the bottom of the normal range (where the block kernel leaves its
+    reciprocal square root estimate for the library's square root) and near the top:
+    scaling A by a power of four scales the factor by a power of two, exactly."""
+    rng = si.rng_for(174, shift)
+    n = 150
+    A = si.spd(rng, n, n, dtype, "L")
+    F1, info1 = run_potrf("L", n, A, n)
+    F2, info2 = run_potrf("L", n, np.ldexp(A, shift).astype(dtype), n)
+    assert info1 == 0 and info2 == 0
+    mask = oracle.triangle_mask("L", n)
+    got = np.ldexp(F2[:, :n][mask].astype(np.float64), -shift // 2)
+    want = F1[:, :n][mask].astype(np.float64)
+    tol = 16 * n * unit_roundoff(dtype)
+    assert np.allclose(got, want, rtol=tol, atol=0.0)
+    rinfo, R, G = oracle.potrf_resid("L", n, np.ldexp(A, shift).astype(dtype), n, F2, n)
+    assert rinfo == 0 and np.all(np.abs(R) <= 4.0 * n * unit_roundoff(dtype) * G)
+
+
 @pytest.mark.parametrize("dtype,R", [(np.float64, 3), (np.float32, 1)])
 @pytest.mark.parametrize("uplo", "LU")
 def test_integer_factor_bit_exact(dtype, R, uplo):

@@ -123,3 +123,23 @@ def test_full_size_sampled_residual(dtype, side, uplo, trans, diag, m, n):
     dim = m if side == "L" else n
     assert np.all(np.abs(R) <= 4.0 * dim * unit_roundoff(dtype) * G)
     assert np.array_equal(X[:, m:], B[:, m:], equal_nan=True)
+
+
+@pytest.mark.parametrize("dtype,side,dim,nrhs",
+                         [(np.float64, "L", 50, 9000), (np.float64, "R", 64, 17000), (np.float64, "L", 200, 5000),
+                          (np.float64, "R", 256, 9000), (np.float32, "L", 60, 17000), (np.float32, "R", 33, 33000),
+                          (np.float32, "L", 130, 17000), (np.float32, "R", 256, 3000)])
+def test_many_right_hand_sides_on_one_small_triangle(dtype, side, dim, nrhs):
+    """The diagonal-block kernels pack 2 to 16 right-hand sides into a wave depending on how
+    many there are; these counts reach the denser packings that the other cases do not."""
+    rng = si.rng_for(124, dim + nrhs)
+    m, n = (dim, nrhs) if side == "L" else (nrhs, dim)
+    for uplo, trans in (("L", "N"), ("U", "T")):
+        A, lda, B, ldb = make(rng, side, uplo, "N", m, n, (3, 5), dtype)
+        X = run_trsm(side, uplo, trans, "N", m, n, 0.75, A, lda, B, ldb)
+        assert np.all(np.isfinite(X[:, :m]))
+        I, J = si.sample_indices(rng, m, n, 4, 4, 8192)
+        info, R, G = oracle.trsm_resid_samples(side, uplo, trans, "N", m, n, 0.75, A, lda, B, ldb, X, ldb, I, J)
+        assert info == 0
+        assert np.all(np.abs(R) <= 4.0 * dim * unit_roundoff(dtype) * G)
+        assert np.array_equal(X[:, m:], B[:, m:], equal_nan=True)
