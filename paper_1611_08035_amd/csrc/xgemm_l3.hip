@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <type_traits>
 
 namespace {
@@ -60,6 +61,20 @@ template <typename T> static __device__ __forceinline__ T lane_value(T v, int la
     } else {
         return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
     }
+}
+
+// Dynamic LDS beyond 64 KiB has to be requested explicitly: once per kernel and device.
+template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
+    if (bytes <= 65536) return hipSuccess;
+    constexpr int MAX_DEV = 64;
+    static std::atomic<int> done[MAX_DEV];               // per instantiation, i.e. per kernel
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done[dev].store(1, std::memory_order_release);
+    return e;
 }
 
 template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trsm_block_kernel(const BlockArgs<T> a) {
@@ -132,97 +147,131 @@ template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trs
 }
 
 // The same solve for diagonal blocks of order up to WIDE = 64 * GROUPS: lane l of a
-// wave holds rows l, l + 64, ... of the RPW (2, 4 or 8) systems of its wave (GROUPS
-// values per system), and E' passes through LDS in panels of PANEL columns: the loads of
-// panel p + 1 are issued before panel p is used and written to LDS after it.
+// solving wave holds rows l, l + 64, ... of the RPW (2, 4 or 8) systems of its wave
+// (GROUPS values per system), and E' passes through LDS in panels of PANEL columns.
+// Feeding a panel (DEPTH of them are on their way from memory at any time, each in
+// registers of its own; each column is scaled by the reciprocal of its diagonal entry
+// and written into one half of a double buffer in LDS while the other half is in
+// use; one barrier per panel) costs about as many instructions as solving with it,
+// and a lone wave issues them slowly.  With FEED > 0 the workgroup therefore has
+// FEED feeding waves beside its WAVES solving waves, which shortens a solve with few
+// right-hand sides by a third; with FEED == 0 every wave does both, which is the
+// better use of a device that is full of workgroups anyway.
 // One kernel of this kind replaces the four block solves and three coupling
 // products that recursion down to order 64 would spend on a block of order 256.
 constexpr int GROUPS = 4, WIDE = 64 * GROUPS, PANEL = 16;
+template <typename T> constexpr size_t wide_lds_bytes() { return (2 * PANEL * WIDE + WIDE) * sizeof(T); }
 
-template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trsm_wide_kernel(const BlockArgs<T> a) {
-    static_assert(64 * WAVES == WIDE && 64 % PANEL == 0, "one thread per row of a panel; panels do not straddle groups");
-    __shared__ T e_pan[PANEL * WIDE];        // E'(r, c0 + k) at [k * WIDE + r], zero on and above the diagonal
-    __shared__ T d_inv[WIDE];                // 1 / E(c, c)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <typename T, int RPW, int DEPTH, int FEED>
+__global__ void __launch_bounds__(64 * (WAVES + FEED)) trsm_wide_kernel(const BlockArgs<T> a) {
+    static_assert(64 * WAVES == WIDE && 64 % PANEL == 0 && DEPTH >= 1, "panels do not straddle groups");
+    constexpr int FT = FEED ? 64 * FEED : 64 * WAVES;   // feeding threads
+    constexpr int EL = PANEL * WIDE / FT;               // elements of a panel per feeding thread
+    static_assert(FT % WIDE == 0 && EL * FT == PANEL * WIDE, "whole columns of a panel per pass");
+    extern __shared__ __align__(16) unsigned char wide_lds[];
+    T *const e_pan = reinterpret_cast<T *>(wide_lds);   // two panels: E'(r, c0 + k) at [half * PANEL * WIDE + k * WIDE + r], zero on and above the diagonal
+    T *const d_inv = e_pan + 2 * PANEL * WIDE;           // 1 / E(c, c)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool feeding = FEED == 0 || wave >= WAVES;     // wave-uniform; FEED == 0: every wave both feeds and solves
+    const bool solving = FEED == 0 || wave < WAVES;
+    const int tid = FEED == 0 ? (int)threadIdx.x : (int)threadIdx.x - 64 * WAVES;   // index among the feeding threads
     const int dim = a.nbk;
     const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
-    const int lowr = a.stored_lower ? 1 : 0;
+    const int npan = (dim + PANEL - 1) / PANEL;
 
-    // right-hand sides q0 .. q0 + RPW - 1 of this wave; lane holds elements lane + 64 g of each
-    const int q0 = (blockIdx.x * WAVES + wave) * RPW;
+    // ---- solving waves: right-hand sides q0 .. q0 + RPW - 1; lane holds elements lane + 64 g of each
+    const int q0 = (blockIdx.x * WAVES + (wave & (WAVES - 1))) * RPW;
     const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;
+    const bool live = solving && q0 < a.nrhs;
     T y[GROUPS][RPW];
     int64_t xoff[GROUPS];
+    if (solving) {
 #pragma unroll
-    for (int g = 0; g < GROUPS; ++g) {
-        const int idx = lane + 64 * g;
-        const int pos = idx < dim ? (e_lower ? idx : dim - 1 - idx) : 0;    // rows past the order re-read element 0
-        xoff[g] = (int64_t)pos * xs;
+        for (int g = 0; g < GROUPS; ++g) {
+            const int idx = lane + 64 * g;
+            const int pos = idx < dim ? (e_lower ? idx : dim - 1 - idx) : 0;    // rows past the order re-read element 0
+            xoff[g] = (int64_t)pos * xs;
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;           // past the last one: a copy that is not stored
-            y[g][j] = a.B[xoff[g] + (int64_t)q * qs];
+            for (int j = 0; j < RPW; ++j) {
+                const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;           // past the last one: a copy that is not stored
+                const T v = a.B[xoff[g] + (int64_t)q * qs];
+                y[g][j] = idx < dim ? v : T(0);
+            }
         }
     }
-    // diagonal: thread t takes entry t of the stored diagonal
-    {
-        const bool has_diag = tid < dim && !a.unit;
-        const T dv = a.A[has_diag ? tid + (int64_t)tid * a.lda : 0];
-        d_inv[tid < dim ? (e_lower ? tid : dim - 1 - tid) : tid] = has_diag ? T(1) / dv : T(1);
+
+    // ---- feeding waves.  Panel p holds columns p * PANEL .. of E.  Thread -> (row r, column k of the
+    // panel), chosen so that consecutive threads read consecutive memory: rows of E are contiguous
+    // unless E is a transpose of the stored block, in which case its columns are.  Element u of a
+    // thread's share of panel p is  E(r0 + u ru, c0 + p PANEL + u cu)  at  tbase + p pstep + u ustep:
+    // the index maps (transposition, reversal of an upper E) are folded into signed strides once, so
+    // that a fetch spends a handful of instructions per element.
+    const int r0 = a.etrans ? tid / PANEL : tid % WIDE, ru = a.etrans ? FT / PANEL : 0;
+    const int c0 = a.etrans ? tid % PANEL : tid / WIDE, cu = a.etrans ? 0 : FT / WIDE;
+    const int64_t sr = (a.etrans ? a.lda : 1) * (e_lower ? 1 : -1), sc = (a.etrans ? 1 : a.lda) * (e_lower ? 1 : -1);
+    const T *const tbase = a.A + (e_lower ? 0 : (int64_t)(dim - 1) * (a.lda + 1)) + r0 * sr + c0 * sc;
+    const int64_t pstep = PANEL * sc, ustep = ru * sr + cu * sc;
+    T stage[DEPTH][EL];
+    auto fetch = [&](int p, int slot) {
+        const T *ptr = tbase + p * pstep;
+        int r = r0, c = c0 + p * PANEL;
+#pragma unroll
+        for (int u = 0; u < EL; ++u) {
+            const int inside = (int)(r < dim) & (int)(r > c);                // strictly lower part of E
+            const T v = *(inside ? ptr : a.A);
+            stage[slot][u] = inside ? v : T(0);
+            ptr += ustep;
+            r += ru;
+            c += cu;
+        }
+    };
+    auto stash = [&](int p, int slot) {
+        int at = (p & 1) * (PANEL * WIDE) + c0 * WIDE + r0, c = c0 + p * PANEL;
+#pragma unroll
+        for (int u = 0; u < EL; ++u) {
+            e_pan[at] = stage[slot][u] * d_inv[c < WIDE ? c : 0];            // column c scaled by 1 / E(c, c)
+            at += cu * WIDE + ru;
+            c += cu;
+        }
+    };
+    if (feeding) {
+#pragma unroll
+        for (int sl = 0; sl < DEPTH; ++sl)
+            if (sl < npan) fetch(sl, sl);
+        // diagonal: thread t takes entry t of the stored diagonal
+        if (tid < WIDE) {
+            const bool has_diag = tid < dim && !a.unit;
+            const T dv = a.A[has_diag ? tid + (int64_t)tid * a.lda : 0];
+            d_inv[tid < dim ? (e_lower ? tid : dim - 1 - tid) : tid] = has_diag ? T(1) / dv : T(1);
+        }
     }
-    // Panel p holds columns c0 = p * PANEL .. of E.  Thread -> (row r, column k of the panel), chosen
-    // so that consecutive threads read consecutive memory: rows of E are contiguous unless E is a
-    // transpose of the stored block, in which case its columns are.
-    T stage[PANEL];
-    auto fetch = [&](int p) {
-#pragma unroll
-        for (int u = 0; u < PANEL; ++u) {
-            const int r = a.etrans ? (tid / PANEL) + (WIDE / PANEL) * u : tid;
-            const int c = p * PANEL + (a.etrans ? tid % PANEL : u);
-            const int inside = (int)(r < dim) & (int)(c < dim) & (int)(r > c);          // strictly lower part of E
-            const int rr = e_lower ? r : dim - 1 - r, cc = e_lower ? c : dim - 1 - c;   // position before the reversal
-            const int64_t off = a.etrans ? cc + (int64_t)rr * a.lda : rr + (int64_t)cc * a.lda;
-            const T v = a.A[inside ? off : 0];
-            stage[u] = inside ? v : T(0);
-        }
-    };
-    auto stash = [&](int p) {
-#pragma unroll
-        for (int u = 0; u < PANEL; ++u) {
-            const int r = a.etrans ? (tid / PANEL) + (WIDE / PANEL) * u : tid;
-            const int k = a.etrans ? tid % PANEL : u;
-            const int c = p * PANEL + k;
-            e_pan[k * WIDE + r] = stage[u] * d_inv[c < WIDE ? c : 0];     // column c scaled by 1 / E(c, c)
-        }
-    };
-    const int npan = (dim + PANEL - 1) / PANEL;
-    fetch(0);
     __syncthreads();                 // d_inv complete
-    stash(0);
+    if (feeding) {
+        stash(0, 0);
+        if (DEPTH < npan) fetch(DEPTH, 0);
+    }
     __syncthreads();
-    const bool live = q0 < a.nrhs;   // a wave without right-hand sides still serves the panels
-#pragma unroll
-    for (int g = 0; g < GROUPS; ++g)
-#pragma unroll
-        for (int j = 0; j < RPW; ++j) y[g][j] = lane + 64 * g < dim ? y[g][j] : T(0);
 
     // columns of group gc (compile-time), panel by panel
     auto group = [&](auto gc_tag) {
         constexpr int gc = decltype(gc_tag)::value;
-#pragma unroll 1
-        for (int p = gc * (64 / PANEL); p < (gc + 1) * (64 / PANEL) && p < npan; ++p) {
-            if (p + 1 < npan) fetch(p + 1);
+        constexpr int PER = 64 / PANEL;
+#pragma unroll
+        for (int pp = 0; pp < PER; ++pp) {
+            const int p = gc * PER + pp;
+            if (p >= npan) break;    // uniform over the workgroup
             if (live) {
+                const T *const pan = e_pan + (p & 1) * (PANEL * WIDE);
                 // the multipliers of column k + 1 are read while column k is applied
                 T e[GROUPS], e_next[GROUPS];
 #pragma unroll
-                for (int g = gc; g < GROUPS; ++g) e[g] = e_pan[lane + 64 * g];
+                for (int g = gc; g < GROUPS; ++g) e[g] = pan[lane + 64 * g];
 #pragma unroll 2
                 for (int k = 0; k < PANEL; ++k) {
                     const int lc = (p * PANEL + k) & 63;                  // lane that holds the pivots
                     const int kn = k + 1 < PANEL ? k + 1 : k;
 #pragma unroll
-                    for (int g = gc; g < GROUPS; ++g) e_next[g] = e_pan[kn * WIDE + lane + 64 * g];
+                    for (int g = gc; g < GROUPS; ++g) e_next[g] = pan[kn * WIDE + lane + 64 * g];
 #pragma unroll
                     for (int j = 0; j < RPW; ++j) {
                         const T piv = lane_value(y[gc][j], lc);
@@ -233,8 +282,11 @@ template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trs
                     for (int g = gc; g < GROUPS; ++g) e[g] = e_next[g];
                 }
             }
-            __syncthreads();         // everybody is done with this panel
-            if (p + 1 < npan) stash(p + 1);
+            if (feeding && p + 1 < npan) {
+                const int slot = (gc * PER + pp + 1) % DEPTH;            // a constant once the loop is unrolled
+                stash(p + 1, slot);              // into the half that the solving waves left at the last barrier
+                if (p + 1 + DEPTH < npan) fetch(p + 1 + DEPTH, slot);
+            }
             __syncthreads();
         }
     };
@@ -383,15 +435,31 @@ template <typename T> struct Tri {
             // precision, where a pivot costs one lane read instead of two, 4 per wave win throughout.)
             constexpr bool DBL = sizeof(T) == 8;
             constexpr int64_t SOLVE_WAVES = DBL ? 2048 : 4096;
+            constexpr int SOLVE_CUS = 256;
             auto fits = [&](int rpw) { return (a.nrhs + rpw - 1) / rpw <= SOLVE_WAVES; };
             if (dim <= NB) {
                 if (fits(4)) hipLaunchKernelGGL((trsm_block_kernel<T, 4>), grid(4), blk, 0, st, a);
                 else if (fits(8)) hipLaunchKernelGGL((trsm_block_kernel<T, 8>), grid(8), blk, 0, st, a);
                 else hipLaunchKernelGGL((trsm_block_kernel<T, 16>), grid(16), blk, 0, st, a);
             } else {
-                if (DBL && fits(2)) hipLaunchKernelGGL((trsm_wide_kernel<T, 2>), grid(2), blk, 0, st, a);
-                else if (fits(4)) hipLaunchKernelGGL((trsm_wide_kernel<T, 4>), grid(4), blk, 0, st, a);
-                else hipLaunchKernelGGL((trsm_wide_kernel<T, 8>), grid(8), blk, 0, st, a);
+                constexpr size_t LDS = wide_lds_bytes<T>();
+                hipError_t e = hipSuccess;
+                auto go = [&](auto kern, int rpw, int feed) {
+                    if ((e = allow_lds(kern, LDS)) == hipSuccess)
+                        hipLaunchKernelGGL(kern, grid(rpw), dim3(64 * (WAVES + feed)), LDS, st, a);
+                };
+                // separate feeding waves pay while a workgroup has a compute unit to itself
+                auto alone = [&](int rpw) { return grid(rpw).x <= (unsigned)SOLVE_CUS; };
+                if (DBL && fits(2)) {
+                    if (alone(2)) go(trsm_wide_kernel<T, 2, 4, 8>, 2, 8);
+                    else go(trsm_wide_kernel<T, 2, 4, 0>, 2, 0);
+                } else if (fits(4)) {
+                    if (alone(4)) go(trsm_wide_kernel<T, 4, 3, 8>, 4, 8);
+                    else go(trsm_wide_kernel<T, 4, 3, 0>, 4, 0);
+                } else {
+                    go(trsm_wide_kernel<T, 8, 2, 0>, 8, 0);
+                }
+                if (e != hipSuccess) return (int)e;
             }
         }
         return (int)hipGetLastError();
