@@ -448,17 +448,15 @@ template <typename T> struct Tri {
                     if ((e = allow_lds(kern, LDS)) == hipSuccess)
                         hipLaunchKernelGGL(kern, grid(rpw), dim3(64 * (WAVES + feed)), LDS, st, a);
                 };
-                // separate feeding waves pay while a workgroup has a compute unit to itself
+                // Separate feeding waves pay while a workgroup has a compute unit to itself: the fewest
+                // right-hand sides per wave that still keep the workgroups within the compute units;
+                // beyond that, workgroups whose waves do both.
                 auto alone = [&](int rpw) { return grid(rpw).x <= (unsigned)SOLVE_CUS; };
-                if (DBL && fits(2)) {
-                    if (alone(2)) go(trsm_wide_kernel<T, 2, 4, 8>, 2, 8);
-                    else go(trsm_wide_kernel<T, 2, 4, 0>, 2, 0);
-                } else if (fits(4)) {
-                    if (alone(4)) go(trsm_wide_kernel<T, 4, 3, 8>, 4, 8);
-                    else go(trsm_wide_kernel<T, 4, 3, 0>, 4, 0);
-                } else {
-                    go(trsm_wide_kernel<T, 8, 2, 0>, 8, 0);
-                }
+                if (DBL && alone(2)) go(trsm_wide_kernel<T, 2, 4, 8>, 2, 8);
+                else if (alone(4)) go(trsm_wide_kernel<T, 4, 3, 8>, 4, 8);
+                else if (alone(8)) go(trsm_wide_kernel<T, 8, 2, 8>, 8, 8);
+                else if (fits(4)) go(trsm_wide_kernel<T, 4, 3, 0>, 4, 0);       // single precision only: more than 2048 waves of 4
+                else go(trsm_wide_kernel<T, 8, 2, 0>, 8, 0);
                 if (e != hipSuccess) return (int)e;
             }
         }
