@@ -48,7 +48,6 @@ template <typename T> struct BlockArgs {
 // and above the diagonal), takes the pivot y_c of each right-hand side from
 // lane c into scalar registers, and updates all rows below in one FMA per
 // right-hand side:  y_r -= E'(r, c) y_c.
-constexpr int RHS_PER_WAVE = 16;     // the product kernels; the solves choose 2 .. 16 by the number of right-hand sides
 constexpr int WAVES = 4;
 
 template <typename T> static __device__ __forceinline__ T lane_value(T v, int lane) {
@@ -62,6 +61,30 @@ template <typename T> static __device__ __forceinline__ T lane_value(T v, int la
         return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
     }
 }
+
+// 16x16x4 matrix instruction of each precision as used by the block kernels below:
+// lane l supplies element (l & 15, l >> 4) of the 16x4 row operand and element
+// (l >> 4, l & 15) of the 4x16 column operand; register r of lane l holds element
+// (drow(l, r), l & 15) of the 16x16 result.
+template <typename T> struct Mma16;
+template <> struct Mma16<double> {
+    typedef double acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t mma(double row_op, double col_op, acc_t c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(row_op, col_op, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int drow(int lane, int r) { return (lane >> 4) + 4 * r; }
+    static __device__ __forceinline__ double rsq(double x) { return __builtin_amdgcn_rsq(x); }
+    static constexpr double TINY = 0x1p-767, BIG = 0x1p1000;   // pivots the fast route accepts
+};
+template <> struct Mma16<float> {
+    typedef float acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t mma(float row_op, float col_op, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(row_op, col_op, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int drow(int lane, int r) { return 4 * (lane >> 4) + r; }
+    static __device__ __forceinline__ float rsq(float x) { return __builtin_amdgcn_rsqf(x); }
+    static constexpr float TINY = 0x1p-96f, BIG = 0x1p100f;
+};
 
 // Dynamic LDS beyond 64 KiB has to be requested explicitly: once per kernel and device.
 template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
@@ -308,28 +331,35 @@ __global__ void __launch_bounds__(64 * (WAVES + FEED)) trsm_wide_kernel(const Bl
     }
 }
 
-// Diagonal-block product x := alpha E x with the same organisation: E (lower
-// after the index maps, diagonal included) in LDS, the rows of the result across
-// the lanes of a wave, 16 right-hand sides per wave; step c adds column c of E
-// times element c of each right-hand side, taken from lane c.
+// Diagonal-block product x := alpha E x on the matrix instruction.  E, with zeros
+// outside its triangle (ones on an implicit diagonal), sits in LDS and supplies the
+// row operands; a wave takes MMA_RHS = 16 right-hand sides, loads them whole as the
+// column operands (so that the product may overwrite them) and accumulates the four
+// 16-row tiles of the result.  No index reversal is needed here: an upper E is
+// simply a matrix with zeros below the diagonal.
+constexpr int MMA_RHS = 16;
+
 template <typename T> __global__ void __launch_bounds__(64 * WAVES) trmm_block_kernel(const BlockArgs<T> a) {
-    __shared__ T e_cols[NB * NB];            // E(r, c) at [c * NB + r], zero above the diagonal
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    using M = Mma16<T>;
+    using acc_t = typename M::acc_t;
+    __shared__ T e_cols[NB * NB];            // E(r, c) at [c * NB + r]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lc = lane & 15, lk = lane >> 4;
     const int nbk = a.nbk;
-    const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
     const int lowr = a.stored_lower ? 1 : 0, unit = a.unit ? 1 : 0;
     constexpr int PER = NB / WAVES;
 
-    const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
-    const int pos = lane < nbk ? (e_lower ? lane : nbk - 1 - lane) : 0;
+    // column operands: step s supplies element (4 s + lk) of right-hand side q
+    const int q = (blockIdx.x * WAVES + wave) * MMA_RHS + lc;
     const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;
-    T *const xp = a.B + (int64_t)pos * xs;
-    T x[RHS_PER_WAVE];
+    T xb[NB / 4];
 #pragma unroll
-    for (int j = 0; j < RHS_PER_WAVE; ++j) {
-        const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;
-        x[j] = xp[(int64_t)q * qs];
+    for (int sx = 0; sx < NB / 4; ++sx) {
+        const int row = 4 * sx + lk;
+        const bool in = q < a.nrhs && row < nbk;
+        const T v = a.B[in ? (int64_t)row * xs + (int64_t)q * qs : 0];
+        xb[sx] = in ? v : T(0);
     }
+    // thread (wave w, lane t): stored row t, stored columns s = w, w + 4, ...
     T row[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
@@ -343,32 +373,32 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trmm_block_k
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
         const int s = wave + u * WAVES;
-        const bool in_blk = lane < nbk && s < nbk;
-        int r = a.etrans ? s : lane, c = a.etrans ? lane : s;
-        if (in_blk && !e_lower) { r = nbk - 1 - r; c = nbk - 1 - c; }
+        const int r = a.etrans ? s : lane, c = a.etrans ? lane : s;
         e_cols[c * NB + r] = row[u];
     }
     __syncthreads();
-    if (q0 >= a.nrhs) return;
+    if ((blockIdx.x * WAVES + wave) * MMA_RHS >= a.nrhs) return;
 
-    T acc[RHS_PER_WAVE];
+    acc_t acc[NB / 16];
 #pragma unroll
-    for (int j = 0; j < RHS_PER_WAVE; ++j) {
-        x[j] = lane < nbk ? x[j] : T(0);
-        acc[j] = T(0);
+    for (int t = 0; t < NB / 16; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[t][r] = T(0);
+#pragma unroll
+    for (int sx = 0; sx < NB / 4; ++sx) {
+        if (4 * sx < nbk) {                              // workgroup-uniform: columns of E past the order are zero
+#pragma unroll
+            for (int t = 0; t < NB / 16; ++t) acc[t] = M::mma(e_cols[(4 * sx + lk) * NB + 16 * t + lc], xb[sx], acc[t]);
+        }
     }
-    T e = e_cols[lane];
-#pragma unroll 1
-    for (int c = 0; c < nbk; ++c) {
-        const T e_next = e_cols[(c + 1 < NB ? c + 1 : c) * NB + lane];
+    if (q < a.nrhs) {
 #pragma unroll
-        for (int j = 0; j < RHS_PER_WAVE; ++j) acc[j] += e * lane_value(x[j], c);
-        e = e_next;
-    }
-    if (lane < nbk) {
+        for (int t = 0; t < NB / 16; ++t)
 #pragma unroll
-        for (int j = 0; j < RHS_PER_WAVE; ++j)
-            if (q0 + j < a.nrhs) xp[(int64_t)(q0 + j) * qs] = a.alpha * acc[j];
+            for (int r = 0; r < 4; ++r) {
+                const int rr = 16 * t + M::drow(lane, r);
+                if (rr < nbk) a.B[(int64_t)rr * xs + (int64_t)q * qs] = a.alpha * acc[t][r];
+            }
     }
 }
 
@@ -426,7 +456,7 @@ template <typename T> struct Tri {
         const dim3 blk(64 * WAVES);
         auto grid = [&](int rpw) { return dim3((unsigned)((a.nrhs + rpw * WAVES - 1) / (rpw * WAVES))); };
         if (product) {
-            hipLaunchKernelGGL(trmm_block_kernel<T>, grid(RHS_PER_WAVE), blk, 0, st, a);
+            hipLaunchKernelGGL(trmm_block_kernel<T>, grid(MMA_RHS), blk, 0, st, a);
         } else {
             // Right-hand sides per wave: a solve is a chain of dependent steps whose length in time
             // grows with the right-hand sides a wave carries, so few right-hand sides are spread
@@ -553,30 +583,6 @@ int trmm_impl(char side, char uplo, char transa, char diag, int64_t m, int64_t n
              true, alpha};
     return s.run(0, left ? m : n);
 }
-
-// 16x16x4 matrix instruction of each precision as used by the block Cholesky:
-// lane l supplies element (l & 15, l >> 4) of the 16x4 row operand and element
-// (l >> 4, l & 15) of the 4x16 column operand; register r of lane l holds element
-// (drow(l, r), l & 15) of the 16x16 result.
-template <typename T> struct Mma16;
-template <> struct Mma16<double> {
-    typedef double acc_t __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ acc_t mma(double row_op, double col_op, acc_t c) {
-        return __builtin_amdgcn_mfma_f64_16x16x4f64(row_op, col_op, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int drow(int lane, int r) { return (lane >> 4) + 4 * r; }
-    static __device__ __forceinline__ double rsq(double x) { return __builtin_amdgcn_rsq(x); }
-    static constexpr double TINY = 0x1p-767, BIG = 0x1p1000;   // pivots the fast route accepts
-};
-template <> struct Mma16<float> {
-    typedef float acc_t __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ acc_t mma(float row_op, float col_op, acc_t c) {
-        return __builtin_amdgcn_mfma_f32_16x16x4f32(row_op, col_op, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int drow(int lane, int r) { return 4 * (lane >> 4) + r; }
-    static __device__ __forceinline__ float rsq(float x) { return __builtin_amdgcn_rsqf(x); }
-    static constexpr float TINY = 0x1p-96f, BIG = 0x1p100f;
-};
 
 // ~ 1 / sqrt(d), good to about an ulp for TINY <= d <= BIG, from the hardware's
 // estimate y (good to about 2^-23):  h = y / 2 is refined once against g = d y with
@@ -826,21 +832,25 @@ template <typename T> struct SymmBlockArgs {
 };
 
 template <typename T> __global__ void __launch_bounds__(64 * WAVES) symm_block_kernel(const SymmBlockArgs<T> a) {
+    using M = Mma16<T>;
+    using acc_t = typename M::acc_t;
     __shared__ T e_cols[NB * NB];            // the full symmetric block, element (r, c) at [c * NB + r]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lc = lane & 15, lk = lane >> 4;
     const int nbk = a.nbk;
     const int lowr = a.stored_lower ? 1 : 0;
     constexpr int PER = NB / WAVES;
 
-    const int q0 = (blockIdx.x * WAVES + wave) * RHS_PER_WAVE;
-    const int pos = lane < nbk ? lane : 0;
+    // column operands of the matrix instruction: step s supplies element (4 s + lk) of right-hand side q
+    const int q = (blockIdx.x * WAVES + wave) * MMA_RHS + lc;
     const int64_t bq = a.left ? a.ldb : 1, bx = a.left ? 1 : a.ldb;      // strides between / inside right-hand sides
     const int64_t cq = a.left ? a.ldc : 1, cx = a.left ? 1 : a.ldc;
-    T x[RHS_PER_WAVE];
+    T xb[NB / 4];
 #pragma unroll
-    for (int j = 0; j < RHS_PER_WAVE; ++j) {
-        const int q = q0 + j < a.nrhs ? q0 + j : a.nrhs - 1;
-        x[j] = a.B[(int64_t)pos * bx + (int64_t)q * bq];
+    for (int sx = 0; sx < NB / 4; ++sx) {
+        const int row = 4 * sx + lk;
+        const bool in = q < a.nrhs && row < nbk;
+        const T v = a.B[in ? (int64_t)row * bx + (int64_t)q * bq : 0];
+        xb[sx] = in ? v : T(0);
     }
     // thread (wave w, lane t): stored row t, stored columns s = w, w + 4, ...; the referenced triangle
     // with its diagonal; everything else counts as zero here and is supplied by the mirror image
@@ -864,28 +874,30 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) symm_block_k
         }
     }
     __syncthreads();
-    if (q0 >= a.nrhs) return;
+    if ((blockIdx.x * WAVES + wave) * MMA_RHS >= a.nrhs) return;
 
-    T acc[RHS_PER_WAVE];
+    acc_t acc[NB / 16];
 #pragma unroll
-    for (int j = 0; j < RHS_PER_WAVE; ++j) {
-        x[j] = lane < nbk ? x[j] : T(0);
-        acc[j] = T(0);
+    for (int t = 0; t < NB / 16; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[t][r] = T(0);
+#pragma unroll
+    for (int sx = 0; sx < NB / 4; ++sx) {
+        if (4 * sx < nbk) {                              // workgroup-uniform: columns past the order are zero
+#pragma unroll
+            for (int t = 0; t < NB / 16; ++t) acc[t] = M::mma(e_cols[(4 * sx + lk) * NB + 16 * t + lc], xb[sx], acc[t]);
+        }
     }
-    T e = e_cols[lane];
-#pragma unroll 1
-    for (int c = 0; c < nbk; ++c) {
-        const T e_next = e_cols[(c + 1 < NB ? c + 1 : c) * NB + lane];
+    if (q < a.nrhs) {
 #pragma unroll
-        for (int j = 0; j < RHS_PER_WAVE; ++j) acc[j] += e * lane_value(x[j], c);
-        e = e_next;
-    }
-    if (lane < nbk) {
+        for (int t = 0; t < NB / 16; ++t)
 #pragma unroll
-        for (int j = 0; j < RHS_PER_WAVE; ++j)
-            if (q0 + j < a.nrhs) {
-                T *c = a.C + (int64_t)lane * cx + (int64_t)(q0 + j) * cq;
-                *c += a.alpha * acc[j];
+            for (int r = 0; r < 4; ++r) {
+                const int rr = 16 * t + M::drow(lane, r);
+                if (rr < nbk) {
+                    T *c = a.C + (int64_t)rr * cx + (int64_t)q * cq;
+                    *c += a.alpha * acc[t][r];
+                }
             }
     }
 }
@@ -915,7 +927,7 @@ template <typename T> struct Symm {
             a.left = left ? 1 : 0;
             a.stored_lower = lower ? 1 : 0;
             a.alpha = alpha;
-            constexpr int PER_WG = RHS_PER_WAVE * WAVES;
+            constexpr int PER_WG = MMA_RHS * WAVES;
             hipLaunchKernelGGL(symm_block_kernel<T>, dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(64 * WAVES), 0,
                                static_cast<hipStream_t>(stream), a);
             return (int)hipGetLastError();
