@@ -402,6 +402,181 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trmm_block_k
     }
 }
 
+// The same products for diagonal blocks of order up to WIDE = 256.  The workgroup has
+// WAVES multiplying waves and as many feeding waves.  A multiplying wave owns MMA_RHS
+// right-hand sides: all 16-row tiles of their result stay in its accumulators, and
+// their elements arrive from memory four steps (one panel) at a time, two panels
+// ahead of their use; nothing of the result is stored before the last panel, so the
+// product may overwrite its input.  E streams through LDS in panels of PANEL columns,
+// two halves in turn as in the solve above, written by the feeding waves.
+// MODE 0: triangular E with zeros above the diagonal; 1: zeros below; 2: symmetric
+// (either triangle stored).  Tiles of E that hold only zeros are passed over.
+// One kernel of this kind replaces the four order-64 products and the three coupling
+// products between them.
+template <typename T> struct WideProdArgs {
+    const T *A;      // top-left element of the diagonal block in the stored matrix
+    int64_t lda;
+    const T *X;      // the block's rows (side L) or columns (side R) of the right-hand sides
+    int64_t ldx;
+    T *Y;            // where the result goes: the same memory as X (triangular) or the block's part of C (symmetric)
+    int64_t ldy;
+    int dim, nrhs, left;
+    int etrans, stored_lower, unit;   // triangular: E(r,c) = A[c + r*lda] if etrans; symmetric: only stored_lower is read
+    T alpha;
+};
+template <typename T> constexpr size_t wide_prod_lds_bytes() { return 2 * PANEL * WIDE * sizeof(T); }
+
+template <typename T, int MODE>
+__global__ void __launch_bounds__(2 * 64 * WAVES) wide_product_kernel(const WideProdArgs<T> a) {
+    using M = Mma16<T>;
+    using acc_t = typename M::acc_t;
+    constexpr int DEPTH = 2, TILES = WIDE / 16, KS = PANEL / 4, NPAN = WIDE / PANEL;
+    extern __shared__ __align__(16) unsigned char prod_lds[];
+    T *const e_pan = reinterpret_cast<T *>(prod_lds);    // E(r, c0 + k) of panel p at [(p & 1) * PANEL * WIDE + k * WIDE + r]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lc = lane & 15, lk = lane >> 4;
+    const bool feeding = wave >= WAVES;                  // wave-uniform
+    const int tid = threadIdx.x & (64 * WAVES - 1);      // index within the waves of one kind
+    const int dim = a.dim, npan = (dim + PANEL - 1) / PANEL;
+
+    // ---- multiplying waves: column operands, step sx supplies element (4 sx + lk) of right-hand side q.
+    // Positions are clamped into the block for the load and sorted out at the point of use.
+    const int q = (blockIdx.x * WAVES + (wave & (WAVES - 1))) * MMA_RHS + lc;
+    const bool live = !feeding && (blockIdx.x * WAVES + (wave & (WAVES - 1))) * MMA_RHS < a.nrhs;
+    const int64_t xq = a.left ? a.ldx : 1, xs = a.left ? 1 : a.ldx;
+    const T *const xcol = a.X + (int64_t)min(q, a.nrhs - 1) * xq;
+    T xr[3][KS];                                         // panel p in xr[p % 3]
+    auto xfetch = [&](int p, int slot) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xr[slot][ks] = xcol[(int64_t)min(p * PANEL + 4 * ks + lk, dim - 1) * xs];
+    };
+
+    // ---- feeding waves: thread -> (row r, column k of the panel) so that consecutive threads read
+    // consecutive memory.  A fetch reads the stored element behind every position of the panel, also
+    // where E holds a zero or an implicit one (the position is clamped into the block, which is memory
+    // of the caller's matrix either way); what the position really holds is sorted out when the panel
+    // is stored, so that no lane mask has to live from the one to the other.
+    const bool by_col = MODE != 2 && a.etrans;           // E is the transpose of the stored block: its columns are contiguous
+    const int r0 = by_col ? tid / PANEL : tid, ru = by_col ? WIDE / PANEL : 0;
+    const int k0 = by_col ? tid % PANEL : 0, ku = by_col ? 0 : 1;
+    int c_next = k0;                                     // column of element 0 of the next panel to fetch
+    T stage[DEPTH][PANEL];
+    // what supplies E(r, c): 0 nothing (a zero), 1 the stored element, 2 an implicit one on the diagonal
+    auto source = [&](int r, int c) {
+        const bool in = r < dim && c < dim;
+        if (MODE == 2) return in ? 1 : 0;
+        const bool off_diag = MODE == 0 ? r > c : r < c;
+        return !in ? 0 : (off_diag || (r == c && !a.unit)) ? 1 : (r == c ? 2 : 0);
+    };
+    auto fetch = [&](int slot) {
+#pragma unroll
+        for (int u = 0; u < PANEL; ++u) {
+            const int r = min(r0 + u * ru, dim - 1), c = min(c_next + u * ku, dim - 1);
+            int i, j;                                    // the stored element that supplies E(r, c)
+            if (MODE == 2) {
+                i = a.stored_lower ? max(r, c) : min(r, c);
+                j = a.stored_lower ? min(r, c) : max(r, c);
+            } else {
+                i = a.etrans ? c : r;
+                j = a.etrans ? r : c;
+            }
+            stage[slot][u] = a.A[i + (int64_t)j * a.lda];
+        }
+        c_next += PANEL;
+    };
+    auto stash = [&](int p, int slot) {
+#pragma unroll
+        for (int u = 0; u < PANEL; ++u) {
+            const int r = r0 + u * ru, k = k0 + u * ku;
+            const int src = source(r, p * PANEL + k);
+            e_pan[(p & 1) * (PANEL * WIDE) + k * WIDE + r] = src == 1 ? stage[slot][u] : src == 2 ? T(1) : T(0);
+        }
+    };
+    acc_t acc[TILES];
+    if (feeding) {
+#pragma unroll
+        for (int sl = 0; sl < DEPTH; ++sl) fetch(sl);    // a panel past the order is read at clamped positions and stored as zeros
+        stash(0, 0);
+        fetch(0);
+    } else {
+        xfetch(0, 0);
+        xfetch(1, 1);
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[t][r] = T(0);
+    }
+    __syncthreads();
+
+    auto panel = [&](auto p_tag) {
+        constexpr int p = decltype(p_tag)::value;
+        if (p >= npan) return;                           // uniform over the workgroup
+        if (feeding) {
+            if (p + 1 < npan) {
+                constexpr int slot = (p + 1) % DEPTH;
+                stash(p + 1, slot);                      // into the half that nobody reads during this step
+                fetch(slot);                             // panel p + 1 + DEPTH
+            }
+        } else if (live) {
+            xfetch(p + 2, (p + 2) % 3);
+            const T *const pan = e_pan + (p & 1) * (PANEL * WIDE);
+            // Every tile takes part whatever the order, in straight-line code: a jump around the
+            // tiles past the order, straight after a tile's last matrix instruction, led the compiler
+            // to schedule the next reader of that tile's registers too early on the path that jumps.
+            // Tiles innermost: consecutive matrix instructions then work on different accumulators.
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int sx = p * KS + ks;
+                const T xv = (4 * sx + lk < dim && q < a.nrhs) ? xr[p % 3][ks] : T(0);
+#pragma unroll
+                for (int t = 0; t < TILES; ++t) {
+                    const bool nonzero = MODE == 0 ? sx <= 4 * t + 3 : MODE == 1 ? sx >= 4 * t : true;   // compile-time
+                    if (nonzero) acc[t] = M::mma(pan[(4 * ks + lk) * WIDE + 16 * t + lc], xv, acc[t]);
+                }
+            }
+        }
+        __syncthreads();
+    };
+    static_assert(NPAN == 16, "sixteen panels, spelled out so that every register index is a constant");
+    panel(std::integral_constant<int, 0>{});
+    panel(std::integral_constant<int, 1>{});
+    panel(std::integral_constant<int, 2>{});
+    panel(std::integral_constant<int, 3>{});
+    panel(std::integral_constant<int, 4>{});
+    panel(std::integral_constant<int, 5>{});
+    panel(std::integral_constant<int, 6>{});
+    panel(std::integral_constant<int, 7>{});
+    panel(std::integral_constant<int, 8>{});
+    panel(std::integral_constant<int, 9>{});
+    panel(std::integral_constant<int, 10>{});
+    panel(std::integral_constant<int, 11>{});
+    panel(std::integral_constant<int, 12>{});
+    panel(std::integral_constant<int, 13>{});
+    panel(std::integral_constant<int, 14>{});
+    panel(std::integral_constant<int, 15>{});
+    if (feeding || q >= a.nrhs) return;
+    const int64_t yq = a.left ? a.ldy : 1, ys = a.left ? 1 : a.ldy;
+#pragma unroll
+    for (int t = 0; t < TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int rr = 16 * t + M::drow(lane, r);
+            if (rr < dim) {
+                T *y = a.Y + (int64_t)rr * ys + (int64_t)q * yq;
+                *y = MODE == 2 ? *y + a.alpha * acc[t][r] : a.alpha * acc[t][r];
+            }
+        }
+}
+
+template <typename T, int MODE> int launch_wide_product(const WideProdArgs<T> &a, void *stream) {
+    constexpr size_t LDS = wide_prod_lds_bytes<T>();
+    constexpr int PER_WG = MMA_RHS * WAVES;
+    const hipError_t e = allow_lds(wide_product_kernel<T, MODE>, LDS);
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL((wide_product_kernel<T, MODE>), dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(2 * 64 * WAVES), LDS,
+                       static_cast<hipStream_t>(stream), a);
+    return (int)hipGetLastError();
+}
+
 // B := alpha * B (alpha == 0 stores zeros without reading)
 template <typename T> __global__ void __launch_bounds__(256) scale_b_kernel(T *B, int64_t ldb, int m, int n, T alpha) {
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -455,7 +630,23 @@ template <typename T> struct Tri {
         hipStream_t st = static_cast<hipStream_t>(stream);
         const dim3 blk(64 * WAVES);
         auto grid = [&](int rpw) { return dim3((unsigned)((a.nrhs + rpw * WAVES - 1) / (rpw * WAVES))); };
-        if (product) {
+        if (product && dim > NB) {
+            WideProdArgs<T> w;
+            w.A = a.A;
+            w.lda = lda;
+            w.X = a.B;
+            w.ldx = ldb;
+            w.Y = a.B;
+            w.ldy = ldb;
+            w.dim = a.nbk;
+            w.nrhs = a.nrhs;
+            w.left = a.left;
+            w.etrans = a.etrans;
+            w.stored_lower = a.stored_lower;
+            w.unit = a.unit;
+            w.alpha = alpha;
+            return e_lower() ? launch_wide_product<T, 0>(w, stream) : launch_wide_product<T, 1>(w, stream);
+        } else if (product) {
             hipLaunchKernelGGL(trmm_block_kernel<T>, grid(MMA_RHS), blk, 0, st, a);
         } else {
             // Right-hand sides per wave: a solve is a chain of dependent steps whose length in time
@@ -510,8 +701,7 @@ template <typename T> struct Tri {
 
     // rows/columns [off, off + dim) of the triangular matrix against the matching part of B
     int run(int64_t off, int64_t dim) const {
-        // the product measured faster with order-64 blocks and GEMMs in between than with a wide block kernel
-        if (dim <= (product ? NB : WIDE)) return block(off, dim);
+        if (dim <= WIDE) return block(off, dim);
         const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1;
         int rc;
         if (!product) {
@@ -914,6 +1104,23 @@ template <typename T> struct Symm {
     void *stream;
 
     int run(int64_t off, int64_t dim) const {
+        if (dim > NB && dim <= WIDE) {
+            WideProdArgs<T> w;
+            w.A = A + off + off * lda;
+            w.lda = lda;
+            w.X = left ? B + off : B + off * ldb;
+            w.ldx = ldb;
+            w.Y = left ? C + off : C + off * ldc;
+            w.ldy = ldc;
+            w.dim = (int)dim;
+            w.nrhs = (int)(left ? n : m);
+            w.left = left ? 1 : 0;
+            w.etrans = 0;
+            w.stored_lower = lower ? 1 : 0;
+            w.unit = 0;
+            w.alpha = alpha;
+            return launch_wide_product<T, 2>(w, stream);
+        }
         if (dim <= NB) {
             SymmBlockArgs<T> a;
             a.A = A + off + off * lda;
