@@ -59,3 +59,13 @@ def test_gemm_kernels_never_spill():
         assert int(k["sgpr_spill_count"] or 0) == 0, k
         assert int(k["private_segment_fixed_size"]) == 0, k
         assert int(k["vgpr_count"]) <= 256 and k["agpr_count"] == 0, k
+
+
+def test_no_kernel_of_the_library_uses_scratch_memory():
+    """The block kernels of the level-3 routines hold whole tiles and panels in registers;
+    none of them (nor any other kernel) may fall back to scratch memory for them."""
+    ks = [k for k in kernel_metadata() if k["name"]]
+    assert len(ks) >= 80
+    for k in ks:
+        assert int(k["vgpr_spill_count"]) == 0, k
+        assert int(k["private_segment_fixed_size"]) == 0, k
