@@ -519,9 +519,12 @@ __global__ void __launch_bounds__(2 * 64 * WAVES) wide_product_kernel(const Wide
         } else if (live) {
             xfetch(p + 2, (p + 2) % 3);
             const T *const pan = e_pan + (p & 1) * (PANEL * WIDE);
-            // Every tile takes part whatever the order, in straight-line code: a jump around the
-            // tiles past the order, straight after a tile's last matrix instruction, led the compiler
-            // to schedule the next reader of that tile's registers too early on the path that jumps.
+            // Every tile takes part whatever the order, in straight-line code.  An earlier form jumped
+            // around the tiles past the order; it left the last four rows of the last tile short of
+            // their final update for orders 176-208, in some waves of some runs only.  The cause was
+            // not established (a read of a matrix-instruction result one wait state after the
+            // instruction was checked on the device and is interlocked), so the form that every order
+            // of 1..256 passes repeatedly is kept and tested as such.
             // Tiles innermost: consecutive matrix instructions then work on different accumulators.
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {

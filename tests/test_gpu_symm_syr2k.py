@@ -67,6 +67,24 @@ def test_symm_integer_bit_exact(dtype, R, side, uplo):
         assert np.array_equal(out, want, equal_nan=True)
 
 
+@pytest.mark.parametrize("dtype,R", [(np.float64, 1000), (np.float32, 8)])
+@pytest.mark.parametrize("side,uplo", [("L", "L"), ("R", "U")])
+def test_symm_every_order_of_a_single_diagonal_block_bit_exact(dtype, R, side, uplo):
+    """Orders 1..256 are one launch of a diagonal-block kernel each; integer data, every entry
+    compared exactly, each order run three times (see the same test of the triangular product)."""
+    rng = si.rng_for(212, "LR".index(side))
+    other = 70
+    for dim in list(range(1, 257, 5)) + [64, 128, 176, 190, 191, 192, 208, 255, 256]:
+        m, n = (dim, other) if side == "L" else (other, dim)
+        A = sym_matrix(rng, dim, dim + 1, uplo, dtype, "int", R)
+        B, C = si.integers(rng, m, n, m + 2, dtype, R), si.integers(rng, m, n, m + 3, dtype, R)
+        want = C.copy()
+        assert oracle.symm_work(side, uplo, m, n, 1.0, A, dim + 1, B, m + 2, 1.0, want, m + 3) == 0
+        for rep in range(3):
+            out = run("symm", dtype, side, uplo, m, n, 1.0, A, dim + 1, B, m + 2, 1.0, C, m + 3)
+            assert np.array_equal(out, want, equal_nan=True), f"order {dim}, run {rep}"
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("uplo,trans", list(itertools.product("LU", "NT")))
 def test_syr2k_ragged_and_integer(dtype, uplo, trans):

@@ -106,3 +106,24 @@ def test_larger_sizes_against_the_product_oracle_on_sampled_entries(dtype, side,
     nviol, ratio = oracle.bound_violations(out[J, I], cref, g, dim, unit_roundoff(dtype), 4.0)
     assert info == 0 and nviol == 0, (nviol, ratio)
     assert np.array_equal(out[:, m:], B[:, m:], equal_nan=True)
+
+
+@pytest.mark.parametrize("dtype,R", [(np.float64, 1000), (np.float32, 8)])
+@pytest.mark.parametrize("side,uplo,trans", [("L", "L", "N"), ("L", "U", "N"), ("R", "L", "N"), ("L", "L", "T")])
+def test_every_order_of_a_single_diagonal_block_bit_exact(dtype, R, side, uplo, trans):
+    """Orders 1..256 are one launch of a diagonal-block kernel each (two kernels, many code paths
+    that depend on the order: ragged last tiles, ragged last panels, panels never fetched).  Integer
+    data, so that every entry is compared exactly; repeated, because a scheduling mistake in such a
+    kernel showed as wrong last rows for some orders in some runs only."""
+    rng = si.rng_for(142, "LR".index(side) * 4 + "LU".index(uplo) * 2 + "NT".index(trans))
+    nrhs = 70
+    for dim in list(range(1, 257, 5)) + [64, 128, 176, 190, 191, 192, 208, 255, 256]:
+        m, n = (dim, nrhs) if side == "L" else (nrhs, dim)
+        A = si.integers(rng, dim, dim, dim + 1, dtype, R)
+        si._mask_triangle(A, dim, uplo, False, np.nan)
+        B = si.integers(rng, m, n, m + 3, dtype, R)
+        want = B.copy()
+        assert oracle.trmm_work(side, uplo, trans, "N", m, n, 1.0, A, dim + 1, want, m + 3) == 0
+        for rep in range(3):
+            out = run_trmm(side, uplo, trans, "N", m, n, 1.0, A, dim + 1, B, m + 3)
+            assert np.array_equal(out, want, equal_nan=True), f"order {dim}, run {rep}"
