@@ -115,3 +115,23 @@ def test_full_size_sampled_residual(dtype, uplo, n):
     # a band of columns in full: outside the triangle nothing changed
     for j0 in (0, n // 2, n - 100):
         assert np.array_equal(np.isnan(F[j0:j0 + 100]), np.isnan(A[j0:j0 + 100]))
+
+
+@pytest.mark.parametrize("dtype,R", [(np.float64, 3), (np.float32, 1)])
+@pytest.mark.parametrize("uplo", "LU")
+def test_every_order_of_a_single_diagonal_block_bit_exact(dtype, R, uplo):
+    """Orders 1..64 are one launch of the block kernel each (ragged last panels and tiles, the
+    careful route for a panel of fewer than four columns); then every multiple of 16 up to 256,
+    where the solve and update kernels join in.  Integer factors recovered exactly, three times each."""
+    rng = si.rng_for(175, "LU".index(uplo))
+    for n in list(range(1, 65)) + list(range(80, 257, 16)):
+        L0 = np.tril(rng.integers(-R, R + 1, size=(n, n)), -1).astype(np.int64)
+        L0[np.arange(n), np.arange(n)] = 2 ** rng.integers(0, 3, size=n)
+        A = np.full((n, n + 1), np.nan, dtype=dtype)
+        A[:, :n] = (L0 @ L0.T).astype(dtype)
+        si._mask_triangle(A, n, uplo, False, np.nan)
+        mask = oracle.triangle_mask(uplo, n)
+        for rep in range(3):
+            F, info = run_potrf(uplo, n, A, n + 1)
+            assert info == 0, f"order {n}, run {rep}"
+            assert np.array_equal(F[:, :n][mask], (L0.T if uplo == "L" else L0)[mask].astype(dtype)), f"order {n}, run {rep}"

@@ -145,3 +145,28 @@ def test_many_right_hand_sides_on_one_small_triangle(dtype, side, dim, nrhs):
         assert info == 0
         assert np.all(np.abs(R) <= 4.0 * dim * unit_roundoff(dtype) * G)
         assert np.array_equal(X[:, m:], B[:, m:], equal_nan=True)
+
+
+@pytest.mark.parametrize("dtype,R", [(np.float64, 4), (np.float32, 2)])
+@pytest.mark.parametrize("side,uplo,trans", [("L", "L", "N"), ("L", "U", "N"), ("R", "L", "N"), ("L", "L", "T")])
+def test_every_order_of_a_single_diagonal_block_bit_exact(dtype, R, side, uplo, trans):
+    """Orders 1..256 are one launch of a diagonal-block kernel each (order <= 64: the block in LDS;
+    above: panels through LDS, with code paths that depend on the order).  Integer systems with a
+    known integer solution, recovered exactly, each order three times."""
+    rng = si.rng_for(125, "LR".index(side) * 4 + "LU".index(uplo) * 2 + "NT".index(trans))
+    nrhs = 70
+    for dim in list(range(1, 257, 5)) + [64, 128, 176, 190, 191, 192, 208, 255, 256]:
+        m, n = (dim, nrhs) if side == "L" else (nrhs, dim)
+        A = si.int_triangular(rng, dim, dim + 1, dtype, uplo, False, R)
+        Xtrue = rng.integers(-R, R + 1, size=(m, n)).astype(np.int64)
+        S = np.nan_to_num(si.view(A, dim), nan=0.0).astype(np.int64)
+        T = np.tril(S) if uplo == "L" else np.triu(S)
+        T = T.T if trans == "T" else T
+        Bint = T @ Xtrue if side == "L" else Xtrue @ T
+        if np.abs(Bint).max() >= (2 ** 52 if dtype == np.float64 else 2 ** 23):
+            continue                                   # right-hand side not exactly representable
+        B = si.constant(m, n, m + 3, dtype)
+        B[:, :m] = Bint.T.astype(dtype)
+        for rep in range(3):
+            X = run_trsm(side, uplo, trans, "N", m, n, 1.0, A, dim + 1, B, m + 3)
+            assert np.array_equal(X[:, :m], Xtrue.T.astype(dtype)), f"order {dim}, run {rep}"
