@@ -451,44 +451,53 @@ __global__ void __launch_bounds__(2 * 64 * WAVES) wide_product_kernel(const Wide
     };
 
     // ---- feeding waves: thread -> (row r, column k of the panel) so that consecutive threads read
-    // consecutive memory.  A fetch reads the stored element behind every position of the panel, also
-    // where E holds a zero or an implicit one (the position is clamped into the block, which is memory
-    // of the caller's matrix either way); what the position really holds is sorted out when the panel
-    // is stored, so that no lane mask has to live from the one to the other.
-    const bool by_col = MODE != 2 && a.etrans;           // E is the transpose of the stored block: its columns are contiguous
+    // consecutive memory: a thread keeps one row of E and walks the panel's columns, unless E is the
+    // transpose of the stored block, in which case it keeps one column and walks rows.  A fetch reads
+    // the stored element behind every position of the panel, also where E holds a zero or an implicit
+    // one (positions are clamped into the block, which is memory of the caller's matrix either way);
+    // what a position really holds is sorted out when the panel is stored, so that no lane mask has to
+    // live from the one to the other.  Only the panel's own 16 rows, the columns past the order and an
+    // implicit diagonal need sorting out: rows above them belong to tiles that are never multiplied,
+    // rows below are plain entries, and rows past the order only reach results that are not stored.
+    const bool by_col = MODE != 2 && a.etrans;
     const int r0 = by_col ? tid / PANEL : tid, ru = by_col ? WIDE / PANEL : 0;
     const int k0 = by_col ? tid % PANEL : 0, ku = by_col ? 0 : 1;
     int c_next = k0;                                     // column of element 0 of the next panel to fetch
+    const int rc = min(r0, dim - 1);                     // the thread's row, clamped (by_col: its first row)
     T stage[DEPTH][PANEL];
-    // what supplies E(r, c): 0 nothing (a zero), 1 the stored element, 2 an implicit one on the diagonal
-    auto source = [&](int r, int c) {
-        const bool in = r < dim && c < dim;
-        if (MODE == 2) return in ? 1 : 0;
-        const bool off_diag = MODE == 0 ? r > c : r < c;
-        return !in ? 0 : (off_diag || (r == c && !a.unit)) ? 1 : (r == c ? 2 : 0);
-    };
     auto fetch = [&](int slot) {
+        if (MODE == 2) {
 #pragma unroll
-        for (int u = 0; u < PANEL; ++u) {
-            const int r = min(r0 + u * ru, dim - 1), c = min(c_next + u * ku, dim - 1);
-            int i, j;                                    // the stored element that supplies E(r, c)
-            if (MODE == 2) {
-                i = a.stored_lower ? max(r, c) : min(r, c);
-                j = a.stored_lower ? min(r, c) : max(r, c);
-            } else {
-                i = a.etrans ? c : r;
-                j = a.etrans ? r : c;
+            for (int u = 0; u < PANEL; ++u) {
+                const int c = min(c_next + u, dim - 1);
+                const int i = a.stored_lower ? max(rc, c) : min(rc, c), j = a.stored_lower ? min(rc, c) : max(rc, c);
+                stage[slot][u] = a.A[i + (int64_t)j * a.lda];
             }
-            stage[slot][u] = a.A[i + (int64_t)j * a.lda];
+        } else if (!by_col) {
+            const T *const rowp = a.A + rc;
+#pragma unroll
+            for (int u = 0; u < PANEL; ++u) stage[slot][u] = rowp[(int64_t)min(c_next + u, dim - 1) * a.lda];   // a uniform offset
+        } else {
+            const T *const colp = a.A + min(c_next, dim - 1);
+#pragma unroll
+            for (int u = 0; u < PANEL; ++u) stage[slot][u] = colp[(int64_t)min(r0 + u * ru, dim - 1) * a.lda];
         }
         c_next += PANEL;
     };
+    const int nonunit = a.unit ? 0 : 1;
     auto stash = [&](int p, int slot) {
 #pragma unroll
         for (int u = 0; u < PANEL; ++u) {
-            const int r = r0 + u * ru, k = k0 + u * ku;
-            const int src = source(r, p * PANEL + k);
-            e_pan[(p & 1) * (PANEL * WIDE) + k * WIDE + r] = src == 1 ? stage[slot][u] : src == 2 ? T(1) : T(0);
+            const int r = r0 + u * ru, k = k0 + u * ku, c = p * PANEL + k;
+            T v = stage[slot][u];
+            if (MODE == 2) {
+                v = c < dim ? v : T(0);
+            } else {
+                const int diag = (int)(r == c), in = (int)(c < dim);
+                const int keep = in & ((int)(MODE == 0 ? r > c : r < c) | (diag & nonunit));
+                v = keep ? v : ((in & diag) ? T(1) : T(0));     // reached with diag set only for an implicit diagonal
+            }
+            e_pan[(p & 1) * (PANEL * WIDE) + k * WIDE + r] = v;
         }
     };
     acc_t acc[TILES];
