@@ -81,6 +81,28 @@ def cpu_baseline(np, oracle, host_ops, m, k, lda, ldb, ldc, alpha, beta, budget_
                       f"(m={m}, k={k}), {dt2:.1f} s, working-precision triple loop"}
 
 
+LATENCY_ROWS = [("FP64 fused multiply-add", 8), ("FP32 fused multiply-add", 8), ("FP64 reciprocal square root (+ one add)", 8),
+                ("LDS write, read from another lane", 4), ("FP64 16x16x4 matrix instruction, same accumulator", 4),
+                ("FP64 matrix instruction -> vector instruction -> matrix instruction", 4),
+                ("lane read to scalar registers -> vector instruction", 8), ("FP32 32x32x2 matrix instruction, same accumulator", 4)]
+
+
+def latencies(torch, xg, iters=4000):
+    out = torch.zeros(8, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(64, dtype=torch.float64, device="cuda")
+    for _ in range(3):                      # the last of three runs is reported (clocks and caches settled)
+        rc = xg.xgemm_latency_probe(out, sink, iters)
+        if rc:
+            raise RuntimeError(f"xgemm_latency_probe returned {rc}")
+        torch.cuda.synchronize()
+    ticks = out.cpu().tolist()
+    rows = []
+    for (name, per), t in zip(LATENCY_ROWS, ticks):
+        ns = 10.0 * t / (iters * per)
+        rows.append({"chain": name, "ns_per_instruction": round(ns, 2), "cycles_at_2.4GHz": round(ns * 2.4, 1)})
+    print(json.dumps({"latency_probe": rows, "iters": iters}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +119,9 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device-to-device copy kernel "
                          "(a known-size reference for scaling HBM traffic counters under rocprofv3)")
+    ap.add_argument("--latencies", action="store_true",
+                    help="instead of the benchmark: run the library's latency probe and print what a dependent "
+                         "chain of each instruction kind costs a lone wave (ns and cycles at 2.4 GHz)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -112,6 +137,8 @@ def main():
     torch.cuda.set_device(0)
     xg.lib()
     xg.xgemm_force_variant(args.variant)
+    if args.latencies:
+        return latencies(torch, xg)
 
     nsz = args.size
     single = args.prec == "s"

@@ -312,6 +312,25 @@ int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *st
 int xgemm_mfma_layout_probe(char prec, int *out, void *stream);
 
 /*
+ * Latency probe: what a dependent chain of instructions costs a lone wave, the
+ * device's counterpart of the latency column of the paper's micro-architecture
+ * table (Sec. 4.3, the k of W = L + n k).  One wave runs `iters` rounds of eight
+ * chains and writes the elapsed ticks of the 100 MHz real-time counter (10 ns each)
+ * to out[0..7] (device, 8 x int64); per round the chains hold
+ *   0: 8 FP64 fused multiply-adds       1: 8 FP32 fused multiply-adds
+ *   2: 8 FP64 reciprocal square roots, each fed through one add
+ *   3: 4 LDS round trips (write, then read what another lane wrote)
+ *   4: 4 FP64 16x16x4 matrix instructions accumulating into one tile
+ *   5: 4 x (matrix instruction, vector instruction on its result, next matrix instruction)
+ *   6: 8 x (lane read into scalar registers, vector instruction that uses them)
+ *   7: 4 FP32 32x32x2 matrix instructions accumulating into one tile
+ * so that ns per instruction = 10 * out[i] / (iters * count_i).  `sink` (device,
+ * 64 doubles) receives the chains' values so that nothing is optimised away.
+ * Returns 0 or a hipError_t (iters must be in 1 .. 2^20).
+ */
+int xgemm_latency_probe(long long *out, double *sink, int iters, void *stream);
+
+/*
  * The paper's analytical kernel-selection model (host only, no device access).
  *
  * xgemm_model_outer_product_rate: Sec. 4.2.  Pipeline i retires rate[i]

@@ -45,6 +45,7 @@ from .xgemm import (  # noqa: F401
     xgemm_mfma_peak_probe,
     xgemm_mfma_layout_probe,
     xgemm_hwid_probe,
+    xgemm_latency_probe,
     xgemm_model_outer_product_rate,
     xgemm_model_stalled_rate,
     xgemm_model_n_updates,

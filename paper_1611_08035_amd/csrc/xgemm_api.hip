@@ -324,6 +324,92 @@ template <typename T> __global__ void __launch_bounds__(64) mfma_layout_kernel(i
     for (int r = 0; r < M::NR; ++r) out[lane * M::NR + r] = 256 * (int)di[r] + (int)dj[r];
 }
 
+// Latencies of dependent instruction chains as one lone wave sees them (the device's
+// counterpart of the per-instruction latency column of the paper's micro-architecture
+// table, Sec. 4.3: the k of W = L + n k).  Each section runs `iters` rounds of a chain
+// in which every instruction needs the result of the one before, bracketed by the
+// 100 MHz real-time counter; out[i] receives the ticks of section i (10 ns each):
+//   0: 8 double-precision fused multiply-adds          1: 8 single-precision ones
+//   2: 8 double-precision reciprocal square roots (each fed through one add)
+//   3: 4 LDS round trips (write, read what another lane wrote)
+//   4: 4 double-precision 16x16x4 matrix instructions accumulating into one tile
+//   5: 4 times matrix instruction -> vector instruction on its result -> matrix instruction
+//   6: 8 times lane read into scalar registers -> vector instruction that uses them
+//   7: 4 single-precision 32x32x2 matrix instructions accumulating into one tile
+__global__ void __launch_bounds__(64) latency_probe_kernel(long long *out, double *sink, int iters, double seed) {
+    __shared__ double buf[64];
+    const int lane = threadIdx.x;
+    double x = seed + lane * 1e-9;
+    const double y = 1.0000001;
+    long long t[9];
+    int n = 0;
+    auto mark = [&] { t[n++] = wall_clock64(); };
+    mark();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x = __builtin_fma(x, y, 1e-12);
+    }
+    mark();
+    {
+        float xf = (float)x;
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xf = __builtin_fmaf(xf, 1.0000001f, 1e-12f);
+        }
+        x = xf;
+    }
+    mark();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x = __builtin_amdgcn_rsq(x + 2.0);
+    }
+    mark();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            buf[lane] = x;
+            __builtin_amdgcn_wave_barrier();
+            x = buf[(lane + 1) & 63] + 1e-12;
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    mark();
+    acc_d4 acc = {x, x, x, x};
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x, y, acc, 0, 0, 0);
+    }
+    mark();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x, y, acc, 0, 0, 0);
+            x = acc[0] * 1e-30 + 1.0;
+        }
+    }
+    mark();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int lo = __builtin_amdgcn_readlane(__double2loint(x), (i + u) & 63);
+            const int hi = __builtin_amdgcn_readlane(__double2hiint(x), (i + u) & 63);
+            x = __builtin_fma(x, 1e-30, __hiloint2double(hi, lo));
+        }
+    }
+    mark();
+    acc_f16 accf;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accf[r] = (float)x;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) accf = __builtin_amdgcn_mfma_f32_32x32x2f32((float)y, 1.0f, accf, 0, 0, 0);
+    }
+    mark();
+    sink[lane] = x + acc[1] + accf[3];
+    if (lane == 0)
+        for (int i = 0; i < 8; ++i) out[i] = t[i + 1] - t[i];
+}
+
 // One record per wave: {HW_ID, XCC_ID, blockIdx.x, wave in block}.  The block
 // asks for `lds_bytes` of LDS so that its CU residency matches a GEMM kernel's.
 __global__ void __launch_bounds__(256, 2) hwid_kernel(unsigned *out) {
@@ -567,6 +653,12 @@ int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream) {
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return (int)attr;
     hipLaunchKernelGGL(hwid_kernel, dim3(blocks), dim3(256), (size_t)lds_bytes, static_cast<hipStream_t>(stream), out);
+    return (int)hipGetLastError();
+}
+
+int xgemm_latency_probe(long long *out, double *sink, int iters, void *stream) {
+    if (!out || !sink || iters <= 0 || iters > (1 << 20)) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(latency_probe_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), out, sink, iters, 1.5);
     return (int)hipGetLastError();
 }
 

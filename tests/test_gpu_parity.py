@@ -381,3 +381,24 @@ def test_config5_zgemm_4096_sampled():
         nviol, ratio = oracle.bound_violations(O[J, I], r, g, nsz, oracle.U64, factor=8.0)
         assert nviol == 0, ratio
         print("config5 zgemm 4096 sampled max err/bound", ratio)
+
+
+def test_latency_probe_reports_plausible_chains():
+    """The probe behind the measured latency table: every chain takes a positive time, a dependent
+    FP64 multiply-add costs a few cycles, and the slower kinds are slower (matrix instruction,
+    LDS round trip, lane read) -- the ordering the block kernels were designed around."""
+    torch = torch_mod()
+    out = torch.zeros(8, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(64, dtype=torch.float64, device="cuda")
+    iters = 2000
+    for _ in range(2):
+        assert xg.xgemm_latency_probe(out, sink, iters) == 0
+        torch.cuda.synchronize()
+    t = out.cpu().numpy().astype(np.float64)
+    per = np.array([8, 8, 8, 4, 4, 4, 8, 4], dtype=np.float64)
+    ns = 10.0 * t / (iters * per)
+    assert np.all(ns > 0.5) and np.all(ns < 500.0), ns
+    fma64, fma32, rsq, lds, mfma64, mfma_valu, lane, mfma32 = ns
+    assert fma64 < 20.0 and fma32 < 20.0
+    assert mfma64 > 2 * fma64 and lds > 2 * fma64 and lane > fma64 and rsq > fma64
+    assert xg.xgemm_latency_probe(out, sink, 0) != 0
