@@ -35,9 +35,15 @@ def hipcc() -> str:
     return exe
 
 
+# Per-file additions.  The block kernels of the level-3 routines read and move their matrix-instruction
+# accumulators with vector instructions (panels leave the tiles, tiles shift), so their accumulators live in
+# ordinary vector registers rather than in the accumulation registers the compiler would pick by default.
+EXTRA_FLAGS = {"xgemm_l3.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
-    cmd = [hipcc()] + HIPCC_FLAGS + ["-c", src, "-o", obj]
+    cmd = [hipcc()] + HIPCC_FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
