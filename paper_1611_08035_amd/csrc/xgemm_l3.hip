@@ -86,6 +86,18 @@ template <> struct Mma16<float> {
     static constexpr float TINY = 0x1p-96f, BIG = 0x1p100f;
 };
 
+// Compute units of the current device (256 on MI355X), read once per device.
+inline int device_cus() {
+    constexpr int MAX_DEV = 64;
+    static std::atomic<int> cached[MAX_DEV];             // 0: not read yet
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return 256;
+    if ((cus = cached[dev].load(std::memory_order_relaxed)) > 0) return cus;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+    cached[dev].store(cus, std::memory_order_relaxed);
+    return cus;
+}
+
 // Dynamic LDS beyond 64 KiB has to be requested explicitly: once per kernel and device.
 template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
     if (bytes <= 65536) return hipSuccess;
@@ -668,7 +680,7 @@ template <typename T> struct Tri {
             // precision, where a pivot costs one lane read instead of two, 4 per wave win throughout.)
             constexpr bool DBL = sizeof(T) == 8;
             constexpr int64_t SOLVE_WAVES = DBL ? 2048 : 4096;
-            constexpr int SOLVE_CUS = 256;
+            const int SOLVE_CUS = device_cus();
             auto fits = [&](int rpw) { return (a.nrhs + rpw - 1) / rpw <= SOLVE_WAVES; };
             if (dim <= NB) {
                 if (fits(4)) hipLaunchKernelGGL((trsm_block_kernel<T, 4>), grid(4), blk, 0, st, a);
