@@ -415,9 +415,10 @@ template <typename T> __global__ void __launch_bounds__(64 * WAVES) trmm_block_k
 }
 
 // The same products for diagonal blocks of order up to WIDE = 256.  The workgroup has
-// WAVES multiplying waves and as many feeding waves.  A multiplying wave owns MMA_RHS
-// right-hand sides: all 16-row tiles of their result stay in its accumulators, and
-// their elements arrive from memory four steps (one panel) at a time, two panels
+// eight multiplying waves and as many feeding waves.  A pair of multiplying waves owns
+// MMA_RHS right-hand sides: the upper and the lower eight 16-row tiles of their result
+// stay in the accumulators of the one and the other, and the elements of the
+// right-hand sides arrive from memory four steps (one panel) at a time, one panel
 // ahead of their use; nothing of the result is stored before the last panel, so the
 // product may overwrite its input.  E streams through LDS in panels of PANEL columns,
 // two halves in turn as in the solve above, written by the feeding waves.
@@ -439,67 +440,73 @@ template <typename T> struct WideProdArgs {
 template <typename T> constexpr size_t wide_prod_lds_bytes() { return 2 * PANEL * WIDE * sizeof(T); }
 
 template <typename T, int MODE>
-__global__ void __launch_bounds__(2 * 64 * WAVES) wide_product_kernel(const WideProdArgs<T> a) {
+__global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArgs<T> a) {
     using M = Mma16<T>;
     using acc_t = typename M::acc_t;
-    constexpr int DEPTH = 2, TILES = WIDE / 16, KS = PANEL / 4, NPAN = WIDE / PANEL;
+    constexpr int DEPTH = 2, TILES = WIDE / 16, HT = TILES / 2, KS = PANEL / 4, NPAN = WIDE / PANEL;
+    constexpr int MW = 2 * WAVES, FT = 64 * MW;          // multiplying waves; feeding threads (as many waves again)
+    constexpr int EL = PANEL * WIDE / FT;                // elements of a panel per feeding thread
+    static_assert(FT == 2 * WIDE && EL * FT == PANEL * WIDE, "two columns of a panel per pass");
     extern __shared__ __align__(16) unsigned char prod_lds[];
     T *const e_pan = reinterpret_cast<T *>(prod_lds);    // E(r, c0 + k) of panel p at [(p & 1) * PANEL * WIDE + k * WIDE + r]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lc = lane & 15, lk = lane >> 4;
-    const bool feeding = wave >= WAVES;                  // wave-uniform
-    const int tid = threadIdx.x & (64 * WAVES - 1);      // index within the waves of one kind
+    const bool feeding = wave >= MW;                     // wave-uniform
+    const int tid = (int)threadIdx.x - (feeding ? FT : 0);   // index within the waves of one kind
     const int dim = a.dim, npan = (dim + PANEL - 1) / PANEL;
 
-    // ---- multiplying waves: column operands, step sx supplies element (4 sx + lk) of right-hand side q.
-    // Positions are clamped into the block for the load and sorted out at the point of use.
-    const int q = (blockIdx.x * WAVES + (wave & (WAVES - 1))) * MMA_RHS + lc;
-    const bool live = !feeding && (blockIdx.x * WAVES + (wave & (WAVES - 1))) * MMA_RHS < a.nrhs;
+    // ---- multiplying waves: wave w takes right-hand sides 16 (w & 3) .. + 15 of the workgroup's 64 and the
+    // upper (w < 4) or lower eight 16-row tiles of their result.  Column operands: step sx supplies element
+    // (4 sx + lk) of right-hand side q; positions are clamped into the block for the load and sorted out at
+    // the point of use.
+    const int half = (wave >> 2) & 1, group = wave & (WAVES - 1);
+    const int q = (blockIdx.x * WAVES + group) * MMA_RHS + lc;
+    const bool live = !feeding && (blockIdx.x * WAVES + group) * MMA_RHS < a.nrhs;
     const int64_t xq = a.left ? a.ldx : 1, xs = a.left ? 1 : a.ldx;
     const T *const xcol = a.X + (int64_t)min(q, a.nrhs - 1) * xq;
-    T xr[3][KS];                                         // panel p in xr[p % 3]
+    T xr[2][KS];                                         // panel p in xr[p % 2]
     auto xfetch = [&](int p, int slot) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) xr[slot][ks] = xcol[(int64_t)min(p * PANEL + 4 * ks + lk, dim - 1) * xs];
     };
 
     // ---- feeding waves: thread -> (row r, column k of the panel) so that consecutive threads read
-    // consecutive memory: a thread keeps one row of E and walks the panel's columns, unless E is the
-    // transpose of the stored block, in which case it keeps one column and walks rows.  A fetch reads
-    // the stored element behind every position of the panel, also where E holds a zero or an implicit
-    // one (positions are clamped into the block, which is memory of the caller's matrix either way);
-    // what a position really holds is sorted out when the panel is stored, so that no lane mask has to
-    // live from the one to the other.  Only the panel's own 16 rows, the columns past the order and an
+    // consecutive memory: a thread keeps one row of E and walks every other column of the panel, unless
+    // E is the transpose of the stored block, in which case it keeps one column and walks rows.  A fetch
+    // reads the stored element behind every position of the panel, also where E holds a zero or an
+    // implicit one (positions are clamped into the block, which is memory of the caller's matrix either
+    // way); what a position really holds is sorted out when the panel is stored, so that no lane mask has
+    // to live from the one to the other.  Only the panel's own 16 rows, the columns past the order and an
     // implicit diagonal need sorting out: rows above them belong to tiles that are never multiplied,
     // rows below are plain entries, and rows past the order only reach results that are not stored.
     const bool by_col = MODE != 2 && a.etrans;
-    const int r0 = by_col ? tid / PANEL : tid, ru = by_col ? WIDE / PANEL : 0;
-    const int k0 = by_col ? tid % PANEL : 0, ku = by_col ? 0 : 1;
+    const int r0 = by_col ? tid / PANEL : tid % WIDE, ru = by_col ? FT / PANEL : 0;
+    const int k0 = by_col ? tid % PANEL : tid / WIDE, ku = by_col ? 0 : FT / WIDE;
     int c_next = k0;                                     // column of element 0 of the next panel to fetch
     const int rc = min(r0, dim - 1);                     // the thread's row, clamped (by_col: its first row)
-    T stage[DEPTH][PANEL];
+    T stage[DEPTH][EL];
     auto fetch = [&](int slot) {
         if (MODE == 2) {
 #pragma unroll
-            for (int u = 0; u < PANEL; ++u) {
-                const int c = min(c_next + u, dim - 1);
+            for (int u = 0; u < EL; ++u) {
+                const int c = min(c_next + u * ku, dim - 1);
                 const int i = a.stored_lower ? max(rc, c) : min(rc, c), j = a.stored_lower ? min(rc, c) : max(rc, c);
                 stage[slot][u] = a.A[i + (int64_t)j * a.lda];
             }
         } else if (!by_col) {
             const T *const rowp = a.A + rc;
 #pragma unroll
-            for (int u = 0; u < PANEL; ++u) stage[slot][u] = rowp[(int64_t)min(c_next + u, dim - 1) * a.lda];   // a uniform offset
+            for (int u = 0; u < EL; ++u) stage[slot][u] = rowp[(int64_t)min(c_next + u * ku, dim - 1) * a.lda];
         } else {
             const T *const colp = a.A + min(c_next, dim - 1);
 #pragma unroll
-            for (int u = 0; u < PANEL; ++u) stage[slot][u] = colp[(int64_t)min(r0 + u * ru, dim - 1) * a.lda];
+            for (int u = 0; u < EL; ++u) stage[slot][u] = colp[(int64_t)min(r0 + u * ru, dim - 1) * a.lda];
         }
         c_next += PANEL;
     };
     const int nonunit = a.unit ? 0 : 1;
     auto stash = [&](int p, int slot) {
 #pragma unroll
-        for (int u = 0; u < PANEL; ++u) {
+        for (int u = 0; u < EL; ++u) {
             const int r = r0 + u * ru, k = k0 + u * ku, c = p * PANEL + k;
             T v = stage[slot][u];
             if (MODE == 2) {
@@ -512,81 +519,101 @@ __global__ void __launch_bounds__(2 * 64 * WAVES) wide_product_kernel(const Wide
             e_pan[(p & 1) * (PANEL * WIDE) + k * WIDE + r] = v;
         }
     };
-    acc_t acc[TILES];
+    acc_t acc[HT];
     if (feeding) {
 #pragma unroll
         for (int sl = 0; sl < DEPTH; ++sl) fetch(sl);    // a panel past the order is read at clamped positions and stored as zeros
         stash(0, 0);
         fetch(0);
+        __syncthreads();
     } else {
         xfetch(0, 0);
-        xfetch(1, 1);
 #pragma unroll
-        for (int t = 0; t < TILES; ++t)
+        for (int t = 0; t < HT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[t][r] = T(0);
+        __syncthreads();
     }
-    __syncthreads();
 
-    auto panel = [&](auto p_tag) {
+    // the products of panel p for the half H of the tiles (both compile-time): straight-line code, tiles
+    // innermost so that consecutive matrix instructions work on different accumulators
+    auto multiply = [&](auto p_tag, auto h_tag) {
+        constexpr int p = decltype(p_tag)::value, H = decltype(h_tag)::value;
+        const T *const pan = e_pan + (p & 1) * (PANEL * WIDE);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int sx = p * KS + ks;
+            const T xv = (4 * sx + lk < dim && q < a.nrhs) ? xr[p % 2][ks] : T(0);
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt) {
+                const int t = H * HT + tt;
+                const bool nonzero = MODE == 0 ? sx <= 4 * t + 3 : MODE == 1 ? sx >= 4 * t : true;   // compile-time
+                if (nonzero) acc[tt] = M::mma(pan[(4 * ks + lk) * WIDE + 16 * t + lc], xv, acc[tt]);
+            }
+        }
+    };
+    // One step per panel and kind of wave; both kinds meet at the same barriers.  The two kinds run
+    // through separate code from here on, so that neither carries the other's registers along.
+    auto feed_step = [&](auto p_tag) {
         constexpr int p = decltype(p_tag)::value;
         if (p >= npan) return;                           // uniform over the workgroup
-        if (feeding) {
-            if (p + 1 < npan) {
-                constexpr int slot = (p + 1) % DEPTH;
-                stash(p + 1, slot);                      // into the half that nobody reads during this step
-                fetch(slot);                             // panel p + 1 + DEPTH
-            }
-        } else if (live) {
-            xfetch(p + 2, (p + 2) % 3);
-            const T *const pan = e_pan + (p & 1) * (PANEL * WIDE);
-            // Every tile takes part whatever the order, in straight-line code.  An earlier form jumped
-            // around the tiles past the order; it left the last four rows of the last tile short of
-            // their final update for orders 176-208, in some waves of some runs only.  The cause was
-            // not established (a read of a matrix-instruction result one wait state after the
-            // instruction was checked on the device and is interlocked), so the form that every order
-            // of 1..256 passes repeatedly is kept and tested as such.
-            // Tiles innermost: consecutive matrix instructions then work on different accumulators.
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int sx = p * KS + ks;
-                const T xv = (4 * sx + lk < dim && q < a.nrhs) ? xr[p % 3][ks] : T(0);
-#pragma unroll
-                for (int t = 0; t < TILES; ++t) {
-                    const bool nonzero = MODE == 0 ? sx <= 4 * t + 3 : MODE == 1 ? sx >= 4 * t : true;   // compile-time
-                    if (nonzero) acc[t] = M::mma(pan[(4 * ks + lk) * WIDE + 16 * t + lc], xv, acc[t]);
-                }
-            }
+        if (p + 1 < npan) {
+            constexpr int slot = (p + 1) % DEPTH;
+            stash(p + 1, slot);                          // into the half that nobody reads during this step
+            fetch(slot);                                 // panel p + 1 + DEPTH
+        }
+        __syncthreads();
+    };
+    auto multiply_step = [&](auto p_tag) {
+        constexpr int p = decltype(p_tag)::value;
+        if (p >= npan) return;                           // uniform over the workgroup
+        if (live) {
+            xfetch(p + 1, (p + 1) % 2);
+            // Every tile of the wave's half takes part whatever the order, in straight-line code.  An
+            // earlier form jumped around the tiles past the order; it left the last four rows of the last
+            // tile short of their final update for orders 176-208, in some waves of some runs only.  The
+            // cause was not established (a read of a matrix-instruction result one wait state after the
+            // instruction was checked on the device and is interlocked), so the form that every order of
+            // 1..256 passes repeatedly is kept and tested as such.
+            if (half == 0) multiply(p_tag, std::integral_constant<int, 0>{});
+            else multiply(p_tag, std::integral_constant<int, 1>{});
         }
         __syncthreads();
     };
     static_assert(NPAN == 16, "sixteen panels, spelled out so that every register index is a constant");
-    panel(std::integral_constant<int, 0>{});
-    panel(std::integral_constant<int, 1>{});
-    panel(std::integral_constant<int, 2>{});
-    panel(std::integral_constant<int, 3>{});
-    panel(std::integral_constant<int, 4>{});
-    panel(std::integral_constant<int, 5>{});
-    panel(std::integral_constant<int, 6>{});
-    panel(std::integral_constant<int, 7>{});
-    panel(std::integral_constant<int, 8>{});
-    panel(std::integral_constant<int, 9>{});
-    panel(std::integral_constant<int, 10>{});
-    panel(std::integral_constant<int, 11>{});
-    panel(std::integral_constant<int, 12>{});
-    panel(std::integral_constant<int, 13>{});
-    panel(std::integral_constant<int, 14>{});
-    panel(std::integral_constant<int, 15>{});
-    if (feeding || q >= a.nrhs) return;
+    auto all_panels = [&](auto step) {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 5>{});
+        step(std::integral_constant<int, 6>{});
+        step(std::integral_constant<int, 7>{});
+        step(std::integral_constant<int, 8>{});
+        step(std::integral_constant<int, 9>{});
+        step(std::integral_constant<int, 10>{});
+        step(std::integral_constant<int, 11>{});
+        step(std::integral_constant<int, 12>{});
+        step(std::integral_constant<int, 13>{});
+        step(std::integral_constant<int, 14>{});
+        step(std::integral_constant<int, 15>{});
+    };
+    if (feeding) {
+        all_panels(feed_step);
+        return;
+    }
+    all_panels(multiply_step);
+    if (q >= a.nrhs) return;
     const int64_t yq = a.left ? a.ldy : 1, ys = a.left ? 1 : a.ldy;
 #pragma unroll
-    for (int t = 0; t < TILES; ++t)
+    for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int rr = 16 * t + M::drow(lane, r);
+            const int rr = 16 * (half * HT + tt) + M::drow(lane, r);
             if (rr < dim) {
                 T *y = a.Y + (int64_t)rr * ys + (int64_t)q * yq;
-                *y = MODE == 2 ? *y + a.alpha * acc[t][r] : a.alpha * acc[t][r];
+                *y = MODE == 2 ? *y + a.alpha * acc[tt][r] : a.alpha * acc[tt][r];
             }
         }
 }
@@ -596,7 +623,7 @@ template <typename T, int MODE> int launch_wide_product(const WideProdArgs<T> &a
     constexpr int PER_WG = MMA_RHS * WAVES;
     const hipError_t e = allow_lds(wide_product_kernel<T, MODE>, LDS);
     if (e != hipSuccess) return (int)e;
-    hipLaunchKernelGGL((wide_product_kernel<T, MODE>), dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(2 * 64 * WAVES), LDS,
+    hipLaunchKernelGGL((wide_product_kernel<T, MODE>), dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(16 * 64), LDS,
                        static_cast<hipStream_t>(stream), a);
     return (int)hipGetLastError();
 }
