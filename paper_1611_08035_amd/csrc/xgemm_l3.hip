@@ -197,25 +197,25 @@ template <typename T, int RPW> __global__ void __launch_bounds__(64 * WAVES) trs
 constexpr int GROUPS = 4, WIDE = 64 * GROUPS, PANEL = 16;
 template <typename T> constexpr size_t wide_lds_bytes() { return (2 * PANEL * WIDE + WIDE) * sizeof(T); }
 
-template <typename T, int RPW, int DEPTH, int FEED>
-__global__ void __launch_bounds__(64 * (WAVES + FEED)) trsm_wide_kernel(const BlockArgs<T> a) {
-    static_assert(64 * WAVES == WIDE && 64 % PANEL == 0 && DEPTH >= 1, "panels do not straddle groups");
-    constexpr int FT = FEED ? 64 * FEED : 64 * WAVES;   // feeding threads
+template <typename T, int RPW, int DEPTH, int FEED, int SW>
+__global__ void __launch_bounds__(64 * (SW + FEED)) trsm_wide_kernel(const BlockArgs<T> a) {
+    static_assert(64 % PANEL == 0 && DEPTH >= 1 && (FEED > 0 || 64 * SW == WIDE), "panels do not straddle groups");
+    constexpr int FT = FEED ? 64 * FEED : 64 * SW;      // feeding threads
     constexpr int EL = PANEL * WIDE / FT;               // elements of a panel per feeding thread
     static_assert(FT % WIDE == 0 && EL * FT == PANEL * WIDE, "whole columns of a panel per pass");
     extern __shared__ __align__(16) unsigned char wide_lds[];
     T *const e_pan = reinterpret_cast<T *>(wide_lds);   // two panels: E'(r, c0 + k) at [half * PANEL * WIDE + k * WIDE + r], zero on and above the diagonal
     T *const d_inv = e_pan + 2 * PANEL * WIDE;           // 1 / E(c, c)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const bool feeding = FEED == 0 || wave >= WAVES;     // wave-uniform; FEED == 0: every wave both feeds and solves
-    const bool solving = FEED == 0 || wave < WAVES;
-    const int tid = FEED == 0 ? (int)threadIdx.x : (int)threadIdx.x - 64 * WAVES;   // index among the feeding threads
+    const bool feeding = FEED == 0 || wave >= SW;        // wave-uniform; FEED == 0: every wave both feeds and solves
+    const bool solving = FEED == 0 || wave < SW;
+    const int tid = FEED == 0 ? (int)threadIdx.x : (int)threadIdx.x - 64 * SW;      // index among the feeding threads
     const int dim = a.nbk;
     const bool e_lower = (a.stored_lower != 0) != (a.etrans != 0);
     const int npan = (dim + PANEL - 1) / PANEL;
 
     // ---- solving waves: right-hand sides q0 .. q0 + RPW - 1; lane holds elements lane + 64 g of each
-    const int q0 = (blockIdx.x * WAVES + (wave & (WAVES - 1))) * RPW;
+    const int q0 = (blockIdx.x * SW + (wave % SW)) * RPW;
     const int64_t qs = a.left ? a.ldb : 1, xs = a.left ? 1 : a.ldb;
     const bool live = solving && q0 < a.nrhs;
     T y[GROUPS][RPW];
@@ -287,15 +287,18 @@ __global__ void __launch_bounds__(64 * (WAVES + FEED)) trsm_wide_kernel(const Bl
     }
     __syncthreads();
 
-    // columns of group gc (compile-time), panel by panel
-    auto group = [&](auto gc_tag) {
+    // columns of group gc (compile-time), panel by panel; SOLVE and FEED_TOO say which of the two jobs
+    // this instance of the code does (both for FEED == 0; otherwise the two kinds of waves run through
+    // separate instances, so that neither carries the other's registers, and meet at the barriers)
+    auto group = [&](auto gc_tag, auto solve_tag, auto feed_tag) {
         constexpr int gc = decltype(gc_tag)::value;
+        constexpr bool SOLVE = decltype(solve_tag)::value, FEED_TOO = decltype(feed_tag)::value;
         constexpr int PER = 64 / PANEL;
 #pragma unroll
         for (int pp = 0; pp < PER; ++pp) {
             const int p = gc * PER + pp;
             if (p >= npan) break;    // uniform over the workgroup
-            if (live) {
+            if (SOLVE && live) {
                 const T *const pan = e_pan + (p & 1) * (PANEL * WIDE);
                 // the multipliers of column k + 1 are read while column k is applied
                 T e[GROUPS], e_next[GROUPS];
@@ -317,7 +320,7 @@ __global__ void __launch_bounds__(64 * (WAVES + FEED)) trsm_wide_kernel(const Bl
                     for (int g = gc; g < GROUPS; ++g) e[g] = e_next[g];
                 }
             }
-            if (feeding && p + 1 < npan) {
+            if (FEED_TOO && p + 1 < npan) {
                 const int slot = (gc * PER + pp + 1) % DEPTH;            // a constant once the loop is unrolled
                 stash(p + 1, slot);              // into the half that the solving waves left at the last barrier
                 if (p + 1 + DEPTH < npan) fetch(p + 1 + DEPTH, slot);
@@ -325,10 +328,20 @@ __global__ void __launch_bounds__(64 * (WAVES + FEED)) trsm_wide_kernel(const Bl
             __syncthreads();
         }
     };
-    group(std::integral_constant<int, 0>{});
-    group(std::integral_constant<int, 1>{});
-    group(std::integral_constant<int, 2>{});
-    group(std::integral_constant<int, 3>{});
+    auto groups = [&](auto solve_tag, auto feed_tag) {
+        group(std::integral_constant<int, 0>{}, solve_tag, feed_tag);
+        group(std::integral_constant<int, 1>{}, solve_tag, feed_tag);
+        group(std::integral_constant<int, 2>{}, solve_tag, feed_tag);
+        group(std::integral_constant<int, 3>{}, solve_tag, feed_tag);
+    };
+    if (FEED == 0) {
+        groups(std::true_type{}, std::true_type{});
+    } else if (feeding) {
+        groups(std::false_type{}, std::true_type{});
+        return;
+    } else {
+        groups(std::true_type{}, std::false_type{});
+    }
 
     if (!live) return;
 #pragma unroll
@@ -716,19 +729,20 @@ template <typename T> struct Tri {
             } else {
                 constexpr size_t LDS = wide_lds_bytes<T>();
                 hipError_t e = hipSuccess;
-                auto go = [&](auto kern, int rpw, int feed) {
+                auto go = [&](auto kern, int rpw, int feed, int sw) {
                     if ((e = allow_lds(kern, LDS)) == hipSuccess)
-                        hipLaunchKernelGGL(kern, grid(rpw), dim3(64 * (WAVES + feed)), LDS, st, a);
+                        hipLaunchKernelGGL(kern, dim3((unsigned)((a.nrhs + rpw * sw - 1) / (rpw * sw))), dim3(64 * (sw + feed)), LDS, st, a);
                 };
-                // Separate feeding waves pay while a workgroup has a compute unit to itself: the fewest
-                // right-hand sides per wave that still keep the workgroups within the compute units;
-                // beyond that, workgroups whose waves do both.
-                auto alone = [&](int rpw) { return grid(rpw).x <= (unsigned)SOLVE_CUS; };
-                if (DBL && alone(2)) go(trsm_wide_kernel<T, 2, 4, 8>, 2, 8);
-                else if (alone(4)) go(trsm_wide_kernel<T, 4, 3, 8>, 4, 8);
-                else if (alone(8)) go(trsm_wide_kernel<T, 8, 2, 8>, 8, 8);
-                else if (fits(4)) go(trsm_wide_kernel<T, 4, 3, 0>, 4, 0);       // single precision only: more than 2048 waves of 4
-                else go(trsm_wide_kernel<T, 8, 2, 0>, 8, 0);
+                // Separate feeding waves pay while a workgroup has a compute unit to itself: four solving
+                // and eight feeding waves, with the fewest right-hand sides per wave that still keep the
+                // workgroups within the compute units; beyond that, workgroups of four waves that do both.
+                // (Eight solving waves with half the right-hand sides each were no faster at 8192
+                // right-hand sides and slower at few.)
+                auto alone = [&](int rpw) { return (a.nrhs + WAVES * rpw - 1) / (WAVES * rpw) <= SOLVE_CUS; };
+                if (DBL && alone(2)) go(trsm_wide_kernel<T, 2, 4, 8, WAVES>, 2, 8, WAVES);
+                else if (alone(4)) go(trsm_wide_kernel<T, 4, 3, 8, WAVES>, 4, 8, WAVES);
+                else if (alone(8)) go(trsm_wide_kernel<T, 8, 2, 8, WAVES>, 8, 8, WAVES);
+                else go(trsm_wide_kernel<T, 8, 2, 0, 4>, 8, 0, 4);
                 if (e != hipSuccess) return (int)e;
             }
         }

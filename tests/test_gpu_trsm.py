@@ -129,7 +129,8 @@ def test_full_size_sampled_residual(dtype, side, uplo, trans, diag, m, n):
                          [(np.float64, "L", 50, 9000), (np.float64, "R", 64, 17000), (np.float64, "L", 200, 5000),
                           (np.float64, "R", 256, 9000), (np.float64, "L", 250, 3000), (np.float64, "R", 256, 700),
                           (np.float32, "L", 60, 17000), (np.float32, "R", 33, 33000), (np.float32, "L", 130, 17000),
-                          (np.float32, "R", 256, 3000), (np.float32, "L", 200, 5000), (np.float32, "R", 256, 10000)])
+                          (np.float32, "R", 256, 3000), (np.float32, "L", 200, 5000), (np.float32, "R", 256, 10000),
+                          (np.float64, "L", 200, 17000), (np.float32, "R", 256, 17000)])
 def test_many_right_hand_sides_on_one_small_triangle(dtype, side, dim, nrhs):
     """The diagonal-block kernels pack 2 to 16 right-hand sides into a wave, and the one for orders
     up to 256 runs with or without separate feeding waves, depending on how many right-hand sides
