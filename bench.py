@@ -239,6 +239,10 @@ def sweep(torch, np, xg, si, args):
         for k in (64, 128, 256):
             rows.append(("d", "N", "N", mn, mn, k, mn, k, mn, -1.0, 1.0, 4, "normal"))
     rows.append(("d", "N", "N", 4097, 3001, 257, 4097, 257, 4097, -1.0, 1.0, 4, "normal"))
+    # ragged everywhere (edge tiles along both sides, a partial last slab, a partly filled last round)
+    rows.append(("d", "N", "N", 5000, 5000, 5000, 5000, 5000, 5000, 1.5, -0.5, 2, "uniform"))
+    rows.append(("d", "T", "N", 7001, 7001, 7001, 7001, 7001, 7001, 1.5, -0.5, 2, "uniform"))
+    rows.append(("s", "N", "T", 7001, 7003, 7000, 7001, 7003, 7001, 1.5, -0.5, 3, "uniform"))
     want = lambda name: args.only is None or args.only in name
     for prec, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, cfg, kind in rows:
         if not want(f"{prec}gemm {ta}{tb} {m}x{n}x{k}"):

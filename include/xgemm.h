@@ -268,10 +268,13 @@ const char *xgemm_last_kernel_name(void);
  */
 int xgemm_force_variant(int variant);
 
-/* Benchmark/tuning control for the *_ws routines on the calling thread: -1 lets
- * the cost model decide (default), 0 never splits, 2..32 splits the tail tiles
- * into that many pieces wherever the shape and workspace allow.  Returns 0, or
- * -1 for any other value.  xgemm_last_split(): pieces per tail tile used by the
+/* Benchmark/tuning control, on the calling thread, of what happens to the tiles
+ * of the last, partly filled round of workgroups: -1 lets the cost model decide
+ * (default); 0 runs them like the others; 1 runs them as quarter tiles in a
+ * second launch wherever the shape has such a tail and a variant of half the
+ * tile size exists (all real products and rank-k updates); 2..32 splits them
+ * along K into that many pieces wherever the shape and workspace allow (the
+ * *_ws routines).  Returns 0, or -1 for any other value.  xgemm_last_split(): pieces per tail tile used by the
  * last call on this thread (1: nothing was split). */
 int xgemm_force_split(int pieces);
 int xgemm_last_split(void);
@@ -280,7 +283,11 @@ int xgemm_last_split(void);
  * What the library would launch for a product of this shape (host only; uses
  * the CU count of the current device, 256 if there is none): out[0] tile
  * variant, out[1] pieces per split tail tile (1: none), out[2] number of tiles
- * computed whole.  prec 'd' / 's'; uplo 0 general, 1 / 2 triangular (syrk,
+ * of that variant computed whole.  If out[1] is 1 and out[2] is less than the
+ * number of tiles, the remaining tiles run as four quarter tiles each, with the
+ * variant of half the tile size, in a second launch (the form the last, partly
+ * filled round of workgroups takes when there is no workspace to split it along K).
+ * prec 'd' / 's'; uplo 0 general, 1 / 2 triangular (syrk,
  * m == n); lwork: size of the workspace the call would be given (0: none).
  * Honours xgemm_force_variant / xgemm_force_split.  Returns 0 or -i.
  */

@@ -113,6 +113,12 @@ template <typename T> struct GemmArgs {
     int ndp, nsplit;
     T *part;
     unsigned *cnt;
+    // Quartered tail (no workspace needed): a first launch computes only the first `first` tiles of the
+    // order (0: all of them); a second launch with the variant of half the tile size in both directions
+    // computes the remaining `sub_count` tiles as four quarter tiles each (sub_count > 0: workgroup b takes
+    // quarter b & 3 of tile sub_base + (b >> 2) of the order over sub_ntm x sub_ntn tiles of twice the size).
+    int first;
+    int sub_count, sub_base, sub_ntm, sub_ntn;
 };
 
 // ---------------------------------------------------------------------------
@@ -211,6 +217,26 @@ template <typename T, int MT, int KT, int S, int NT, bool KCONTIG> struct Stager
                 }
             }
         }
+    }
+
+    // Edge tile, once per tile: vectors that lie wholly at or beyond mn_lim are sent
+    // out of range for good (they load zeros in every slab), so that full-depth
+    // slabs of an edge tile take the same 16-byte loads as an interior tile.  A
+    // vector that straddles the limit (MN-contiguous slabs with mn_lim not a
+    // multiple of V) is still loaded whole: what it picks up beyond the limit
+    // comes from the same stored column of the operand and only ever feeds rows
+    // or columns of C that are never stored.
+    static __device__ __forceinline__ void trim(uint32_t (&off)[NV], int tid, int mn_lim) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            int mn, p;
+            pos(tid, q, mn, p);
+            if (mn >= mn_lim) off[q] = RANGE;
+        }
+    }
+    // whether some vector of an edge tile straddles the limit (the same for every thread)
+    static __device__ __forceinline__ bool straddles(int mn_lim) {
+        return !KCONTIG && mn_lim < MT && (mn_lim % V) != 0;
     }
 
     // fallback without buffer addressing (leading dimensions too large for 32-bit
@@ -450,8 +476,17 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     } else {
         lin = lin_of_block(blockIdx.x, (int)gridDim.x);
     }
-    const TilePos tp = tile_of_lin(lin, g.ntm, g.ntn, g.uplo, MT_M, MT_N);
-    const int tm = tp.tm, tn = tp.tn;
+    int tm, tn;
+    if (!SPLIT && g.sub_count > 0) {
+        const int b = blockIdx.x;
+        const TilePos big = tile_of_lin(g.sub_base + (b >> 2), g.sub_ntm, g.sub_ntn, g.uplo, 2 * MT_M, 2 * MT_N);
+        tm = 2 * big.tm + (b & 1);
+        tn = 2 * big.tn + ((b >> 1) & 1);
+    } else {
+        const TilePos tp = tile_of_lin(lin, g.ntm, g.ntn, g.uplo, MT_M, MT_N);
+        tm = tp.tm;
+        tn = tp.tn;
+    }
     if (tm >= g.ntm || tn >= g.ntn) return;   // cannot happen when the grid is tile_count() workgroups
     const int m0 = tm * MT_M, n0 = tn * MT_N;
     const int m_lim = g.m - m0, n_lim = g.n - n0;   // rows / cols of this tile inside C
@@ -466,7 +501,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
         if (n0 + MT_N - 1 < m0) return;
         on_diagonal = n0 < m0 + MT_M - 1;
     }
-    const bool interior = FAST && m_lim >= MT_M && n_lim >= MT_N;
+    const bool edge = m_lim < MT_M || n_lim < MT_N;
 
     // K range of this workgroup: all of it, or piece `piece` of `npieces` in whole slabs
     int k_begin = 0, k_len = g.k;
@@ -506,12 +541,26 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     uint32_t offa[StA::NV], offb[StB::NV];
     StA::offsets(offa, g.lda, tid);
     StB::offsets(offb, g.ldb, tid);
+    // Full-depth slabs go the 16-byte way on edge tiles too, with the vectors
+    // outside the tile's rows and columns switched off.  A vector that straddles
+    // the edge reads up to V - 1 elements past it; in the last stored column of
+    // the operand those could lie past the end of the array, so with a straddle
+    // a slab goes the fast way only while another column follows it (guard), and
+    // not at all if the columns are shorter than a vector.
+    bool hot = FAST;
+    int guard = 0;
+    if (FAST && edge) {
+        StA::trim(offa, tid, m_lim);
+        StB::trim(offb, tid, n_lim);
+        if (StA::straddles(m_lim)) { guard = 1; hot = hot && g.lda >= StA::V; }
+        if (StB::straddles(n_lim)) { guard = 1; hot = hot && g.ldb >= StB::V; }
+    }
 
     const int nslab = (k_len + KT - 1) / KT;
 
     auto fetch = [&](int t) {
         const int k_lim = k_len - t * KT;
-        if (interior && k_lim >= KT) {
+        if (hot && k_lim >= KT + guard) {
             StA::load_fast(ra, pa, offa);
             StB::load_fast(rb, pb, offb);
         } else if (FAST) {
@@ -640,8 +689,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     };
     // Two slabs per trip so that the LDS buffer index is a constant in the code.
     int t = 0;
-    if (interior) {
-        const int nfull = k_len / KT;   // slabs 0..nfull-1 are full
+    if (hot) {
+        const int nfull = (k_len - guard) / KT;   // slabs 0..nfull-1 are full (and, with a straddle, not the last column)
         for (; t + 2 < nfull; t += 2) {
             slab_hot(0);
             slab_hot(1);

@@ -13,7 +13,7 @@ using namespace xg;
 
 thread_local const char *t_last_kernel = "";
 thread_local int t_forced_variant = -1;
-thread_local int t_forced_split = -1;   // -1: the model decides; 0: never split; S >= 2: split into S pieces where feasible
+thread_local int t_forced_split = -1;   // -1: the model decides; 0: plain tail; 1: quartered tail; S >= 2: S pieces where feasible
 thread_local int t_last_split = 1;
 // tuning knob (environment XGEMM_REQUIRE_ALIGNED=1): send operands that are not
 // 16-byte aligned to the element-wise fallback instead of the buffer-load path
@@ -56,11 +56,14 @@ constexpr double LONE_EFF = 0.95;        // a CU holding one workgroup, relative
 constexpr double REDUCE_GBS = 80.0;      // rate at which one workgroup reads partial tiles back
 constexpr double PART_TBS = 6.0;         // rate at which all partial tiles are written and read
 constexpr double T_SPLIT0 = 2.0;         // arrival counting
+constexpr double T_LAUNCH = 4.0;         // a second launch on the same stream
+constexpr int64_t QUARTER_MIN_K = 1024;  // shallower products gain nothing from a quartered tail (measured)
 
 struct Plan {
     int v;          // tile variant
     int nsplit;     // pieces per split tile (1: nothing is split)
     int64_t ndp;    // tiles computed whole
+    int vq;         // >= 0: the tiles past ndp run as quarter tiles of this variant in a second launch
 };
 
 // Pick a tile variant, and whether to split the last partial round along K, with
@@ -75,12 +78,15 @@ struct Plan {
 // tiles of that round may instead be cut into S <= slots / rem pieces of depth
 // k / S each; that adds the write and read of rem * S partial tiles and the
 // serial read of S partial tiles by the workgroup that finishes each tile.
+// Without a workspace the rem tiles may instead run as 4 rem quarter tiles of the variant with
+// half the tile size in both directions, in a second launch: a quarter of the depth-k work per
+// workgroup, at that variant's efficiency, plus the launch.
 template <typename T>
 Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> *tab, int nv, bool fast,
                size_t lwork) {
     const int64_t cus = num_cus();
     const double cu_flops_per_us = (sizeof(T) == 8 ? 32.0 : 64.0) * 4.0 * CLOCK_GHZ * 1e3;   // flop / us
-    Plan best{0, 1, 0};
+    Plan best{0, 1, 0, -1};
     double best_cost = 0.0;
     const bool forced_v = t_forced_variant >= 0 && t_forced_variant < nv;
     const int v_lo = forced_v ? t_forced_variant : 0, v_hi = forced_v ? t_forced_variant + 1 : nv;
@@ -98,8 +104,19 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
             return T_ROUND0 + (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : 1.0);
         };
         const double rounds = (double)full * e.wgs_per_cu * t_tile((double)k);
-        Plan p{v, 1, tiles};
+        Plan p{v, 1, tiles, -1};
         double cost = rounds + (rem > 0 ? t_tail(rem, (double)k) : 0.0);
+        if (rem > 0 && full > 0 && fast && t_forced_split != 0 && (k >= QUARTER_MIN_K || t_forced_split == 1)) {
+            for (int w = 0; w < nv; ++w) {
+                if (tab[w].mt_m * 2 != e.mt_m || tab[w].mt_n * 2 != e.mt_n) continue;
+                const double qarea = (double)tab[w].mt_m * (double)tab[w].mt_n;
+                const int64_t occ = (4 * rem + cus - 1) / cus;
+                const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * tab[w].eff);
+                const double c = rounds + T_LAUNCH + T_ROUND0 + (double)occ * tq / (occ == 1 ? LONE_EFF : 1.0);
+                if (c < cost || t_forced_split == 1) { cost = c; p.ndp = full * slots; p.vq = w; }
+                break;
+            }
+        }
         if (rem > 0 && e.has_split && fast && lwork > WS_CNT_BYTES && t_forced_split != 0 &&
             rem <= (int64_t)(WS_CNT_BYTES / sizeof(unsigned))) {
             const int64_t nslab = (k + e.kt - 1) / e.kt;
@@ -117,11 +134,12 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
                 const int64_t S = t_forced_split < smax ? t_forced_split : smax;
                 p.nsplit = (int)S;
                 p.ndp = full * slots;
+                p.vq = -1;
                 cost = t_split(S);
             } else if (t_forced_split < 0) {
                 for (int64_t S = 2; S <= smax; ++S) {
                     const double c = t_split(S);
-                    if (c < cost) { cost = c; p.nsplit = (int)S; p.ndp = full * slots; }
+                    if (c < cost) { cost = c; p.nsplit = (int)S; p.ndp = full * slots; p.vq = -1; }
                 }
             }
         }
@@ -189,6 +207,8 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     g.nsplit = 1;
     g.part = nullptr;
     g.cnt = nullptr;
+    g.first = 0;
+    g.sub_count = g.sub_base = g.sub_ntm = g.sub_ntn = 0;
     if (fast && plan.nsplit > 1) {
         g.ndp = (int)plan.ndp;
         g.nsplit = plan.nsplit;
@@ -198,6 +218,20 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     }
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
+    if (fast && plan.nsplit == 1 && plan.vq >= 0 && v == plan.v) {
+        // the full rounds with this variant, then the tail as quarter tiles of the smaller one
+        const int big_ntm = (int)((m + tab[v].mt_m - 1) / tab[v].mt_m), big_ntn = (int)((n + tab[v].mt_n - 1) / tab[v].mt_n);
+        const int64_t tiles = tile_count(uplo, big_ntm, big_ntn, tab[v].mt_m, tab[v].mt_n);
+        g.first = (int)plan.ndp;
+        const hipError_t e1 = tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
+        if (e1 != hipSuccess) return (int)e1;
+        g.first = 0;
+        g.sub_count = (int)(tiles - plan.ndp);
+        g.sub_base = (int)plan.ndp;
+        g.sub_ntm = big_ntm;
+        g.sub_ntn = big_ntn;
+        return (int)tab[plan.vq].launch(is_t(ta), is_n(tb), fast, g, st);
+    }
     return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
 }
 
@@ -511,7 +545,7 @@ int xgemm_plan(char prec, int uplo, int64_t m, int64_t n, int64_t k, size_t lwor
 }
 
 int xgemm_force_split(int pieces) {
-    if (pieces < -1 || pieces == 1 || pieces > SPLIT_MAX) return -1;
+    if (pieces < -1 || pieces > SPLIT_MAX) return -1;
     t_forced_split = pieces;
     return 0;
 }

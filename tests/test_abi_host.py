@@ -186,7 +186,7 @@ def test_workspace_routines_host_side():
         assert f("L", "N", 3, 2, 1.0, P, 3, 0.0, P, 2, P, 1 << 20, stream=0) == -10
         assert f("L", "N", 2, 2, 1.0, P, 2, 0.0, P, 2, P + 4, 1 << 20, stream=0) == -11
         assert f("L", "N", 0, 2, 1.0, None, 1, 0.0, None, 1, None, 0, stream=0) == 0
-    assert xg.xgemm_force_split(1) == -1 and xg.xgemm_force_split(33) == -1 and xg.xgemm_force_split(-2) == -1
+    assert xg.xgemm_force_split(33) == -1 and xg.xgemm_force_split(-2) == -1 and xg.xgemm_force_split(1) == 0
     assert xg.xgemm_force_split(4) == 0 and xg.xgemm_force_split(0) == 0 and xg.xgemm_force_split(-1) == 0
     assert xg.xgemm_last_split() == 1
 

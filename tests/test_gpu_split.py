@@ -117,7 +117,9 @@ def test_model_splits_only_the_last_round_and_small_workspaces_split_less(ws):
         out = dC.cpu().numpy()
         nviol, ratio = oracle.bound_violations(out[J, I], cref, gb, k, oracle.U64, 4.0)
         assert nviol == 0, (nbytes, nviol, ratio)
-    assert seen[0] >= 8 and seen[1] == 3 and seen[2] == 1 and seen[3] == 1, seen
+    # room for 3 pieces per tile: a 3-way split, unless the model rates running the tail as quarter
+    # tiles (which needs no workspace) cheaper than so shallow a split
+    assert seen[0] >= 8 and seen[1] in (1, 3) and seen[2] == 1 and seen[3] == 1, seen
     assert counters_are_zero(w)
     # without a workspace the routine is the plain one
     dC = to_dev(C)

@@ -55,6 +55,31 @@ def test_tail_round_is_split_only_with_a_workspace_and_only_the_tail():
     assert name("d", v) == "d_128x128x16_w2x2" and whole == 2048 and pieces == 8      # 2080 tiles: 32 in the tail
 
 
+def test_without_a_workspace_the_tail_round_of_a_deep_product_runs_as_quarter_tiles():
+    # the rank-8192 update of a triangle of order 8192: 2080 tiles of 128 x 128 on 512 slots,
+    # four full rounds and 32 tiles that a second launch computes as 128 tiles of 64 x 64
+    v, pieces, whole = xg.xgemm_plan("d", 1, 8192, 8192, 8192, 0)
+    assert name("d", v) == "d_128x128x16_w2x2" and pieces == 1 and whole == 2048
+    # 40 x 40 tiles: three full rounds and 64 tiles
+    v, pieces, whole = xg.xgemm_plan("d", 0, 5120, 5120, 5120, 0)
+    assert name("d", v) == "d_128x128x16_w2x2" and pieces == 1 and whole == 1536
+    # shallow products are left alone unless the tuning control asks for it
+    v, pieces, whole = xg.xgemm_plan("d", 0, 5120, 5120, 256, 0)
+    mt = [int(x) for x in name("d", v).split("_")[1].split("x")[:2]]
+    assert pieces == 1 and whole == (5120 // mt[0]) * (5120 // mt[1])
+    xg.xgemm_force_variant(0)
+    xg.xgemm_force_split(1)
+    assert xg.xgemm_plan("d", 0, 5120, 5120, 256, 0) == (0, 1, 1536)
+    xg.xgemm_force_split(0)
+    assert xg.xgemm_plan("d", 0, 5120, 5120, 5120, 0) == (0, 1, 1600)
+    # nothing to quarter: fewer tiles than one round, or a variant with no half-size partner
+    xg.xgemm_force_split(1)
+    assert xg.xgemm_plan("d", 0, 1024, 1024, 4096, 0) == (0, 1, 64)
+    v64 = [i for i in range(16) if (name("d", i) or "").startswith("d_64x64")][0]
+    xg.xgemm_force_variant(v64)
+    assert xg.xgemm_plan("d", 0, 5120, 5120, 5120, 0) == (v64, 1, 6400)
+
+
 def test_forcing_and_errors():
     ws = xg.xgemm_workspace_bytes()
     xg.xgemm_force_variant(3)
