@@ -153,7 +153,16 @@ int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t
  * other triangle is neither read nor written.  Recursive: factor the leading
  * half, solve for the off-diagonal block (xgemm_*trsm), update the trailing
  * half (xgemm_*syrk), factor it; diagonal blocks of order <= 64 are factored by
- * one workgroup.  `info` is a DEVICE int written on the stream: 0 on success,
+ * one workgroup.  Blocks of order 3072 to 16384 (fp32: from 3072 on; larger
+ * fp64 matrices are halved down to that first) are instead swept right-looking
+ * over panels of 256 or 512 columns with one panel of look-ahead: the
+ * factorisation of the next panel (the recursion above) runs on a second stream
+ * beside the trailing update of the current one.  That stream belongs to the
+ * library (one per host thread and device, created by the first such call and
+ * kept); it branches off `stream` at the start of the call and is joined to it
+ * before the call returns, so the call orders like work on `stream` alone and
+ * can be captured with it (make the first call outside the capture).
+ * `info` is a DEVICE int written on the stream: 0 on success,
  * j > 0 if the leading minor of order j is not positive definite (the factor is
  * then undefined from column j on, and only the first failure is recorded).
  * The computed factor satisfies |A - L L^T| <= 4 n u |L| |L|^T on the triangle.
@@ -162,6 +171,12 @@ int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t
  */
 int xgemm_dpotrf(char uplo, int64_t n, double *A, int64_t lda, int *info, void *stream);
 int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *stream);
+
+/* Benchmark/tuning control of xgemm_*potrf on the calling thread: panel width of
+ * the look-ahead sweep.  -1: chosen from the order (default); 0: the recursion
+ * alone, on the caller's stream; W > 0: panels of W columns whenever W < n.
+ * Returns 0, or -1 for any other value. */
+int xgemm_force_potrf_panel(int64_t width);
 
 /*
  * GEMM and SYRK with a caller-owned workspace, which lets the library

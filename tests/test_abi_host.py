@@ -189,6 +189,8 @@ def test_workspace_routines_host_side():
     assert xg.xgemm_force_split(33) == -1 and xg.xgemm_force_split(-2) == -1 and xg.xgemm_force_split(1) == 0
     assert xg.xgemm_force_split(4) == 0 and xg.xgemm_force_split(0) == 0 and xg.xgemm_force_split(-1) == 0
     assert xg.xgemm_last_split() == 1
+    assert xg.xgemm_force_potrf_panel(-2) == -1 and xg.xgemm_force_potrf_panel(512) == 0 and xg.xgemm_force_potrf_panel(0) == 0
+    assert xg.xgemm_force_potrf_panel(-1) == 0
 
 
 @pytest.mark.parametrize("mt_m,mt_n", [(128, 128), (256, 128), (64, 64), (128, 64), (64, 128)])

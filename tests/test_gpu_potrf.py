@@ -14,6 +14,13 @@ from gpu_util import to_dev, torch_mod, unit_roundoff
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _panel_by_order():
+    xg.xgemm_force_potrf_panel(-1)
+    yield
+    xg.xgemm_force_potrf_panel(-1)
+
+
 def run_potrf(uplo, n, A, lda):
     torch = torch_mod()
     f = xg.xgemm_dpotrf if A.dtype == np.float64 else xg.xgemm_spotrf
@@ -135,3 +142,88 @@ def test_every_order_of_a_single_diagonal_block_bit_exact(dtype, R, uplo):
             F, info = run_potrf(uplo, n, A, n + 1)
             assert info == 0, f"order {n}, run {rep}"
             assert np.array_equal(F[:, :n][mask], (L0.T if uplo == "L" else L0)[mask].astype(dtype)), f"order {n}, run {rep}"
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("uplo", "LU")
+def test_look_ahead_sweep_with_small_panels(dtype, uplo):
+    """The panel sweep with look-ahead on a second stream (the form large orders take), forced onto small
+    orders so that the oracle can check every element: two panels, many panels, a ragged last panel, a
+    last panel of one column, panels narrower and wider than the diagonal-block kernel's order."""
+    rng = si.rng_for(175, 0 if uplo == "L" else 1)
+    for n, W, pad in [(517, 128, 2), (1000, 192, 0), (700, 64, 1), (300, 256, 0), (257, 256, 3), (640, 320, 0), (130, 40, 1)]:
+        A = si.spd(rng, n, n + pad, dtype, uplo)
+        assert xg.xgemm_force_potrf_panel(W) == 0
+        F, info = run_potrf(uplo, n, A, n + pad)
+        assert info == 0
+        assert np.array_equal(np.isnan(F), np.isnan(A)), "something outside the triangle was written"
+        rinfo, R, G = oracle.potrf_resid(uplo, n, A, n + pad, F, n + pad)
+        assert rinfo == 0
+        bound = 4.0 * n * unit_roundoff(dtype) * G
+        assert np.all(np.abs(R) <= bound), f"{uplo} n={n} W={W}: max ratio {float(np.max(np.abs(R) / np.maximum(bound, 1e-300)))}"
+        # the same run again gives the same bits (the two streams are ordered by events, not by luck)
+        F2, _ = run_potrf(uplo, n, A, n + pad)
+        assert np.array_equal(F, F2, equal_nan=True)
+        # and agrees with the recursion on one stream to rounding
+        assert xg.xgemm_force_potrf_panel(0) == 0
+        F1, info1 = run_potrf(uplo, n, A, n + pad)
+        tol = 16 * n * unit_roundoff(dtype)
+        mask = oracle.triangle_mask(uplo, n)
+        assert info1 == 0 and np.allclose(F[:, :n][mask], F1[:, :n][mask], rtol=tol, atol=tol)
+
+
+@pytest.mark.parametrize("uplo", "LU")
+def test_look_ahead_sweep_integer_factor_and_failure_report(uplo):
+    rng = si.rng_for(176, 0)
+    n, R = 300, 3
+    L0 = np.tril(rng.integers(-R, R + 1, size=(n, n)), -1).astype(np.int64)
+    L0[np.arange(n), np.arange(n)] = 2 ** rng.integers(0, 3, size=n)
+    A = np.full((n, n + 1), np.nan)
+    A[:, :n] = (L0 @ L0.T).astype(np.float64)
+    si._mask_triangle(A, n, uplo, False, np.nan)
+    assert xg.xgemm_force_potrf_panel(64) == 0
+    F, info = run_potrf(uplo, n, A, n + 1)
+    mask = oracle.triangle_mask(uplo, n)
+    assert info == 0 and np.array_equal(F[:, :n][mask], (L0.T if uplo == "L" else L0)[mask].astype(np.float64))
+    # the first failing minor is reported whichever panel it falls into
+    for bad in (10, 64, 131, 299):
+        B = si.spd(rng, n, n, np.float64, uplo)
+        B[bad, bad] = -1.0
+        _, info = run_potrf(uplo, n, B, n)
+        assert info == bad + 1
+
+
+def test_look_ahead_sweep_is_the_default_for_large_orders_and_graph_safe():
+    """n = 3200 takes the sweep by itself; captured in a graph after one eager call, every replay gives the eager bits."""
+    torch = torch_mod()
+    rng = si.rng_for(177, 0)
+    n = 3200
+    S0 = to_dev(si.spd(rng, n, n, np.float64, "L", sentinel=0.0))
+    S = S0.clone()
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert xg.xgemm_dpotrf("L", n, S, n, info) == 0
+    torch.cuda.synchronize()
+    want = S.clone()
+    assert int(info.item()) == 0
+    assert xg.xgemm_force_potrf_panel(0) == 0
+    S.copy_(S0)
+    assert xg.xgemm_dpotrf("L", n, S, n, info) == 0
+    torch.cuda.synchronize()
+    assert not torch.equal(S, want), "the default at this order was meant to differ from the recursion (another order of sums)"
+    assert torch.allclose(torch.tril(S), torch.tril(want), rtol=1e-10, atol=1e-10)
+    assert xg.xgemm_force_potrf_panel(-1) == 0
+    graph = torch.cuda.CUDAGraph()
+    S.copy_(S0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        assert xg.xgemm_dpotrf("L", n, S, n, info) == 0
+    for rep in range(3):
+        S.copy_(S0)
+        info.fill_(7)
+        scratch = torch.rand(512, 512, device="cuda") @ torch.rand(512, 512, device="cuda")
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(S, want), f"replay {rep} differs from the eager run"
+        assert int(info.item()) == 0
+        del scratch
