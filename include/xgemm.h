@@ -15,7 +15,9 @@
  *     library never allocates, frees or keeps them.  A and B must not overlap
  *     C.  Scalars are passed by value from the host.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
- *     only enqueue work; they do not synchronise.
+ *     only enqueue work; they do not synchronise.  All work goes to `stream`
+ *     (xgemm_*potrf may also use a stream of the library's between a fork from
+ *     and a join to `stream`, see there).
  *   - trans is one of N n T t C c.  For the real routines C means T.
  *   - beta == 0: C is write-only; whatever it held (NaN, Inf) is overwritten.
  *     alpha == 0 or k == 0: A and B are not read (and may be NULL).

@@ -1,6 +1,7 @@
 """The entry points only enqueue kernels on the caller's stream (no allocation,
 no memset, no synchronisation), so a chain of them can be captured in a HIP
-graph.  A captured chain -- product, triangular update with workspace, solve,
+graph.  (The factorisation of large orders also uses a stream of the library's
+that forks from and joins the caller's; tests/test_gpu_potrf.py captures that.)  A captured chain -- product, triangular update with workspace, solve,
 factorisation -- is replayed several times with eager work in between; every
 replay must reproduce the eager result bit for bit."""
 import numpy as np
