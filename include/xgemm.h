@@ -154,7 +154,7 @@ int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t
  * A is n x n symmetric positive definite, given by its `uplo` triangle; the
  * other triangle is neither read nor written.  Recursive: factor the leading
  * half, solve for the off-diagonal block (xgemm_*trsm), update the trailing
- * half (xgemm_*syrk), factor it; diagonal blocks of order <= 64 are factored by
+ * half (xgemm_*syrk), factor it; diagonal blocks of order <= 256 are factored by
  * one workgroup.  Blocks of order 3072 to 16384 (fp32: from 3072 on; larger
  * fp64 matrices are halved down to that first) are instead swept right-looking
  * over panels of 256 or 512 columns with one panel of look-ahead: the
@@ -179,6 +179,12 @@ int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *s
  * alone, on the caller's stream; W > 0: panels of W columns whenever W < n.
  * Returns 0, or -1 for any other value. */
 int xgemm_force_potrf_panel(int64_t width);
+
+/* Benchmark/tuning control of xgemm_*potrf on the calling thread: the largest
+ * order of a diagonal block that one workgroup factors by itself (64: one wave;
+ * 128: three waves; 256: ten waves, the default, also chosen by -1); larger
+ * blocks are halved.  Returns 0, or -1 for any other value. */
+int xgemm_force_potrf_block(int order);
 
 /*
  * GEMM and SYRK with a caller-owned workspace, which lets the library

@@ -1019,7 +1019,335 @@ __global__ void __launch_bounds__(64) potf2_kernel(T *A, int64_t lda, int nbk, i
     }
 }
 
+// Cholesky factorisation of a diagonal block of order nbk <= 64 NBLK by one workgroup of
+// NBLK (NBLK + 1) / 2 waves: one wave per 64x64 block of the lower triangle, which holds
+// its block in 16x16 accumulator tiles from start to end (the diagonal blocks as in
+// potf2_kernel, tile rows >= tile columns only).  Block column jc is worked through in
+// panels of four columns; per panel
+//   A  the wave of the diagonal block (jc, jc) factors the panel exactly as potf2_kernel
+//      does, and leaves in LDS the finished panel in operand format and the scalars that
+//      the rows below need (reciprocal pivot roots and the 4x4 block's entries of L; pivot
+//      roots instead on the careful route);
+//   B  each wave (bi, jc) below it takes its 64 rows of the panel out of its tiles, applies
+//      those scalars (one row per lane, the same operations as the diagonal wave applies
+//      to its own rows), stores them, leaves them in LDS in operand format and updates
+//      the rest of its block;
+//   C  each wave (bi, bj), bj > jc, subtracts L(bi, panel) L(bj, panel)^T from its block:
+//      one instruction per tile, operands read from LDS.
+// The three run as a pipeline, A on panel s while B is on s - 1 and C on s - 2, with one
+// workgroup barrier per step and the LDS panels in a ring of three, so a block column costs
+// 18 steps of about the time potf2_kernel takes per panel whatever NBLK is.  When a block
+// column is done the diagonal block of the next one has received all its updates and
+// its wave turns from C to A.  Waves whose blocks lie beyond nbk, or whose block column is
+// finished, only keep the barriers company.  A pivot that is not positive is reported as in
+// potf2_kernel and ends all further work (never the barriers).
+template <typename T, int NBLK>
+__global__ void __launch_bounds__(64 * NBLK * (NBLK + 1) / 2)
+potrf_multi_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
+    using M = Mma16<T>;
+    using acc_t = typename M::acc_t;
+    constexpr int RING = 3, PANELS = 16, STEPS = PANELS + 2, BS = 64;
+    const int lane = threadIdx.x & 63, lc = lane & 15, lk = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    int bi = 0;
+    while ((bi + 1) * (bi + 2) / 2 <= wave) ++bi;
+    const int bj = wave - bi * (bi + 1) / 2;
+    const int64_t rs = lower ? 1 : lda, cs = lower ? lda : 1;
+    __shared__ T panL[NBLK][RING][4 * BS];   // finished panels of each block row, column k at [k * BS + row]
+    __shared__ T panX[NBLK][4 * BS];         // a block row's way from tiles to one row per lane
+    __shared__ T scal[RING][16];             // [0] route (0 none, 1 fast, 2 careful), [1] columns, [2..5] roots, [6..11] block entries
+    __shared__ int dead;
+    if (threadIdx.x == 0) dead = 0;
+    __syncthreads();
+
+    auto run = [&](auto diag_tag) {
+        constexpr bool DIAG = decltype(diag_tag)::value;
+        acc_t acc[4][4];
+#pragma unroll
+        for (int J = 0; J < 4; ++J)
+#pragma unroll
+            for (int I = DIAG ? J : 0; I < 4; ++I)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = BS * bi + 16 * I + M::drow(lane, r), col = BS * bj + 16 * J + lc;
+                    const bool inside = row < nbk && col <= row;
+                    const T v = A[inside ? row * rs + col * cs : 0];
+                    acc[I][J][r] = inside ? v : T(0);
+                }
+
+        // C: block (bi, bj) -= L(bi, panel) L(bj, panel)^T
+        auto trailing = [&](int slot) {
+            const T *rowp = &panL[bi][slot][lk * BS + lc], *colp = &panL[bj][slot][lk * BS + lc];
+            T op[4], nop[4];
+#pragma unroll
+            for (int I = 0; I < 4; ++I) {
+                nop[I] = -rowp[16 * I];
+                op[I] = colp[16 * I];
+            }
+#pragma unroll
+            for (int J = 0; J < 4; ++J)
+#pragma unroll
+                for (int I = DIAG ? J : 0; I < 4; ++I) acc[I][J] = M::mma(nop[I], op[J], acc[I][J]);
+        };
+
+        // A: panel p of the diagonal block (DIAG only); tile (0, 0) holds the rows and columns from 16 (p / 4) on
+        auto factor = [&](int jc, int p) {
+            const int slot = p % RING, jj = 4 * (p & 3), row0 = BS * jc + 16 * (p >> 2), c0 = row0 + jj;
+            const int grow = row0 + lane;
+            const int rlim = nbk < BS * (jc + 1) ? nbk : BS * (jc + 1);   // rows of this block
+            T *const px = &panX[bi][0], *const pl = &panL[bi][slot][0];
+            const int kk = lc - jj;
+            if (kk >= 0 && kk < 4) {
+#pragma unroll
+                for (int I = 0; I < 4; ++I)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) px[kk * BS + 16 * I + M::drow(lane, r)] = acc[I][0][r];
+            }
+            __builtin_amdgcn_wave_barrier();
+            T pk[4], l[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pk[k] = px[k * BS + lane];
+            __builtin_amdgcn_wave_barrier();
+            bool fast;
+            {
+                const T a00 = lane_value(pk[0], jj), a10 = lane_value(pk[0], jj + 1), a20 = lane_value(pk[0], jj + 2),
+                        a30 = lane_value(pk[0], jj + 3), a11 = lane_value(pk[1], jj + 1), a21 = lane_value(pk[1], jj + 2),
+                        a31 = lane_value(pk[1], jj + 3), a22 = lane_value(pk[2], jj + 2), a32 = lane_value(pk[2], jj + 3),
+                        a33 = lane_value(pk[3], jj + 3);
+                T d[4], ri[4], q[4];
+                d[0] = a00;
+                ri[0] = inverse_root<T>(d[0]);
+                const T l10 = a10 * ri[0], l20 = a20 * ri[0], l30 = a30 * ri[0];
+                d[1] = __builtin_fma(-l10, l10, a11);
+                ri[1] = inverse_root<T>(d[1]);
+                const T l21 = __builtin_fma(-l20, l10, a21) * ri[1], l31 = __builtin_fma(-l30, l10, a31) * ri[1];
+                d[2] = __builtin_fma(-l21, l21, __builtin_fma(-l20, l20, a22));
+                ri[2] = inverse_root<T>(d[2]);
+                const T l32 = __builtin_fma(-l31, l21, __builtin_fma(-l30, l20, a32)) * ri[2];
+                d[3] = __builtin_fma(-l32, l32, __builtin_fma(-l31, l31, __builtin_fma(-l30, l30, a33)));
+                ri[3] = inverse_root<T>(d[3]);
+                q[0] = pk[0] * ri[0];
+                q[1] = __builtin_fma(-q[0], l10, pk[1]) * ri[1];
+                q[2] = __builtin_fma(-q[1], l21, __builtin_fma(-q[0], l20, pk[2])) * ri[2];
+                q[3] = __builtin_fma(-q[2], l32, __builtin_fma(-q[1], l31, __builtin_fma(-q[0], l30, pk[3]))) * ri[3];
+                int valid = (int)(c0 + 4 <= nbk);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) valid &= (int)(d[k] >= M::TINY) & (int)(d[k] <= M::BIG);
+                fast = valid != 0;
+                if (fast) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const T g = d[k] * ri[k];
+                        const T sd = __builtin_fma(__builtin_fma(-g, g, d[k]), T(0.5) * ri[k], g);
+                        l[k] = q[k];
+                        if (lane >= jj + k && grow < rlim) A[grow * rs + (c0 + k) * cs] = lane == jj + k ? sd : q[k];
+                    }
+                    if (lane == 0) {
+                        T *sc = &scal[slot][0];
+                        sc[0] = T(1);
+                        sc[1] = T(4);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) sc[2 + k] = ri[k];
+                        sc[6] = l10; sc[7] = l20; sc[8] = l30; sc[9] = l21; sc[10] = l31; sc[11] = l32;
+                    }
+                }
+            }
+            if (!fast) {
+                int done = 0;
+                bool failed = false;
+                T sq[4] = {T(1), T(1), T(1), T(1)}, lb[6] = {T(0), T(0), T(0), T(0), T(0), T(0)};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int piv = jj + k;
+                    l[k] = T(0);
+                    if (!failed && c0 + k < nbk) {            // wave-uniform
+                        const T d = lane_value(pk[k], piv);
+                        if (!(d > T(0))) {
+                            if (lane == 0 && *info == 0) *info = base + c0 + k + 1;
+                            failed = true;
+                        } else {
+                            const T sd = sqrt(d);
+                            sq[k] = sd;
+                            l[k] = lane == piv ? sd : pk[k] / sd;
+                            if (lane >= piv && grow < rlim) A[grow * rs + (c0 + k) * cs] = l[k];
+                            int e = k == 0 ? 0 : k == 1 ? 3 : 5;   // entries (k+1.., k) of the block: 6 + {0,1,2}, {3,4}, {5}
+#pragma unroll
+                            for (int k2 = k + 1; k2 < 4; ++k2) {
+                                const T x = lane_value(l[k], jj + k2);
+                                lb[e++] = x;
+                                pk[k2] -= l[k] * x;
+                            }
+                            done = k + 1;
+                        }
+                    }
+                }
+                if (lane == 0) {
+                    T *sc = &scal[slot][0];
+                    sc[0] = failed ? T(0) : T(2);
+                    sc[1] = (T)done;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) sc[2 + k] = sq[k];
+#pragma unroll
+                    for (int e = 0; e < 6; ++e) sc[6 + e] = lb[e];
+                    if (failed) dead = 1;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pl[k * BS + lane] = l[k];
+            __builtin_amdgcn_wave_barrier();
+            T op[4], nop[4];
+#pragma unroll
+            for (int I = 0; I < 4; ++I) {
+                op[I] = pl[lk * BS + 16 * I + lc];
+                nop[I] = -op[I];
+            }
+            const int live = 4 - (p >> 2);
+#pragma unroll
+            for (int J2 = 0; J2 < 4; ++J2) {
+                if (J2 < live && (J2 > 0 || jj < 12)) {
+#pragma unroll
+                    for (int I = J2; I < 4; ++I) acc[I][J2] = M::mma(nop[I], op[J2], acc[I][J2]);
+                }
+            }
+        };
+        // after four panels the first tile row and column of a diagonal block are finished: up and to the left by one tile
+        auto shift_diag = [&]() {
+#pragma unroll
+            for (int J2 = 0; J2 + 1 < 4; ++J2)
+#pragma unroll
+                for (int I = J2; I + 1 < 4; ++I) acc[I][J2] = acc[I + 1][J2 + 1];
+#pragma unroll
+            for (int J2 = 0; J2 < 4; ++J2)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[3][J2][r] = T(0);
+        };
+
+        // B: panel p of block (bi, jc) below the diagonal block (not DIAG); tile column 0 holds the columns from 16 (p / 4) on
+        auto below = [&](int jc, int p) {
+            const int slot = p % RING, jj = 4 * (p & 3), c0 = BS * jc + 16 * (p >> 2) + jj;
+            const int grow = BS * bi + lane;
+            T *const px = &panX[bi][0], *const pl = &panL[bi][slot][0];
+            const T *sc = &scal[slot][0];
+            const int route = (int)lane_value(sc[0], 0), cols = (int)lane_value(sc[1], 0);
+            if (route == 0) return;
+            const int kk = lc - jj;
+            if (kk >= 0 && kk < 4) {
+#pragma unroll
+                for (int I = 0; I < 4; ++I)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) px[kk * BS + 16 * I + M::drow(lane, r)] = acc[I][0][r];
+            }
+            __builtin_amdgcn_wave_barrier();
+            T pk[4], l[4], root[4], lb[6];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pk[k] = px[k * BS + lane];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) root[k] = lane_value(sc[2 + k], 0);
+#pragma unroll
+            for (int e = 0; e < 6; ++e) lb[e] = lane_value(sc[6 + e], 0);
+            __builtin_amdgcn_wave_barrier();
+            if (route == 1) {
+                l[0] = pk[0] * root[0];
+                l[1] = __builtin_fma(-l[0], lb[0], pk[1]) * root[1];
+                l[2] = __builtin_fma(-l[1], lb[3], __builtin_fma(-l[0], lb[1], pk[2])) * root[2];
+                l[3] = __builtin_fma(-l[2], lb[5], __builtin_fma(-l[1], lb[4], __builtin_fma(-l[0], lb[2], pk[3]))) * root[3];
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    l[k] = T(0);
+                    if (k < cols) {                           // wave-uniform
+                        l[k] = pk[k] / root[k];
+                        int e = k == 0 ? 0 : k == 1 ? 3 : 5;
+#pragma unroll
+                        for (int k2 = k + 1; k2 < 4; ++k2) pk[k2] -= l[k] * lb[e++];
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (k < cols && grow < nbk) A[grow * rs + (c0 + k) * cs] = l[k];
+                pl[k * BS + lane] = l[k];
+            }
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);   // the operands below are not to be fetched while the panel's values are still held
+            const T *dp = &panL[jc][slot][lk * BS + lc];
+            T op[4], nop[4];
+#pragma unroll
+            for (int I = 0; I < 4; ++I) {
+                nop[I] = -pl[lk * BS + 16 * I + lc];
+                op[I] = dp[16 * I];
+            }
+            const int live = 4 - (p >> 2);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (t < live && (t > 0 || jj < 12)) {
+#pragma unroll
+                    for (int I = 0; I < 4; ++I) acc[I][t] = M::mma(nop[I], op[t], acc[I][t]);
+                }
+            }
+        };
+        // after four panels the first tile column of a block below the diagonal is finished: to the left by one tile
+        auto shift_below = [&]() {
+#pragma unroll
+            for (int t = 0; t + 1 < 4; ++t)
+#pragma unroll
+                for (int I = 0; I < 4; ++I) acc[I][t] = acc[I][t + 1];
+#pragma unroll
+            for (int I = 0; I < 4; ++I)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[I][3][r] = T(0);
+        };
+
+        // Every wave passes NBLK * STEPS barriers.  The roles have loops of their own so that the
+        // tile shifts sit at fixed places in straight code (a shift under a condition would keep two
+        // copies of the block alive).
+        auto alive = [&]() { return dead == 0 && BS * bi < nbk; };   // the same for every lane of the wave
+#pragma unroll 1
+        for (int jc = 0; jc < bj; ++jc) {                 // C: block columns to the left of this block
+#pragma unroll 1
+            for (int s = 0; s < STEPS; ++s) {
+                const int p = s - 2;
+                if (p >= 0 && alive() && BS * jc + 4 * p < nbk) trailing(p % RING);
+                __syncthreads();
+            }
+        }
+        if constexpr (DIAG) {                             // A: this block's own column
+#pragma unroll 1
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll 1
+                for (int u = 0; u < 4; ++u) {
+                    const int p = 4 * q + u;
+                    if (alive() && BS * bj + 4 * p < nbk) factor(bj, p);
+                    __syncthreads();
+                }
+                shift_diag();
+            }
+            __syncthreads();
+            __syncthreads();
+        } else {                                          // B: one step behind the diagonal wave
+            __syncthreads();
+#pragma unroll 1
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll 1
+                for (int u = 0; u < 4; ++u) {
+                    const int p = 4 * q + u;
+                    if (alive() && BS * bj + 4 * p < nbk) below(bj, p);
+                    __syncthreads();
+                }
+                shift_below();
+            }
+            __syncthreads();
+        }
+#pragma unroll 1
+        for (int n = (NBLK - 1 - bj) * STEPS; n > 0; --n) __syncthreads();   // finished: keep the others' barriers company
+    };
+    if (bi == bj) run(std::true_type{});
+    else run(std::false_type{});
+}
+
 __global__ void clear_info_kernel(int *info) { *info = 0; }
+
+thread_local int64_t t_potrf_block = 256;   // largest order handed to one workgroup (64, 128 or 256)
 
 int syrk_call(char uplo, char trans, int64_t n, int64_t k, double alpha, const double *A, int64_t lda, double beta,
               double *C, int64_t ldc, void *stream) {
@@ -1038,6 +1366,19 @@ template <typename T> int potrf_run(bool lower, int64_t off, int64_t dim, T *A, 
         hipLaunchKernelGGL(potf2_kernel<T>, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), D, lda, (int)dim,
                            lower ? 1 : 0, info, (int)off);
         return (int)hipGetLastError();
+    }
+    if (dim <= 2 * NB && dim <= t_potrf_block) {
+        hipLaunchKernelGGL((potrf_multi_kernel<T, 2>), dim3(1), dim3(3 * 64), 0, static_cast<hipStream_t>(stream), D, lda,
+                           (int)dim, lower ? 1 : 0, info, (int)off);
+        return (int)hipGetLastError();
+    }
+    // ten waves leave each 168 registers, which the fp64 blocks (128 for the tiles alone) do not fit
+    if constexpr (sizeof(T) == 4) {
+        if (dim <= 4 * NB && dim <= t_potrf_block) {
+            hipLaunchKernelGGL((potrf_multi_kernel<T, 4>), dim3(1), dim3(10 * 64), 0, static_cast<hipStream_t>(stream), D,
+                               lda, (int)dim, lower ? 1 : 0, info, (int)off);
+            return (int)hipGetLastError();
+        }
     }
     const int64_t n1 = ((dim / 2 + NB - 1) / NB) * NB, n2 = dim - n1;
     int rc;
@@ -1388,6 +1729,12 @@ int xgemm_ssymm(char side, char uplo, int64_t m, int64_t n, float alpha, const f
 int xgemm_force_potrf_panel(int64_t width) {
     if (width < -1 || width > DIM_MAX) return -1;
     t_potrf_panel = width;
+    return 0;
+}
+
+int xgemm_force_potrf_block(int order) {
+    if (order != -1 && order != 64 && order != 128 && order != 256) return -1;
+    t_potrf_block = order < 0 ? 256 : order;
     return 0;
 }
 

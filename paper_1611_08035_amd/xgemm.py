@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block",
 ]
 
 
@@ -115,6 +115,8 @@ def lib():
     L.xgemm_mfma_layout_probe.argtypes = [_c, _p, _p]
     L.xgemm_hwid_probe.restype = ctypes.c_int
     L.xgemm_hwid_probe.argtypes = [ctypes.c_int, ctypes.c_int, _p, _p]
+    L.xgemm_force_potrf_block.restype = ctypes.c_int
+    L.xgemm_force_potrf_block.argtypes = [ctypes.c_int]
     L.xgemm_force_potrf_panel.restype = ctypes.c_int
     L.xgemm_force_potrf_panel.argtypes = [ctypes.c_int64]
     L.xgemm_latency_probe.restype = ctypes.c_int
@@ -313,6 +315,10 @@ def xgemm_mfma_layout_probe(prec, out, stream=None) -> int:
 
 def xgemm_hwid_probe(blocks, lds_bytes, out, stream=None) -> int:
     return int(lib().xgemm_hwid_probe(blocks, lds_bytes, _ptr(out), _stream(stream)))
+
+
+def xgemm_force_potrf_block(order) -> int:
+    return int(lib().xgemm_force_potrf_block(int(order)))
 
 
 def xgemm_force_potrf_panel(width) -> int:

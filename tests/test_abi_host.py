@@ -191,6 +191,7 @@ def test_workspace_routines_host_side():
     assert xg.xgemm_last_split() == 1
     assert xg.xgemm_force_potrf_panel(-2) == -1 and xg.xgemm_force_potrf_panel(512) == 0 and xg.xgemm_force_potrf_panel(0) == 0
     assert xg.xgemm_force_potrf_panel(-1) == 0
+    assert xg.xgemm_force_potrf_block(100) == -1 and xg.xgemm_force_potrf_block(128) == 0 and xg.xgemm_force_potrf_block(-1) == 0
 
 
 @pytest.mark.parametrize("mt_m,mt_n", [(128, 128), (256, 128), (64, 64), (128, 64), (64, 128)])
