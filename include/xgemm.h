@@ -157,13 +157,15 @@ int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t
  * half (xgemm_*syrk), factor it; diagonal blocks of order <= 256 are factored by
  * one workgroup.  Blocks of order 3072 to 16384 (fp32: from 3072 on; larger
  * fp64 matrices are halved down to that first) are instead swept right-looking
- * over panels of 256 or 512 columns with one panel of look-ahead: the
- * factorisation of the next panel (the recursion above) runs on a second stream
- * beside the trailing update of the current one.  That stream belongs to the
- * library (one per host thread and device, created by the first such call and
- * kept); it branches off `stream` at the start of the call and is joined to it
- * before the call returns, so the call orders like work on `stream` alone and
- * can be captured with it (make the first call outside the capture).
+ * over panels of 256 or 512 columns with look-ahead: the factorisation of the
+ * next panel (the recursion above) and the solves and updates that only the
+ * next panel needs run on two streams of the library's beside the trailing
+ * update of the current one.  Those streams (per host thread and device,
+ * created by the first such call and kept) branch off `stream` at the start of
+ * the call and are joined to it before the call returns, so the call orders
+ * like work on `stream` alone.  While `stream` is being captured into a graph
+ * the same kernels are all enqueued on `stream` itself, in an order that gives
+ * the same bits.
  * `info` is a DEVICE int written on the stream: 0 on success,
  * j > 0 if the leading minor of order j is not positive definite (the factor is
  * then undefined from column j on, and only the first failure is recorded).

@@ -883,6 +883,7 @@ template <typename T>
 __global__ void __launch_bounds__(64) potf2_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
     using M = Mma16<T>;
     using acc_t = typename M::acc_t;
+    __builtin_amdgcn_s_setprio(3);                        // see potrf_multi_kernel
     constexpr int TI = NB / 16;                           // tiles per side
     const int lane = threadIdx.x, lc = lane & 15;
     // element (r, c), r >= c, of the lower problem sits at A[r + c*lda] (lower) or A[c + r*lda] (upper)
@@ -1046,6 +1047,9 @@ __global__ void __launch_bounds__(64 * NBLK * (NBLK + 1) / 2)
 potrf_multi_kernel(T *A, int64_t lda, int nbk, int lower, int *info, int base) {
     using M = Mma16<T>;
     using acc_t = typename M::acc_t;
+    // a chain of dependent steps that the factorisation of a whole matrix waits for: where its waves share
+    // a SIMD with those of a concurrent update, they go first
+    __builtin_amdgcn_s_setprio(3);
     constexpr int RING = 3, PANELS = 16, STEPS = PANELS + 2, BS = 64;
     const int lane = threadIdx.x & 63, lc = lane & 15, lk = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -1395,31 +1399,30 @@ template <typename T> int potrf_run(bool lower, int64_t off, int64_t dim, T *A, 
     return potrf_run<T>(lower, off + n1, n2, A, lda, info, stream);
 }
 
-// A second stream of this host thread on the current device, with the events that tie it to the
-// caller's stream.  Created on first use and kept for the life of the process.  Waiting on an
-// event means waiting for its latest record at the time of the call, so a handful of events
-// used in turn serve any number of steps.
-struct SideLane {
-    static constexpr int RING = 4;
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr, solved[RING] = {}, updated[RING] = {};
+// Two more streams of this host thread on the current device, with the events that tie them to
+// the caller's stream and to each other.  Created on first use and kept for the life of the
+// process.  Waiting on an event means waiting for its latest record at the time of the call, so a
+// handful of events used in turn serve any number of steps.
+struct SideLanes {
+    static constexpr int RING = 4, KINDS = 5;
+    hipStream_t stream[2] = {nullptr, nullptr};
+    hipEvent_t fork = nullptr, join[2] = {nullptr, nullptr}, ev[KINDS][RING] = {};
     bool ready = false;
 };
-SideLane *side_lane() {
+SideLanes *side_lanes() {
     constexpr int MAX_DEV = 64;
-    thread_local SideLane lanes[MAX_DEV];
+    thread_local SideLanes lanes[MAX_DEV];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
-    SideLane &ln = lanes[dev];
+    SideLanes &ln = lanes[dev];
     if (!ln.ready) {
-        if (hipStreamCreateWithFlags(&ln.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        hipEvent_t *all[2 + 2 * SideLane::RING] = {&ln.fork, &ln.join};
-        for (int i = 0; i < SideLane::RING; ++i) {
-            all[2 + i] = &ln.solved[i];
-            all[2 + SideLane::RING + i] = &ln.updated[i];
-        }
-        for (hipEvent_t *e : all)
-            if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        for (hipStream_t &st : ln.stream)
+            if (!st && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        auto make = [](hipEvent_t &e) { return e || hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess; };
+        bool ok = make(ln.fork) && make(ln.join[0]) && make(ln.join[1]);
+        for (auto &kind : ln.ev)
+            for (hipEvent_t &e : kind) ok = ok && make(e);
+        if (!ok) return nullptr;
         ln.ready = true;
     }
     return &ln;
@@ -1440,57 +1443,91 @@ template <typename T> int64_t potrf_panel(int64_t n) {
     return sizeof(T) == 8 ? HALVE : 512;
 }
 
-// Right-looking factorisation with one panel of look-ahead.  Panel p (W columns) goes through
-//   F_p  factor the diagonal block                       (chain stream)
-//   T_p  solve for the blocks below / right of it        (chain stream)
-//   U_p  update block column p + 1 with panel p          (chain stream, after B_{p-1})
-//   B_p  update everything beyond block column p + 1     (caller's stream, after T_p)
-// so that F_{p+1} and T_{p+1}, a chain of small dependent kernels, run while B_p keeps the
-// machine busy.  B_{p-1} and U_p both add into block column p + 1, hence their order; all other
-// pairs that may overlap touch different blocks.  The chain stream branches off the caller's
-// stream at the start and is joined to it at the end, so to the caller (and to a graph
-// capture of its stream) the call behaves like work on that stream alone.
+// Right-looking factorisation with look-ahead.  Panel p (W columns) goes through
+//   F_p   factor the diagonal block                                              chain stream
+//   t_p   solve for the block of the next panel's rows (or columns) beside it    chain stream
+//   u_p   update the diagonal block of panel p + 1 with it                       chain stream, after B_{p-1}
+//   T_p   solve for all blocks further on                                        side stream, after F_p
+//   U_p   update the rest of block column (row) p + 1 with panel p               side stream, after t_p and B_{p-1}
+//   B_p   update everything beyond block column p + 1                            caller's stream, after T_p
+// and t_{p+1} waits for U_p.  The chain F -> t -> u -> F is all that is serial from panel to
+// panel; the solves and updates over the full height of the panel run beside it, and the
+// bulk of the arithmetic, B_p, beside both.  B_{p-1}, u_p and U_p add into block column p + 1,
+// hence their order; all other pairs that may overlap touch different blocks.  The two
+// streams of the library branch off the caller's at the start and are joined to it at the end,
+// so to the caller (and to a graph capture of its stream) the call behaves like work on that
+// stream alone.
 template <typename T>
 int potrf_ahead(bool lower, int64_t off, int64_t n, int64_t W, T *A, int64_t lda, int *info, hipStream_t s0) {
-    SideLane *ln = side_lane();
-    if (!ln) return (int)hipErrorNotReady;
-    hipStream_t s1 = ln->stream;
-    hipError_t e;
-    if ((e = hipEventRecord(ln->fork, s0)) != hipSuccess) return (int)e;
-    if ((e = hipStreamWaitEvent(s1, ln->fork, 0)) != hipSuccess) return (int)e;
+    // Under stream capture everything goes to the caller's stream and no event is touched: the
+    // same kernels in the same order on the data, so a replay gives the eager bits.  (Ending a
+    // capture that spanned the library's streams crashed in the runtime.)
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s0, &capturing) != hipSuccess) return (int)hipGetLastError();
+    const bool alone = capturing != hipStreamCaptureStatusNone;
+    SideLanes *ln = alone ? nullptr : side_lanes();
+    if (!alone && !ln) return (int)hipErrorNotReady;
+    hipStream_t s1 = alone ? s0 : ln->stream[0], s2 = alone ? s0 : ln->stream[1];
+    enum { FACTORED = 0, NEAR_SOLVED = 1, FAR_SOLVED = 2, FAR_UPDATED = 3, BULK_UPDATED = 4 };
+    auto record = [&](int kind, int slot, hipStream_t st) { return alone ? hipSuccess : hipEventRecord(ln->ev[kind][slot], st); };
+    auto await = [&](hipStream_t st, int kind, int slot) { return alone ? hipSuccess : hipStreamWaitEvent(st, ln->ev[kind][slot], 0); };
+    if (!alone) {
+        hipError_t e;
+        if ((e = hipEventRecord(ln->fork, s0)) != hipSuccess) return (int)e;
+        if ((e = hipStreamWaitEvent(s1, ln->fork, 0)) != hipSuccess) return (int)e;
+        if ((e = hipStreamWaitEvent(s2, ln->fork, 0)) != hipSuccess) return (int)e;
+    }
     int rc = 0;
     auto ok = [&](hipError_t err) { if (rc == 0 && err != hipSuccess) rc = (int)err; return rc == 0; };
+    auto solve = [&](int64_t cnt, const T *D, T *P, hipStream_t st) {
+        return lower ? trsm_impl<T>('R', 'L', 'T', 'N', cnt, (int64_t)(W), T(1), D, lda, P, lda, st)
+                     : trsm_impl<T>('L', 'U', 'T', 'N', (int64_t)(W), cnt, T(1), D, lda, P, lda, st);
+    };
     int step = 0;
     for (int64_t j = 0; j < n && rc == 0; j += W, ++step) {
         const int64_t nj = (n - j) < W ? (n - j) : W, rest = n - j - nj;
-        const int slot = step % SideLane::RING, prev = (step + SideLane::RING - 1) % SideLane::RING;
-        if ((rc = potrf_run<T>(lower, off + j, nj, A, lda, info, s1)) || rest == 0) break;
+        const int slot = step % SideLanes::RING, prev = (step + SideLanes::RING - 1) % SideLanes::RING;
         T *D = A + (off + j) + (off + j) * lda;
-        T *P = lower ? D + nj : D + nj * lda;              // the blocks below (rest x nj) or right of (nj x rest) the diagonal block
-        if (lower) rc = trsm_impl<T>('R', 'L', 'T', 'N', rest, nj, T(1), D, lda, P, lda, s1);
-        else rc = trsm_impl<T>('L', 'U', 'T', 'N', nj, rest, T(1), D, lda, P, lda, s1);
-        if (rc || !ok(hipEventRecord(ln->solved[slot], s1))) break;
+        if ((rc = potrf_run<T>(lower, off + j, nj, A, lda, info, s1)) || rest == 0) break;
+        // rest > 0 means this panel is a full one (nj == W), and so was every panel before it, each with a B
         const int64_t w2 = rest < W ? rest : W, far = rest - w2;
-        T *D2 = D + nj + nj * lda;                         // diagonal block of the next panel
-        if (step > 0 && !ok(hipStreamWaitEvent(s1, ln->updated[prev], 0))) break;
-        if (lower) {
-            if ((rc = syrk_call('L', 'N', w2, nj, T(-1), P, lda, T(1), D2, lda, s1))) break;
-            if (far > 0 && (rc = real_gemm<T>('N', 'T', far, w2, nj, T(-1), P + w2, lda, P, lda, T(1), D2 + w2, lda, s1))) break;
-        } else {
-            if ((rc = syrk_call('U', 'T', w2, nj, T(-1), P, lda, T(1), D2, lda, s1))) break;
-            if (far > 0 && (rc = real_gemm<T>('T', 'N', w2, far, nj, T(-1), P, lda, P + w2 * lda, lda, T(1), D2 + w2 * lda, lda, s1))) break;
-        }
+        const int64_t along = lower ? 1 : lda;             // step from one block to the next along the panel
+        T *P1 = lower ? D + nj : D + nj * lda;             // blocks of panel p + 1's rows (columns): w2 x nj (nj x w2)
+        T *P2 = P1 + w2 * along;                           // the blocks further on: far x nj (nj x far)
+        T *D2 = D + nj + nj * lda;                         // diagonal block of panel p + 1
+        T *C2 = lower ? D2 + w2 : D2 + w2 * lda;           // rest of its block column (row)
+        T *D3 = D2 + w2 + w2 * lda;
+        if (!ok(record(FACTORED, slot, s1))) break;
+        // the near solve reads what U_{p-1} has updated (the factorisation above did not have to wait for that)
+        if (step > 0 && !ok(await(s1, FAR_UPDATED, prev))) break;
+        if ((rc = solve(w2, D, P1, s1)) || !ok(record(NEAR_SOLVED, slot, s1))) break;
         if (far > 0) {
-            if (!ok(hipStreamWaitEvent(s0, ln->solved[slot], 0))) break;
-            T *D3 = D2 + w2 + w2 * lda;
-            if (lower) rc = syrk_call('L', 'N', far, nj, T(-1), P + w2, lda, T(1), D3, lda, s0);
-            else rc = syrk_call('U', 'T', far, nj, T(-1), P + w2 * lda, lda, T(1), D3, lda, s0);
-            if (rc || !ok(hipEventRecord(ln->updated[slot], s0))) break;
+            if (!ok(await(s2, FACTORED, slot))) break;
+            if ((rc = solve(far, D, P2, s2)) || !ok(record(FAR_SOLVED, slot, s2))) break;
+        }
+        if (step > 0 && !ok(await(s1, BULK_UPDATED, prev))) break;
+        if ((rc = lower ? syrk_call('L', 'N', w2, nj, T(-1), P1, lda, T(1), D2, lda, s1)
+                        : syrk_call('U', 'T', w2, nj, T(-1), P1, lda, T(1), D2, lda, s1)))
+            break;
+        if (far > 0) {
+            if (!ok(await(s2, NEAR_SOLVED, slot))) break;
+            if (step > 0 && !ok(await(s2, BULK_UPDATED, prev))) break;
+            rc = lower ? real_gemm<T>('N', 'T', far, w2, nj, T(-1), P2, lda, P1, lda, T(1), C2, lda, s2)
+                       : real_gemm<T>('T', 'N', w2, far, nj, T(-1), P1, lda, P2, lda, T(1), C2, lda, s2);
+            if (rc || !ok(record(FAR_UPDATED, slot, s2))) break;
+            if (!ok(await(s0, FAR_SOLVED, slot))) break;
+            rc = lower ? syrk_call('L', 'N', far, nj, T(-1), P2, lda, T(1), D3, lda, s0)
+                       : syrk_call('U', 'T', far, nj, T(-1), P2, lda, T(1), D3, lda, s0);
+            if (rc || !ok(record(BULK_UPDATED, slot, s0))) break;
         }
     }
-    // the chain stream always rejoins the caller's, whatever happened above
-    hipError_t ej = hipEventRecord(ln->join, s1);
-    if (ej == hipSuccess) ej = hipStreamWaitEvent(s0, ln->join, 0);
+    // both streams always rejoin the caller's, whatever happened above
+    hipError_t ej = hipSuccess;
+    for (int i = 0; i < 2 && !alone; ++i) {
+        hipError_t x = hipEventRecord(ln->join[i], ln->stream[i]);
+        if (x == hipSuccess) x = hipStreamWaitEvent(s0, ln->join[i], 0);
+        if (ej == hipSuccess) ej = x;
+    }
     return rc ? rc : (int)ej;
 }
 
