@@ -1470,7 +1470,7 @@ int potrf_ahead(bool lower, int64_t off, int64_t n, int64_t W, T *A, int64_t lda
     hipStream_t s1 = alone ? s0 : ln->stream[0], s2 = alone ? s0 : ln->stream[1];
     enum { FACTORED = 0, NEAR_SOLVED = 1, FAR_SOLVED = 2, FAR_UPDATED = 3, BULK_UPDATED = 4 };
     auto record = [&](int kind, int slot, hipStream_t st) { return alone ? hipSuccess : hipEventRecord(ln->ev[kind][slot], st); };
-    auto await = [&](hipStream_t st, int kind, int slot) { return alone ? hipSuccess : hipStreamWaitEvent(st, ln->ev[kind][slot], 0); };
+    auto wait_for = [&](hipStream_t st, int kind, int slot) { return alone ? hipSuccess : hipStreamWaitEvent(st, ln->ev[kind][slot], 0); };
     if (!alone) {
         hipError_t e;
         if ((e = hipEventRecord(ln->fork, s0)) != hipSuccess) return (int)e;
@@ -1499,23 +1499,23 @@ int potrf_ahead(bool lower, int64_t off, int64_t n, int64_t W, T *A, int64_t lda
         T *D3 = D2 + w2 + w2 * lda;
         if (!ok(record(FACTORED, slot, s1))) break;
         // the near solve reads what U_{p-1} has updated (the factorisation above did not have to wait for that)
-        if (step > 0 && !ok(await(s1, FAR_UPDATED, prev))) break;
+        if (step > 0 && !ok(wait_for(s1, FAR_UPDATED, prev))) break;
         if ((rc = solve(w2, D, P1, s1)) || !ok(record(NEAR_SOLVED, slot, s1))) break;
         if (far > 0) {
-            if (!ok(await(s2, FACTORED, slot))) break;
+            if (!ok(wait_for(s2, FACTORED, slot))) break;
             if ((rc = solve(far, D, P2, s2)) || !ok(record(FAR_SOLVED, slot, s2))) break;
         }
-        if (step > 0 && !ok(await(s1, BULK_UPDATED, prev))) break;
+        if (step > 0 && !ok(wait_for(s1, BULK_UPDATED, prev))) break;
         if ((rc = lower ? syrk_call('L', 'N', w2, nj, T(-1), P1, lda, T(1), D2, lda, s1)
                         : syrk_call('U', 'T', w2, nj, T(-1), P1, lda, T(1), D2, lda, s1)))
             break;
         if (far > 0) {
-            if (!ok(await(s2, NEAR_SOLVED, slot))) break;
-            if (step > 0 && !ok(await(s2, BULK_UPDATED, prev))) break;
+            if (!ok(wait_for(s2, NEAR_SOLVED, slot))) break;
+            if (step > 0 && !ok(wait_for(s2, BULK_UPDATED, prev))) break;
             rc = lower ? real_gemm<T>('N', 'T', far, w2, nj, T(-1), P2, lda, P1, lda, T(1), C2, lda, s2)
                        : real_gemm<T>('T', 'N', w2, far, nj, T(-1), P1, lda, P2, lda, T(1), C2, lda, s2);
             if (rc || !ok(record(FAR_UPDATED, slot, s2))) break;
-            if (!ok(await(s0, FAR_SOLVED, slot))) break;
+            if (!ok(wait_for(s0, FAR_SOLVED, slot))) break;
             rc = lower ? syrk_call('L', 'N', far, nj, T(-1), P2, lda, T(1), D3, lda, s0)
                        : syrk_call('U', 'T', far, nj, T(-1), P2, lda, T(1), D3, lda, s0);
             if (rc || !ok(record(BULK_UPDATED, slot, s0))) break;
