@@ -269,3 +269,28 @@ def test_diagonal_block_kernels_of_every_size(dtype, uplo, block):
     got = np.ldexp(F2[:, :n][mask].astype(np.float64), -shift // 2)
     want = F1[:, :n][mask].astype(np.float64)
     assert np.allclose(got, want, rtol=16 * n * u, atol=1e-3 * 16 * n * u * float(np.max(np.abs(want))))
+
+
+def test_look_ahead_sweep_on_a_stream_of_the_callers():
+    """The sweep forks from and joins whatever stream it is given: on a stream of the caller's, with work
+    of the caller's before and after it on that stream and no synchronisation in between, it gives the
+    bits of the call on the default stream."""
+    torch = torch_mod()
+    rng = si.rng_for(179, 0)
+    n = 3200
+    S0 = to_dev(si.spd(rng, n, n, np.float64, "U", sentinel=0.0))
+    S = S0.clone()
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert xg.xgemm_dpotrf("U", n, S, n, info) == 0
+    torch.cuda.synchronize()
+    want = S.clone()
+    side = torch.cuda.Stream()
+    for rep in range(2):
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            S.copy_(S0)                                        # the factorisation must wait for this copy ...
+            assert xg.xgemm_dpotrf("U", n, S, n, info, stream=side) == 0
+            got = S.clone()                                    # ... and this copy for the factorisation
+        side.synchronize()
+        assert torch.equal(got, want), f"run {rep}"
+        assert int(info.item()) == 0
