@@ -119,6 +119,12 @@ template <typename T> struct GemmArgs {
     // quarter b & 3 of tile sub_base + (b >> 2) of the order over sub_ntm x sub_ntn tiles of twice the size).
     int first;
     int sub_count, sub_base, sub_ntm, sub_ntn;
+    // Depth range that depends on the tile (the two passes of a symmetric product over the strict
+    // triangles of its matrix; used with beta == 1 only).  With d = kblk * floor(x0 / kblk), x0 the
+    // tile's first row (kaxis 0) or column (kaxis 1), and kblk a multiple of the tile size:
+    // kcut 1 sums over k in [0, d), kcut 2 over [d + kblk, k); 0: all of k.  `reverse` walks the
+    // tile order backwards (deepest tiles first for kcut 1 along the rows).
+    int kcut, kaxis, kblk, reverse;
 };
 
 // ---------------------------------------------------------------------------
@@ -474,7 +480,17 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
             piece = (bid - g.ndp) % npieces;
         }
     } else {
-        lin = lin_of_block(blockIdx.x, (int)gridDim.x);
+        if (g.kcut == 0) {
+            lin = lin_of_block(blockIdx.x, (int)gridDim.x);
+        } else {
+            // Tiles of unequal depth: one contiguous run of the order per XCD would give the XCDs unequal
+            // work, so the order is dealt to them in squares of 64 tiles (8 x 8 tiles of one band) in turn.
+            // The grid is a whole number of rounds of such squares; positions past the order have no tile.
+            const int x = blockIdx.x % NUM_XCD, loc = blockIdx.x / NUM_XCD, total = g.ntm * g.ntn;
+            lin = ((loc / 64) * NUM_XCD + x) * 64 + (loc % 64);
+            if (lin >= total) return;
+            if (g.reverse) lin = total - 1 - lin;
+        }
     }
     int tm, tn;
     if (!SPLIT && g.sub_count > 0) {
@@ -513,6 +529,15 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
             k_begin = s0 * KT;
             k_len = (g.k - k_begin) < cnt * KT ? (g.k - k_begin) : cnt * KT;
         }
+    } else if (g.kcut != 0) {
+        const int d = ((g.kaxis ? n0 : m0) / g.kblk) * g.kblk;
+        if (g.kcut == 1) {
+            k_len = d;
+        } else {
+            k_begin = d + g.kblk;
+            k_len = g.k - k_begin;
+        }
+        if (k_len <= 0) return;   // nothing to add to this tile
     }
 
     // slab origins at depth k_begin

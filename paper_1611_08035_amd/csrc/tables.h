@@ -6,4 +6,11 @@ namespace xg {
 // Each returns its table and writes the number of entries to *n.
 const VariantEntry<double> *d_variant_table(int *n);
 const VariantEntry<float> *s_variant_table(int *n);
+
+// C += alpha op(A) op(B) with a depth range per tile (GemmArgs::kcut, kaxis, kblk, reverse): not
+// part of the C interface, used by the symmetric product.  Returns as the real products do.
+int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+             const double *B, int64_t ldb, double *C, int64_t ldc, void *stream, int kcut, int kaxis, int kblk);
+int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+             const float *B, int64_t ldb, float *C, int64_t ldc, void *stream, int kcut, int kaxis, int kblk);
 }  // namespace xg

@@ -35,7 +35,8 @@ static hipError_t launch_one(const GemmArgs<T> &g, hipStream_t st) {
         }
     }
     int64_t nt = tile_count(g.uplo, g.ntm, g.ntn, Cfg::MT_M, Cfg::MT_N);
-    if (!SPLIT && g.sub_count > 0) nt = 4 * (int64_t)g.sub_count;          // quarter tiles of the tail
+    if (!SPLIT && g.kcut != 0) nt = (nt + 64 * NUM_XCD - 1) / (64 * NUM_XCD) * (64 * NUM_XCD);   // whole rounds of squares
+    else if (!SPLIT && g.sub_count > 0) nt = 4 * (int64_t)g.sub_count;          // quarter tiles of the tail
     else if (!SPLIT && g.first > 0 && g.first < nt) nt = g.first;          // the leading tiles only
     if constexpr (SPLIT) {
         if (g.ndp < 0 || g.ndp > nt || g.nsplit < 1 || !g.part || !g.cnt) return hipErrorInvalidValue;

@@ -152,7 +152,7 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
 template <typename T>
 int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
               const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream, int uplo = 0, void *work = nullptr,
-              size_t lwork = 0) {
+              size_t lwork = 0, int kcut = 0, int kaxis = 0, int kblk = 0) {
     t_last_kernel = "none";
     t_last_split = 1;
     if (!is_n(ta) && !is_t(ta)) return -1;
@@ -209,6 +209,10 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     g.cnt = nullptr;
     g.first = 0;
     g.sub_count = g.sub_base = g.sub_ntm = g.sub_ntn = 0;
+    g.kcut = kcut;
+    g.kaxis = kaxis;
+    g.kblk = kblk;
+    g.reverse = (kcut == 1 && kaxis == 0) ? 1 : 0;
     if (fast && plan.nsplit > 1) {
         g.ndp = (int)plan.ndp;
         g.nsplit = plan.nsplit;
@@ -218,7 +222,8 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     }
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
-    if (fast && plan.nsplit == 1 && plan.vq >= 0 && v == plan.v) {
+    if (kcut != 0 && (!fast || plan.nsplit != 1 || kblk % tab[v].mt_m != 0 || kblk % tab[v].mt_n != 0)) return (int)hipErrorInvalidValue;
+    if (fast && plan.nsplit == 1 && plan.vq >= 0 && v == plan.v && kcut == 0) {
         // the full rounds with this variant, then the tail as quarter tiles of the smaller one
         const int big_ntm = (int)((m + tab[v].mt_m - 1) / tab[v].mt_m), big_ntn = (int)((n + tab[v].mt_n - 1) / tab[v].mt_n);
         const int64_t tiles = tile_count(uplo, big_ntm, big_ntn, tab[v].mt_m, tab[v].mt_n);
@@ -461,6 +466,17 @@ __global__ void __launch_bounds__(256, 2) hwid_kernel(unsigned *out) {
 }
 
 }  // namespace
+
+namespace xg {
+int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+             const double *B, int64_t ldb, double *C, int64_t ldc, void *stream, int kcut, int kaxis, int kblk) {
+    return gemm_impl<double>(ta, tb, m, n, k, alpha, A, lda, B, ldb, 1.0, C, ldc, stream, 0, nullptr, 0, kcut, kaxis, kblk);
+}
+int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+             const float *B, int64_t ldb, float *C, int64_t ldc, void *stream, int kcut, int kaxis, int kblk) {
+    return gemm_impl<float>(ta, tb, m, n, k, alpha, A, lda, B, ldb, 1.0f, C, ldc, stream, 0, nullptr, 0, kcut, kaxis, kblk);
+}
+}  // namespace xg
 
 extern "C" {
 

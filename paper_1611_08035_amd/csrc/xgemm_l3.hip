@@ -7,6 +7,7 @@
 // (depth = half the order, so the products are large).  Diagonal blocks of
 // order <= NB are solved (multiplied) in a small kernel of their own.
 #include "../../include/xgemm.h"
+#include "tables.h"
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -449,11 +450,23 @@ template <typename T> struct WideProdArgs {
     int dim, nrhs, left;
     int etrans, stored_lower, unit;   // triangular: E(r,c) = A[c + r*lda] if etrans; symmetric: only stored_lower is read
     T alpha;
+    // > 0: the launch covers every diagonal block of order WIDE of a matrix of this order (the last one
+    // may be smaller), workgroups (x, y) taking block y; A, X and Y then point at the first block and
+    // dim is not read.  Blocks that do not depend on each other only (the symmetric product).
+    int batch_order;
 };
 template <typename T> constexpr size_t wide_prod_lds_bytes() { return 2 * PANEL * WIDE * sizeof(T); }
 
 template <typename T, int MODE>
-__global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArgs<T> a) {
+__global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArgs<T> a0) {
+    WideProdArgs<T> a = a0;
+    if (a0.batch_order > 0) {
+        const int64_t off = (int64_t)blockIdx.y * WIDE;
+        a.A += off + off * a0.lda;
+        a.X += a0.left ? off : off * a0.ldx;
+        a.Y += a0.left ? off : off * a0.ldy;
+        a.dim = (int)(a0.batch_order - off < WIDE ? a0.batch_order - off : WIDE);
+    }
     using M = Mma16<T>;
     using acc_t = typename M::acc_t;
     constexpr int DEPTH = 2, TILES = WIDE / 16, HT = TILES / 2, KS = PANEL / 4, NPAN = WIDE / PANEL;
@@ -636,8 +649,9 @@ template <typename T, int MODE> int launch_wide_product(const WideProdArgs<T> &a
     constexpr int PER_WG = MMA_RHS * WAVES;
     const hipError_t e = allow_lds(wide_product_kernel<T, MODE>, LDS);
     if (e != hipSuccess) return (int)e;
-    hipLaunchKernelGGL((wide_product_kernel<T, MODE>), dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG)), dim3(16 * 64), LDS,
-                       static_cast<hipStream_t>(stream), a);
+    const unsigned blocks = a.batch_order > 0 ? (unsigned)((a.batch_order + WIDE - 1) / WIDE) : 1u;
+    hipLaunchKernelGGL((wide_product_kernel<T, MODE>), dim3((unsigned)((a.nrhs + PER_WG - 1) / PER_WG), blocks), dim3(16 * 64),
+                       LDS, static_cast<hipStream_t>(stream), a);
     return (int)hipGetLastError();
 }
 
@@ -709,6 +723,7 @@ template <typename T> struct Tri {
             w.stored_lower = a.stored_lower;
             w.unit = a.unit;
             w.alpha = alpha;
+            w.batch_order = 0;
             return e_lower() ? launch_wide_product<T, 0>(w, stream) : launch_wide_product<T, 1>(w, stream);
         } else if (product) {
             hipLaunchKernelGGL(trmm_block_kernel<T>, grid(MMA_RHS), blk, 0, st, a);
@@ -1667,7 +1682,53 @@ template <typename T> struct Symm {
     T alpha;
     void *stream;
 
+    // Orders from 2 WIDE to FLAT_MAX, flat: with the block cut into diagonal blocks of order WIDE,
+    // everything strictly below the block diagonal is one product whose depth per tile ends where the
+    // tile's diagonal block begins, everything strictly above it one product whose depth starts where
+    // that block ends (the stored triangle read as it is for one of them, transposed for the other),
+    // and the diagonal blocks, which do not depend on each other, are one launch of the block
+    // kernel.  Three launches in place of a recursion whose lower levels are small products.  Above
+    // FLAT_MAX the recursion's full-depth products are the faster ones (measured at 16384).
+    static constexpr int64_t FLAT_MAX = 8192;
+    int flat(int64_t off, int64_t dim) const {
+        const T *Ad = A + off + off * lda;
+        const T *Bd = left ? B + off : B + off * ldb;
+        T *Cd = left ? C + off : C + off * ldc;
+        const int64_t mm = left ? dim : m, nn = left ? n : dim;
+        // The first pass needs the entries (i, k), k < i, on the left (the stored triangle of a lower
+        // matrix as it is) and the entries (k, j), k < j, on the right (the same triangle transposed);
+        // the second pass the other way round.
+        const char p1 = (left == lower) ? 'N' : 'T', p2 = p1 == 'N' ? 'T' : 'N';
+        int rc = left ? xg::gemm_cut(p1, 'N', mm, nn, dim, alpha, Ad, lda, Bd, ldb, Cd, ldc, stream, 1, 0, (int)WIDE)
+                      : xg::gemm_cut('N', p1, mm, nn, dim, alpha, Bd, ldb, Ad, lda, Cd, ldc, stream, 1, 1, (int)WIDE);
+        if (rc == (int)hipErrorInvalidValue) return -1;   // not a shape for that kernel path; nothing was enqueued
+        if (rc) return rc;
+        rc = left ? xg::gemm_cut(p2, 'N', mm, nn, dim, alpha, Ad, lda, Bd, ldb, Cd, ldc, stream, 2, 0, (int)WIDE)
+                  : xg::gemm_cut('N', p2, mm, nn, dim, alpha, Bd, ldb, Ad, lda, Cd, ldc, stream, 2, 1, (int)WIDE);
+        if (rc) return rc;
+        WideProdArgs<T> w;
+        w.A = Ad;
+        w.lda = lda;
+        w.X = Bd;
+        w.ldx = ldb;
+        w.Y = Cd;
+        w.ldy = ldc;
+        w.dim = 0;
+        w.nrhs = (int)(left ? n : m);
+        w.left = left ? 1 : 0;
+        w.etrans = 0;
+        w.stored_lower = lower ? 1 : 0;
+        w.unit = 0;
+        w.alpha = alpha;
+        w.batch_order = (int)dim;
+        return launch_wide_product<T, 2>(w, stream);
+    }
+
     int run(int64_t off, int64_t dim) const {
+        if (dim >= 2 * WIDE && dim <= FLAT_MAX) {
+            const int rc = flat(off, dim);
+            if (rc != -1) return rc;                      // -1: take the recursion instead
+        }
         if (dim > NB && dim <= WIDE) {
             WideProdArgs<T> w;
             w.A = A + off + off * lda;
@@ -1683,6 +1744,7 @@ template <typename T> struct Symm {
             w.stored_lower = lower ? 1 : 0;
             w.unit = 0;
             w.alpha = alpha;
+            w.batch_order = 0;
             return launch_wide_product<T, 2>(w, stream);
         }
         if (dim <= NB) {

@@ -54,10 +54,14 @@ def test_symm_from_one_block_to_several_levels(dtype, side, uplo):
 
 @pytest.mark.parametrize("dtype,R", [(np.float64, 1000), (np.float32, 8)])
 @pytest.mark.parametrize("side,uplo", list(itertools.product("LR", "LU")))
-def test_symm_integer_bit_exact(dtype, R, side, uplo):
-    rng = si.rng_for(211, 0)
-    m, n = (300, 130) if side == "L" else (130, 300)
-    dim = m if side == "L" else n
+@pytest.mark.parametrize("dim,other", [(300, 130), (1030, 200), (768, 257)])
+def test_symm_integer_bit_exact(dtype, R, side, uplo, dim, other):
+    """Order 300: the recursion down to the block kernels.  Orders from 512 on: two products whose
+    depth per tile stops short of (starts beyond) the tile's diagonal block, then the diagonal blocks;
+    a ragged last diagonal block (1030) and a whole number of them (768).  The unreferenced triangle
+    holds NaN throughout."""
+    rng = si.rng_for(211, dim)
+    m, n = (dim, other) if side == "L" else (other, dim)
     A = sym_matrix(rng, dim, dim + 1, uplo, dtype, "int", R)
     B, C = si.integers(rng, m, n, m + 2, dtype, R), si.integers(rng, m, n, m + 3, dtype, R)
     for alpha, beta in [(1.0, 0.0), (-2.0, 1.0), (1.0, -1.0)]:
