@@ -54,7 +54,7 @@ def test_symm_from_one_block_to_several_levels(dtype, side, uplo):
 
 @pytest.mark.parametrize("dtype,R", [(np.float64, 1000), (np.float32, 8)])
 @pytest.mark.parametrize("side,uplo", list(itertools.product("LR", "LU")))
-@pytest.mark.parametrize("dim,other", [(300, 130), (1030, 200), (768, 257)])
+@pytest.mark.parametrize("dim,other", [(300, 130), (1030, 200), (768, 257), (513, 1)])
 def test_symm_integer_bit_exact(dtype, R, side, uplo, dim, other):
     """Order 300: the recursion down to the block kernels.  Orders from 512 on: two products whose
     depth per tile stops short of (starts beyond) the tile's diagonal block, then the diagonal blocks;
