@@ -162,3 +162,26 @@ def test_4096_sampled(name):
         assert info2 == 0
         nviol, ratio = oracle.bound_violations(out[J, I], c1 + c2, g1 + g2, 2 * k, oracle.U64, 4.0)
     assert info == 0 and nviol == 0, ratio
+
+
+@pytest.mark.parametrize("dtype,prec,R", [(np.float64, "d", 1000), (np.float32, "s", 8)])
+@pytest.mark.parametrize("side,uplo", [("L", "L"), ("R", "U")])
+def test_symm_flat_passes_with_every_tile_variant(dtype, prec, R, side, uplo):
+    """The two products with a depth range per tile, forced through every tile variant in turn (the range is
+    taken from the tile's first row or column, so every tile size has to land on the block boundaries)."""
+    rng = si.rng_for(213, 0)
+    dim, other = 1030, 150
+    m, n = (dim, other) if side == "L" else (other, dim)
+    A = sym_matrix(rng, dim, dim + 1, uplo, dtype, "int", R)
+    B, C = si.integers(rng, m, n, m + 2, dtype, R), si.integers(rng, m, n, m + 3, dtype, R)
+    want = C.copy()
+    assert oracle.symm_work(side, uplo, m, n, -1.0, A, dim + 1, B, m + 2, 1.0, want, m + 3) == 0
+    try:
+        for v in range(16):
+            if xg.xgemm_variant_name(prec, v) is None:
+                break
+            assert xg.xgemm_force_variant(v) == 0
+            out = run("symm", dtype, side, uplo, m, n, -1.0, A, dim + 1, B, m + 2, 1.0, C, m + 3)
+            assert np.array_equal(out, want, equal_nan=True), xg.xgemm_variant_name(prec, v)
+    finally:
+        xg.xgemm_force_variant(-1)
