@@ -53,6 +53,7 @@ constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece m
 constexpr double CLOCK_GHZ = 2.4;
 constexpr double T_ROUND0 = 10.0;        // ramp-up and flush of a workgroup that nothing else hides
 constexpr double LONE_EFF = 0.95;        // a CU holding one workgroup, relative to a full one
+constexpr double PART_EFF = 0.96;        // a CU holding more than one but fewer than it has room for
 constexpr double REDUCE_GBS = 80.0;      // rate at which one workgroup reads partial tiles back
 constexpr double PART_TBS = 6.0;         // rate at which all partial tiles are written and read
 constexpr double T_SPLIT0 = 2.0;         // arrival counting
@@ -74,7 +75,9 @@ struct Plan {
 // tiles of a variant run in rounds of (CUs x workgroups per CU); a full round
 // costs wgs * t(k); the last, partly filled round costs occ * t(k) with occ
 // workgroups per CU (a lone workgroup has nobody to hide its stalls behind:
-// LONE_EFF) plus its unhidden ramp-up and flush.  With a workspace the rem
+// LONE_EFF; more than one but fewer than fit: PART_EFF).  Every launch pays one
+// ramp-up (at its start) and one flush (at its end) that nothing hides, T_ROUND0
+// together, whether its last round is full or not.  With a workspace the rem
 // tiles of that round may instead be cut into S <= slots / rem pieces of depth
 // k / S each; that adds the write and read of rem * S partial tiles and the
 // serial read of S partial tiles by the workgroup that finishes each tile.
@@ -101,9 +104,11 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
         auto t_tile = [&](double depth) { return 2.0 * area * depth / (cu_flops_per_us * e.eff); };
         auto t_tail = [&](int64_t units, double depth) {
             const int64_t occ = (units + cus - 1) / cus;
-            return T_ROUND0 + (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : 1.0);
+            return (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : occ < e.wgs_per_cu ? PART_EFF : 1.0);
         };
-        const double rounds = (double)full * e.wgs_per_cu * t_tile((double)k);
+        // every launch ramps up once and flushes once with nothing to hide behind, whether its last
+        // round is a full one or not
+        const double rounds = T_ROUND0 + (double)full * e.wgs_per_cu * t_tile((double)k);
         Plan p{v, 1, tiles, -1};
         double cost = rounds + (rem > 0 ? t_tail(rem, (double)k) : 0.0);
         if (rem > 0 && full > 0 && fast && t_forced_split != 0 && (k >= QUARTER_MIN_K || t_forced_split == 1)) {
