@@ -54,6 +54,8 @@ constexpr double CLOCK_GHZ = 2.4;
 constexpr double T_ROUND0 = 10.0;        // ramp-up and flush of a workgroup that nothing else hides
 constexpr double LONE_EFF = 0.95;        // a CU holding one workgroup, relative to a full one
 constexpr double PART_EFF = 0.96;        // a CU holding more than one but fewer than it has room for
+constexpr double T_FLUSH0 = 2.0;         // per round of workgroups: what of their ramp-up and flush the others do not hide,
+constexpr double T_FLUSH_KIB = 0.13;     //   T_FLUSH0 + T_FLUSH_KIB * (KiB of the C tile) / (workgroups per CU)
 constexpr double REDUCE_GBS = 80.0;      // rate at which one workgroup reads partial tiles back
 constexpr double PART_TBS = 6.0;         // rate at which all partial tiles are written and read
 constexpr double T_SPLIT0 = 2.0;         // arrival counting
@@ -102,13 +104,18 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
         const double tile_bytes = area * sizeof(T);
         const int64_t full = tiles / slots, rem = tiles % slots;
         auto t_tile = [&](double depth) { return 2.0 * area * depth / (cu_flops_per_us * e.eff); };
+        // per round: the read-modify-write of the C tiles is only partly hidden by the other workgroups of the
+        // CU, the less so the larger the tile, the fewer of them and the shorter their K loops (fitted to rank-k
+        // updates: 10.5 us per round of 128x128 tiles at k = 256, 3.9 at k = 1024)
+        const double t_flush = (T_FLUSH0 + T_FLUSH_KIB * (tile_bytes / 1024.0) / (double)e.wgs_per_cu) *
+                               (k < 256 ? 1.0 : 256.0 / (double)k);
         auto t_tail = [&](int64_t units, double depth) {
             const int64_t occ = (units + cus - 1) / cus;
-            return (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : occ < e.wgs_per_cu ? PART_EFF : 1.0);
+            return t_flush + (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : occ < e.wgs_per_cu ? PART_EFF : 1.0);
         };
         // every launch ramps up once and flushes once with nothing to hide behind, whether its last
         // round is a full one or not
-        const double rounds = T_ROUND0 + (double)full * e.wgs_per_cu * t_tile((double)k);
+        const double rounds = T_ROUND0 + (double)full * (e.wgs_per_cu * t_tile((double)k) + t_flush);
         Plan p{v, 1, tiles, -1};
         double cost = rounds + (rem > 0 ? t_tail(rem, (double)k) : 0.0);
         if (rem > 0 && full > 0 && fast && t_forced_split != 0 && (k >= QUARTER_MIN_K || t_forced_split == 1)) {

@@ -24,7 +24,9 @@ def test_benchmark_configurations_fill_their_rounds_and_are_never_split():
     ws = xg.xgemm_workspace_bytes()
     for prec, shape, want in [("d", (8192, 8192, 8192), "d_128x128x16_w2x2"), ("d", (4096, 4096, 4096), "d_128x128x16_w2x2"),
                               ("s", (8192, 8192, 8192), "s_256x128x16_w2x2"), ("s", (16384, 16384, 16384), "s_256x128x16_w2x2"),
-                              ("d", (16384, 16384, 64), "d_128x128x16_w2x2"), ("d", (16384, 16384, 256), "d_128x128x16_w2x2")]:
+                              # rank-k updates: the smaller tile, three workgroups per CU to hide each other's flush of C
+                              ("d", (16384, 16384, 64), "d_128x64x16_w2x2"), ("d", (16384, 16384, 256), "d_128x64x16_w2x2"),
+                              ("d", (16384, 16384, 1024), "d_128x128x16_w2x2")]:
         for lwork in (0, ws):
             v, pieces, whole = xg.xgemm_plan(prec, 0, *shape, lwork)
             assert name(prec, v) == want and pieces == 1, (prec, shape, lwork)
