@@ -494,7 +494,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     }
     int tm, tn;
     if (!SPLIT && g.sub_count > 0) {
-        const int b = blockIdx.x;
+        // position among the quarter tiles: one contiguous run of them per XCD, so that the quarters of a
+        // tile and its neighbours share that XCD's L2
+        const int b = lin_of_block(blockIdx.x, (int)gridDim.x);
         const TilePos big = tile_of_lin(g.sub_base + (b >> 2), g.sub_ntm, g.sub_ntn, g.uplo, 2 * MT_M, 2 * MT_N);
         tm = 2 * big.tm + (b & 1);
         tn = 2 * big.tn + ((b >> 1) & 1);

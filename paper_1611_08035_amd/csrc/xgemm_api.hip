@@ -60,6 +60,9 @@ constexpr double REDUCE_GBS = 80.0;      // rate at which one workgroup reads pa
 constexpr double PART_TBS = 6.0;         // rate at which all partial tiles are written and read
 constexpr double T_SPLIT0 = 2.0;         // arrival counting
 constexpr double T_LAUNCH = 4.0;         // a second launch on the same stream
+constexpr double DRAIN_FRAC = 0.25;      // ... which starts only when the first has drained: the workgroups of its last round end
+constexpr double T_DRAIN_MAX = 60.0;     // spread over about this fraction of that round's time, up to this much (measured:
+                                         // 56 us at depth 1024, no more than that at depth 8192)
 constexpr int64_t QUARTER_MIN_K = 1024;  // shallower products gain nothing from a quartered tail (measured)
 
 struct Plan {
@@ -124,7 +127,9 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
                 const double qarea = (double)tab[w].mt_m * (double)tab[w].mt_n;
                 const int64_t occ = (4 * rem + cus - 1) / cus;
                 const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * tab[w].eff);
-                const double c = rounds + T_LAUNCH + T_ROUND0 + (double)occ * tq / (occ == 1 ? LONE_EFF : 1.0);
+                const double drain = DRAIN_FRAC * e.wgs_per_cu * t_tile((double)k);
+                const double c = rounds + T_LAUNCH + T_ROUND0 + (drain < T_DRAIN_MAX ? drain : T_DRAIN_MAX) +
+                                 (double)occ * tq / (occ == 1 ? LONE_EFF : 1.0);
                 if (c < cost || t_forced_split == 1) { cost = c; p.ndp = full * slots; p.vq = w; }
                 break;
             }
