@@ -53,6 +53,7 @@ constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece m
 constexpr double CLOCK_GHZ = 2.4;
 constexpr double T_ROUND0 = 10.0;        // ramp-up and flush of a workgroup that nothing else hides
 constexpr double LONE_EFF = 0.95;        // a CU holding one workgroup, relative to a full one
+constexpr double LONE_EFF_SINGLE = 0.4;  // the same for a variant whose waves hold a single fp64 accumulator tile
 constexpr double PART_EFF = 0.96;        // a CU holding more than one but fewer than it has room for
 constexpr double T_FLUSH0 = 2.0;         // per round of workgroups: what of their ramp-up and flush the others do not hide,
 constexpr double T_FLUSH_KIB = 0.13;     //   T_FLUSH0 + T_FLUSH_KIB * (KiB of the C tile) / (workgroups per CU)
@@ -112,9 +113,14 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
         // updates: 10.5 us per round of 128x128 tiles at k = 256, 3.9 at k = 1024)
         const double t_flush = (T_FLUSH0 + T_FLUSH_KIB * (tile_bytes / 1024.0) / (double)e.wgs_per_cu) *
                                (k < 256 ? 1.0 : 256.0 / (double)k);
+        // a wave with a single fp64 accumulator tile issues each matrix instruction only when the one before
+        // has finished (95 cycles against 64) and waits for every fragment read; alone on its SIMD nothing
+        // fills those gaps (measured: 0.31 of peak alone against 0.78 with four workgroups on the CU)
+        const bool single_tile = sizeof(T) == 8 && e.mt_m / e.wgm == 16 && e.mt_n / e.wgn == 16;
+        const double lone_eff = single_tile ? LONE_EFF_SINGLE : LONE_EFF;
         auto t_tail = [&](int64_t units, double depth) {
             const int64_t occ = (units + cus - 1) / cus;
-            return t_flush + (double)occ * t_tile(depth) / (occ == 1 ? LONE_EFF : occ < e.wgs_per_cu ? PART_EFF : 1.0);
+            return t_flush + (double)occ * t_tile(depth) / (occ == 1 ? lone_eff : occ < e.wgs_per_cu ? PART_EFF : 1.0);
         };
         // every launch ramps up once and flushes once with nothing to hide behind, whether its last
         // round is a full one or not
@@ -128,8 +134,10 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
                 const int64_t occ = (4 * rem + cus - 1) / cus;
                 const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * tab[w].eff);
                 const double drain = DRAIN_FRAC * e.wgs_per_cu * t_tile((double)k);
+                const bool single_w = sizeof(T) == 8 && tab[w].mt_m / tab[w].wgm == 16 && tab[w].mt_n / tab[w].wgn == 16;
                 const double c = rounds + T_LAUNCH + T_ROUND0 + (drain < T_DRAIN_MAX ? drain : T_DRAIN_MAX) +
-                                 (double)occ * tq / (occ == 1 ? LONE_EFF : 1.0);
+                                 (double)occ * tq / (occ == 1 ? (single_w ? LONE_EFF_SINGLE : LONE_EFF)
+                                                              : occ < tab[w].wgs_per_cu ? PART_EFF : 1.0);
                 if (c < cost || t_forced_split == 1) { cost = c; p.ndp = full * slots; p.vq = w; }
                 break;
             }

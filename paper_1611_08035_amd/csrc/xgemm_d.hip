@@ -10,6 +10,7 @@ using D_256x128x8 = TileCfg<double, 256, 128, 8, 4, 2, 2>;
 using D_64x64x16 = TileCfg<double, 64, 64, 16, 2, 2, 2>;
 using D_128x64x16 = TileCfg<double, 128, 64, 16, 2, 2, 2>;
 using D_64x128x16 = TileCfg<double, 64, 128, 16, 2, 2, 2>;
+using D_32x32x16 = TileCfg<double, 32, 32, 16, 2, 2, 2>;   // one matrix-instruction tile per wave: for products too small to fill the device with larger tiles
 
 #define XG_ENTRY(T, CFG, NAME, WGS, EFF) {NAME, CFG::MT_M, CFG::MT_N, CFG::KT, CFG::WGM, CFG::WGN, WGS, EFF, false, &launch_cfg<T, CFG, false>}
 // the same with the split-tail kernels built as well
@@ -23,6 +24,7 @@ const VariantEntry<double> *d_variant_table(int *n) {
     XG_ENTRY(double, D_64x64x16, "d_64x64x16_w2x2", 4, 0.90f),
     XG_ENTRY(double, D_128x64x16, "d_128x64x16_w2x2", 3, 0.95f),
     XG_ENTRY(double, D_64x128x16, "d_64x128x16_w2x2", 3, 0.93f),
+    XG_ENTRY(double, D_32x32x16, "d_32x32x16_w2x2", 8, 0.70f),
     };
     *n = (int)(sizeof(table) / sizeof(table[0]));
     return table;

@@ -35,9 +35,12 @@ def test_benchmark_configurations_fill_their_rounds_and_are_never_split():
 
 
 def test_small_problems_take_small_tiles():
-    for prec in "ds":
+    # one matrix-instruction tile per wave: 32x32 tiles in fp64 (16x16x4), 64x64 in fp32 (32x32x2)
+    for prec, tile, count in (("d", "32x32", 256), ("s", "64x64", 64)):
         v, pieces, whole = xg.xgemm_plan(prec, 0, 512, 512, 512, 0)
-        assert name(prec, v).startswith(f"{prec}_64x64") and pieces == 1 and whole == 64
+        assert name(prec, v).startswith(f"{prec}_{tile}") and pieces == 1 and whole == count
+    v, pieces, whole = xg.xgemm_plan("d", 0, 1024, 1024, 1024, 0)
+    assert name("d", v).startswith("d_64x64") and whole == 256
 
 
 def test_tail_round_is_split_only_with_a_workspace_and_only_the_tail():
@@ -77,9 +80,13 @@ def test_without_a_workspace_the_tail_round_of_a_deep_product_runs_as_quarter_ti
     # nothing to quarter: fewer tiles than one round, or a variant with no half-size partner
     xg.xgemm_force_split(1)
     assert xg.xgemm_plan("d", 0, 1024, 1024, 4096, 0) == (0, 1, 64)
+    v32 = [i for i in range(16) if (name("d", i) or "").startswith("d_32x32")][0]
+    xg.xgemm_force_variant(v32)
+    assert xg.xgemm_plan("d", 0, 5120, 5120, 5120, 0) == (v32, 1, 25600)
+    # 64x64 tiles have 32x32 quarters: 6400 tiles on 1024 slots, six full rounds and 256 tiles
     v64 = [i for i in range(16) if (name("d", i) or "").startswith("d_64x64")][0]
     xg.xgemm_force_variant(v64)
-    assert xg.xgemm_plan("d", 0, 5120, 5120, 5120, 0) == (v64, 1, 6400)
+    assert xg.xgemm_plan("d", 0, 5120, 5120, 5120, 0) == (v64, 1, 6144)
 
 
 def test_forcing_and_errors():
