@@ -58,6 +58,31 @@ def check_full(xg, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, factor=
     return ratio
 
 
+def check_out_full(out, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, factor=4.0, chunk=1024, label=""):
+    """A result already on the host against the extended-precision oracle on EVERY element,
+    a block of `chunk` columns of C at a time (op(B) and C cut along n, so that the wide
+    reference and magnitude arrays stay small); padding rows of C untouched.  Prints one
+    progress line per block.  Returns the largest err/bound ratio."""
+    import sys
+    import time
+    worst = 0.0
+    t0 = time.time()
+    for j0 in range(0, n, chunk):
+        j1 = min(n, j0 + chunk)
+        Bc = B[j0:j1] if tb in "Nn" else np.ascontiguousarray(B[:, j0:j1])
+        ldbc = ldb if tb in "Nn" else j1 - j0
+        info, Cref, G = oracle.gemm_ext(ta, tb, m, j1 - j0, k, alpha, A, lda, Bc, ldbc, beta, C[j0:j1], ldc)
+        assert info == 0
+        nviol, ratio = oracle.bound_violations(out[j0:j1, :m], Cref, G, k, unit_roundoff(C.dtype), factor)
+        assert nviol == 0, f"{nviol} elements outside the bound (max ratio {ratio}) in columns {j0}:{j1} of {ta}{tb} {m}x{n}x{k}"
+        worst = max(worst, ratio)
+        print(f"  {label} columns {j0}:{j1} of {n} checked, {time.time() - t0:.1f} s", flush=True)
+        sys.stdout.flush()
+    if ldc > m:
+        assert np.array_equal(C[:, m:], out[:, m:], equal_nan=True), "padding rows of C were written"
+    return worst
+
+
 def check_samples(out, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, I, J, factor=4.0):
     info, cref, g = oracle.gemm_samples(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, I, J)
     assert info == 0

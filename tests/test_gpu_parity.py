@@ -13,7 +13,7 @@ import pytest
 import oracle
 import paper_1611_08035_amd as xg
 import synth_inputs as si
-from gpu_util import (check_full, check_samples, make_operands, run_real, to_dev, torch_mod, unit_roundoff)
+from gpu_util import (check_full, check_out_full, check_samples, make_operands, run_real, to_dev, torch_mod, unit_roundoff)
 
 pytestmark = pytest.mark.gpu
 
@@ -228,33 +228,33 @@ def test_config2_dgemm_square_full_check(nsz):
 
 
 @pytest.mark.parametrize("nsz", [2048, 4096, 8192])
-def test_config2_dgemm_square_sampled(nsz):
-    """Full-size runs in the launch configuration the benchmark times, checked
-    on sampled rows, columns and entries, and bit-exactly on integer data."""
+def test_config2_dgemm_square_large_full_check(nsz):
+    """The sizes the benchmark times, in its launch configuration (padded leading dimensions,
+    alpha 1.5, beta -0.5), every element against the extended-precision oracle."""
     rng = si.rng_for(2, nsz)
     ld = si.padded_ld(nsz)
     A, B, C = (si.uniform(rng, nsz, nsz, ld) for _ in range(3))
     out = run_real(xg, "N", "N", nsz, nsz, nsz, 1.5, A, ld, B, ld, -0.5, C, ld)
-    assert np.array_equal(out[:, nsz:], C[:, nsz:], equal_nan=True)
-    assert np.all(np.isfinite(out[:, :nsz]))
-    I, J = si.sample_indices(rng, nsz, nsz, 4, 4, 8192)
-    ratio = check_samples(out, "N", "N", nsz, nsz, nsz, 1.5, A, ld, B, ld, -0.5, C, ld, I, J)
-    print("config2", nsz, "sampled max err/bound", ratio, xg.xgemm_last_kernel_name())
+    kern = xg.xgemm_last_kernel_name()
+    ratio = check_out_full(out, "N", "N", nsz, nsz, nsz, 1.5, A, ld, B, ld, -0.5, C, ld, label=f"config2 {nsz}")
+    print("config2", nsz, "every element, max err/bound", ratio, kern)
 
 
 def test_headline_size_integer_data_bit_exact():
-    """8192^3 on integer-valued operands: every partial sum is exactly
-    representable, so any summation order gives the same bits; numpy's float64
-    matmul on the same data is therefore an exact reference."""
+    """8192^3 on integer-valued operands: every partial sum is exactly representable, so any
+    summation order gives the same bits and the working-precision oracle is an exact reference
+    for every element (numpy's float64 matmul on the same data is a third opinion)."""
     nsz = 8192
     rng = si.rng_for(2, 1)
     ld = si.padded_ld(nsz)
     A, B, C = (si.integers(rng, nsz, nsz, ld, R=1000) for _ in range(3))
     out = run_real(xg, "N", "N", nsz, nsz, nsz, 2.0, A, ld, B, ld, -1.0, C, ld)
+    want = C.copy()
+    assert oracle.gemm_work("N", "N", nsz, nsz, nsz, 2.0, A, ld, B, ld, -1.0, want, ld) == 0
+    assert np.abs(want[:, :nsz]).max() < 2.0 ** 53
+    assert np.array_equal(out, want, equal_nan=True)
     # column-major product C = A B is, on the (cols, ld) arrays, out_rows = B_rows @ A_rows
-    want = 2.0 * (B[:, :nsz] @ A[:, :nsz]) - C[:, :nsz]
-    assert np.abs(want).max() < 2.0 ** 53
-    assert np.array_equal(out[:, :nsz], want)
+    assert np.array_equal(out[:, :nsz], 2.0 * (B[:, :nsz] @ A[:, :nsz]) - C[:, :nsz])
     # all ones at the same size: C == k
     ones = si.constant(nsz, nsz, ld)
     out = run_real(xg, "N", "N", nsz, nsz, nsz, 1.0, ones, ld, ones, ld, 0.0, C, ld)
@@ -273,16 +273,29 @@ def test_config3_sgemm_1024_full_check():
 
 
 @pytest.mark.parametrize("nsz,ta,tb", [(4096, "N", "N"), (4096, "N", "T"), (4096, "T", "N"), (4096, "T", "T"),
-                                       (8192, "N", "N"), (16384, "N", "N")])
-def test_config3_sgemm_sampled(nsz, ta, tb):
+                                       (8192, "N", "N")])
+def test_config3_sgemm_large_full_check(nsz, ta, tb):
+    """Every element against the oracle that accumulates in double."""
     rng = si.rng_for(3, nsz + (ta == "T") + 2 * (tb == "T"))
     A, B, C = (si.uniform(rng, nsz, nsz, nsz, np.float32) for _ in range(3))
     out = run_real(xg, ta, tb, nsz, nsz, nsz, 1.0, A, nsz, B, nsz, 1.0, C, nsz)
+    kern = xg.xgemm_last_kernel_name()
+    ratio = check_out_full(out, ta, tb, nsz, nsz, nsz, 1.0, A, nsz, B, nsz, 1.0, C, nsz, chunk=2048,
+                           label=f"config3 {nsz} {ta}{tb}")
+    print("config3", nsz, ta + tb, "every element, max err/bound", ratio, kern)
+
+
+def test_config3_sgemm_16384_sampled():
+    """The one size whose full oracle (8.8 Tflop) does not fit a test: 64 full rows, 64 full
+    columns and 2^16 random entries."""
+    nsz = 16384
+    rng = si.rng_for(3, nsz)
+    A, B, C = (si.uniform(rng, nsz, nsz, nsz, np.float32) for _ in range(3))
+    out = run_real(xg, "N", "N", nsz, nsz, nsz, 1.0, A, nsz, B, nsz, 1.0, C, nsz)
     assert np.all(np.isfinite(out))
-    # the largest size: 16 full rows, 16 full columns and 2^16 random entries; the others a lighter sample
-    I, J = si.sample_indices(rng, nsz, nsz, 16, 16, 65536) if nsz == 16384 else si.sample_indices(rng, nsz, nsz, 4, 4, 8192)
-    ratio = check_samples(out, ta, tb, nsz, nsz, nsz, 1.0, A, nsz, B, nsz, 1.0, C, nsz, I, J)
-    print("config3", nsz, ta + tb, "sampled max err/bound", ratio, xg.xgemm_last_kernel_name())
+    I, J = si.sample_indices(rng, nsz, nsz, 64, 64, 65536)
+    ratio = check_samples(out, "N", "N", nsz, nsz, nsz, 1.0, A, nsz, B, nsz, 1.0, C, nsz, I, J)
+    print("config3", nsz, "sampled max err/bound", ratio, xg.xgemm_last_kernel_name())
 
 
 # --------------------------------------------------------------------------
@@ -290,13 +303,14 @@ def test_config3_sgemm_sampled(nsz, ta, tb):
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("mn,k", [(4096, 64), (4096, 128), (4096, 256), (16384, 64), (16384, 128), (16384, 256)])
 def test_config4_rank_k_update(mn, k):
+    """Rank-k updates, every element (the depth is small, so the full oracle is cheap)."""
     rng = si.rng_for(4, mn + k)
     A, B, C = si.normal(rng, mn, k), si.normal(rng, k, mn), si.normal(rng, mn, mn)
     out = run_real(xg, "N", "N", mn, mn, k, -1.0, A, mn, B, k, 1.0, C, mn)
-    assert np.all(np.isfinite(out))
-    I, J = si.sample_indices(rng, mn, mn, 8, 8, 1 << 16)
-    ratio = check_samples(out, "N", "N", mn, mn, k, -1.0, A, mn, B, k, 1.0, C, mn, I, J)
-    print("config4", mn, k, "sampled max err/bound", ratio, xg.xgemm_last_kernel_name())
+    kern = xg.xgemm_last_kernel_name()
+    ratio = check_out_full(out, "N", "N", mn, mn, k, -1.0, A, mn, B, k, 1.0, C, mn, chunk=2048,
+                           label=f"config4 {mn} k={k}")
+    print("config4", mn, k, "every element, max err/bound", ratio, kern)
 
 
 @pytest.mark.parametrize("pads", [(0, 0, 0), (7, 7, 7)])
