@@ -16,7 +16,7 @@
  *     C.  Scalars are passed by value from the host.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work; they do not synchronise.  All work goes to `stream`
- *     (xgemm_*potrf may also use a stream of the library's between a fork from
+ *     (xgemm_*potrf may also use streams of the library's between a fork from
  *     and a join to `stream`, see there).
  *   - trans is one of N n T t C c.  For the real routines C means T.
  *   - beta == 0: C is write-only; whatever it held (NaN, Inf) is overwritten.
@@ -26,8 +26,24 @@
  *   - Return value: 0 on success; -i if argument i (1-based, in the order of
  *     the prototype) is illegal, in which case nothing was enqueued; a positive
  *     value is the hipError_t of a failed launch.
- *   - Thread-safe and re-entrant; no global state except the name of the kernel
- *     variant last chosen by the calling thread (see xgemm_last_kernel_name).
+ *   - Thread-safe and re-entrant.  State the library keeps, all of it per host
+ *     thread unless said otherwise:
+ *       . the name of the kernel variant its last call chose
+ *         (xgemm_last_kernel_name) and the pieces of its last split;
+ *       . the benchmark controls of xgemm_tuning.h, which stay as set until
+ *         xgemm_tuning_reset() and are never touched by the routines below;
+ *       . per thread and device, two streams and 23 events that xgemm_*potrf
+ *         creates on its first look-ahead sweep and keeps for later calls
+ *         (xgemm_release_thread_resources() destroys them);
+ *       . per process and device, read once: the number of compute units, and which
+ *         kernels have been granted more than 64 KiB of LDS;
+ *       . per process, read at load: the environment variable
+ *         XGEMM_REQUIRE_ALIGNED (a test switch that sends operands that are not
+ *         16-byte aligned to the element-wise fallback kernels).
+ *
+ * This header is the BLAS-level surface.  Benchmark and tuning controls, the
+ * launch planner, the tile order and the analytical model are declared in
+ * xgemm_tuning.h; the device probes in xgemm_probe.h.
  */
 #ifndef XGEMM_H
 #define XGEMM_H
@@ -38,6 +54,11 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* ------------------------------------------------------------------------
+ * The hot path: real GEMM in two precisions, complex GEMM on split planes as
+ * four real GEMMs (with its workspace query), and two queries.
+ * ------------------------------------------------------------------------ */
 
 /*
  * Double-precision real GEMM (the micro-kernel sum of Sec. 2.1 in fp64, FP64 MFMA).
@@ -57,6 +78,47 @@ int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k,
                 float alpha, const float *A, int64_t lda,
                 const float *B, int64_t ldb,
                 float beta, float *C, int64_t ldc, void *stream);
+
+/*
+ * Double-precision complex GEMM on split planes, built from the real kernel
+ * (the paper's point that real GEMM carries complex GEMM, Abstract and Sec. 1;
+ * the "4m" arrangement: four real products per complex product):
+ *     Pr = Ar Br - Ai Bi,   Pi = Ar Bi + Ai Br,   C := alpha P + beta C.
+ * Xr / Xi are the real / imaginary planes of X, each column-major with the
+ * same leading dimension.  trans = C takes the conjugate transpose.
+ * alpha and beta are host arrays {re, im}.
+ * When alpha and beta are both real the routine is four real GEMM launches and
+ * needs no workspace.  Otherwise it needs `work`: a device buffer of `lwork`
+ * doubles, lwork >= xgemm_zgemm_worksize(m, n, alpha, beta); it holds Pr and Pi
+ * and its contents are undefined afterwards.
+ * Illegal-argument numbering: transa 1, transb 2, m 3, n 4, k 5, alpha 6, Ar 7,
+ * Ai 8, lda 9, Br 10, Bi 11, ldb 12, beta 13, Cr 14, Ci 15, ldc 16, work 17,
+ * lwork 18.
+ */
+int xgemm_zgemm_split(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                      const double alpha[2],
+                      const double *Ar, const double *Ai, int64_t lda,
+                      const double *Br, const double *Bi, int64_t ldb,
+                      const double beta[2],
+                      double *Cr, double *Ci, int64_t ldc,
+                      double *work, int64_t lwork, void *stream);
+
+/* Number of doubles of workspace xgemm_zgemm_split needs (0 when alpha and
+ * beta are real, else 2*m*n).  Host-only; touches no device. */
+size_t xgemm_zgemm_worksize(int64_t m, int64_t n, const double alpha[2], const double beta[2]);
+
+/* Library version string (static storage). */
+const char *xgemm_version(void);
+
+/* Name of the kernel variant chosen by the last xgemm_* call on the calling
+ * thread ("" before the first call, "scale" for the alpha == 0 / k == 0 path,
+ * "none" for a quick return).  For benchmarks and profiles.  Static storage. */
+const char *xgemm_last_kernel_name(void);
+
+/* ------------------------------------------------------------------------
+ * Beyond the hot path: the level-3 routines and drivers built on the real
+ * kernel, the forms with a workspace, complex GEMM on interleaved storage.
+ * ------------------------------------------------------------------------ */
 
 /*
  * Symmetric rank-k update on the real kernel (the paper's point that the level-3
@@ -176,18 +238,6 @@ int xgemm_strmm(char side, char uplo, char transa, char diag, int64_t m, int64_t
 int xgemm_dpotrf(char uplo, int64_t n, double *A, int64_t lda, int *info, void *stream);
 int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *stream);
 
-/* Benchmark/tuning control of xgemm_*potrf on the calling thread: panel width of
- * the look-ahead sweep.  -1: chosen from the order (default); 0: the recursion
- * alone, on the caller's stream; W > 0: panels of W columns whenever W < n.
- * Returns 0, or -1 for any other value. */
-int xgemm_force_potrf_panel(int64_t width);
-
-/* Benchmark/tuning control of xgemm_*potrf on the calling thread: the largest
- * order of a diagonal block that one workgroup factors by itself (64: one wave;
- * 128: three waves; 256: ten waves, the default, also chosen by -1); larger
- * blocks are halved.  Returns 0, or -1 for any other value. */
-int xgemm_force_potrf_block(int order);
-
 /*
  * GEMM and SYRK with a caller-owned workspace, which lets the library
  * cut the tiles of the last, partly filled round of workgroups along K (the k_c
@@ -223,34 +273,6 @@ int xgemm_ssyrk_ws(char uplo, char trans, int64_t n, int64_t k, float alpha, con
                    float beta, float *C, int64_t ldc, void *work, size_t lwork, void *stream);
 
 /*
- * Double-precision complex GEMM on split planes, built from the real kernel
- * (the paper's point that real GEMM carries complex GEMM, Abstract and Sec. 1;
- * the "4m" arrangement: four real products per complex product):
- *     Pr = Ar Br - Ai Bi,   Pi = Ar Bi + Ai Br,   C := alpha P + beta C.
- * Xr / Xi are the real / imaginary planes of X, each column-major with the
- * same leading dimension.  trans = C takes the conjugate transpose.
- * alpha and beta are host arrays {re, im}.
- * When alpha and beta are both real the routine is four real GEMM launches and
- * needs no workspace.  Otherwise it needs `work`: a device buffer of `lwork`
- * doubles, lwork >= xgemm_zgemm_worksize(m, n, alpha, beta); it holds Pr and Pi
- * and its contents are undefined afterwards.
- * Illegal-argument numbering: transa 1, transb 2, m 3, n 4, k 5, alpha 6, Ar 7,
- * Ai 8, lda 9, Br 10, Bi 11, ldb 12, beta 13, Cr 14, Ci 15, ldc 16, work 17,
- * lwork 18.
- */
-int xgemm_zgemm_split(char transa, char transb, int64_t m, int64_t n, int64_t k,
-                      const double alpha[2],
-                      const double *Ar, const double *Ai, int64_t lda,
-                      const double *Br, const double *Bi, int64_t ldb,
-                      const double beta[2],
-                      double *Cr, double *Ci, int64_t ldc,
-                      double *work, int64_t lwork, void *stream);
-
-/* Number of doubles of workspace xgemm_zgemm_split needs (0 when alpha and
- * beta are real, else 2*m*n).  Host-only; touches no device. */
-size_t xgemm_zgemm_worksize(int64_t m, int64_t n, const double alpha[2], const double beta[2]);
-
-/*
  * Double-precision complex GEMM on interleaved storage (the BLAS layout: element
  * (i, j) of X is the pair X[2*(i + j*ldx)], X[2*(i + j*ldx) + 1]; leading
  * dimensions count complex elements; A, B, C 16-byte aligned), built from the
@@ -277,141 +299,14 @@ int xgemm_zgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, const
                 double *C, int64_t ldc, int method, void *work, size_t lwork, void *stream);
 size_t xgemm_zgemm_workbytes(int64_t m, int64_t n, int64_t k, int method);
 
-/* Library version string (static storage). */
-const char *xgemm_version(void);
-
-/* Name of the kernel variant chosen by the last xgemm_* call on the calling
- * thread ("" before the first call, "scale" for the alpha == 0 / k == 0 path,
- * "none" for a quick return).  For benchmarks and profiles.  Static storage. */
-const char *xgemm_last_kernel_name(void);
-
 /*
- * Benchmark/tuning control: force the tile variant used by the real GEMM
- * entry points on the calling thread.  `variant` is an index into the list
- * reported by xgemm_variant_name(); -1 restores automatic selection.
- * Returns 0, or -1 if the index is out of range.
+ * Destroys the streams and events that xgemm_*potrf keeps for the calling thread on
+ * the current device (after waiting for the work on them); the next call that needs
+ * them creates them again.  For threads that end, and for callers that count handles.
+ * Must not be called while a call of this thread is being captured.  Returns 0 or a
+ * hipError_t.
  */
-int xgemm_force_variant(int variant);
-
-/* Benchmark/tuning control, on the calling thread, of what happens to the tiles
- * of the last, partly filled round of workgroups: -1 lets the cost model decide
- * (default); 0 runs them like the others; 1 runs them as quarter tiles in a
- * second launch wherever the shape has such a tail and a variant of half the
- * tile size exists (all real products and rank-k updates); 2..32 splits them
- * along K into that many pieces wherever the shape and workspace allow (the
- * *_ws routines).  Returns 0, or -1 for any other value.  xgemm_last_split(): pieces per tail tile used by the
- * last call on this thread (1: nothing was split). */
-int xgemm_force_split(int pieces);
-int xgemm_last_split(void);
-
-/*
- * What the library would launch for a product of this shape (host only; uses
- * the CU count of the current device, 256 if there is none): out[0] tile
- * variant, out[1] pieces per split tail tile (1: none), out[2] number of tiles
- * of that variant computed whole.  If out[1] is 1 and out[2] is less than the
- * number of tiles, the remaining tiles run as four quarter tiles each, with the
- * variant of half the tile size, in a second launch (the form the last, partly
- * filled round of workgroups takes when there is no workspace to split it along K).
- * prec 'd' / 's'; uplo 0 general, 1 / 2 triangular (syrk,
- * m == n); lwork: size of the workspace the call would be given (0: none).
- * Honours xgemm_force_variant / xgemm_force_split.  Returns 0 or -i.
- */
-int xgemm_plan(char prec, int uplo, int64_t m, int64_t n, int64_t k, size_t lwork, int out[3]);
-
-/* Name of tile variant `variant` for precision `prec` ('d' or 's'), or NULL
- * past the end of the list. */
-const char *xgemm_variant_name(char prec, int variant);
-
-/*
- * MFMA-only micro-benchmark (confirms the matrix-core peak that percentages
- * are quoted against): launches `blocks` workgroups of 256 threads, each wave
- * issuing `iters` rounds of back-to-back register-resident MFMAs with no
- * memory traffic in the loop: 16 FP64 16x16x4 per round for prec 'd', 8 FP32
- * 32x32x2 per round for 's'.  `sink` is a device buffer of at least blocks*256
- * elements of that precision, written once at the end.  Returns 0 or a
- * hipError_t.  flops per launch = blocks * 4 waves * iters * 32768 for both
- * precisions (16 * 2*16*16*4 = 8 * 2*32*32*2 = 32768).
- */
-int xgemm_mfma_peak_probe(char prec, int blocks, int iters, void *sink, void *stream);
-
-/*
- * Writes the register layout of one MFMA result to `out` (device, 64*R ints
- * where R = 4 for 'd', 16 for 's'): out[lane*R + r] = 256*i + j for the matrix
- * element D(i, j) held by lane `lane`, register r, found by multiplying one-hot
- * operands.  Used by the tests to confirm the accumulator layout the kernels
- * assume.  Returns 0 or a hipError_t.
- */
-int xgemm_mfma_layout_probe(char prec, int *out, void *stream);
-
-/*
- * Latency probe: what a dependent chain of instructions costs a lone wave, the
- * device's counterpart of the latency column of the paper's micro-architecture
- * table (Sec. 4.3, the k of W = L + n k).  One wave runs `iters` rounds of eight
- * chains and writes the elapsed ticks of the 100 MHz real-time counter (10 ns each)
- * to out[0..7] (device, 8 x int64); per round the chains hold
- *   0: 8 FP64 fused multiply-adds       1: 8 FP32 fused multiply-adds
- *   2: 8 FP64 reciprocal square roots, each fed through one add
- *   3: 4 LDS round trips (write, then read what another lane wrote)
- *   4: 4 FP64 16x16x4 matrix instructions accumulating into one tile
- *   5: 4 x (matrix instruction, vector instruction on its result, next matrix instruction)
- *   6: 8 x (lane read into scalar registers, vector instruction that uses them)
- *   7: 4 FP32 32x32x2 matrix instructions accumulating into one tile
- * so that ns per instruction = 10 * out[i] / (iters * count_i).  `sink` (device,
- * 64 doubles) receives the chains' values so that nothing is optimised away.
- * Returns 0 or a hipError_t (iters must be in 1 .. 2^20).
- */
-int xgemm_latency_probe(long long *out, double *sink, int iters, void *stream);
-
-/*
- * The paper's analytical kernel-selection model (host only, no device access).
- *
- * xgemm_model_outer_product_rate: Sec. 4.2.  Pipeline i retires rate[i]
- *   instructions per cycle and receives count[i] instructions per outer
- *   product; returns min_i rate[i] / count[i] over the pipelines with
- *   count[i] > 0 (infinity if there is none), in outer products per cycle.
- * xgemm_model_stalled_rate: Sec. 4.3.  A pipeline with L instructions of which
- *   n_dependent expose a latency of `latency` cycles needs W = L + n*latency;
- *   returns its instruction rate L / W (Little's law).
- * xgemm_model_n_updates: Sec. 5.4, floor((r_total - m_r*n_r/v - r_a) / r_r);
- *   r_a <= 0 means ceil(m_r / v).  Returns -1 on v <= 0 or r_r <= 0.
- * xgemm_model_predict: the model instantiated for tile variant `variant` of
- *   precision `prec` ('d' / 's') and the given transposes, per K slab:
- *   out[0] MFMAs, out[1] global loads, out[2] LDS reads, out[3] LDS writes
- *   (each per wave); out[4] matrix-pipe cycles per SIMD, out[5] LDS cycles per
- *   CU, out[6] vector-memory cycles per CU; out[7] memory instructions that must
- *   share one MFMA shadow (0: they do not fit); out[8] barrier stall in cycles;
- *   out[9] predicted MFMA utilisation; out[10] vector registers per lane
- *   (accumulators + staging + two fragment sets); out[11] waves per SIMD.
- *   Returns 0; 1 if the register limit is violated; -1 bad prec, -2 bad variant,
- *   -5 out == NULL.
- */
-double xgemm_model_outer_product_rate(int n_pipes, const double *rate, const double *count);
-double xgemm_model_stalled_rate(double L, double n_dependent, double latency);
-int xgemm_model_n_updates(int r_total, int m_r, int n_r, int v, int r_a, int r_r);
-int xgemm_model_predict(char prec, int variant, char transa, char transb, double out[12]);
-
-/*
- * Placement probe: launches `blocks` workgroups of 256 threads, each asking for
- * `lds_bytes` of LDS (0..163840) and staying resident for a fixed ~200k cycles,
- * and writes 4 unsigned ints per wave to `out` (device, 16*blocks values):
- * {HW_ID register, XCC_ID register, workgroup index, wave index in workgroup}.
- * Shows which XCD, CU, SIMD and wave slot the hardware dispatcher gives to
- * consecutive workgroups (the assumption behind the XCD-aware tile order).
- * Returns 0 or a hipError_t.
- */
-int xgemm_hwid_probe(int blocks, int lds_bytes, unsigned *out, void *stream);
-
-/*
- * The workgroup -> macro-tile order the kernels use (host only, no device
- * access), for tests and for reasoning about L2 reuse: for an m x n result cut
- * into mt_m x mt_n tiles, uplo 0 (general), 1 (lower triangle) or 2 (upper
- * triangle, m == n expected for 1 and 2), returns the number of workgroups a
- * launch has and, when `out` is non-NULL, writes {tile row, tile column} of
- * workgroup b to out[2b], out[2b+1] for b < min(count, cap).  Workgroup b runs
- * on the same XCD as every workgroup b' = b (mod 8).  Exactly the tiles that intersect the requested part of C
- * appear, each once.  Returns -i for an illegal argument i.
- */
-int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *out, int64_t cap);
+int xgemm_release_thread_resources(void);
 
 #ifdef __cplusplus
 }

@@ -13,4 +13,8 @@ int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, double alpha, co
              const double *B, int64_t ldb, double *C, int64_t ldc, void *stream, int kcut, int kaxis, int kblk);
 int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
              const float *B, int64_t ldb, float *C, int64_t ldc, void *stream, int kcut, int kaxis, int kblk);
+
+// Puts the benchmark controls of the factorisation (panel width, block order) back to automatic on the
+// calling thread; defined beside them.
+void reset_l3_tuning();
 }  // namespace xg

@@ -1,6 +1,8 @@
 // xgemm_api.hip -- the C ABI: argument checks, quick returns, variant choice,
 // launches; the split-plane complex GEMM as four real GEMMs; probes.
 #include "../../include/xgemm.h"
+#include "../../include/xgemm_probe.h"
+#include "../../include/xgemm_tuning.h"
 #include "tables.h"
 
 #include <atomic>
@@ -173,6 +175,13 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
     return best;
 }
 
+// Clears the arrival counters of a workspace (a kernel, not a memset, so that a
+// caller may capture it in a graph).
+__global__ void __launch_bounds__(256) zero_words_kernel(unsigned *p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 // uplo: 0 general, 1 lower, 2 upper (the caller has checked m == n for those).
 template <typename T>
 int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
@@ -285,13 +294,6 @@ int syrk_impl(char uplo, char trans, int64_t n, int64_t k, T alpha, const T *A, 
     const int rc = gemm_impl<T>(is_n(trans) ? 'N' : 'T', is_n(trans) ? 'T' : 'N', n, n, k, alpha, A, lda, A, lda, beta,
                                 C, ldc, stream, lower ? 1 : 2, work, lwork);
     return rc;   // the argument checks above cover every error gemm_impl could report
-}
-
-// Clears the arrival counters of a workspace (a kernel, not a memset, so that a
-// caller may capture it in a graph).
-__global__ void __launch_bounds__(256) zero_words_kernel(unsigned *p, int n) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0u;
 }
 
 // C := alpha op(A) op(B)^T + alpha op(B) op(A)^T + beta C on one triangle: two launches of the GEMM
@@ -583,6 +585,12 @@ int xgemm_plan(char prec, int uplo, int64_t m, int64_t n, int64_t k, size_t lwor
     out[1] = p.nsplit;
     out[2] = (int)p.ndp;
     return 0;
+}
+
+void xgemm_tuning_reset(void) {
+    t_forced_variant = -1;
+    t_forced_split = -1;
+    xg::reset_l3_tuning();
 }
 
 int xgemm_force_split(int pieces) {

@@ -7,6 +7,8 @@
 // (depth = half the order, so the products are large).  Diagonal blocks of
 // order <= NB are solved (multiplied) in a small kernel of their own.
 #include "../../include/xgemm.h"
+#include "../../include/xgemm_probe.h"
+#include "../../include/xgemm_tuning.h"
 #include "tables.h"
 
 #include <hip/hip_runtime.h>
@@ -1424,12 +1426,15 @@ struct SideLanes {
     hipEvent_t fork = nullptr, join[2] = {nullptr, nullptr}, ev[KINDS][RING] = {};
     bool ready = false;
 };
-SideLanes *side_lanes() {
+SideLanes *side_lanes_slot(int dev) {
     constexpr int MAX_DEV = 64;
     thread_local SideLanes lanes[MAX_DEV];
+    return (dev < 0 || dev >= MAX_DEV) ? nullptr : &lanes[dev];
+}
+SideLanes *side_lanes() {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
-    SideLanes &ln = lanes[dev];
+    if (hipGetDevice(&dev) != hipSuccess || !side_lanes_slot(dev)) return nullptr;
+    SideLanes &ln = *side_lanes_slot(dev);
     if (!ln.ready) {
         for (hipStream_t &st : ln.stream)
             if (!st && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
@@ -1441,6 +1446,28 @@ SideLanes *side_lanes() {
         ln.ready = true;
     }
     return &ln;
+}
+
+// Gives back what side_lanes() created for this thread on the current device.  The streams are idle
+// between calls (every call joins them to the caller's stream), but that join may not have run yet.
+int release_side_lanes() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    SideLanes *ln = side_lanes_slot(dev);
+    if (!ln) return (int)hipErrorInvalidDevice;
+    hipError_t first = hipSuccess;
+    auto note = [&](hipError_t x) { if (first == hipSuccess && x != hipSuccess) first = x; };
+    for (hipStream_t &st : ln->stream)
+        if (st) { note(hipStreamSynchronize(st)); note(hipStreamDestroy(st)); st = nullptr; }
+    auto drop = [&](hipEvent_t &ev) { if (ev) { note(hipEventDestroy(ev)); ev = nullptr; } };
+    drop(ln->fork);
+    drop(ln->join[0]);
+    drop(ln->join[1]);
+    for (auto &kind : ln->ev)
+        for (hipEvent_t &ev : kind) drop(ev);
+    ln->ready = false;
+    return (int)first;
 }
 
 thread_local int64_t t_potrf_panel = -1;   // -1: by the order; 0: the recursion on one stream; W > 0: panels of W columns
@@ -1813,6 +1840,13 @@ int symm_impl(char side, char uplo, int64_t m, int64_t n, T alpha, const T *A, i
 
 }  // namespace
 
+namespace xg {
+void reset_l3_tuning() {
+    t_potrf_panel = -1;
+    t_potrf_block = 256;
+}
+}  // namespace xg
+
 extern "C" {
 
 int xgemm_dsymm(char side, char uplo, int64_t m, int64_t n, double alpha, const double *A, int64_t lda, const double *B,
@@ -1824,6 +1858,8 @@ int xgemm_ssymm(char side, char uplo, int64_t m, int64_t n, float alpha, const f
                 int64_t ldb, float beta, float *C, int64_t ldc, void *stream) {
     return symm_impl<float>(side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, stream);
 }
+
+int xgemm_release_thread_resources(void) { return release_side_lanes(); }
 
 int xgemm_force_potrf_panel(int64_t width) {
     if (width < -1 || width > DIM_MAX) return -1;

@@ -12,6 +12,8 @@
 // pipelines are the matrix pipe of a SIMD, the LDS pipe and the vector-memory
 // pipe of a CU, and the stall term is the one barrier per slab.
 #include "../../include/xgemm.h"
+#include "../../include/xgemm_probe.h"
+#include "../../include/xgemm_tuning.h"
 #include "tables.h"
 
 #include <math.h>

@@ -7,6 +7,8 @@
 //   3m:  T1 = Ar Br, T2 = Ai Bi, T3 = (Ar + Ai)(Br + Bi),
 //        Pr = T1 - T2,                  Pi = T3 - T1 - T2           (three real products)
 #include "../../include/xgemm.h"
+#include "../../include/xgemm_probe.h"
+#include "../../include/xgemm_tuning.h"
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -1,4 +1,4 @@
-"""ctypes binding of libxgemm.so -- same names as the C ABI (include/xgemm.h).
+"""ctypes binding of libxgemm.so -- same names as the C ABI (include/xgemm.h, xgemm_tuning.h, xgemm_probe.h).
 
 Matrix arguments may be torch tensors on the GPU (their ``data_ptr()`` is
 passed) or plain integer device addresses; ``None`` is a NULL pointer.  The
@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel", "xgemm_force_potrf_block",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_tuning_reset", "xgemm_release_thread_resources",
 ]
 
 
@@ -115,6 +115,10 @@ def lib():
     L.xgemm_mfma_layout_probe.argtypes = [_c, _p, _p]
     L.xgemm_hwid_probe.restype = ctypes.c_int
     L.xgemm_hwid_probe.argtypes = [ctypes.c_int, ctypes.c_int, _p, _p]
+    L.xgemm_tuning_reset.restype = None
+    L.xgemm_tuning_reset.argtypes = []
+    L.xgemm_release_thread_resources.restype = ctypes.c_int
+    L.xgemm_release_thread_resources.argtypes = []
     L.xgemm_force_potrf_block.restype = ctypes.c_int
     L.xgemm_force_potrf_block.argtypes = [ctypes.c_int]
     L.xgemm_force_potrf_panel.restype = ctypes.c_int
@@ -242,6 +246,14 @@ def xgemm_dsyrk_ws(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, work, lwork, 
 def xgemm_ssyrk_ws(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, work, lwork, stream=None) -> int:
     return int(lib().xgemm_ssyrk_ws(_ch(uplo), _ch(trans), n, k, alpha, _ptr(A), lda, beta, _ptr(C), ldc,
                                     _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_tuning_reset() -> None:
+    lib().xgemm_tuning_reset()
+
+
+def xgemm_release_thread_resources() -> int:
+    return int(lib().xgemm_release_thread_resources())
 
 
 def xgemm_force_split(pieces) -> int:

@@ -11,19 +11,51 @@ import paper_1611_08035_amd as xg
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "xgemm.h")).read()
+HEADERS = ("xgemm.h", "xgemm_tuning.h", "xgemm_probe.h")
+
+
+def declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(xgemm_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     L = xg.lib()
-    names = declared_symbols()
-    assert len(names) >= 10
-    for name in names:
-        assert hasattr(L, name), f"{name} declared in xgemm.h but not exported"
-    assert sorted(xg.EXPORTS) == names
+    names = []
+    for header in HEADERS:
+        mine = declared_symbols(header)
+        assert len(mine) >= 4, header
+        for name in mine:
+            assert hasattr(L, name), f"{name} declared in {header} but not exported"
+            assert name not in names, f"{name} declared in two headers"
+        names += mine
+    assert sorted(xg.EXPORTS) == sorted(names)
+
+
+def test_blas_header_leads_with_the_hot_path_and_holds_no_controls():
+    """The six calls of the hot path come first in xgemm.h; benchmark controls, the planner, the model and
+    the probes live in the two other headers."""
+    blas = declared_symbols("xgemm.h")
+    text = open(os.path.join(ROOT, "include", "xgemm.h")).read()
+    order = [m.group(1) for m in re.finditer(r"^(?:int|size_t|const char \*)\s*\*?(xgemm_[a-z0-9_]+)\(", text, flags=re.M)]
+    assert order[:6] == ["xgemm_dgemm", "xgemm_sgemm", "xgemm_zgemm_split", "xgemm_zgemm_worksize", "xgemm_version",
+                         "xgemm_last_kernel_name"]
+    for name in blas:
+        assert not any(w in name for w in ("force", "probe", "model", "plan", "tile_map", "variant")), name
+    assert "xgemm_tuning_reset" in declared_symbols("xgemm_tuning.h")
+
+
+def test_tuning_controls_are_sticky_until_reset():
+    """A forced variant or split stays in force on the calling thread until it is set back or everything is reset."""
+    full = xg.xgemm_workspace_bytes()
+    auto = xg.xgemm_plan("d", 0, 4096, 4096, 4096, full)
+    assert xg.xgemm_force_variant(3) == 0 and xg.xgemm_force_split(0) == 0
+    assert xg.xgemm_force_potrf_panel(512) == 0 and xg.xgemm_force_potrf_block(64) == 0
+    assert xg.xgemm_plan("d", 0, 4096, 4096, 4096, full)[0] == 3
+    assert xg.xgemm_plan("d", 0, 4096, 4096, 4096, full)[0] == 3          # still
+    xg.xgemm_tuning_reset()
+    assert xg.xgemm_plan("d", 0, 4096, 4096, 4096, full) == auto
 
 
 def test_version_and_variant_names():

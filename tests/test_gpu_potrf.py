@@ -294,3 +294,20 @@ def test_look_ahead_sweep_on_a_stream_of_the_callers():
         side.synchronize()
         assert torch.equal(got, want), f"run {rep}"
         assert int(info.item()) == 0
+
+
+def test_thread_resources_can_be_released_and_come_back():
+    """The sweep's streams and events are kept per thread and device; releasing them (also when there are
+    none, and twice in a row) is harmless, and the next sweep creates them again and gives the same bits."""
+    assert xg.xgemm_release_thread_resources() == 0           # whatever earlier tests left, or nothing
+    assert xg.xgemm_release_thread_resources() == 0
+    rng = si.rng_for(179, 1)
+    n = 900
+    A = si.spd(rng, n, n + 1, np.float64, "L")
+    assert xg.xgemm_force_potrf_panel(128) == 0
+    F1, info1 = run_potrf("L", n, A, n + 1)
+    assert xg.xgemm_release_thread_resources() == 0
+    F2, info2 = run_potrf("L", n, A, n + 1)
+    assert info1 == 0 and info2 == 0 and np.array_equal(F1, F2, equal_nan=True)
+    rinfo, R, G = oracle.potrf_resid("L", n, A, n + 1, F2, n + 1)
+    assert rinfo == 0 and np.all(np.abs(R) <= 4.0 * n * oracle.U64 * G)
