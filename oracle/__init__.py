@@ -104,6 +104,14 @@ def _declare(L):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.c_char, _i64, _p, _i64, _p, _i64, _i64, _p, _p, _p, _p]
+    for name in ("ref_dgetrf", "ref_sgetrf"):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [_i64, _i64, _p, _i64, _p]
+    for name in ("ref_dgetrf_resid", "ref_sgetrf_resid"):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [_i64, _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p, _p, _p]
     for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
         for suf in ("ext", "wp"):
             f = getattr(L, f"ref_{pre}syr2k_{suf}")
@@ -290,6 +298,34 @@ def potrf_resid(uplo, n, A0, lda, F, ldf, I=None, J=None):
     R = np.zeros(I.size, dtype=wide)
     G = np.zeros(I.size, dtype=wide)
     info = int(f(_ch(uplo), n, _ptr(A0), lda, _ptr(F), ldf, I.size, _ptr(I), _ptr(J), _ptr(R), _ptr(G)))
+    return info, R, G
+
+
+def getrf(m, n, A, lda):
+    """In-place working-precision LU with partial pivoting (first largest entry of the column); returns
+    (info, ipiv) with ipiv 1-based int32 of length min(m, n), LAPACK's conventions."""
+    pre, _ = _names(A.dtype if A is not None else np.float64)
+    ipiv = np.zeros(max(min(m, n), 0), dtype=np.int32)
+    info = int(getattr(lib(), f"ref_{pre}getrf")(m, n, _ptr(A), lda, _ptr(ipiv) if ipiv.size else None))
+    return info, ipiv
+
+
+def getrf_resid(m, n, A0, lda, F, ldf, ipiv, I=None, J=None):
+    """Extended-precision residual P A0 - L U and magnitude |L||U| of a candidate factorisation:
+    dense (n, m) arrays in the (col, row) layout, or 1-d arrays at the entries (I, J)."""
+    pre, wide = _names(A0.dtype)
+    f = getattr(lib(), f"ref_{pre}getrf_resid")
+    ipiv = np.ascontiguousarray(ipiv, dtype=np.int32)
+    if I is None:
+        R = np.zeros((max(n, 0), max(m, 0)), dtype=wide)
+        G = np.zeros_like(R)
+        info = int(f(m, n, _ptr(A0), lda, _ptr(F), ldf, _ptr(ipiv), -1, None, None, _ptr(R), _ptr(G)))
+        return info, R, G
+    I = np.ascontiguousarray(I, dtype=np.int64)
+    J = np.ascontiguousarray(J, dtype=np.int64)
+    R = np.zeros(I.size, dtype=wide)
+    G = np.zeros(I.size, dtype=wide)
+    info = int(f(m, n, _ptr(A0), lda, _ptr(F), ldf, _ptr(ipiv), I.size, _ptr(I), _ptr(J), _ptr(R), _ptr(G)))
     return info, R, G
 
 

@@ -950,3 +950,122 @@ int ref_zgemm_split_work(char ta, char tb, i64 m, i64 n, i64 k, const double *al
     }
     return 0;
 }
+
+
+/* ------------------------------------------------------------------ */
+/* LU factorisation with partial pivoting (the other LAPACK-level       */
+/* driver the paper names as resting on GEMM, Abstract and Sec. 1; the  */
+/* paper gives no algorithm for it, so the semantics are LAPACK's):     */
+/*     P A = L U,   A m x n,  L m x min(m,n) unit lower trapezoidal,    */
+/*     U min(m,n) x n upper trapezoidal,                                */
+/* both overwrite A (the unit diagonal of L is not stored).  Plain      */
+/* Gaussian elimination, one column at a time, in the natural order:    */
+/*   for j = 0 .. min(m,n)-1                                            */
+/*     p = the FIRST row index i >= j with |A(i,j)| largest             */
+/*     ipiv[j] = p + 1                    (1-based, as LAPACK reports)  */
+/*     if A(p,j) != 0: swap rows j and p over all n columns,            */
+/*                     A(i,j) /= A(j,j) for i > j   (a true division)   */
+/*     else record info = j + 1 (first such j only) and go on           */
+/*     A(i,c) -= A(i,j) A(j,c)  for i > j, c > j   (multiply, then subtract) */
+/* Returns info >= 0 as above, or -i for an illegal argument (m 1, n 2, */
+/* A 3, lda 4, ipiv 5).                                                 */
+/* ------------------------------------------------------------------ */
+#define DEFINE_REF_GETRF(NAME, T, TABS)                                        \
+int NAME(i64 m, i64 n, T *A, i64 lda, int *ipiv)                               \
+{                                                                              \
+    if (m < 0) return -1;                                                      \
+    if (n < 0) return -2;                                                      \
+    if (m > 0 && n > 0 && A == NULL) return -3;                                \
+    if (lda < max64(1, m)) return -4;                                          \
+    if (m > 0 && n > 0 && ipiv == NULL) return -5;                             \
+    const i64 steps = m < n ? m : n;                                           \
+    int info = 0;                                                              \
+    for (i64 j = 0; j < steps; ++j) {                                          \
+        i64 p = j;                                                             \
+        T best = TABS(A[j + j * lda]);                                         \
+        for (i64 i = j + 1; i < m; ++i) {                                      \
+            const T v = TABS(A[i + j * lda]);                                  \
+            if (v > best) { best = v; p = i; }                                 \
+        }                                                                      \
+        ipiv[j] = (int)(p + 1);                                                \
+        if (A[p + j * lda] != (T)0) {                                          \
+            if (p != j)                                                        \
+                for (i64 c = 0; c < n; ++c) {                                  \
+                    const T x = A[j + c * lda];                                \
+                    A[j + c * lda] = A[p + c * lda];                           \
+                    A[p + c * lda] = x;                                        \
+                }                                                              \
+            const T d = A[j + j * lda];                                        \
+            for (i64 i = j + 1; i < m; ++i) A[i + j * lda] = A[i + j * lda] / d; \
+        } else if (info == 0) {                                                \
+            info = (int)(j + 1);                                               \
+        }                                                                      \
+        _Pragma("omp parallel for schedule(static) if ((n - j) * (m - j) > 65536)") \
+        for (i64 c = j + 1; c < n; ++c) {                                      \
+            const T u = A[j + c * lda];                                        \
+            for (i64 i = j + 1; i < m; ++i) {                                  \
+                const T prod = A[i + j * lda] * u;                             \
+                A[i + c * lda] = A[i + c * lda] - prod;                        \
+            }                                                                  \
+        }                                                                      \
+    }                                                                          \
+    return info;                                                               \
+}
+
+DEFINE_REF_GETRF(ref_dgetrf, double, fabs)
+DEFINE_REF_GETRF(ref_sgetrf, float, fabsf)
+
+/* Residual of a candidate factorisation (F holding L below and U on and above
+ * the diagonal, ipiv 1-based as above) against the original A0, in extended
+ * precision:  R = P A0 - L U,  G = |L| |U|  (the unit diagonal of L included),
+ * where P A0 is A0 with the row interchanges ipiv[0], ipiv[1], ... applied in
+ * that order.  Either dense m x n (ns < 0, leading dimension m) or at ns
+ * sampled entries (I[s], J[s]).  Returns 0, -i for an illegal argument (m 1,
+ * n 2, A0 3, lda 4, F 5, ldf 6, ipiv 7, samples 9), or 7 if an entry of ipiv is
+ * not a legal interchange (ipiv[j] outside j+1 .. m). */
+#define DEFINE_REF_GETRF_RESID(NAME, T, W, WABS)                               \
+int NAME(i64 m, i64 n, const T *A0, i64 lda, const T *F, i64 ldf,              \
+         const int *ipiv, i64 ns, const i64 *I, const i64 *J, W *R, W *G)      \
+{                                                                              \
+    if (m < 0) return -1;                                                      \
+    if (n < 0) return -2;                                                      \
+    if (m > 0 && n > 0 && A0 == NULL) return -3;                               \
+    if (lda < max64(1, m)) return -4;                                          \
+    if (m > 0 && n > 0 && F == NULL) return -5;                                \
+    if (ldf < max64(1, m)) return -6;                                          \
+    if (m > 0 && n > 0 && ipiv == NULL) return -7;                             \
+    const i64 steps = m < n ? m : n;                                           \
+    for (i64 s = 0; s < (ns < 0 ? 0 : ns); ++s)                                \
+        if (I[s] < 0 || I[s] >= m || J[s] < 0 || J[s] >= n) return -9;         \
+    for (i64 j = 0; j < steps; ++j)                                            \
+        if (ipiv[j] < j + 1 || ipiv[j] > m) return 7;                          \
+    /* row i of P A0 is row src[i] of A0 */                                    \
+    i64 *src = (i64 *)malloc((size_t)(m > 0 ? m : 1) * sizeof(i64));           \
+    if (!src) return 1000;                                                     \
+    for (i64 i = 0; i < m; ++i) src[i] = i;                                    \
+    for (i64 j = 0; j < steps; ++j) {                                          \
+        const i64 p = ipiv[j] - 1, x = src[j];                                 \
+        src[j] = src[p];                                                       \
+        src[p] = x;                                                            \
+    }                                                                          \
+    const i64 cnt = ns < 0 ? m * n : ns;                                       \
+    _Pragma("omp parallel for schedule(dynamic, 64)")                          \
+    for (i64 s = 0; s < cnt; ++s) {                                            \
+        const i64 i = ns < 0 ? s % m : I[s], j = ns < 0 ? s / m : J[s];        \
+        const i64 top = i < j ? i : j;          /* (L U)(i,j) = sum_{p <= min(i,j), p < steps} L(i,p) U(p,j) */ \
+        W acc = (W)A0[src[i] + j * lda], mag = 0;                              \
+        for (i64 p = 0; p <= top && p < steps; ++p) {                          \
+            const W l = (p == i) ? (W)1 : (W)F[i + p * ldf];                   \
+            const W prod = l * (W)F[p + j * ldf];                              \
+            acc -= prod;                                                       \
+            mag += WABS(prod);                                                 \
+        }                                                                      \
+        R[s] = acc;                                                            \
+        G[s] = mag;                                                            \
+    }                                                                          \
+    free(src);                                                                 \
+    return 0;                                                                  \
+}
+
+DEFINE_REF_GETRF_RESID(ref_dgetrf_resid, double, long double, fabsl)
+DEFINE_REF_GETRF_RESID(ref_sgetrf_resid, float, double, fabs)
