@@ -35,8 +35,9 @@
  *       . per thread and device, two streams and 23 events that xgemm_*potrf
  *         creates on its first look-ahead sweep and keeps for later calls
  *         (xgemm_release_thread_resources() destroys them);
- *       . per process and device, read once: the number of compute units, and which
- *         kernels have been granted more than 64 KiB of LDS;
+ *       . per process and device, read once: the number of compute units, the
+ *         address of the static scratch of xgemm_dgemm_static, and which kernels
+ *         have been granted more than 64 KiB of LDS;
  *       . per process, read at load: the environment variable
  *         XGEMM_REQUIRE_ALIGNED (a test switch that sends operands that are not
  *         16-byte aligned to the element-wise fallback kernels).
@@ -271,6 +272,35 @@ int xgemm_dsyrk_ws(char uplo, char trans, int64_t n, int64_t k, double alpha, co
                    double beta, double *C, int64_t ldc, void *work, size_t lwork, void *stream);
 int xgemm_ssyrk_ws(char uplo, char trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
                    float beta, float *C, int64_t ldc, void *work, size_t lwork, void *stream);
+
+/*
+ * xgemm_dgemm_ws for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * split tail, with the workspace taken from a fixed array of
+ * XGEMM_STATIC_SCRATCH_BYTES that is part of the library's code object (every
+ * device the library runs on holds its own copy from load until the process
+ * ends).  The call allocates and frees nothing, in the library or through the
+ * runtime; the caller passes only the operands.  Arguments, numbering, results
+ * and error bound are those of xgemm_dgemm_ws given a full-size workspace: the
+ * same plan, hence the same bits.
+ *   - A shape whose split tail would use more than the array holds (counters +
+ *     pieces * tail tiles * 128 KiB) is refused with XGEMM_E_SCRATCH and nothing
+ *     is enqueued; xgemm_dgemm, which needs no workspace, serves it.
+ *   - The counters in the array are cleared by a kernel on `stream` at the start
+ *     of every call that splits (no memset, so the call can be captured).
+ *   - All calls on one device share that device's array: calls that may overlap
+ *     in time (different streams without ordering, several host threads) race on
+ *     it and give undefined results.  Order them, or use xgemm_dgemm_ws with a
+ *     workspace per stream.
+ *   - The first call on a device looks the array's address up in the runtime;
+ *     make that call outside a stream capture.
+ * Returns 0, -i, XGEMM_E_SCRATCH or a hipError_t.
+ */
+#define XGEMM_STATIC_SCRATCH_BYTES (8192 + (32 << 20))
+#define XGEMM_E_SCRATCH (-1000)
+int xgemm_dgemm_static(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                       double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
+                       double beta, double *C, int64_t ldc, void *stream);
 
 /*
  * Double-precision complex GEMM on interleaved storage (the BLAS layout: element

@@ -9,6 +9,12 @@
 #include <stdlib.h>
 #include <string.h>
 
+// Scratch of xgemm_dgemm_static (arrival counters, then partial tiles): lives in the code object, so every
+// device the library runs on holds its own copy at its own address from load to process exit.  Host code
+// never uses this name as an address; it asks the runtime for the device's copy once (static_scratch()).
+#define XG_STATIC_CNT_BYTES 8192
+static __device__ __align__(256) unsigned char scratch[XGEMM_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace xg;
@@ -48,6 +54,8 @@ int num_cus() {
 // Workspace of the *_ws entry points: arrival counters, then partial tiles.
 constexpr size_t WS_CNT_BYTES = 8192;                       // 2048 counters
 constexpr size_t WS_PART_BYTES = size_t(64) << 20;          // 512 tiles of 128 KiB
+static_assert(WS_CNT_BYTES == XG_STATIC_CNT_BYTES && XGEMM_STATIC_SCRATCH_BYTES > WS_CNT_BYTES &&
+                  XGEMM_STATIC_SCRATCH_BYTES <= WS_CNT_BYTES + WS_PART_BYTES, "static scratch: counters, then partial tiles");
 constexpr int SPLIT_MAX = 32;                               // pieces per tile
 constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece must keep
 
@@ -182,11 +190,30 @@ __global__ void __launch_bounds__(256) zero_words_kernel(unsigned *p, int n) {
     if (i < n) p[i] = 0u;
 }
 
+// Address of the current device's copy of `scratch`, asked of the runtime on the first call on that device
+// and kept (each device has its own copy at its own address).
+void *static_scratch(hipError_t *err) {
+    constexpr int MAX_DEV = 64;
+    static std::atomic<void *> ptrs[MAX_DEV];
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= MAX_DEV) { *err = hipErrorInvalidDevice; return nullptr; }
+    void *p = ptrs[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err == hipSuccess && !p) *err = hipErrorInvalidSymbol;
+    if (*err != hipSuccess) return nullptr;
+    ptrs[dev].store(p, std::memory_order_release);
+    return p;
+}
+
 // uplo: 0 general, 1 lower, 2 upper (the caller has checked m == n for those).
+// static_ws: the workspace is the library's static scratch (xgemm_dgemm_static); work and lwork are ignored.
 template <typename T>
 int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
               const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream, int uplo = 0, void *work = nullptr,
-              size_t lwork = 0, int kcut = 0, int kaxis = 0, int kblk = 0) {
+              size_t lwork = 0, int kcut = 0, int kaxis = 0, int kblk = 0, bool static_ws = false) {
     t_last_kernel = "none";
     t_last_split = 1;
     if (!is_n(ta) && !is_t(ta)) return -1;
@@ -231,6 +258,23 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     bool fast = lda <= ld_max && ldb <= ld_max;
     if (t_require_aligned)
         fast = fast && aligned16(A) && aligned16(B) && (lda * sizeof(T)) % 16 == 0 && (ldb * sizeof(T)) % 16 == 0;
+    if (static_ws) {
+        // What the same call would use of a full-size workspace must fit the static array; then the plan
+        // below, made for the array's size, is that same plan.
+        const Plan full = make_plan<T>(m, n, k, uplo, tab, nv, fast, WS_CNT_BYTES + WS_PART_BYTES);
+        if (full.nsplit > 1) {
+            const VariantEntry<T> &e = tab[full.v];
+            const int64_t tiles = tile_count(uplo, (int)((m + e.mt_m - 1) / e.mt_m), (int)((n + e.mt_n - 1) / e.mt_n),
+                                             e.mt_m, e.mt_n);
+            const size_t need = WS_CNT_BYTES + (size_t)(tiles - full.ndp) * (size_t)full.nsplit * (size_t)e.mt_m *
+                                                   (size_t)e.mt_n * sizeof(T);
+            if (need > (size_t)XGEMM_STATIC_SCRATCH_BYTES) return XGEMM_E_SCRATCH;
+        }
+        hipError_t e = hipSuccess;
+        work = static_scratch(&e);
+        if (!work) return (int)e;
+        lwork = XGEMM_STATIC_SCRATCH_BYTES;
+    }
     if (!work || (reinterpret_cast<uintptr_t>(work) & 15u)) lwork = 0;
     const Plan plan = make_plan<T>(m, n, k, uplo, tab, nv, fast, lwork);
     int v = plan.v;
@@ -253,6 +297,13 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
         g.cnt = static_cast<unsigned *>(work);
         g.part = reinterpret_cast<T *>(static_cast<unsigned char *>(work) + WS_CNT_BYTES);
         t_last_split = plan.nsplit;
+        if (static_ws) {
+            // the array keeps whatever the last call (or an aborted one) left: the counters start at zero
+            constexpr int N = (int)(WS_CNT_BYTES / sizeof(unsigned));
+            hipLaunchKernelGGL(zero_words_kernel, dim3(N / 256), dim3(256), 0, st, g.cnt, N);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return (int)e;
+        }
     }
     t_last_kernel = tab[v].name;
     // op(A) is K-contiguous when A is transposed; op(B) is K-contiguous when B is not
@@ -543,6 +594,12 @@ int xgemm_dgemm_ws(char transa, char transb, int64_t m, int64_t n, int64_t k, do
                    size_t lwork, void *stream) {
     if (work && (reinterpret_cast<uintptr_t>(work) & 15u)) return -14;
     return gemm_impl<double>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 0, work, lwork);
+}
+
+int xgemm_dgemm_static(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double *A,
+                       int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream) {
+    return gemm_impl<double>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 0, nullptr, 0, 0, 0, 0,
+                             true);
 }
 
 int xgemm_sgemm_ws(char transa, char transb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,

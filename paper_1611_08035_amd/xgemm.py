@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_tuning_reset", "xgemm_release_thread_resources",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_release_thread_resources",
 ]
 
 
@@ -57,6 +57,8 @@ def lib():
         f = getattr(L, f"xgemm_{pre}gemm")
         f.restype = ctypes.c_int
         f.argtypes = [_c, _c, _i64, _i64, _i64, sc, _p, _i64, _p, _i64, sc, _p, _i64, _p]
+    L.xgemm_dgemm_static.restype = ctypes.c_int
+    L.xgemm_dgemm_static.argtypes = L.xgemm_dgemm.argtypes
     for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
         f = getattr(L, f"xgemm_{pre}syrk")
         f.restype = ctypes.c_int
@@ -231,6 +233,15 @@ def xgemm_workspace_init(work, lwork, stream=None) -> int:
 def xgemm_dgemm_ws(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, work, lwork, stream=None) -> int:
     return int(lib().xgemm_dgemm_ws(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                     _ptr(C), ldc, _ptr(work), lwork, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 8192 + (32 << 20)   # XGEMM_STATIC_SCRATCH_BYTES
+E_SCRATCH = -1000                           # XGEMM_E_SCRATCH
+
+
+def xgemm_dgemm_static(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_dgemm_static(_ch(transa), _ch(transb), m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                        _ptr(C), ldc, _stream(stream)))
 
 
 def xgemm_sgemm_ws(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, work, lwork, stream=None) -> int:
