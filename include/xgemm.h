@@ -240,6 +240,28 @@ int xgemm_dpotrf(char uplo, int64_t n, double *A, int64_t lda, int *info, void *
 int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *stream);
 
 /*
+ * LU factorisation with partial pivoting on the level-3 routines (the other LAPACK-level
+ * driver of the kind the paper names as the reason for a fast GEMM, Abstract and Sec. 1;
+ * the paper gives no algorithm for it, the semantics are LAPACK's getrf):
+ *     P A = L U,   A is m x n,
+ * L (m x min(m,n), unit lower trapezoidal, its diagonal not stored) and U (min(m,n) x n,
+ * upper trapezoidal) overwrite A.  ipiv (DEVICE, min(m,n) ints) receives the interchanges,
+ * 1-based: at step j, row j changed places with row ipiv[j] >= j; the pivot of a column is
+ * the first of its entries of largest magnitude.  `info` (DEVICE int, written on the
+ * stream): 0, or j > 0 if U(j,j) is exactly zero (the first such j; the factorisation is
+ * completed all the same, as in LAPACK).  Right-looking over panels of 64 or 128 columns;
+ * a panel is halved recursively onto xgemm_*trsm and xgemm_*gemm, its leaves of 8 columns
+ * are factored by one workgroup each; interchanges are applied to the rest of the rows by
+ * a kernel of their own, the block row of U comes from xgemm_*trsm and the trailing
+ * matrix from one xgemm_*gemm of the panel's depth.  Every multiplier satisfies
+ * |L(i,j)| <= 1 and the factors satisfy |P A - L U| <= 4 min(m,n) u |L| |U| element by
+ * element.  Returns 0, -i for an illegal argument (m 1, n 2, A 3, lda 4, ipiv 5, info 6)
+ * or a hipError_t.  flops: m n^2 - n^3 / 3 for m >= n (2 n^3 / 3 when square).
+ */
+int xgemm_dgetrf(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int *info, void *stream);
+int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *stream);
+
+/*
  * GEMM and SYRK with a caller-owned workspace, which lets the library
  * cut the tiles of the last, partly filled round of workgroups along K (the k_c
  * loop of Fig. 1 moved across workgroups for those tiles only): each piece

@@ -70,6 +70,11 @@ int xgemm_force_potrf_panel(int64_t width);
  * blocks are halved.  Returns 0, or -1 for any other value. */
 int xgemm_force_potrf_block(int order);
 
+/* Benchmark/tuning control of xgemm_*getrf on the calling thread: width of the panels of the
+ * right-looking sweep.  -1: chosen from the order (default); W > 0: panels of W columns.
+ * Returns 0, or -1 for any other value. */
+int xgemm_force_getrf_panel(int64_t width);
+
 /*
  * The workgroup -> macro-tile order the kernels use (host only, no device
  * access), for tests and for reasoning about L2 reuse: for an m x n result cut

@@ -17,4 +17,5 @@ int gemm_cut(char ta, char tb, int64_t m, int64_t n, int64_t k, float alpha, con
 // Puts the benchmark controls of the factorisation (panel width, block order) back to automatic on the
 // calling thread; defined beside them.
 void reset_l3_tuning();
+void reset_lu_tuning();
 }  // namespace xg

@@ -648,6 +648,7 @@ void xgemm_tuning_reset(void) {
     t_forced_variant = -1;
     t_forced_split = -1;
     xg::reset_l3_tuning();
+    xg::reset_lu_tuning();
 }
 
 int xgemm_force_split(int pieces) {

@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_release_thread_resources",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_release_thread_resources",
 ]
 
 
@@ -79,6 +79,12 @@ def lib():
         f = getattr(L, f"xgemm_{pre}potrf")
         f.restype = ctypes.c_int
         f.argtypes = [_c, _i64, _p, _i64, _p, _p]
+    for pre in "ds":
+        f = getattr(L, f"xgemm_{pre}getrf")
+        f.restype = ctypes.c_int
+        f.argtypes = [_i64, _i64, _p, _i64, _p, _p, _p]
+    L.xgemm_force_getrf_panel.restype = ctypes.c_int
+    L.xgemm_force_getrf_panel.argtypes = [ctypes.c_int64]
     for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
         for op in ("syr2k", "symm"):
             f = getattr(L, f"xgemm_{pre}{op}")
@@ -206,6 +212,18 @@ def xgemm_dpotrf(uplo, n, A, lda, info, stream=None) -> int:
 
 def xgemm_spotrf(uplo, n, A, lda, info, stream=None) -> int:
     return int(lib().xgemm_spotrf(_ch(uplo), n, _ptr(A), lda, _ptr(info), _stream(stream)))
+
+
+def xgemm_dgetrf(m, n, A, lda, ipiv, info, stream=None) -> int:
+    return int(lib().xgemm_dgetrf(m, n, _ptr(A), lda, _ptr(ipiv), _ptr(info), _stream(stream)))
+
+
+def xgemm_sgetrf(m, n, A, lda, ipiv, info, stream=None) -> int:
+    return int(lib().xgemm_sgetrf(m, n, _ptr(A), lda, _ptr(ipiv), _ptr(info), _stream(stream)))
+
+
+def xgemm_force_getrf_panel(width) -> int:
+    return int(lib().xgemm_force_getrf_panel(int(width)))
 
 
 def _two_flag_op(name):

@@ -168,6 +168,20 @@ def test_potrf_illegal_arguments(fn):
     assert f("L", 4, P, 4, None, stream=0) == -5
 
 
+@pytest.mark.parametrize("fn", ["xgemm_dgetrf", "xgemm_sgetrf"])
+def test_getrf_illegal_arguments(fn):
+    f = getattr(xg, fn)
+    P = 4096                                       # never dereferenced: every call below is refused on the host
+    assert f(-1, 4, P, 4, P, P, stream=0) == -1
+    assert f(4, -1, P, 4, P, P, stream=0) == -2
+    assert f(4, 4, None, 4, P, P, stream=0) == -3
+    assert f(5, 4, P, 4, P, P, stream=0) == -4
+    assert f(4, 4, P, 4, None, P, stream=0) == -5
+    assert f(4, 4, P, 4, P, None, stream=0) == -6
+    assert xg.xgemm_force_getrf_panel(0) == -1 and xg.xgemm_force_getrf_panel(-2) == -1
+    assert xg.xgemm_force_getrf_panel(64) == 0 and xg.xgemm_force_getrf_panel(-1) == 0
+
+
 @pytest.mark.parametrize("pre", "ds")
 def test_syr2k_and_symm_illegal_arguments(pre):
     P = 4096

@@ -1,0 +1,133 @@
+"""GPU parity of the LU driver against the CPU oracle.  Several factorisations are correct when candidates
+for a pivot tie or differ by a rounding, so the statement checked everywhere is the complete validity
+statement (legal interchanges, no multiplier above one, |P A - L U| <= 4 min(m,n) u |L||U| element by element,
+evaluated by the oracle in extended precision); equality with the oracle's interchanges and factors is asked
+for where it is determined: matrices whose factorisation is exact, and tie-free random matrices."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1611_08035_amd as xg
+import synth_inputs as si
+from gpu_util import to_dev, torch_mod, unit_roundoff
+from lu_util import check_valid, perm_of, planted_lu, unpack
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _auto():
+    xg.xgemm_tuning_reset()
+    yield
+    xg.xgemm_tuning_reset()
+
+
+def run_getrf(m, n, A, lda, stream=None):
+    torch = torch_mod()
+    f = xg.xgemm_dgetrf if A.dtype == np.float64 else xg.xgemm_sgetrf
+    dA = to_dev(A)
+    k = max(min(m, n), 1)
+    dpiv = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+    dinfo = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    assert f(m, n, dA, lda, dpiv, dinfo, stream=stream) == 0
+    torch.cuda.synchronize()
+    return dA.cpu().numpy(), dpiv.cpu().numpy()[:min(m, n)], int(dinfo.item())
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("panel", [-1, 16, 40])
+def test_planted_factorisations_are_recovered_exactly(dtype, panel):
+    """Every operation on these matrices is exact, so interchanges and factors must come out bit for bit,
+    whatever the blocking: one leaf, several leaves, several panels, ragged last leaf and panel, tall, wide."""
+    rng = si.rng_for(310, panel + 1)
+    for m, n in [(1, 1), (7, 5), (5, 7), (8, 8), (9, 9), (64, 64), (200, 131), (131, 200), (300, 300), (517, 517), (1100, 700)]:
+        A, L, U, perm = planted_lu(rng, m, n, dtype, ld=m + 3)
+        assert xg.xgemm_force_getrf_panel(panel) == 0
+        F, ipiv, info = run_getrf(m, n, A, m + 3)
+        assert info == 0, (m, n)
+        k = min(m, n)
+        assert np.all(ipiv >= np.arange(1, k + 1)) and np.all(ipiv <= m)
+        src, where = perm_of(ipiv, m), np.argsort(perm)
+        assert np.array_equal(src[:k], perm[:k]), (m, n, panel)
+        Lg, Ug = unpack(F, m, n)
+        assert np.array_equal(Ug, U) and np.array_equal(Lg, L[where[src], :]), (m, n, panel)
+        assert np.all(np.isnan(F[:, m:])), "padding rows were written"
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_random_matrices_every_element_and_against_the_oracle(dtype):
+    rng = si.rng_for(311, 0)
+    u = unit_roundoff(dtype)
+    for (m, n), panel in [((50, 50), -1), ((257, 257), 64), ((300, 120), -1), ((120, 300), 32), ((1000, 1000), -1),
+                          ((777, 1031), 128), ((1031, 777), 24)]:
+        A = si.uniform(rng, m, n, m + 1, dtype)
+        assert xg.xgemm_force_getrf_panel(panel) == 0
+        F, ipiv, info = run_getrf(m, n, A, m + 1)
+        assert info == 0
+        ratio = check_valid(m, n, A, m + 1, F, m + 1, ipiv, u)
+        assert np.all(np.isnan(F[:, m:]))
+        # tie-free data: the oracle makes the same choices, and the factors agree to rounding
+        W = A.copy()
+        oinfo, opiv = oracle.getrf(m, n, W, m + 1)
+        assert oinfo == 0 and np.array_equal(ipiv, opiv), (m, n)
+        tol = 64 * min(m, n) * u
+        assert np.allclose(F[:, :m], W[:, :m], rtol=tol, atol=tol), (m, n)
+        print("getrf", dtype.__name__, m, n, "panel", panel, "max err/bound", ratio)
+
+
+def test_tie_rule_and_zero_pivots():
+    # the first of equal candidates is taken (exact small integers: the arithmetic decides nothing)
+    A = np.array([[2.0, -2.0, 2.0], [1.0, 3.0, 5.0], [0.0, 1.0, 4.0]])
+    F, ipiv, info = run_getrf(3, 3, A, 3)
+    W = A.copy()
+    oinfo, opiv = oracle.getrf(3, 3, W, 3)
+    assert info == 0 and list(ipiv) == [1, 2, 3] and np.array_equal(ipiv, opiv) and np.array_equal(F, W)
+    # a matrix full of ties (entries -1, 0, 1): whatever is chosen, the statement must hold
+    rng = si.rng_for(312, 0)
+    n = 200
+    A = si.integers(rng, n, n, n, np.float64, R=1)
+    F, ipiv, info = run_getrf(n, n, A, n)
+    if info == 0:
+        check_valid(n, n, A, n, F, n, ipiv, oracle.U64)
+    # zero columns: reported (first one), nothing divided, the elimination goes on
+    Z = np.zeros((3, 4))
+    F, ipiv, info = run_getrf(4, 3, Z, 4)
+    assert info == 1 and list(ipiv) == [1, 2, 3] and not F.any()
+    A = si.uniform(rng, 40, 40, 40)
+    A[17, :] = 0.0                                           # column 18 is zero
+    A[:, :] = A                                              # (col, row) layout: A[17] is the column
+    F, ipiv, info = run_getrf(40, 40, A, 40)
+    W = A.copy()
+    oinfo, opiv = oracle.getrf(40, 40, W, 40)
+    assert info == oinfo == 18 and np.array_equal(ipiv, opiv)
+    assert np.allclose(F, W, rtol=1e-12, atol=1e-13)
+    check_valid(40, 40, A, 40, F, 40, ipiv, oracle.U64)
+
+
+@pytest.mark.parametrize("dtype,n", [(np.float64, 4096), (np.float64, 8192), (np.float32, 8192)])
+def test_full_size_sampled(dtype, n):
+    """The sizes of the sweep: legal interchanges, multipliers within one, the residual bound on 16 full rows,
+    16 full columns and 2^15 entries; the planted matrix of the same size bit for bit."""
+    rng = si.rng_for(313, n)
+    A = si.uniform(rng, n, n, n, dtype)
+    F, ipiv, info = run_getrf(n, n, A, n)
+    assert info == 0
+    I, J = si.sample_indices(rng, n, n, 16, 16, 1 << 15)
+    ratio = check_valid(n, n, A, n, F, n, ipiv, unit_roundoff(dtype), I=I, J=J)
+    print("getrf", dtype.__name__, n, "sampled max err/bound", ratio)
+    if dtype == np.float64 and n == 4096:
+        A, L, U, perm = planted_lu(rng, n, n, dtype)
+        F, ipiv, info = run_getrf(n, n, A, n)
+        Lg, Ug = unpack(F, n, n)
+        assert info == 0 and np.array_equal(perm_of(ipiv, n), perm) and np.array_equal(Ug, U) and np.array_equal(Lg, L)
+
+
+def test_on_a_stream_of_the_callers_and_twice_the_same_bits():
+    torch = torch_mod()
+    rng = si.rng_for(314, 0)
+    n = 900
+    A = si.uniform(rng, n, n, n)
+    F1, p1, i1 = run_getrf(n, n, A, n)
+    side = torch.cuda.Stream()
+    F2, p2, i2 = run_getrf(n, n, A, n, stream=side)
+    assert i1 == 0 and i2 == 0 and np.array_equal(p1, p2) and np.array_equal(F1, F2)
