@@ -26,21 +26,27 @@ PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}   # MI355X dense MFMA peaks
 HBM_TBPS = 8.0
 
 
-def time_calls(torch, fn, steps, warmup):
+def time_calls(torch, fn, steps, warmup, per_step=None):
     """Wall time (host clock, synchronised both sides) and device time (events
-    on the stream the kernels are launched on) of `steps` calls."""
+    on the stream the kernels are launched on) of `steps` calls; with a list as
+    `per_step`, also the device time of every single call (events between the calls)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1 if per_step is not None else 2)]
     t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         fn()
-    e1.record()
+        if per_step is not None:
+            marks[i + 1].record()
+    if per_step is None:
+        marks[1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    return (t1 - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
+    if per_step is not None:
+        per_step.extend(marks[i].elapsed_time(marks[i + 1]) * 1e-3 for i in range(steps))
+    return (t1 - t0) / steps, marks[0].elapsed_time(marks[-1]) * 1e-3 / steps
 
 
 def device_operands(torch, np, si, dtype, ta, tb, m, n, k, lda, ldb, ldc, seed_cfg, kind="uniform"):
@@ -75,10 +81,29 @@ def cpu_baseline(np, oracle, host_ops, m, k, lda, ldb, ldc, alpha, beta, budget_
     ns2 -= ns2 % cores or 0
     ns2 = max(ns2, ns)
     dt2 = run(ns2)
-    return {"value": round(2.0 * m * ns2 * k / dt2 / 1e9, 3), "unit": "GFLOP/s", "cores": cores,
-            "kind": "oracle",
-            "sample": f"first {ns2} of {C.shape[0]} columns of C of the same dgemm "
-                      f"(m={m}, k={k}), {dt2:.1f} s, working-precision triple loop"}
+    out = {"value": round(2.0 * m * ns2 * k / dt2 / 1e9, 3), "unit": "GFLOP/s", "cores": cores,
+           "kind": "oracle",
+           "sample": f"first {ns2} of {C.shape[0]} columns of C of the same dgemm "
+                     f"(m={m}, k={k}), {dt2:.1f} s, working-precision triple loop"}
+    # the same oracle on one core (n = 1024) and on all cores (n = 4096): leading blocks of the same operands
+    also = []
+    for nn, threads in ((1024, 1), (4096, cores)):
+        if nn > m or nn > C.shape[0]:
+            continue
+        oracle.set_num_threads(threads)
+        Cs = C[:nn].copy()
+        t0 = time.perf_counter()
+        info = oracle.gemm_work("N", "N", nn, nn, nn, alpha, A, lda, B, ldb, beta, Cs, ldc)
+        dt = time.perf_counter() - t0
+        assert info == 0
+        also.append({"n": nn, "cores": threads, "GFLOP/s": round(2.0 * nn ** 3 / dt / 1e9, 3), "s": round(dt, 2)})
+    oracle.set_num_threads(cores)
+    out["also"] = also
+    return out
+
+
+def xg_cus(torch):
+    return torch.cuda.get_device_properties(0).multi_processor_count
 
 
 def mfma_probe_tflops(torch, xg, prec, blocks=512, iters=10000):
@@ -170,7 +195,9 @@ def main():
         if rc:
             raise RuntimeError(f"xgemm gemm returned {rc}")
 
-    wall, dev = time_calls(torch, step, args.steps, args.warmup)
+    each = []
+    wall, dev = time_calls(torch, step, args.steps, args.warmup, each)
+    each.sort()
     kernel = xg.xgemm_last_kernel_name()
     flops = 2.0 * nsz ** 3
     gflops = flops / wall / 1e9
@@ -189,6 +216,7 @@ def main():
     out = {
         "metric": metric, "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 4),
+        "ms_median": round(each[len(each) // 2] * 1e3, 4), "ms_min": round(each[0] * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": fkey,
         "data": "synthetic",
         "config": {"workload": f"{'s' if single else 'd'}gemm NN m=n=k={nsz} alpha={alpha} beta={beta} "
@@ -197,13 +225,19 @@ def main():
         f"pct_of_fp{fkey[1:]}_mfma_peak": round(100.0 * gflops / 1e3 / peak, 2),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": traffic, "kernel": kernel, "avg_launch_ms": round(dev * 1e3, 4)},
+                     "traffic": traffic,
+                     "traffic_source": "stored: rocprofv3 FETCH_SIZE / WRITE_SIZE of this command in a run of its own "
+                                       "(profiles/dgemm_8192_counters.md), not measured in this run" if traffic else None,
+                     "kernel": kernel, "avg_launch_ms": round(dev * 1e3, 4)},
     }
     # the matrix-core rate this device sustains right now (register-resident MFMA loop, no memory
     # traffic), so that the headline can also be read against the clock of the box it ran on
     probe = mfma_probe_tflops(torch, xg, "s" if single else "d")
     out["mfma_probe"] = {"tflops": round(probe, 2), "frac_of_published_peak": round(probe / peak, 4),
-                         "headline_frac_of_probe": round(achieved / probe, 4)}
+                         "headline_frac_of_probe": round(achieved / probe, 4),
+                         # matrix-instruction rate of the probe over the flops per cycle of the device (CUs x 4 SIMDs x
+                         # 32 or 64 flop): the engine clock the matrix cores sustained just after the timed region
+                         "sustained_clock_ghz": round(probe * 1e3 / (xg_cus(torch) * 4 * (64 if single else 32)), 3)}
     if not args.no_cpu and not single:
         import oracle
         out["cpu_baseline"] = cpu_baseline(np, oracle, host_ops, nsz, nsz, ld, ld, ld, alpha, beta)
@@ -394,6 +428,25 @@ def sweep(torch, np, xg, si, args):
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dA0, dA
+    for prec, nsz in (("d", 4096), ("d", 8192), ("d", 16384), ("s", 8192)):
+        if not want(f"{prec}getrf {nsz}"):
+            continue
+        dtype = np.float64 if prec == "d" else np.float32
+        ld = si.padded_ld(nsz)
+        dA0 = torch.from_numpy(si.uniform(si.rng_for(9, nsz), nsz, nsz, ld, dtype, sentinel=0.0)).cuda()
+        dA = dA0.clone()
+        dinfo = torch.zeros(1, dtype=torch.int32, device="cuda")
+        dpiv = torch.zeros(nsz, dtype=torch.int32, device="cuda")
+        f = getattr(xg, f"xgemm_{prec}getrf")
+        dev = timed_in_place(lambda: dA.copy_(dA0), lambda: f(nsz, nsz, dA, ld, dpiv, dinfo), reps=4, skip=1)
+        if int(dinfo.item()) != 0:
+            raise RuntimeError("getrf info %d" % int(dinfo.item()))
+        flops = 2.0 * float(nsz) ** 3 / 3.0
+        peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
+        print(json.dumps({"shape": f"{prec}getrf {nsz}", "ms": round(dev * 1e3, 4),
+                          "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
+              file=sys.stderr, flush=True)
+        del dA0, dA
     if not want("zgemm"):
         return
     # zgemm 4096^3 on split planes: four real launches, 8 m n k flops
@@ -428,9 +481,12 @@ def sweep(torch, np, xg, si, args):
                 raise RuntimeError(rc)
 
         wall, dev = time_calls(torch, zistep, 10, 5)
+        own = flops if method == 0 else 6.0 * nsz ** 3           # what the method itself computes: 4 or 3 real products
         print(json.dumps({"shape": f"zgemm interleaved ({name}) NN {nsz}^3", "ms": round(dev * 1e3, 4),
-                          "GFLOP/s(8mnk)": round(flops / dev / 1e9, 1),
-                          "frac_of_mfma_peak(8mnk)": round(flops / dev / (PEAK_TFLOPS['f64'] * 1e12), 4)}),
+                          "GFLOP/s": round(own / dev / 1e9, 1),
+                          "frac_of_mfma_peak": round(own / dev / (PEAK_TFLOPS['f64'] * 1e12), 4),
+                          "flops_counted": "8mnk" if method == 0 else "6mnk (three real products)",
+                          "GFLOP/s_as_8mnk": round(flops / dev / 1e9, 1)}),
               file=sys.stderr, flush=True)
         del zwork
 
