@@ -598,11 +598,12 @@ __global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArg
         if (live) {
             xfetch(p + 1, (p + 1) % 2);
             // Every tile of the wave's half takes part whatever the order, in straight-line code.  An
-            // earlier form jumped around the tiles past the order; it left the last four rows of the last
-            // tile short of their final update for orders 176-208, in some waves of some runs only.  The
-            // cause was not established (a read of a matrix-instruction result one wait state after the
-            // instruction was checked on the device and is interlocked), so the form that every order of
-            // 1..256 passes repeatedly is kept and tested as such.
+            // earlier form jumped around the tiles past the order, each jump straight after a tile's matrix
+            // instruction and all to one block that copies accumulator registers; on that edge the compiler
+            // left fewer wait states before the copy than the instruction needs to finish its last-written
+            // register pair (it finds the nearest matrix instruction along one path per block only), and
+            // rows 12-15 of the last tile missed their final update in some waves.  Rule: no runtime branch
+            // between a matrix instruction and the next reader of its accumulator.
             if (half == 0) multiply(p_tag, std::integral_constant<int, 0>{});
             else multiply(p_tag, std::integral_constant<int, 1>{});
         }

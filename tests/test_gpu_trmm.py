@@ -113,8 +113,9 @@ def test_larger_sizes_against_the_product_oracle_on_sampled_entries(dtype, side,
 def test_every_order_of_a_single_diagonal_block_bit_exact(dtype, R, side, uplo, trans):
     """Orders 1..256 are one launch of a diagonal-block kernel each (two kernels, many code paths
     that depend on the order: ragged last tiles, ragged last panels, panels never fetched).  Integer
-    data, so that every entry is compared exactly; repeated, because a scheduling mistake in such a
-    kernel showed as wrong last rows for some orders in some runs only."""
+    data, so that every entry is compared exactly; repeated, because an earlier form of the order-256
+    kernel (runtime jumps around whole tiles, which left the compiler's wait states short on the jumping
+    path) showed wrong last rows for some orders in some runs only."""
     rng = si.rng_for(142, "LR".index(side) * 4 + "LU".index(uplo) * 2 + "NT".index(trans))
     nrhs = 70
     for dim in list(range(1, 257, 5)) + [64, 128, 176, 190, 191, 192, 208, 255, 256]:
