@@ -10,9 +10,10 @@
 // arithmetic of a panel except its leaves runs in the solve and product kernels.  A leaf of up
 // to LEAF columns is factored by ONE workgroup (getf2_kernel): the search for the pivot is a
 // reduction inside the workgroup, so nothing in the library ever waits for another workgroup,
-// and a leaf costs one launch, not one per column.  After a panel its interchanges are applied
-// to the columns on both sides of it (laswp_kernel), the block row of U comes from a triangular
-// solve and the rest of the matrix is updated by one product of depth PANEL.
+// and a leaf costs one launch, not one per column; it carries its interchanges through all
+// columns of its panel.  After a panel its interchanges are applied to the columns on both
+// sides of it (laswp_kernel), the block row of U comes from a triangular solve and the rest
+// of the matrix is updated by one product of depth PANEL.
 #include "../../include/xgemm.h"
 #include "../../include/xgemm_tuning.h"
 
@@ -24,13 +25,18 @@ namespace {
 inline int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
 inline int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
 constexpr int64_t DIM_MAX = 0x7fffffff;
-constexpr int LEAF = 8;          // columns one workgroup factors by itself
-constexpr int LEAF_NT = 1024;    // its threads
+constexpr int LEAF = 8;          // most columns one workgroup factors by itself
+constexpr int LEAF_NT = 512;     // its threads (two waves per SIMD, so that each thread may hold 64 elements in registers)
 constexpr int LEAF_WAVES = LEAF_NT / 64;
+constexpr int LEAF_ELEMS = 64;   // elements of the leaf per thread: ROWS x W with W = 8, 4, 2 or 1 columns
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
 
 template <typename T> __device__ __forceinline__ T abs_of(T x) { return x < T(0) ? -x : x; }
+// smallest magnitude whose reciprocal is finite and normal (LAPACK's safe minimum)
+template <typename T> struct RcpLimit;
+template <> struct RcpLimit<double> { static __device__ __forceinline__ double tiny() { return 2.2250738585072014e-308; } };
+template <> struct RcpLimit<float> { static __device__ __forceinline__ float tiny() { return 1.17549435e-38f; } };
 
 // Candidate for the pivot: the largest magnitude, and among equal magnitudes the smallest row.
 template <typename T> struct Cand {
@@ -51,96 +57,289 @@ template <typename T> __device__ __forceinline__ Cand<T> wave_best(Cand<T> c) {
     return c;
 }
 
-// Columns [j0, j0 + w) of A, rows j0 .. m - 1, w <= LEAF: Gaussian elimination with partial pivoting, one
-// column at a time, by one workgroup; the leaf stays in memory (the caches of this CU), the rows are dealt to
-// the threads.  Per column: the pivot is the first largest entry (reduction over the workgroup); the pivot row
-// and row j0 + c change places within the leaf's columns; the column is divided by the pivot (a true division,
-// so that no multiplier exceeds one); the columns to its right inside the leaf are updated, and the search for
-// the next column's pivot rides on that pass.  A zero pivot is recorded in *info (first one only, 1-based
+// ---------------------------------------------------------------------------
+// Row interchanges, a batch at a time.  The interchanges k = 0 .. cnt - 1 (row top + k with row piv[k], in that
+// order, cnt <= G) touch at most 2 G rows and permute them the same way in every column, so the permutation is
+// worked out once per batch and workgroup, and a thread then moves its column with loads and stores that do not
+// depend on each other, instead of a chain of cnt dependent exchanges.
+//   slots 0 .. G-1 stand for the rows top + k, slots G .. 2G-1 for the rows piv[k]; a row that occurs several
+//   times is represented by its first slot (canon); lane j of the first wave follows the content that started in
+//   slot j through the interchanges, which gives each slot the slot its final content comes from (src).
+// LDS: rows[2G], canon[2G], src[2G] ints and vals[2G][NTHR] elements.  Every thread of the workgroup must call
+// (barriers inside); a thread without a column passes col == nullptr.
+// ---------------------------------------------------------------------------
+template <typename T, int G, int NTHR> struct SwapLds {
+    int rows[2 * G], canon[2 * G], src[2 * G];
+    T vals[2 * G][NTHR];
+};
+template <typename T, int G, int NTHR>
+__device__ __forceinline__ void swap_batch(SwapLds<T, G, NTHR> &L, T *col, int top, const int *piv, int piv_bias, int cnt,
+                                           int tid) {
+    static_assert(2 * G <= 64, "the slots are the lanes of one wave");
+    if (tid < 2 * G) {
+        const int k = tid < G ? tid : tid - G;
+        L.rows[tid] = k < cnt ? (tid < G ? top + k : piv[k] + piv_bias) : -1 - tid;   // unused slots: distinct, never a row
+    }
+    __syncthreads();
+    if (tid < 2 * G) {
+        int c = tid;
+        for (int j = tid - 1; j >= 0; --j)
+            if (L.rows[j] == L.rows[tid]) c = j;
+        L.canon[tid] = c;
+    }
+    __syncthreads();
+    if (tid < 2 * G) {
+        // lane j follows the content that started in slot j through the interchanges: no lane needs another's state
+        int pos = tid;
+        for (int k = 0; k < cnt; ++k) {
+            const int a = L.canon[k], b = L.canon[G + k];
+            pos = pos == a ? b : (pos == b ? a : pos);
+        }
+        L.src[tid] = -1;
+        __builtin_amdgcn_wave_barrier();
+        if (L.canon[tid] == tid && L.rows[tid] >= 0) L.src[pos] = tid;
+    }
+    __syncthreads();
+    if (col) {
+        T v[2 * G];
+#pragma unroll
+        for (int j = 0; j < 2 * G; ++j) v[j] = L.src[j] >= 0 ? col[L.rows[j]] : T(0);
+#pragma unroll
+        for (int j = 0; j < 2 * G; ++j) L.vals[j][tid % NTHR] = v[j];
+#pragma unroll 4
+        for (int j = 0; j < 2 * G; ++j) {
+            const int sj = L.src[j];
+            if (sj >= 0 && sj != j) col[L.rows[j]] = L.vals[sj][tid % NTHR];
+        }
+    }
+    __syncthreads();
+}
+
+// Columns [j0, j0 + w) of A, rows j0 .. m - 1, w <= W: Gaussian elimination with partial pivoting, one column
+// at a time, by one workgroup.  Row j0 + t + q * LEAF_NT belongs to thread t for the whole leaf.
+// RESIDENT: the leaf fits the registers (at most LEAF_NT * ROWS rows, ROWS x W = 64 elements per thread): it is
+// loaded once and stored once.  Otherwise it stays in memory (the caches of this CU) and every column is one
+// pass over the rows below it, ROWS rows of a thread at a time.
+// Per column c (row r = j0 + c), with ONE barrier:
+//   - every thread knows the largest entry among its own rows (found while the column before was updated);
+//     a reduction over each wave picks the wave's candidate (largest magnitude, smallest row among equals),
+//     and the lane that owns it leaves the whole candidate row (all w columns) in LDS, as thread c does
+//     with row r;
+//   - barrier; every thread reduces the waves' candidates alike, so all know the pivot row p, its values U and
+//     the old row r without reading either from memory;
+//   - rows r and p change places: the owner of r takes U, the owner of p takes the old row r (no other thread
+//     touches either row);
+//   - the column is divided by the pivot (times its reciprocal; no multiplier exceeds one), the columns to
+//     its right inside the leaf are updated, and the search for the next pivot rides on that pass.
+// The LDS slots alternate with the parity of c, so that a wave that is a column ahead does not overwrite what
+// a slower one still reads.  At the end the leaf's interchanges are carried through the other columns of the
+// enclosing panel [c_lo, c_hi) in one batch.  A zero pivot is recorded in *info (first one only, 1-based
 // column) and its column left as it is.  ipiv[j0 + c] receives the pivot's row + 1.
-template <typename T>
-__global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m, int j0, int w, int *ipiv, int *info) {
-    __shared__ T s_val[LEAF_WAVES];
-    __shared__ int s_row[LEAF_WAVES];
-    __shared__ int s_piv;
+template <typename T, int ROWS, int W, bool RESIDENT>
+__global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m, int j0, int w, int c_lo, int c_hi,
+                                                        int *ipiv, int *info) {
+    __shared__ T s_val[2][LEAF_WAVES];
+    __shared__ int s_row[2][LEAF_WAVES];
+    __shared__ T s_cand[2][LEAF_WAVES][W];
+    __shared__ T s_top[2][W];
+    __shared__ int s_piv[LEAF];
+    __shared__ SwapLds<T, LEAF, 128> s_swap;
+    constexpr int NONE = 0x7fffffff;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     T *const P = A + (int64_t)j0 * lda;          // column j0 of the matrix
-    Cand<T> mine{T(-1), 0x7fffffff};
-    for (int i = j0 + tid; i < m; i += LEAF_NT) {
-        const T v = abs_of(P[i]);
-        if (v > mine.val) { mine.val = v; mine.row = i; }
+    T a[ROWS][W];
+    Cand<T> mine{T(-1), NONE};
+    if (RESIDENT) {
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int i = j0 + tid + q * LEAF_NT;
+#pragma unroll
+            for (int d = 0; d < W; ++d) a[q][d] = (i < m && d < w) ? P[i + (int64_t)d * lda] : T(0);
+            if (i < m) {
+                const T v = abs_of(a[q][0]);
+                if (v > mine.val) { mine.val = v; mine.row = i; }
+            }
+        }
+    } else {
+        for (int i = j0 + tid; i < m; i += LEAF_NT) {
+            const T v = abs_of(P[i]);
+            if (v > mine.val) { mine.val = v; mine.row = i; }
+        }
     }
     for (int c = 0; c < w; ++c) {
-        const int r = j0 + c;
-        // the pivot of column c
+        const int r = j0 + c, buf = c & 1;
         const Cand<T> wb = wave_best(mine);
-        if (lane == 0) { s_val[wave] = wb.val; s_row[wave] = wb.row; }
-        __syncthreads();
-        if (wave == 0) {
-            Cand<T> x{lane < LEAF_WAVES ? s_val[lane & (LEAF_WAVES - 1)] : T(-1), lane < LEAF_WAVES ? s_row[lane & (LEAF_WAVES - 1)] : 0x7fffffff};
-            x = wave_best(x);
-            if (lane == 0) {
-                s_piv = x.row;
-                ipiv[r] = x.row + 1;
-                if (x.val == T(0) && *info == 0) *info = r + 1;
+        if (wb.row == NONE) {
+            if (lane == 0) { s_val[buf][wave] = T(-1); s_row[buf][wave] = NONE; }
+        } else if (mine.row == wb.row) {          // one lane: rows are distinct
+            s_val[buf][wave] = wb.val;
+            s_row[buf][wave] = wb.row;
+            if (RESIDENT) {
+                const int qc = (wb.row - j0) / LEAF_NT;
+#pragma unroll
+                for (int q = 0; q < ROWS; ++q)
+                    if (q == qc) {
+#pragma unroll
+                        for (int d = 0; d < W; ++d) s_cand[buf][wave][d] = a[q][d];
+                    }
+            } else {
+#pragma unroll
+                for (int d = 0; d < W; ++d) s_cand[buf][wave][d] = d < w ? P[wb.row + (int64_t)d * lda] : T(0);
             }
         }
-        __syncthreads();
-        const int p = s_piv;
-        T *const Pc = P + (int64_t)c * lda;
-        const bool nonzero = Pc[p] != T(0);
-        __syncthreads();                          // everybody has read the pivot before rows move
-        if (tid < w && p != r && nonzero) {
-            T *const q = P + (int64_t)tid * lda;
-            const T x = q[r];
-            q[r] = q[p];
-            q[p] = x;
+        if (tid == c) {                           // row r is this thread's first row
+#pragma unroll
+            for (int d = 0; d < W; ++d) s_top[buf][d] = RESIDENT ? a[0][d] : (d < w ? P[r + (int64_t)d * lda] : T(0));
         }
         __syncthreads();
-        const T pivot = Pc[r];
-        T u[LEAF];
+        Cand<T> best{T(-1), NONE};
+        int bw = 0;
 #pragma unroll
-        for (int d = 1; d < LEAF; ++d) u[d] = (c + d < w) ? P[r + (int64_t)(c + d) * lda] : T(0);
+        for (int v = 0; v < LEAF_WAVES; ++v) {
+            const Cand<T> x{s_val[buf][v], s_row[buf][v]};
+            if (x.val > best.val || (x.val == best.val && x.row < best.row)) { best = x; bw = v; }
+        }
+        const int p = best.row;
+        T U[W], top[W];
+#pragma unroll
+        for (int d = 0; d < W; ++d) { U[d] = s_cand[buf][bw][d]; top[d] = s_top[buf][d]; }
+        T pivot = T(0);
+#pragma unroll
+        for (int d = 0; d < W; ++d) pivot = (d == c) ? U[d] : pivot;
+        // wave-uniform facts about the pivot, as scalars: what depends on them is branched over, not computed and
+        // thrown away (a double-precision division costs some thirty instructions)
+        const bool nonzero = __builtin_amdgcn_readfirstlane((int)(pivot != T(0))) != 0;
+        // the column is scaled by the reciprocal of the pivot, as LAPACK does (one division per column instead of
+        // one per row; |a| <= |pivot| still gives |a * (1 / pivot)| <= 1 after rounding), unless the reciprocal
+        // would overflow
+        const bool by_rcp = __builtin_amdgcn_readfirstlane((int)(abs_of(pivot) >= RcpLimit<T>::tiny())) != 0;
+        const T rcp = by_rcp ? T(1) / pivot : T(0);
+        if (tid == 0) {
+            ipiv[r] = p + 1;
+            s_piv[c] = p;
+            if (!nonzero && *info == 0) *info = r + 1;
+        }
+        const bool exchange = nonzero && p != r;
         mine.val = T(-1);
-        mine.row = 0x7fffffff;
-        for (int i = r + 1 + tid; i < m; i += LEAF_NT) {
-            T l = Pc[i];
-            if (nonzero) {
-                l = l / pivot;
-                Pc[i] = l;
+        mine.row = NONE;
+        if (RESIDENT) {
+            if (exchange) {
+                const int tp = (p - j0) % LEAF_NT, qp = (p - j0) / LEAF_NT;
+                if (tid == c) {
+#pragma unroll
+                    for (int d = 0; d < W; ++d) a[0][d] = U[d];
+                }
+                if (tid == tp) {
+#pragma unroll
+                    for (int q = 0; q < ROWS; ++q)
+                        if (q == qp) {
+#pragma unroll
+                            for (int d = 0; d < W; ++d) a[q][d] = top[d];
+                        }
+                }
             }
 #pragma unroll
-            for (int d = 1; d < LEAF; ++d) {
-                if (c + d < w) {
-                    T *const q = P + i + (int64_t)(c + d) * lda;
-                    const T x = *q - l * u[d];
-                    *q = x;
-                    if (d == 1) {
-                        const T v = abs_of(x);
-                        if (v > mine.val) { mine.val = v; mine.row = i; }
+            for (int q = 0; q < ROWS; ++q) {
+                const int i = j0 + tid + q * LEAF_NT;
+                if (i > r && i < m) {
+                    T l = T(0);
+#pragma unroll
+                    for (int d = 0; d < W; ++d) l = (d == c) ? a[q][d] : l;
+                    if (nonzero) {
+                        if (by_rcp) l = l * rcp;
+                        else l = l / pivot;
+                    }
+#pragma unroll
+                    for (int d = 0; d < W; ++d) {
+                        if (d == c) a[q][d] = l;
+                        else if (d > c && d < w) a[q][d] = a[q][d] - l * U[d];
+                        if (d == c + 1 && d < w) {
+                            const T v = abs_of(a[q][d]);
+                            if (v > mine.val) { mine.val = v; mine.row = i; }
+                        }
+                    }
+                }
+            }
+        } else {
+            if (exchange && tid == c) {
+#pragma unroll
+                for (int d = 0; d < W; ++d)
+                    if (d < w) P[r + (int64_t)d * lda] = U[d];
+            }
+            for (int i0 = j0 + tid; i0 < m; i0 += ROWS * LEAF_NT) {
+                T x[ROWS][W];
+#pragma unroll
+                for (int q = 0; q < ROWS; ++q) {
+                    const int i = i0 + q * LEAF_NT;
+                    const bool live = i > r && i < m, moved = exchange && i == p;
+#pragma unroll
+                    for (int d = 0; d < W; ++d)
+                        x[q][d] = moved ? top[d] : ((live && d >= c && d < w) ? P[i + (int64_t)d * lda] : T(0));
+                }
+#pragma unroll
+                for (int q = 0; q < ROWS; ++q) {
+                    const int i = i0 + q * LEAF_NT;
+                    const bool live = i > r && i < m, moved = exchange && i == p;
+                    if (!live) continue;
+                    T l = T(0);
+#pragma unroll
+                    for (int d = 0; d < W; ++d) l = (d == c) ? x[q][d] : l;
+                    if (nonzero) {
+                        if (by_rcp) l = l * rcp;
+                        else l = l / pivot;
+                    }
+#pragma unroll
+                    for (int d = 0; d < W; ++d) {
+                        if (d >= w) continue;
+                        T *const dst = P + i + (int64_t)d * lda;
+                        if (d < c) {
+                            if (moved) *dst = x[q][d];          // the part of the old row r left of column c moves too
+                        } else if (d == c) {
+                            if (nonzero || moved) *dst = l;
+                        } else {
+                            const T y = x[q][d] - l * U[d];
+                            *dst = y;
+                            if (d == c + 1) {
+                                const T v = abs_of(y);
+                                if (v > mine.val) { mine.val = v; mine.row = i; }
+                            }
+                        }
                     }
                 }
             }
         }
-        __syncthreads();                          // the updated columns are complete before the next search reads them
+    }
+    if (RESIDENT) {
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int i = j0 + tid + q * LEAF_NT;
+            if (i < m) {
+#pragma unroll
+                for (int d = 0; d < W; ++d)
+                    if (d < w) P[i + (int64_t)d * lda] = a[q][d];
+            }
+        }
+    }
+    // the leaf's interchanges in the other columns of the enclosing panel, 128 columns at a time
+    const int outside = (c_hi - c_lo) - w;
+    for (int x0 = 0; x0 < outside; x0 += 128) {       // uniform trip count; s_piv is complete after the first barrier inside
+        const int x = x0 + tid;
+        T *col = nullptr;
+        if (tid < 128 && x < outside) col = A + (int64_t)(c_lo + x + (c_lo + x >= j0 ? w : 0)) * lda;
+        swap_batch<T, LEAF, 128>(s_swap, col, j0, s_piv, 0, w, tid);
     }
 }
 
 // Row interchanges k = k0 .. k1 - 1 (row k with row ipiv[k] - 1, in that order) applied to columns
-// [c0, c1) of A; one thread per column.
+// [c0, c1) of A: 64 columns per workgroup, one per thread, 32 interchanges per batch.
+constexpr int SWAP_G = 32, SWAP_NT = 64;
 template <typename T>
-__global__ void __launch_bounds__(256) laswp_kernel(T *A, int64_t lda, int c0, int c1, int k0, int k1, const int *ipiv) {
-    const int col = c0 + blockIdx.x * 256 + threadIdx.x;
-    if (col >= c1) return;
-    T *const q = A + (int64_t)col * lda;
-    for (int k = k0; k < k1; ++k) {
-        const int p = ipiv[k] - 1;
-        if (p != k) {
-            const T x = q[k];
-            q[k] = q[p];
-            q[p] = x;
-        }
-    }
+__global__ void __launch_bounds__(SWAP_NT) laswp_kernel(T *A, int64_t lda, int c0, int c1, int k0, int k1, const int *ipiv) {
+    __shared__ SwapLds<T, SWAP_G, SWAP_NT> s_swap;
+    const int tid = threadIdx.x, c = c0 + blockIdx.x * SWAP_NT + tid;
+    T *const col = c < c1 ? A + (int64_t)c * lda : nullptr;
+    for (int k = k0; k < k1; k += SWAP_G)
+        swap_batch<T, SWAP_G, SWAP_NT>(s_swap, col, k, ipiv + k, -1, (k1 - k) < SWAP_G ? (k1 - k) : SWAP_G, tid);
 }
 
 __global__ void clear_int_kernel(int *p) { *p = 0; }
@@ -157,28 +356,52 @@ template <typename T> struct Lu {
 
     int swap_rows(int64_t c0, int64_t c1, int64_t k0, int64_t k1) const {
         if (c1 <= c0 || k1 <= k0) return 0;
-        hipLaunchKernelGGL(laswp_kernel<T>, dim3((unsigned)((c1 - c0 + 255) / 256)), dim3(256), 0,
+        hipLaunchKernelGGL(laswp_kernel<T>, dim3((unsigned)((c1 - c0 + SWAP_NT - 1) / SWAP_NT)), dim3(SWAP_NT), 0,
                            static_cast<hipStream_t>(stream), A, lda, (int)c0, (int)c1, (int)k0, (int)k1, ipiv);
         return (int)hipGetLastError();
     }
 
-    // columns [j0, j0 + w) below and including row j0, w <= min(m, n) - j0; interchanges stay inside those columns
-    int panel(int64_t j0, int64_t w) const {
-        if (w <= LEAF) {
-            hipLaunchKernelGGL(getf2_kernel<T>, dim3(1), dim3(LEAF_NT), 0, static_cast<hipStream_t>(stream), A, lda, (int)m,
-                               (int)j0, (int)w, ipiv, info);
-            return (int)hipGetLastError();
+    // columns [j0, j0 + w) below and including row j0, w <= min(m, n) - j0, inside the panel [c_lo, c_hi) of the
+    // sweep: the leaves carry their interchanges through all of that panel's columns
+    // Widest leaf for rows j0 .. m - 1: what keeps the leaf in the registers of one workgroup (64 elements per
+    // thread); leaves taller than that at a single column go through memory at full width.
+    static constexpr int MIN_W = sizeof(T) == 8 ? 4 : 1;   // fp64: narrower leaves would need more registers than a lane has
+    int64_t leaf_width(int64_t j0) const {
+        const int64_t rows_per_thread = (m - j0 + LEAF_NT - 1) / LEAF_NT;
+        for (int64_t wd = LEAF; wd >= MIN_W; wd /= 2)
+            if (rows_per_thread * wd <= LEAF_ELEMS) return wd;
+        return LEAF;
+    }
+    template <int W> int leaf(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi, bool resident) const {
+        const hipStream_t st = static_cast<hipStream_t>(stream);
+        if (resident)
+            hipLaunchKernelGGL((getf2_kernel<T, LEAF_ELEMS / W, W, true>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
+                               (int)w, (int)c_lo, (int)c_hi, ipiv, info);
+        else
+            hipLaunchKernelGGL((getf2_kernel<T, LEAF_ELEMS / W, W, false>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
+                               (int)w, (int)c_lo, (int)c_hi, ipiv, info);
+        return (int)hipGetLastError();
+    }
+    int panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
+        const int64_t lw = leaf_width(j0);
+        if (w <= lw) {
+            const bool resident = ((m - j0 + LEAF_NT - 1) / LEAF_NT) * lw <= LEAF_ELEMS;
+            switch (lw) {
+                case 8: return leaf<8>(j0, w, c_lo, c_hi, resident);
+                case 4: return leaf<4>(j0, w, c_lo, c_hi, resident);
+                default:
+                    if constexpr (MIN_W < 4) return lw == 2 ? leaf<2>(j0, w, c_lo, c_hi, resident) : leaf<1>(j0, w, c_lo, c_hi, resident);
+                    return (int)hipErrorInvalidValue;
+            }
         }
-        const int64_t w1 = ((w / 2 + LEAF - 1) / LEAF) * LEAF, w2 = w - w1, j1 = j0 + w1;
+        const int64_t w1 = ((w / 2 + lw - 1) / lw) * lw, w2 = w - w1, j1 = j0 + w1;
         int rc;
-        if ((rc = panel(j0, w1))) return rc;
-        if ((rc = swap_rows(j1, j0 + w, j0, j1))) return rc;
+        if ((rc = panel(j0, w1, c_lo, c_hi))) return rc;
         T *const A11 = A + j0 + j0 * lda, *const A12 = A + j0 + j1 * lda;
         T *const A21 = A + j1 + j0 * lda, *const A22 = A + j1 + j1 * lda;
         if ((rc = trsm(w1, w2, A11, A12))) return rc;
         if (m > j1 && (rc = gemm(m - j1, w2, w1, A21, A12, A22))) return rc;
-        if ((rc = panel(j1, w2))) return rc;
-        return swap_rows(j0, j1, j1, j0 + w);
+        return panel(j1, w2, c_lo, c_hi);
     }
 
     int run() const {
@@ -187,7 +410,7 @@ template <typename T> struct Lu {
         int rc;
         for (int64_t j = 0; j < steps; j += W) {
             const int64_t nb = min64(W, steps - j), j1 = j + nb;
-            if ((rc = panel(j, nb))) return rc;
+            if ((rc = panel(j, nb, j, j1))) return rc;
             if ((rc = swap_rows(0, j, j, j1))) return rc;
             if (j1 < n) {
                 if ((rc = swap_rows(j1, n, j, j1))) return rc;
