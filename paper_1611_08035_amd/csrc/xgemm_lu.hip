@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace {
 
 inline int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
@@ -28,7 +30,9 @@ constexpr int64_t DIM_MAX = 0x7fffffff;
 constexpr int LEAF = 8;          // most columns one workgroup factors by itself
 constexpr int LEAF_NT = 512;     // its threads (two waves per SIMD, so that each thread may hold 64 elements in registers)
 constexpr int LEAF_WAVES = LEAF_NT / 64;
-constexpr int LEAF_ELEMS = 64;   // elements of the leaf per thread: ROWS x W with W = 8, 4, 2 or 1 columns
+// elements of the leaf per thread, ROWS x W with W = 8, 4, 2 or 1 columns: what the registers of a lane hold
+// beside the rest of the kernel's state
+template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : 64; }
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
 
@@ -238,27 +242,41 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
                         }
                 }
             }
+            // the update of the rows below r, with the column index as a compile-time constant inside each case so
+            // that every register of the leaf is addressed statically
+            auto update = [&](auto c_tag) {
+                constexpr int C = decltype(c_tag)::value;
 #pragma unroll
-            for (int q = 0; q < ROWS; ++q) {
-                const int i = j0 + tid + q * LEAF_NT;
-                if (i > r && i < m) {
-                    T l = T(0);
+                for (int q = 0; q < ROWS; ++q) {
+                    const int i = j0 + tid + q * LEAF_NT;
+                    if (i > r && i < m) {
+                        T l = a[q][C];
+                        if (nonzero) {
+                            if (by_rcp) l = l * rcp;
+                            else l = l / pivot;
+                        }
+                        a[q][C] = l;
 #pragma unroll
-                    for (int d = 0; d < W; ++d) l = (d == c) ? a[q][d] : l;
-                    if (nonzero) {
-                        if (by_rcp) l = l * rcp;
-                        else l = l / pivot;
-                    }
-#pragma unroll
-                    for (int d = 0; d < W; ++d) {
-                        if (d == c) a[q][d] = l;
-                        else if (d > c && d < w) a[q][d] = a[q][d] - l * U[d];
-                        if (d == c + 1 && d < w) {
-                            const T v = abs_of(a[q][d]);
-                            if (v > mine.val) { mine.val = v; mine.row = i; }
+                        for (int d = C + 1; d < W; ++d)
+                            if (d < w) a[q][d] = a[q][d] - l * U[d];
+                        if constexpr (C + 1 < W) {
+                            if (C + 1 < w) {
+                                const T v = abs_of(a[q][C + 1]);
+                                if (v > mine.val) { mine.val = v; mine.row = i; }
+                            }
                         }
                     }
                 }
+            };
+            switch (c) {
+                case 0: update(std::integral_constant<int, 0>{}); break;
+                case 1: if constexpr (W > 1) update(std::integral_constant<int, 1>{}); break;
+                case 2: if constexpr (W > 2) update(std::integral_constant<int, 2>{}); break;
+                case 3: if constexpr (W > 3) update(std::integral_constant<int, 3>{}); break;
+                case 4: if constexpr (W > 4) update(std::integral_constant<int, 4>{}); break;
+                case 5: if constexpr (W > 5) update(std::integral_constant<int, 5>{}); break;
+                case 6: if constexpr (W > 6) update(std::integral_constant<int, 6>{}); break;
+                default: if constexpr (W > 7) update(std::integral_constant<int, 7>{}); break;
             }
         } else {
             if (exchange && tid == c) {
@@ -365,33 +383,32 @@ template <typename T> struct Lu {
     // sweep: the leaves carry their interchanges through all of that panel's columns
     // Widest leaf for rows j0 .. m - 1: what keeps the leaf in the registers of one workgroup (64 elements per
     // thread); leaves taller than that at a single column go through memory at full width.
-    static constexpr int MIN_W = sizeof(T) == 8 ? 4 : 1;   // fp64: narrower leaves would need more registers than a lane has
+    static constexpr int MIN_W = 1;
     int64_t leaf_width(int64_t j0) const {
         const int64_t rows_per_thread = (m - j0 + LEAF_NT - 1) / LEAF_NT;
         for (int64_t wd = LEAF; wd >= MIN_W; wd /= 2)
-            if (rows_per_thread * wd <= LEAF_ELEMS) return wd;
+            if (rows_per_thread * wd <= leaf_elems<T>((int)wd)) return wd;
         return LEAF;
     }
     template <int W> int leaf(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi, bool resident) const {
         const hipStream_t st = static_cast<hipStream_t>(stream);
         if (resident)
-            hipLaunchKernelGGL((getf2_kernel<T, LEAF_ELEMS / W, W, true>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
+            hipLaunchKernelGGL((getf2_kernel<T, leaf_elems<T>(W) / W, W, true>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
                                (int)w, (int)c_lo, (int)c_hi, ipiv, info);
         else
-            hipLaunchKernelGGL((getf2_kernel<T, LEAF_ELEMS / W, W, false>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
+            hipLaunchKernelGGL((getf2_kernel<T, leaf_elems<T>(W) / W, W, false>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
                                (int)w, (int)c_lo, (int)c_hi, ipiv, info);
         return (int)hipGetLastError();
     }
     int panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
         const int64_t lw = leaf_width(j0);
         if (w <= lw) {
-            const bool resident = ((m - j0 + LEAF_NT - 1) / LEAF_NT) * lw <= LEAF_ELEMS;
+            const bool resident = ((m - j0 + LEAF_NT - 1) / LEAF_NT) * lw <= leaf_elems<T>((int)lw);
             switch (lw) {
                 case 8: return leaf<8>(j0, w, c_lo, c_hi, resident);
                 case 4: return leaf<4>(j0, w, c_lo, c_hi, resident);
-                default:
-                    if constexpr (MIN_W < 4) return lw == 2 ? leaf<2>(j0, w, c_lo, c_hi, resident) : leaf<1>(j0, w, c_lo, c_hi, resident);
-                    return (int)hipErrorInvalidValue;
+                case 2: return leaf<2>(j0, w, c_lo, c_hi, resident);
+                default: return leaf<1>(j0, w, c_lo, c_hi, resident);
             }
         }
         const int64_t w1 = ((w / 2 + lw - 1) / lw) * lw, w2 = w - w1, j1 = j0 + w1;
