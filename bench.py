@@ -144,6 +144,56 @@ def latencies(torch, xg, iters=4000):
     print(json.dumps({"latency_probe": rows, "iters": iters}))
 
 
+def model_table(torch, np, xg, args):
+    """The paper's Sec. 6.1 experiment: predicted against measured efficiency over a family of kernels."""
+    from math import gcd
+    cus = xg_cus(torch)
+    print("| Variant | WG/CU | m x n | rounds | MFMA / slab / wave | loads | LDS reads | LDS writes | stall cycles / slab "
+          "| predicted | measured NN | measured NT | better of the two / probe | table | planner uses |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for prec, dtype, gemm, fkey in (("d", torch.float64, xg.xgemm_dgemm, "f64"), ("s", torch.float32, xg.xgemm_sgemm, "f32")):
+        probe = mfma_probe_tflops(torch, xg, prec)
+        v = 0
+        while xg.xgemm_variant_name(prec, v) is not None:
+            name = xg.xgemm_variant_name(prec, v)
+            mt_m, mt_n, _kt = (int(x) for x in name.split("_")[1].split("x"))
+            wgm, wgn = (int(x) for x in name.split("_")[2][1:].split("x"))
+            _rc, o = xg.xgemm_model_predict(prec, v, "N", "N")
+            _rc, (e_meas, e_model, e_used) = xg.xgemm_model_efficiency(prec, v)
+            wgs = int(o[11] * 4 / (wgm * wgn))
+            slots = cus * wgs
+            tiles_m = 4096 // mt_m
+            q = slots // gcd(slots, tiles_m)
+            tiles_n = q * max(1, round(4096 / mt_n / q))
+            m, n = tiles_m * mt_m, tiles_n * mt_n
+            k = 8192
+            lda, ldb = m + 8, max(k, n) + 8
+            A = torch.rand(lda * k, dtype=dtype, device="cuda") * 2 - 1
+            B = torch.rand(ldb * max(k, n), dtype=dtype, device="cuda") * 2 - 1
+            C = torch.zeros(lda * n, dtype=dtype, device="cuda")
+            xg.xgemm_force_variant(v)
+            xg.xgemm_force_split(1)
+            frac = {}
+            for tb in ("N", "T"):
+                def step():
+                    rc = gemm("N", tb, m, n, k, 1.0, A, lda, B, ldb, 1.0, C, lda)
+                    if rc:
+                        raise RuntimeError(f"{name}: gemm returned {rc}")
+
+                each = []
+                time_calls(torch, step, 12, 4, each)
+                assert name in xg.xgemm_last_kernel_name(), (name, xg.xgemm_last_kernel_name())
+                frac[tb] = 2.0 * m * n * k / sorted(each)[len(each) // 2] / 1e12 / PEAK_TFLOPS[fkey]
+            best = max(frac.values())
+            print(f"| {name} | {wgs} | {m} x {n} x {k} | {tiles_m * tiles_n // slots} | {o[0]:.0f} | {o[1]:.0f} | {o[2]:.0f} "
+                  f"| {o[3]:.0f} | {o[8]:.0f} | {e_model:.3f} | {frac['N']:.3f} | {frac['T']:.3f} "
+                  f"| {best * PEAK_TFLOPS[fkey] / probe:.3f} | {e_meas:.3f} | {e_used:.3f} |", flush=True)
+            del A, B, C
+            v += 1
+        print(f"<!-- {prec}: MFMA-only probe {probe:.1f} TFLOP/s = {probe / PEAK_TFLOPS[fkey]:.3f} of the published peak -->")
+    xg.xgemm_tuning_reset()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,6 +213,10 @@ def main():
     ap.add_argument("--latencies", action="store_true",
                     help="instead of the benchmark: run the library's latency probe and print what a dependent "
                          "chain of each instruction kind costs a lone wave (ns and cycles at 2.4 GHz)")
+    ap.add_argument("--model-table", action="store_true",
+                    help="instead of the benchmark: every tile variant forced in turn on a product whose tiles fill "
+                         "every CU in every round (k = 4096), its fraction of the MFMA peak beside the analytical "
+                         "model's prediction, as a markdown table")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -180,6 +234,8 @@ def main():
     xg.xgemm_force_variant(args.variant)
     if args.latencies:
         return latencies(torch, xg)
+    if args.model_table:
+        return model_table(torch, np, xg, args)
 
     nsz = args.size
     single = args.prec == "s"

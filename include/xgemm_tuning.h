@@ -104,16 +104,37 @@ int64_t xgemm_tile_map(int uplo, int64_t m, int64_t n, int mt_m, int mt_n, int *
  *   out[0] MFMAs, out[1] global loads, out[2] LDS reads, out[3] LDS writes
  *   (each per wave); out[4] matrix-pipe cycles per SIMD, out[5] LDS cycles per
  *   CU, out[6] vector-memory cycles per CU; out[7] memory instructions that must
- *   share one MFMA shadow (0: they do not fit); out[8] barrier stall in cycles;
- *   out[9] predicted MFMA utilisation; out[10] vector registers per lane
- *   (accumulators + staging + two fragment sets); out[11] waves per SIMD.
+ *   share one MFMA shadow (0: they do not fit); out[8] stall cycles of the matrix
+ *   pipe per slab (Sec. 4.3's n k: one barrier per workgroup on the CU, plus the
+ *   memory instructions beyond one per MFMA); out[9] predicted MFMA utilisation
+ *   = out[4] / max(out[4] + out[8], out[5], out[6]); out[10] vector registers per
+ *   lane (accumulators + staging + two fragment sets + 30); out[11] waves per SIMD.
  *   Returns 0; 1 if the register limit is violated; -1 bad prec, -2 bad variant,
  *   -5 out == NULL.
+ * xgemm_model_efficiency: for a built variant, out[0] the fraction of the MFMA
+ *   peak measured with its CUs fully occupied (the figure stored in the variant
+ *   table), out[1] the model's prediction of it (transposes N, N), out[2] the one
+ *   the planner prices tiles with: the model's where the two differ by at most
+ *   0.025, the measured one otherwise.  Returns as xgemm_model_predict.
+ * xgemm_model_enumerate: the design space the variants were taken from, in the
+ *   spirit of Sec. 3.3: MFMA shape (fp64 16x16x4; fp32 32x32x2 and 16x16x4) x
+ *   wave tile (MFMA tile .. 128 per side, powers of two) x waves per workgroup
+ *   (1x1, 2x1, 1x2, 2x2, 4x2, 2x4) x slab depth (8, 16, 32), filtered by the
+ *   register constraint of Sec. 5.4 (accumulators, one slab in flight and two
+ *   fragment sets in a lane's 512 registers at the assumed occupancy), by the
+ *   160 KB of LDS and by what the staging can deal to the threads, each with the
+ *   utilisation the model predicts at the occupancy that fits.  Returns the
+ *   number of points that pass; writes the best min(cap, count) of them to
+ *   rows[12 * i + ...], best first: MFMA tile, wave tile m, n, waves along m, n,
+ *   slab depth, registers, LDS bytes, workgroups per CU, predicted utilisation,
+ *   macro tile m, n.  -1 bad prec, -2 cap < 0, -3 rows == NULL with cap > 0.
  */
 double xgemm_model_outer_product_rate(int n_pipes, const double *rate, const double *count);
 double xgemm_model_stalled_rate(double L, double n_dependent, double latency);
 int xgemm_model_n_updates(int r_total, int m_r, int n_r, int v, int r_a, int r_r);
 int xgemm_model_predict(char prec, int variant, char transa, char transb, double out[12]);
+int xgemm_model_efficiency(char prec, int variant, double out[3]);
+int xgemm_model_enumerate(char prec, int cap, double *rows);
 
 #ifdef __cplusplus
 }

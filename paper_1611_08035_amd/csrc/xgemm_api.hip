@@ -117,7 +117,8 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
         const double area = (double)e.mt_m * (double)e.mt_n;
         const double tile_bytes = area * sizeof(T);
         const int64_t full = tiles / slots, rem = tiles % slots;
-        auto t_tile = [&](double depth) { return 2.0 * area * depth / (cu_flops_per_us * e.eff); };
+        const double eff_v = planner_eff(e);
+        auto t_tile = [&](double depth) { return 2.0 * area * depth / (cu_flops_per_us * eff_v); };
         // per round: the read-modify-write of the C tiles is only partly hidden by the other workgroups of the
         // CU, the less so the larger the tile, the fewer of them and the shorter their K loops (fitted to rank-k
         // updates: 10.5 us per round of 128x128 tiles at k = 256, 3.9 at k = 1024)
@@ -142,7 +143,7 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
                 if (tab[w].mt_m * 2 != e.mt_m || tab[w].mt_n * 2 != e.mt_n) continue;
                 const double qarea = (double)tab[w].mt_m * (double)tab[w].mt_n;
                 const int64_t occ = (4 * rem + cus - 1) / cus;
-                const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * tab[w].eff);
+                const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * planner_eff(tab[w]));
                 const double drain = DRAIN_FRAC * e.wgs_per_cu * t_tile((double)k);
                 const bool single_w = sizeof(T) == 8 && tab[w].mt_m / tab[w].wgm == 16 && tab[w].mt_n / tab[w].wgn == 16;
                 const double c = rounds + T_LAUNCH + T_ROUND0 + (drain < T_DRAIN_MAX ? drain : T_DRAIN_MAX) +

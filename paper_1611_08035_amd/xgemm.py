@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_release_thread_resources",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_model_enumerate", "xgemm_model_efficiency", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_release_thread_resources",
 ]
 
 
@@ -139,6 +139,10 @@ def lib():
     L.xgemm_model_stalled_rate.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double]
     L.xgemm_model_n_updates.restype = ctypes.c_int
     L.xgemm_model_n_updates.argtypes = [ctypes.c_int] * 6
+    L.xgemm_model_efficiency.restype = ctypes.c_int
+    L.xgemm_model_efficiency.argtypes = [_c, ctypes.c_int, _p]
+    L.xgemm_model_enumerate.restype = ctypes.c_int
+    L.xgemm_model_enumerate.argtypes = [_c, ctypes.c_int, _p]
     L.xgemm_model_predict.restype = ctypes.c_int
     L.xgemm_model_predict.argtypes = [_c, ctypes.c_int, _c, _c, _p]
     _lib = L
@@ -390,6 +394,23 @@ def xgemm_model_predict(prec, variant, transa="N", transb="N"):
     out = (ctypes.c_double * 12)()
     rc = int(lib().xgemm_model_predict(_ch(prec), int(variant), _ch(transa), _ch(transb), out))
     return rc, list(out)
+
+
+def xgemm_model_efficiency(prec, variant):
+    """Returns (rc, (measured, model, planner's))."""
+    out = (ctypes.c_double * 3)()
+    rc = int(lib().xgemm_model_efficiency(_ch(prec), int(variant), out))
+    return rc, tuple(out)
+
+
+def xgemm_model_enumerate(prec, cap=4096):
+    """Returns (count, rows): rows is a list of 12-tuples, best predicted utilisation first; see include/xgemm_tuning.h."""
+    buf = (ctypes.c_double * (12 * max(cap, 1)))()
+    cnt = int(lib().xgemm_model_enumerate(_ch(prec), int(cap), buf))
+    if cnt < 0:
+        return cnt, None
+    n = min(cnt, cap)
+    return cnt, [tuple(buf[12 * i + c] for c in range(12)) for i in range(n)]
 
 
 def xgemm_tile_map(uplo, m, n, mt_m, mt_n, want_tiles=True):
