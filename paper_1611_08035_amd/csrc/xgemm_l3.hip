@@ -256,26 +256,36 @@ __global__ void __launch_bounds__(64 * (SW + FEED)) trsm_wide_kernel(const Block
 #pragma unroll
         for (int u = 0; u < EL; ++u) {
             const int inside = (int)(r < dim) & (int)(r > c);                // strictly lower part of E
-            const T v = *(inside ? ptr : a.A);
-            stage[slot][u] = inside ? v : T(0);
+            stage[slot][u] = *(inside ? ptr : a.A);                          // looked at in stash, not here: no load is waited for
             ptr += ustep;
             r += ru;
             c += cu;
         }
     };
+    // all reads of d_inv come before the first write of the panel: LDS reads and writes keep their order,
+    // so a read between two writes would cost a round trip each
     auto stash = [&](int p, int slot) {
-        int at = (p & 1) * (PANEL * WIDE) + c0 * WIDE + r0, c = c0 + p * PANEL;
+        T scale[EL];
+        int c = c0 + p * PANEL;
 #pragma unroll
         for (int u = 0; u < EL; ++u) {
-            e_pan[at] = stage[slot][u] * d_inv[c < WIDE ? c : 0];            // column c scaled by 1 / E(c, c)
+            scale[u] = d_inv[c < WIDE ? c : 0];                              // column c scaled by 1 / E(c, c)
+            c += cu;
+        }
+        int at = (p & 1) * (PANEL * WIDE) + c0 * WIDE + r0, r = r0;
+        c = c0 + p * PANEL;
+#pragma unroll
+        for (int u = 0; u < EL; ++u) {
+            const int inside = (int)(r < dim) & (int)(r > c);
+            e_pan[at] = inside ? stage[slot][u] * scale[u] : T(0);
             at += cu * WIDE + ru;
+            r += ru;
             c += cu;
         }
     };
     if (feeding) {
 #pragma unroll
-        for (int sl = 0; sl < DEPTH; ++sl)
-            if (sl < npan) fetch(sl, sl);
+        for (int sl = 0; sl < DEPTH; ++sl) fetch(sl, sl);
         // diagonal: thread t takes entry t of the stored diagonal
         if (tid < WIDE) {
             const bool has_diag = tid < dim && !a.unit;
@@ -286,7 +296,7 @@ __global__ void __launch_bounds__(64 * (SW + FEED)) trsm_wide_kernel(const Block
     __syncthreads();                 // d_inv complete
     if (feeding) {
         stash(0, 0);
-        if (DEPTH < npan) fetch(DEPTH, 0);
+        fetch(DEPTH, 0);
     }
     __syncthreads();
 
@@ -326,7 +336,9 @@ __global__ void __launch_bounds__(64 * (SW + FEED)) trsm_wide_kernel(const Block
             if (FEED_TOO && p + 1 < npan) {
                 const int slot = (gc * PER + pp + 1) % DEPTH;            // a constant once the loop is unrolled
                 stash(p + 1, slot);              // into the half that the solving waves left at the last barrier
-                if (p + 1 + DEPTH < npan) fetch(p + 1 + DEPTH, slot);
+                // unconditional (past the last panel it re-reads the block's first element): a fetch that might
+                // not have been issued would turn every wait for an older one into a wait for all loads
+                fetch(p + 1 + DEPTH, slot);
             }
             __syncthreads();
         }
