@@ -50,15 +50,47 @@ template <typename T> struct Cand {
 template <typename T> __device__ __forceinline__ Cand<T> better(Cand<T> a, Cand<T> b) {
     return (b.val > a.val || (b.val == a.val && b.row < a.row)) ? b : a;
 }
-template <typename T> __device__ __forceinline__ Cand<T> wave_best(Cand<T> c) {
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        Cand<T> o;
-        o.val = __shfl_xor(c.val, d, 64);
-        o.row = __shfl_xor(c.row, d, 64);
-        c = better(c, o);
+// A candidate as another lane holds it, the lanes paired by a data-parallel-primitive pattern (register moves
+// between lanes of a row of 16, no LDS round trip): 0xB1 and 0x4E exchange neighbours inside a quad (lane ^ 1,
+// lane ^ 2), 0x141 mirrors each half row (lane i <-> 7 - i), 0x140 each row (i <-> 15 - i).
+template <int CTRL> __device__ __forceinline__ int dpp_word(int v) { return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false); }
+template <int CTRL, typename T> __device__ __forceinline__ Cand<T> dpp_cand(Cand<T> c) {
+    Cand<T> o;
+    if constexpr (sizeof(T) == 8) {
+        typedef int i32x2 __attribute__((ext_vector_type(2)));
+        i32x2 p = __builtin_bit_cast(i32x2, c.val);
+        p[0] = dpp_word<CTRL>(p[0]);
+        p[1] = dpp_word<CTRL>(p[1]);
+        o.val = __builtin_bit_cast(T, p);
+    } else {
+        o.val = __builtin_bit_cast(T, dpp_word<CTRL>(__builtin_bit_cast(int, c.val)));
     }
-    return c;
+    o.row = dpp_word<CTRL>(c.row);
+    return o;
+}
+template <typename T> __device__ __forceinline__ Cand<T> lane_cand(Cand<T> c, int lane) {
+    Cand<T> o;
+    if constexpr (sizeof(T) == 8) {
+        typedef int i32x2 __attribute__((ext_vector_type(2)));
+        i32x2 p = __builtin_bit_cast(i32x2, c.val);
+        p[0] = __builtin_amdgcn_readlane(p[0], lane);
+        p[1] = __builtin_amdgcn_readlane(p[1], lane);
+        o.val = __builtin_bit_cast(T, p);
+    } else {
+        o.val = __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c.val), lane));
+    }
+    o.row = __builtin_amdgcn_readlane(c.row, lane);
+    return o;
+}
+// The best candidate of the wave, in every lane.  `better` picks the same winner whichever way round two
+// different candidates are given, so after each pairing both partners hold it: four pairings make every row of 16
+// lanes agree, and the four rows are compared as scalars.
+template <typename T> __device__ __forceinline__ Cand<T> wave_best(Cand<T> c) {
+    c = better(c, dpp_cand<0xB1>(c));
+    c = better(c, dpp_cand<0x4E>(c));
+    c = better(c, dpp_cand<0x141>(c));
+    c = better(c, dpp_cand<0x140>(c));
+    return better(better(lane_cand(c, 0), lane_cand(c, 16)), better(lane_cand(c, 32), lane_cand(c, 48)));
 }
 
 // ---------------------------------------------------------------------------
@@ -327,6 +359,16 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
             }
         }
     }
+    // the leaf's interchanges in the other columns of the enclosing panel, 128 columns at a time; before the leaf
+    // itself goes back to memory, so that these loads do not queue behind its stores
+    const int outside = (c_hi - c_lo) - w;
+    for (int x0 = 0; x0 < outside; x0 += 128) {       // uniform trip count; s_piv is complete after the first barrier inside
+        const int x = x0 + tid;
+        T *col = nullptr;
+        if (tid < 128 && x < outside) col = A + (int64_t)(c_lo + x + (c_lo + x >= j0 ? w : 0)) * lda;
+        swap_batch<T, LEAF, 128>(s_swap, col, j0, s_piv, 0, w, tid);
+    }
+    // the leaf back to memory
     if (RESIDENT) {
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
@@ -337,14 +379,6 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
                     if (d < w) P[i + (int64_t)d * lda] = a[q][d];
             }
         }
-    }
-    // the leaf's interchanges in the other columns of the enclosing panel, 128 columns at a time
-    const int outside = (c_hi - c_lo) - w;
-    for (int x0 = 0; x0 < outside; x0 += 128) {       // uniform trip count; s_piv is complete after the first barrier inside
-        const int x = x0 + tid;
-        T *col = nullptr;
-        if (tid < 128 && x < outside) col = A + (int64_t)(c_lo + x + (c_lo + x >= j0 ? w : 0)) * lda;
-        swap_batch<T, LEAF, 128>(s_swap, col, j0, s_piv, 0, w, tid);
     }
 }
 
