@@ -362,6 +362,44 @@ def sweep(torch, np, xg, si, args):
                           "frac_of_min_mfma_hbm_bound": round(flops / dev / bound, 4),
                           "GB/s_algorithmic": round(bytes_alg / dev / 1e9, 1)}), file=sys.stderr, flush=True)
         del dA, dB, dC
+    # the same products on packed operands (pack once, multiply many times): the product alone, and the two
+    # packing passes as the HBM traffic they are (read once, written once)
+    packed = [("d", "N", "N", 8192, 8192, 8192), ("d", "T", "N", 7001, 7001, 7001), ("d", "N", "N", 16384, 16384, 128),
+              ("d", "N", "N", 4096, 4096, 4096), ("s", "N", "N", 8192, 8192, 8192), ("s", "N", "N", 4096, 4096, 4096)]
+    for prec, ta, tb, m, n, k in packed:
+        if not want(f"{prec}gemm_packed {ta}{tb} {m}x{n}x{k}"):
+            continue
+        dtype = np.float64 if prec == "d" else np.float32
+        tdt = torch.float64 if prec == "d" else torch.float32
+        es = 8 if prec == "d" else 4
+        ra, rb = (m if ta == "N" else k), (k if tb == "N" else n)
+        _, (dA, dB, dC) = device_operands(torch, np, si, dtype, ta, tb, m, n, k, ra, rb, m, 2)
+        Ap = torch.empty(xg.xgemm_pack_elems(m, k), dtype=tdt, device="cuda")
+        Bp = torch.empty(xg.xgemm_pack_elems(n, k), dtype=tdt, device="cuda")
+        pa, pb = getattr(xg, f"xgemm_{prec}pack_a"), getattr(xg, f"xgemm_{prec}pack_b")
+        fp, f = getattr(xg, f"xgemm_{prec}gemm_packed"), getattr(xg, f"xgemm_{prec}gemm")
+        peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
+        flops = 2.0 * m * n * k
+
+        def check(rc):
+            if rc:
+                raise RuntimeError(rc)
+
+        est = max(flops / 60e12, 20e-6)
+        steps, warm = max(5, min(200, int(0.1 / est))), max(3, min(400, int(0.2 / est)))
+        _, t_pa = time_calls(torch, lambda: check(pa(ta, m, k, dA, ra, Ap)), 10, 3)
+        _, t_pb = time_calls(torch, lambda: check(pb(tb, k, n, dB, rb, Bp)), 10, 3)
+        _, t_plain = time_calls(torch, lambda: check(f(ta, tb, m, n, k, 1.5, dA, ra, dB, rb, -0.5, dC, m)), steps, warm)
+        k_plain = xg.xgemm_last_kernel_name()
+        _, t_pack = time_calls(torch, lambda: check(fp(m, n, k, 1.5, Ap, Bp, -0.5, dC, m)), steps, warm)
+        print(json.dumps({"shape": f"{prec}gemm_packed {ta}{tb} {m}x{n}x{k}", "kernel": xg.xgemm_last_kernel_name(),
+                          "ms": round(t_pack * 1e3, 4), "GFLOP/s": round(flops / t_pack / 1e9, 1),
+                          "frac_of_mfma_peak": round(flops / t_pack / peak, 4),
+                          "plain_ms": round(t_plain * 1e3, 4), "plain_kernel": k_plain,
+                          "pack_a_ms": round(t_pa * 1e3, 4), "pack_b_ms": round(t_pb * 1e3, 4),
+                          "pack_a_GB/s": round(2.0 * es * m * k / t_pa / 1e9, 1),
+                          "pack_b_GB/s": round(2.0 * es * n * k / t_pb / 1e9, 1)}), file=sys.stderr, flush=True)
+        del dA, dB, dC, Ap, Bp
     # beyond the configurations: symmetric rank-k updates (n (n + 1) k flops) and
     # shapes whose last round of tiles is nearly empty, plain and with a workspace
     lw = xg.xgemm_workspace_bytes()
@@ -523,10 +561,10 @@ def sweep(torch, np, xg, si, args):
                       "frac_of_mfma_peak": round(flops / dev / (PEAK_TFLOPS['f64'] * 1e12), 4)}),
           file=sys.stderr, flush=True)
     del planes
-    # the same product on interleaved storage (split into planes, real GEMMs, merge), 4m and 3m;
-    # both counted as 8 m n k flops
+    # the same product on interleaved storage: split into planes, real GEMMs, merge (4m and 3m), and the fused
+    # form (two packing passes and one real product of twice the rows and depth, written straight into C)
     zs = [torch.from_numpy(si.uniform(rng, 2 * nsz, nsz)).cuda() for _ in range(3)]
-    for method, name in ((0, "4m"), (1, "3m")):
+    for method, name in ((0, "4m"), (1, "3m"), (2, "fused")):
         lw = xg.xgemm_zgemm_workbytes(nsz, nsz, nsz, method)
         zwork = torch.empty(lw, dtype=torch.uint8, device="cuda")
 
@@ -537,11 +575,11 @@ def sweep(torch, np, xg, si, args):
                 raise RuntimeError(rc)
 
         wall, dev = time_calls(torch, zistep, 10, 5)
-        own = flops if method == 0 else 6.0 * nsz ** 3           # what the method itself computes: 4 or 3 real products
+        own = 6.0 * nsz ** 3 if method == 1 else flops           # what the method itself computes: 3 real products, or 4 (one launch when fused)
         print(json.dumps({"shape": f"zgemm interleaved ({name}) NN {nsz}^3", "ms": round(dev * 1e3, 4),
                           "GFLOP/s": round(own / dev / 1e9, 1),
                           "frac_of_mfma_peak": round(own / dev / (PEAK_TFLOPS['f64'] * 1e12), 4),
-                          "flops_counted": "8mnk" if method == 0 else "6mnk (three real products)",
+                          "flops_counted": "6mnk (three real products)" if method == 1 else "8mnk",
                           "GFLOP/s_as_8mnk": round(flops / dev / 1e9, 1)}),
               file=sys.stderr, flush=True)
         del zwork

@@ -325,6 +325,30 @@ int xgemm_dgemm_static(char transa, char transb, int64_t m, int64_t n, int64_t k
                        double beta, double *C, int64_t ldc, void *stream);
 
 /*
+ * Packed operands (the explicit packing of Fig. 1 and Sec. 2.2, done once in device memory for operands
+ * that enter several products).  xgemm_*pack_a writes op(A) (m x k), xgemm_*pack_b writes op(B) (k x n) into a
+ * buffer of xgemm_pack_elems(m, k) resp. xgemm_pack_elems(n, k) elements, 16-byte aligned, in panels of 256 rows
+ * of op(A) (columns of op(B)), depth-major inside a panel:
+ *     element (i, p)  at  [(i / 256) * 256 * Kpad + p * 256 + i % 256],   Kpad = k rounded up to 32,
+ * zero beyond the matrix.  The transpose (N, T; C is T) and the leading dimension of the source are absorbed:
+ * xgemm_*gemm_packed computes  C := alpha op(A) op(B) + beta C  from the two buffers alone, with every slab of
+ * every tile a run of whole 16-byte vectors.  A packed operand may be used by any number of products; it must
+ * not overlap C.  Same element-wise result as xgemm_*gemm on the unpacked operands wherever both take the same
+ * tile variant (the sums run over k in the same order).
+ * Illegal-argument numbering: pack_a: transa 1, m 2, k 3, A 4, lda 5, Ap 6;  pack_b: transb 1, k 2, n 3, B 4,
+ * ldb 5, Bp 6;  gemm_packed: m 1, n 2, k 3, Ap 5, Bp 6, C 8, ldc 9.  Positive: a HIP error.
+ */
+size_t xgemm_pack_elems(int64_t rows, int64_t k);
+int xgemm_dpack_a(char transa, int64_t m, int64_t k, const double *A, int64_t lda, double *Ap, void *stream);
+int xgemm_dpack_b(char transb, int64_t k, int64_t n, const double *B, int64_t ldb, double *Bp, void *stream);
+int xgemm_spack_a(char transa, int64_t m, int64_t k, const float *A, int64_t lda, float *Ap, void *stream);
+int xgemm_spack_b(char transb, int64_t k, int64_t n, const float *B, int64_t ldb, float *Bp, void *stream);
+int xgemm_dgemm_packed(int64_t m, int64_t n, int64_t k, double alpha, const double *Ap, const double *Bp, double beta,
+                       double *C, int64_t ldc, void *stream);
+int xgemm_sgemm_packed(int64_t m, int64_t n, int64_t k, float alpha, const float *Ap, const float *Bp, float beta,
+                       float *C, int64_t ldc, void *stream);
+
+/*
  * Double-precision complex GEMM on interleaved storage (the BLAS layout: element
  * (i, j) of X is the pair X[2*(i + j*ldx)], X[2*(i + j*ldx) + 1]; leading
  * dimensions count complex elements; A, B, C 16-byte aligned), built from the
@@ -339,8 +363,17 @@ int xgemm_dgemm_static(char transa, char transb, int64_t m, int64_t n, int64_t k
  *            T3 = (Ar + Ai)(Br + Bi), Pr = T1 - T2, Pi = T3 - T1 - T2: a quarter
  *            fewer flops, but the imaginary part is only accurate relative to
  *            (|Ar| + |Ai|)(|Br| + |Bi|), i.e. to the magnitudes of both planes.
+ *   method 2 (fused): one real product written straight into C.  C as a real matrix has
+ *            twice the rows (re, im alternating); alpha op(A) is packed with every entry
+ *            x blown up to [[xr, -xi], [xi, xr]] (2m x 2k), op(B) with re, im alternating
+ *            along the depth (2k x n), both in the layout of xgemm_dpack_a / _b, and
+ *            xgemm_dgemm_packed(2m, n, 2k) adds their product to beta C (a complex beta
+ *            scales C in a pass of its own first).  8 m n k flops, the same sums of
+ *            magnitudes per plane as 4m, no planes and no pass over C after the product.
+ *            Needs 2 m, 2 k and 2 ldc within 2^31 - 1 (else -14).
  * work: device buffer, 16-byte aligned, lwork >= xgemm_zgemm_workbytes(m, n, k,
- * method) bytes (2 or 3 planes each of A, B and the product); contents undefined
+ * method) bytes (methods 0, 1: 2 or 3 planes each of A, B and the product; method 2:
+ * the two packed operands, xgemm_pack_elems(2m, 2k) + xgemm_pack_elems(n, 2k) doubles); contents undefined
  * afterwards; not needed when alpha == 0 or k == 0.  alpha, beta: host {re, im}.
  * Illegal-argument numbering: transa 1, transb 2, m 3, n 4, k 5, alpha 6, A 7,
  * lda 8, B 9, ldb 10, beta 11, C 12, ldc 13, method 14, work 15, lwork 16.

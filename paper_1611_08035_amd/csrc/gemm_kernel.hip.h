@@ -125,7 +125,14 @@ template <typename T> struct GemmArgs {
     // kcut 1 sums over k in [0, d), kcut 2 over [d + kblk, k); 0: all of k.  `reverse` walks the
     // tile order backwards (deepest tiles first for kcut 1 along the rows).
     int kcut, kaxis, kblk, reverse;
+    // Packed operands (0: plain).  A packed op(A) is stored in panels of PACK_W rows, each panel a
+    // PACK_W x Kpad column-major block (element (i, p) at [(i / PACK_W) * a_panel + p * PACK_W + i % PACK_W],
+    // a_panel = PACK_W * Kpad, zero beyond the matrix), so that every slab of every tile is one run of
+    // memory whatever the transpose or leading dimension of the source was; the call then has
+    // lda = PACK_W and an MN-contiguous A.  The same for op(B)^T with b_panel.
+    int64_t a_panel, b_panel;
 };
+constexpr int PACK_W = 256;
 
 // ---------------------------------------------------------------------------
 // Staging of one MT x KT slab of an operand from global memory into LDS in
@@ -543,8 +550,10 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     }
 
     // slab origins at depth k_begin
-    const T *pa = AK ? g.A + (int64_t)m0 * g.lda + k_begin : g.A + m0 + (int64_t)k_begin * g.lda;
-    const T *pb = BK ? g.B + (int64_t)n0 * g.ldb + k_begin : g.B + (int64_t)n0 + (int64_t)k_begin * g.ldb;
+    const int64_t am0 = g.a_panel ? (int64_t)(m0 / PACK_W) * g.a_panel + m0 % PACK_W : (int64_t)m0;   // where row m0 starts
+    const int64_t bn0 = g.b_panel ? (int64_t)(n0 / PACK_W) * g.b_panel + n0 % PACK_W : (int64_t)n0;
+    const T *pa = AK ? g.A + (int64_t)m0 * g.lda + k_begin : g.A + am0 + (int64_t)k_begin * g.lda;
+    const T *pb = BK ? g.B + (int64_t)n0 * g.ldb + k_begin : g.B + bn0 + (int64_t)k_begin * g.ldb;
     const int64_t step_a = AK ? (int64_t)KT : (int64_t)KT * g.lda;
     const int64_t step_b = BK ? (int64_t)KT : (int64_t)KT * g.ldb;
 

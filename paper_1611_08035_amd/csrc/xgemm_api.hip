@@ -214,7 +214,10 @@ void *static_scratch(hipError_t *err) {
 template <typename T>
 int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const T *A, int64_t lda,
               const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream, int uplo = 0, void *work = nullptr,
-              size_t lwork = 0, int kcut = 0, int kaxis = 0, int kblk = 0, bool static_ws = false) {
+              size_t lwork = 0, int kcut = 0, int kaxis = 0, int kblk = 0, bool static_ws = false,
+              int64_t a_panel = 0, int64_t b_panel = 0) {
+    // a_panel, b_panel != 0: A and B are packed operands (GemmArgs::a_panel) whose sizes the caller has checked;
+    // then ta = N, tb = T, lda = ldb = PACK_W and k is a multiple of every slab depth
     t_last_kernel = "none";
     t_last_split = 1;
     if (!is_n(ta) && !is_t(ta)) return -1;
@@ -225,9 +228,9 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     const bool ab_read = (alpha != T(0)) && m > 0 && n > 0 && k > 0;
     const int64_t rows_a = is_n(ta) ? m : k, rows_b = is_n(tb) ? k : n;
     if (ab_read && !A) return -7;
-    if (lda < max64(1, rows_a)) return -8;
+    if (!a_panel && lda < max64(1, rows_a)) return -8;
     if (ab_read && !B) return -9;
-    if (ldb < max64(1, rows_b)) return -10;
+    if (!b_panel && ldb < max64(1, rows_b)) return -10;
     if (m > 0 && n > 0 && !C) return -12;
     if (ldc < max64(1, m)) return -13;
 
@@ -251,6 +254,8 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     g.alpha = alpha; g.beta = beta;
     g.ntm = g.ntn = 0;
     g.uplo = uplo;
+    g.a_panel = a_panel;
+    g.b_panel = b_panel;
     // The buffer-load path addresses one slab (at most 256 rows or columns of
     // the stored operand) with 31-bit byte offsets; beyond that the element-wise
     // fallback runs.  16-byte loads of 4- or 8-byte aligned data are legal for
@@ -324,6 +329,26 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
         return (int)tab[plan.vq].launch(is_t(ta), is_n(tb), fast, g, st);
     }
     return (int)tab[v].launch(is_t(ta), is_n(tb), fast, g, st);
+}
+
+// C := alpha op(A) op(B) + beta C with both operands packed by xgemm_*pack_a / xgemm_*pack_b: the kernels of the
+// N, T form with the tile origins taken from the panel layout.  The packed depth is a multiple of 32 and zero
+// beyond k, so the product runs over the padded depth and never meets a ragged slab.
+template <typename T>
+int gemm_packed_impl(int64_t m, int64_t n, int64_t k, T alpha, const T *Ap, const T *Bp, T beta, T *C, int64_t ldc,
+                     void *stream) {
+    if (m < 0 || m > DIM_MAX) return -1;
+    if (n < 0 || n > DIM_MAX) return -2;
+    if (k < 0 || k > DIM_MAX) return -3;
+    const bool ab_read = alpha != T(0) && m > 0 && n > 0 && k > 0;
+    if (ab_read && !Ap) return -5;
+    if (ab_read && !Bp) return -6;
+    if (m > 0 && n > 0 && !C) return -8;
+    if (ldc < max64(1, m)) return -9;
+    const int64_t kpad = (k + 31) / 32 * 32;
+    if (kpad > DIM_MAX) return -3;
+    return gemm_impl<T>('N', 'T', m, n, kpad, alpha, Ap, PACK_W, Bp, PACK_W, beta, C, ldc, stream, 0, nullptr, 0, 0, 0, 0,
+                        false, (int64_t)PACK_W * kpad, (int64_t)PACK_W * kpad);
 }
 
 // C := alpha op(A) op(A)^T + beta C on one triangle: the GEMM kernel with B = A,
@@ -562,6 +587,16 @@ extern "C" {
 int xgemm_dgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double *A,
                 int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream) {
     return gemm_impl<double>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+int xgemm_dgemm_packed(int64_t m, int64_t n, int64_t k, double alpha, const double *Ap, const double *Bp, double beta,
+                       double *C, int64_t ldc, void *stream) {
+    return gemm_packed_impl<double>(m, n, k, alpha, Ap, Bp, beta, C, ldc, stream);
+}
+
+int xgemm_sgemm_packed(int64_t m, int64_t n, int64_t k, float alpha, const float *Ap, const float *Bp, float beta,
+                       float *C, int64_t ldc, void *stream) {
+    return gemm_packed_impl<float>(m, n, k, alpha, Ap, Bp, beta, C, ldc, stream);
 }
 
 int xgemm_sgemm(char transa, char transb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,

@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_model_enumerate", "xgemm_model_efficiency", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_release_thread_resources",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_model_enumerate", "xgemm_model_efficiency", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_pack_elems", "xgemm_dpack_a", "xgemm_dpack_b", "xgemm_spack_a", "xgemm_spack_b", "xgemm_dgemm_packed", "xgemm_sgemm_packed", "xgemm_release_thread_resources",
 ]
 
 
@@ -83,6 +83,16 @@ def lib():
         f = getattr(L, f"xgemm_{pre}getrf")
         f.restype = ctypes.c_int
         f.argtypes = [_i64, _i64, _p, _i64, _p, _p, _p]
+    L.xgemm_pack_elems.restype = ctypes.c_size_t
+    L.xgemm_pack_elems.argtypes = [_i64, _i64]
+    for nm in ("xgemm_dpack_a", "xgemm_dpack_b", "xgemm_spack_a", "xgemm_spack_b"):
+        f = getattr(L, nm)
+        f.restype = ctypes.c_int
+        f.argtypes = [_c, _i64, _i64, _p, _i64, _p, _p]
+    for nm, ft in (("xgemm_dgemm_packed", ctypes.c_double), ("xgemm_sgemm_packed", ctypes.c_float)):
+        f = getattr(L, nm)
+        f.restype = ctypes.c_int
+        f.argtypes = [_i64, _i64, _i64, ft, _p, _p, ft, _p, _i64, _p]
     L.xgemm_force_getrf_panel.restype = ctypes.c_int
     L.xgemm_force_getrf_panel.argtypes = [ctypes.c_int64]
     for pre, sc in (("d", ctypes.c_double), ("s", ctypes.c_float)):
@@ -224,6 +234,31 @@ def xgemm_dgetrf(m, n, A, lda, ipiv, info, stream=None) -> int:
 
 def xgemm_sgetrf(m, n, A, lda, ipiv, info, stream=None) -> int:
     return int(lib().xgemm_sgetrf(m, n, _ptr(A), lda, _ptr(ipiv), _ptr(info), _stream(stream)))
+
+
+def xgemm_pack_elems(rows, k) -> int:
+    return int(lib().xgemm_pack_elems(int(rows), int(k)))
+
+
+def _pack_op(name):
+    def call(trans, d1, d2, X, ld, Xp, stream=None) -> int:
+        return int(getattr(lib(), name)(_ch(trans), d1, d2, _ptr(X), ld, _ptr(Xp), _stream(stream)))
+    call.__name__ = name
+    return call
+
+
+xgemm_dpack_a = _pack_op("xgemm_dpack_a")
+xgemm_dpack_b = _pack_op("xgemm_dpack_b")
+xgemm_spack_a = _pack_op("xgemm_spack_a")
+xgemm_spack_b = _pack_op("xgemm_spack_b")
+
+
+def xgemm_dgemm_packed(m, n, k, alpha, Ap, Bp, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_dgemm_packed(m, n, k, alpha, _ptr(Ap), _ptr(Bp), beta, _ptr(C), ldc, _stream(stream)))
+
+
+def xgemm_sgemm_packed(m, n, k, alpha, Ap, Bp, beta, C, ldc, stream=None) -> int:
+    return int(lib().xgemm_sgemm_packed(m, n, k, alpha, _ptr(Ap), _ptr(Bp), beta, _ptr(C), ldc, _stream(stream)))
 
 
 def xgemm_force_getrf_panel(width) -> int:

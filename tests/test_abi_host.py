@@ -291,7 +291,12 @@ def test_interleaved_zgemm_illegal_arguments_and_work_size():
     assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, None, P, 2, **ok) == -11
     assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), None, 2, **ok) == -12
     assert z("N", "N", 3, 2, 2, (1, 0), P, 3, P, 2, (0, 0), P, 2, **ok) == -13
-    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, method=2, **ok) == -14
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, method=3, **ok) == -14
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, method=-1, **ok) == -14
+    # the fused form packs a 2m x 2k and an n x 2k operand
+    assert xg.xgemm_zgemm_workbytes(5, 7, 3, 2) == 8 * (xg.xgemm_pack_elems(10, 6) + xg.xgemm_pack_elems(7, 6)) == 8 * 2 * 256 * 32
+    assert xg.xgemm_zgemm_workbytes(5, 7, 0, 2) == 0
+    assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, method=2, work=P, lwork=8 * 2 * 256 * 32 - 1) == -16
     assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, work=None, lwork=big) == -15
     assert z("N", "N", 2, 2, 2, (1, 0), P, 2, P, 2, (0, 0), P, 2, work=P, lwork=8 * 2 * 12 - 1) == -16
     assert z("N", "N", 0, 2, 2, (1, 0), None, 1, None, 2, (0, 0), None, 1) == 0
@@ -304,3 +309,31 @@ def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(mod, "_LIBPATH", "/nonexistent/libxgemm.so")
     with pytest.raises(mod.XgemmError):
         mod.lib()
+
+
+def test_pack_argument_checks_and_sizes():
+    """Host side of the packed-operand calls: sizes and the illegal-argument numbers of include/xgemm.h."""
+    assert xg.xgemm_pack_elems(1, 1) == 256 * 32 and xg.xgemm_pack_elems(257, 33) == 512 * 64
+    assert xg.xgemm_pack_elems(0, 5) == 0 and xg.xgemm_pack_elems(-1, 5) == 0
+    one = 16      # a non-null address that is never dereferenced: every call below fails its checks first
+    for f in (xg.xgemm_dpack_a, xg.xgemm_spack_a):
+        assert f("X", 4, 4, one, 4, one, stream=0) == -1
+        assert f("N", -1, 4, one, 4, one, stream=0) == -2
+        assert f("N", 4, -1, one, 4, one, stream=0) == -3
+        assert f("N", 4, 4, None, 4, one, stream=0) == -4
+        assert f("N", 4, 6, one, 3, one, stream=0) == -5      # stored 4 x 6: lda >= 4
+        assert f("T", 4, 6, one, 5, one, stream=0) == -5      # stored 6 x 4: lda >= 6
+        assert f("N", 4, 4, one, 4, None, stream=0) == -6
+    for f in (xg.xgemm_dpack_b, xg.xgemm_spack_b):
+        assert f("N", 6, 4, one, 5, one, stream=0) == -5      # stored 6 x 4 (k x n): ldb >= 6
+        assert f("T", 6, 4, one, 3, one, stream=0) == -5      # stored 4 x 6 (n x k): ldb >= 4
+        assert f("N", 6, 4, one, 6, None, stream=0) == -6
+    for f in (xg.xgemm_dgemm_packed, xg.xgemm_sgemm_packed):
+        assert f(-1, 2, 2, 1.0, one, one, 0.0, one, 2, stream=0) == -1
+        assert f(2, -1, 2, 1.0, one, one, 0.0, one, 2, stream=0) == -2
+        assert f(2, 2, -1, 1.0, one, one, 0.0, one, 2, stream=0) == -3
+        assert f(2, 2, 2, 1.0, None, one, 0.0, one, 2, stream=0) == -5
+        assert f(2, 2, 2, 1.0, one, None, 0.0, one, 2, stream=0) == -6
+        assert f(2, 2, 2, 1.0, one, one, 0.0, None, 2, stream=0) == -8
+        assert f(2, 2, 2, 1.0, one, one, 0.0, one, 1, stream=0) == -9
+        assert f(0, 2, 2, 1.0, None, None, 0.0, None, 1, stream=0) == 0

@@ -3,7 +3,9 @@ oracle.  The oracle works on split planes; the interleaved operands are taken
 apart with numpy slicing (layout only) before it is called.
 
 Bounds per plane, u = 2^-53: 4m: 8 k u G_plane, G_plane the sum of magnitudes of
-the real products entering that plane (two chained real GEMMs of depth k).
+the real products entering that plane (two chained real GEMMs of depth k).  The fused
+form (method 2) is one real GEMM of depth 2k over the same products (alpha folded into
+the expanded A, which costs two roundings per entry): the same bound.
 3m: the imaginary part is T3 - T1 - T2 with T3 = (Ar + Ai)(Br + Bi), whose
 magnitudes are those of both planes together: 8 k u (G_re + G_im) for both."""
 import itertools
@@ -46,7 +48,7 @@ def run(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, method):
     return out[:, 0::2], out[:, 1::2]
 
 
-@pytest.mark.parametrize("method", [0, 1])
+@pytest.mark.parametrize("method", [0, 1, 2])
 @pytest.mark.parametrize("ta,tb", list(itertools.product("NTC", "NTC")))
 def test_small_full_check(ta, tb, method):
     rng = si.rng_for(150, method)
@@ -59,13 +61,13 @@ def test_small_full_check(ta, tb, method):
         info, Rr, Ri, Gr, Gi = oracle.zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc)
         assert info == 0
         for O, R, G, P in ((Or, Rr, Gr, Cr), (Oi, Ri, Gi, Ci)):
-            Gb = G if method == 0 else Gr + Gi
+            Gb = Gr + Gi if method == 1 else G
             nviol, ratio = oracle.bound_violations(O[:, :m], R, Gb, k, oracle.U64, factor=8.0)
             assert nviol == 0, (ta, tb, method, alpha, beta, ratio)
             assert np.array_equal(O[:, m:], P[:, m:], equal_nan=True), "padding of C was written"
 
 
-@pytest.mark.parametrize("method", [0, 1])
+@pytest.mark.parametrize("method", [0, 1, 2])
 def test_gaussian_integers_bit_exact(method):
     rng = si.rng_for(151, method)
     m, n, k = 200, 260, 129
@@ -100,7 +102,7 @@ def test_scalar_paths():
     assert np.array_equal(dC.cpu().numpy(), C, equal_nan=True)
 
 
-@pytest.mark.parametrize("method", [0, 1])
+@pytest.mark.parametrize("method", [0, 1, 2])
 def test_4096_sampled(method):
     nsz = 4096
     rng = si.rng_for(153, method)
@@ -112,6 +114,26 @@ def test_4096_sampled(method):
                                                       Cr, Ci, ldc, I, J)
     assert info == 0
     for O, r, g in ((Or, rr, gr), (Oi, ri, gi)):
-        gb = g if method == 0 else gr + gi
+        gb = gr + gi if method == 1 else g
         nviol, ratio = oracle.bound_violations(O[J, I], r, gb, nsz, oracle.U64, factor=8.0)
         assert nviol == 0, ratio
+
+
+def test_fused_ragged_shapes_and_complex_beta():
+    """Method 2 on shapes that leave partial panels and slabs in both packed operands, with a complex beta
+    (the pass over C of its own) and with beta = 0 on a C full of NaN."""
+    rng = si.rng_for(154, 0)
+    for (m, n, k), (ta, tb), (alpha, beta) in zip([(129, 257, 17), (1, 1, 1), (300, 70, 130), (64, 513, 33)],
+                                                  [("N", "N"), ("C", "C"), ("T", "N"), ("N", "C")],
+                                                  [((1.0, 0.0), (0.0, 0.0)), ((0.5, -2.0), (0.25, 1.5)),
+                                                   ((-1.0, 0.0), (1.0, 0.0)), ((0.0, 1.0), (0.0, -1.0))]):
+        (A, Ar, Ai), lda, (B, Br, Bi), ldb, (C, Cr, Ci), ldc = operands(rng, ta, tb, m, n, k, (1, 0, 3))
+        if beta == (0.0, 0.0):
+            C[:, : 2 * m] = np.nan
+        Or, Oi = run(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, 2)
+        info, Rr, Ri, Gr, Gi = oracle.zgemm_split_ext(ta, tb, m, n, k, alpha, Ar, Ai, lda, Br, Bi, ldb, beta, Cr, Ci, ldc)
+        assert info == 0
+        for O, R, G, P in ((Or, Rr, Gr, Cr), (Oi, Ri, Gi, Ci)):
+            nviol, ratio = oracle.bound_violations(O[:, :m], R, G, k, oracle.U64, factor=8.0)
+            assert nviol == 0, (m, n, k, ta, tb, ratio)
+            assert np.array_equal(O[:, m:], P[:, m:], equal_nan=True), "padding of C was written"
