@@ -436,8 +436,13 @@ template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC
     static constexpr int TM = WT_M / M::MI, TN = WT_N / M::MI;
     static_assert(WT_M % M::MI == 0 && WT_N % M::MI == 0, "wave tile must be whole MFMA tiles");
     static_assert(KT % M::KI == 0, "slab depth must be whole MFMA depths");
-    // LDS row strides.  A slab row is read 16 (fp64) / 32 (fp32) consecutive
-    // elements at a time, which touches every bank once for any stride.  The
+    // LDS row strides.  A fragment read takes 16-byte pieces of four slab rows at
+    // once (the four depth steps of a matrix instruction), each row a run of 16
+    // (fp64) / 32 (fp32) consecutive elements; with the row stride a multiple of
+    // 256 bytes the four runs start on the same bank, and the counters show what
+    // that costs: bank-conflict cycles are 20 % of the LDS-active cycles of the
+    // fp64 N,N product, half a cycle per matrix instruction of 64, all of it in
+    // the shadow of the matrix pipe.  The
     // stride matters for the writes of K-contiguous slabs: the KT/V lanes that
     // hold one row-vector mn write V rows apart, and with a power-of-two stride
     // they would all hit the same banks.  With W = 128 B / sizeof(T) elements per
