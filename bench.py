@@ -407,6 +407,7 @@ def sweep(torch, np, xg, si, args):
     extra = [("syrk", "d", 8192, 8192, 8192), ("syrk", "d", 16384, 16384, 16384), ("syrk", "d", 4096, 4096, 4096),
              ("syrk", "s", 8192, 8192, 8192), ("syrk", "s", 16384, 16384, 16384),
              ("gemm", "d", 3328, 2560, 2048), ("gemm", "d", 3072, 3072, 3072), ("gemm", "d", 512, 512, 8192),
+             ("gemm", "d", 1024, 1024, 1024), ("gemm", "d", 2048, 2048, 2048),
              ("gemm", "s", 3328, 2560, 2048)]
     for op, prec, m, n, k in extra:
         if not (want(f"{prec}{op} {m}x{n}x{k}") or want(f"{prec}{op}_ws {m}x{n}x{k}")):
