@@ -18,10 +18,10 @@
 //   register budget (Sec. 5.4, the       accumulators + two operand fragment sets +
 //     N_updates equation), no spills       in-flight global loads <= 256 VGPRs so two
 //                                          waves share a SIMD; zero scratch
-//   software pipelining: ramp-up /       global loads of slab t+1 are issued before
-//     steady state / flush (Sec. 1,        the MFMAs of slab t and written to the
-//     Sec. 5.5)                            other LDS buffer after them; one barrier
-//                                          per slab
+//   software pipelining: ramp-up /       global loads of slab t+1 (t+2 for the small
+//     steady state / flush (Sec. 1,        tiles, TileCfg::PF) are issued before the
+//     Sec. 5.5)                            MFMAs of slab t and written to the other
+//                                          LDS buffer after them; one barrier per slab
 //   C += c_reg (Fig. "code skeleton")    epilogue C = alpha*acc + beta*C, predicated
 //                                          on the ragged edges
 //
@@ -428,9 +428,13 @@ static __host__ __device__ __forceinline__ TilePos tile_of_lin(int lin, int ntm,
 // ---------------------------------------------------------------------------
 // Tile configuration.
 // ---------------------------------------------------------------------------
-template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC_> struct TileCfg {
+// PF_: slabs between the global loads of a slab and its use (1: loaded while the slab before it is multiplied;
+// 2: one slab earlier still, in a second set of staging registers, for variants whose slab is shorter than a
+// memory round trip).
+template <typename T, int MT_M_, int MT_N_, int KT_, int WGM_, int WGN_, int OCC_, int PF_ = 1> struct TileCfg {
     using M = Mfma<T>;
-    static constexpr int MT_M = MT_M_, MT_N = MT_N_, KT = KT_, WGM = WGM_, WGN = WGN_, OCC = OCC_;
+    static constexpr int MT_M = MT_M_, MT_N = MT_N_, KT = KT_, WGM = WGM_, WGN = WGN_, OCC = OCC_, PF = PF_;
+    static_assert(PF == 1 || PF == 2, "prefetch distance in slabs");
     static constexpr int NT = WGM * WGN * 64;
     static constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
     static constexpr int TM = WT_M / M::MI, TN = WT_N / M::MI;
@@ -577,8 +581,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
 #pragma unroll
             for (int r = 0; r < M::NR; ++r) acc[j][i][r] = T(0);
 
-    typename StA::vec_t ra[StA::NV];
-    typename StB::vec_t rb[StB::NV];
+    constexpr int PF = Cfg::PF;
+    typename StA::vec_t ra[PF][StA::NV];      // staging registers: set s holds the slabs t with t % PF == s
+    typename StB::vec_t rb[PF][StB::NV];
     uint32_t offa[StA::NV], offb[StB::NV];
     StA::offsets(offa, g.lda, tid);
     StB::offsets(offb, g.ldb, tid);
@@ -599,26 +604,28 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
 
     const int nslab = (k_len + KT - 1) / KT;
 
-    auto fetch = [&](int t) {
+    // slab t (the next one in order: pa, pb walk along K) into its set of staging registers; `set` is t % PF as a
+    // constant at every call site
+    auto fetch = [&](int t, int set) {
         const int k_lim = k_len - t * KT;
         if (hot && k_lim >= KT + guard) {
-            StA::load_fast(ra, pa, offa);
-            StB::load_fast(rb, pb, offb);
+            StA::load_fast(ra[set], pa, offa);
+            StB::load_fast(rb[set], pb, offb);
         } else if (FAST) {
-            StA::load_edge(ra, pa, offa, tid, m_lim, k_lim);
-            StB::load_edge(rb, pb, offb, tid, n_lim, k_lim);
+            StA::load_edge(ra[set], pa, offa, tid, m_lim, k_lim);
+            StB::load_edge(rb[set], pb, offb, tid, n_lim, k_lim);
         } else {
-            StA::load_guarded(ra, pa, g.lda, tid, m_lim, k_lim);
-            StB::load_guarded(rb, pb, g.ldb, tid, n_lim, k_lim);
+            StA::load_guarded(ra[set], pa, g.lda, tid, m_lim, k_lim);
+            StB::load_guarded(rb[set], pb, g.ldb, tid, n_lim, k_lim);
         }
         pa += step_a;
         pb += step_b;
     };
     T *const stash_a = lds + StA::lds_origin(tid);
     T *const stash_b = lds + KT * SA + StB::lds_origin(tid);
-    auto stash = [&](int buf) {
-        StA::store(ra, stash_a + buf * BUF);
-        StB::store(rb, stash_b + buf * BUF);
+    auto stash = [&](int buf, int set) {
+        StA::store(ra[set], stash_a + buf * BUF);
+        StB::store(rb[set], stash_b + buf * BUF);
     };
 
     // Operand fragments are double-buffered in registers: the LDS reads of
@@ -660,8 +667,11 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     };
 
     // ramp-up: slab 0 into LDS buffer 0, first fragments into registers
-    fetch(0);
-    stash(0);
+    fetch(0, 0);
+    stash(0, 0);
+    if constexpr (PF == 2) {
+        if (nslab > 1) fetch(1, 1);
+    }
     __syncthreads();
     load_frags(0, 0, 0);
 
@@ -671,15 +681,21 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     // workgroup synchronises; the last MFMA group of slab t is issued AFTER the
     // barrier, together with the first fragment reads of slab t+1, so the
     // post-barrier LDS latency is covered by a full group of MFMAs.
+    // (the LDS buffer of slab t is t & 1 = cur; with PF == 2 that is also its set of staging registers, and the
+    // slab asked for here is t + 2, into the set that slab t has left)
     auto slab = [&](int t, int cur) {
         const bool more = (t + 1 < nslab);
-        if (more) fetch(t + 1);
+        if constexpr (PF == 2) {
+            if (t + 2 < nslab) fetch(t + 2, cur);
+        } else {
+            if (more) fetch(t + 1, 0);
+        }
 #pragma unroll
         for (int grp = 0; grp + 1 < NG; ++grp) {
             load_frags(cur, grp + 1, (grp + 1) & 1);
             mma_group(grp & 1);
         }
-        if (more) stash(cur ^ 1);
+        if (more) stash(cur ^ 1, PF == 2 ? cur ^ 1 : 0);
         __syncthreads();
         if (more) load_frags(cur ^ 1, 0, 0);
         mma_group((NG - 1) & 1);
@@ -694,8 +710,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     constexpr int N_LD = StA::NV + StB::NV;              // global loads per slab
     constexpr int N_ST = (AK ? StA::NV * StA::V : StA::NV) + (BK ? StB::NV * StB::V : StB::NV);   // LDS writes (upper bound)
     auto slab_hot = [&](int cur) {
-        StA::load_fast(ra, pa, offa);
-        StB::load_fast(rb, pb, offb);
+        StA::load_fast(ra[PF == 2 ? cur : 0], pa, offa);      // slab t + PF
+        StB::load_fast(rb[PF == 2 ? cur : 0], pb, offb);
         pa += step_a;
         pb += step_b;
 #pragma unroll
@@ -703,7 +719,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
             load_frags(cur, grp + 1, (grp + 1) & 1);
             mma_group(grp & 1);
         }
-        stash(cur ^ 1);
+        stash(cur ^ 1, PF == 2 ? cur ^ 1 : 0);
         // schedule of the region that ends at the barrier: global loads under
         // the first MFMAs, each group's fragment reads under its predecessor,
         // LDS writes under the last MFMAs before the barrier
@@ -732,11 +748,11 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
     int t = 0;
     if (hot) {
         const int nfull = (k_len - guard) / KT;   // slabs 0..nfull-1 are full (and, with a straddle, not the last column)
-        for (; t + 2 < nfull; t += 2) {
+        for (; t + 1 + PF < nfull; t += 2) {
             slab_hot(0);
             slab_hot(1);
         }
-        if (t + 1 < nfull) {   // one more slab whose successor is full
+        if (t + PF < nfull) {   // one more slab whose successor (second successor) is full
             slab_hot(0);
             ++t;
         }

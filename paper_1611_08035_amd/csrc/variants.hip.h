@@ -13,6 +13,7 @@ template <typename T> struct VariantEntry {
     int kt, wgm, wgn;   // slab depth, waves along m and n
     int wgs_per_cu;   // workgroups resident on one CU (register and LDS budget of the variant)
     float eff;        // fraction of the MFMA peak the variant sustains with its CU fully occupied (measured)
+    float lone;       // what of that is left when a CU holds a single workgroup of the variant (measured)
     bool has_split;   // kernels with the split tail (GemmArgs::nsplit > 1) are built for this variant
     // launch(transA is K-contiguous, transB is K-contiguous, fast path allowed, args, stream)
     hipError_t (*launch)(bool ak, bool bk, bool fast, const GemmArgs<T> &g, hipStream_t st);

@@ -62,8 +62,6 @@ constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece m
 // Constants of the cost model below, measured on MI355X (times in microseconds).
 constexpr double CLOCK_GHZ = 2.4;
 constexpr double T_ROUND0 = 10.0;        // ramp-up and flush of a workgroup that nothing else hides
-constexpr double LONE_EFF = 0.95;        // a CU holding one workgroup, relative to a full one
-constexpr double LONE_EFF_SINGLE = 0.4;  // the same for a variant whose waves hold a single fp64 accumulator tile
 constexpr double PART_EFF = 0.96;        // a CU holding more than one but fewer than it has room for
 constexpr double T_FLUSH0 = 2.0;         // per round of workgroups: what of their ramp-up and flush the others do not hide,
 constexpr double T_FLUSH_KIB = 0.13;     //   T_FLUSH0 + T_FLUSH_KIB * (KiB of the C tile) / (workgroups per CU)
@@ -91,7 +89,7 @@ struct Plan {
 // tiles of a variant run in rounds of (CUs x workgroups per CU); a full round
 // costs wgs * t(k); the last, partly filled round costs occ * t(k) with occ
 // workgroups per CU (a lone workgroup has nobody to hide its stalls behind:
-// LONE_EFF; more than one but fewer than fit: PART_EFF).  Every launch pays one
+// the variant's `lone` factor; more than one but fewer than fit: PART_EFF).  Every launch pays one
 // ramp-up (at its start) and one flush (at its end) that nothing hides, T_ROUND0
 // together, whether its last round is full or not.  With a workspace the rem
 // tiles of that round may instead be cut into S <= slots / rem pieces of depth
@@ -124,11 +122,10 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
         // updates: 10.5 us per round of 128x128 tiles at k = 256, 3.9 at k = 1024)
         const double t_flush = (T_FLUSH0 + T_FLUSH_KIB * (tile_bytes / 1024.0) / (double)e.wgs_per_cu) *
                                (k < 256 ? 1.0 : 256.0 / (double)k);
-        // a wave with a single fp64 accumulator tile issues each matrix instruction only when the one before
-        // has finished (95 cycles against 64) and waits for every fragment read; alone on its SIMD nothing
-        // fills those gaps (measured: 0.31 of peak alone against 0.78 with four workgroups on the CU)
-        const bool single_tile = sizeof(T) == 8 && e.mt_m / e.wgm == 16 && e.mt_n / e.wgn == 16;
-        const double lone_eff = single_tile ? LONE_EFF_SINGLE : LONE_EFF;
+        // a workgroup alone on its CU has nobody to hide its barriers and memory round trips behind; how much that
+        // costs depends on the variant (least for the large tiles, most for the tile of one matrix instruction per
+        // wave, which also waits for each instruction before it issues the next) and is measured per variant
+        const double lone_eff = e.lone;
         auto t_tail = [&](int64_t units, double depth) {
             const int64_t occ = (units + cus - 1) / cus;
             return t_flush + (double)occ * t_tile(depth) / (occ == 1 ? lone_eff : occ < e.wgs_per_cu ? PART_EFF : 1.0);
@@ -145,9 +142,8 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
                 const int64_t occ = (4 * rem + cus - 1) / cus;
                 const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * planner_eff(tab[w]));
                 const double drain = DRAIN_FRAC * e.wgs_per_cu * t_tile((double)k);
-                const bool single_w = sizeof(T) == 8 && tab[w].mt_m / tab[w].wgm == 16 && tab[w].mt_n / tab[w].wgn == 16;
                 const double c = rounds + T_LAUNCH + T_ROUND0 + (drain < T_DRAIN_MAX ? drain : T_DRAIN_MAX) +
-                                 (double)occ * tq / (occ == 1 ? (single_w ? LONE_EFF_SINGLE : LONE_EFF)
+                                 (double)occ * tq / (occ == 1 ? (double)tab[w].lone
                                                               : occ < tab[w].wgs_per_cu ? PART_EFF : 1.0);
                 if (c < cost || t_forced_split == 1) { cost = c; p.ndp = full * slots; p.vq = w; }
                 break;
