@@ -51,6 +51,20 @@ int num_cus() {
     return cus;
 }
 
+// Engine clock of the current device in GHz as the runtime reports it (2.4 on MI355X), read once per device;
+// 2.4 where there is no device to ask (the planner is also called on hosts without one).
+double clock_ghz() {
+    constexpr int MAX_DEV = 64;
+    static std::atomic<int> cached[MAX_DEV];          // kHz; 0: not read yet
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return 2.4;
+    if ((khz = cached[dev].load(std::memory_order_relaxed)) <= 0) {
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess || khz < 500000 || khz > 5000000) return 2.4;
+        cached[dev].store(khz, std::memory_order_relaxed);
+    }
+    return khz * 1e-6;
+}
+
 // Workspace of the *_ws entry points: arrival counters, then partial tiles.
 constexpr size_t WS_CNT_BYTES = 8192;                       // 2048 counters
 constexpr size_t WS_PART_BYTES = size_t(64) << 20;          // 512 tiles of 128 KiB
@@ -60,7 +74,6 @@ constexpr int SPLIT_MAX = 32;                               // pieces per tile
 constexpr int SPLIT_MIN_SLABS = 4;                          // K slabs a piece must keep
 
 // Constants of the cost model below, measured on MI355X (times in microseconds).
-constexpr double CLOCK_GHZ = 2.4;
 constexpr double T_ROUND0 = 10.0;        // ramp-up and flush of a workgroup that nothing else hides
 constexpr double PART_EFF = 0.96;        // a CU holding more than one but fewer than it has room for
 constexpr double T_FLUSH0 = 2.0;         // per round of workgroups: what of their ramp-up and flush the others do not hide,
@@ -102,7 +115,7 @@ template <typename T>
 Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> *tab, int nv, bool fast,
                size_t lwork) {
     const int64_t cus = num_cus();
-    const double cu_flops_per_us = (sizeof(T) == 8 ? 32.0 : 64.0) * 4.0 * CLOCK_GHZ * 1e3;   // flop / us
+    const double cu_flops_per_us = (sizeof(T) == 8 ? 32.0 : 64.0) * 4.0 * clock_ghz() * 1e3;   // flop / us
     Plan best{0, 1, 0, -1};
     double best_cost = 0.0;
     const bool forced_v = t_forced_variant >= 0 && t_forced_variant < nv;
