@@ -81,6 +81,7 @@ constexpr double T_FLUSH_KIB = 0.13;     //   T_FLUSH0 + T_FLUSH_KIB * (KiB of t
 constexpr double REDUCE_GBS = 80.0;      // rate at which one workgroup reads partial tiles back
 constexpr double PART_TBS = 6.0;         // rate at which all partial tiles are written and read
 constexpr double T_SPLIT0 = 2.0;         // arrival counting
+constexpr double B_HALF_LINE = 0.86;     // see make_plan
 constexpr double T_LAUNCH = 4.0;         // a second launch on the same stream
 constexpr double DRAIN_FRAC = 0.25;      // ... which starts only when the first has drained: the workgroups of its last round end
 constexpr double T_DRAIN_MAX = 60.0;     // spread over about this fraction of that round's time, up to this much (measured:
@@ -113,7 +114,7 @@ struct Plan {
 // workgroup, at that variant's efficiency, plus the launch.
 template <typename T>
 Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> *tab, int nv, bool fast,
-               size_t lwork) {
+               size_t lwork, bool b_kcontig = false) {
     const int64_t cus = num_cus();
     const double cu_flops_per_us = (sizeof(T) == 8 ? 32.0 : 64.0) * 4.0 * clock_ghz() * 1e3;   // flop / us
     Plan best{0, 1, 0, -1};
@@ -128,7 +129,14 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
         const double area = (double)e.mt_m * (double)e.mt_n;
         const double tile_bytes = area * sizeof(T);
         const int64_t full = tiles / slots, rem = tiles % slots;
-        const double eff_v = planner_eff(e);
+        double eff_v = planner_eff(e);
+        // fp32, op(B) K-contiguous, 128x128 tile with slabs of depth 16: a slab takes half a cache line from each
+        // of 128 rows of B, and whether the other half is still near when the next slab wants it depends on the
+        // size and on where the matrix lies: measured 0.73-0.95 of the variant's rate with nothing in between
+        // (4096, 4352, 4608, 5000 slow on one box, 4096 and 4608 on another; never below two full rounds of
+        // tiles).  From two rounds on the planner takes the low figure;
+        // the depth-32 tile, which takes whole lines, or the 256x128 tile then win where they should.
+        if (sizeof(T) == 4 && b_kcontig && e.mt_m == 128 && e.mt_n == 128 && e.kt == 16 && full >= 2) eff_v *= B_HALF_LINE;
         auto t_tile = [&](double depth) { return 2.0 * area * depth / (cu_flops_per_us * eff_v); };
         // per round: the read-modify-write of the C tiles is only partly hidden by the other workgroups of the
         // CU, the less so the larger the tile, the fewer of them and the shorter their K loops (fitted to rank-k
@@ -154,10 +162,14 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int uplo, const VariantEntry<T> 
                 const double qarea = (double)tab[w].mt_m * (double)tab[w].mt_n;
                 const int64_t occ = (4 * rem + cus - 1) / cus;
                 const double tq = 2.0 * qarea * (double)k / (cu_flops_per_us * planner_eff(tab[w]));
+                // The second launch starts as the first one drains: its quarter tiles take the CUs as the large tiles
+                // leave them and run beside the stragglers, so they neither pay a ramp-up of their own nor run alone;
+                // the tail costs the longer of the drain and the quarter tiles' own time at their full rate
+                // (measured at 3072^3: 100 us in fp64, 54 us in fp32).
                 const double drain = DRAIN_FRAC * e.wgs_per_cu * t_tile((double)k);
-                const double c = rounds + T_LAUNCH + T_ROUND0 + (drain < T_DRAIN_MAX ? drain : T_DRAIN_MAX) +
-                                 (double)occ * tq / (occ == 1 ? (double)tab[w].lone
-                                                              : occ < tab[w].wgs_per_cu ? PART_EFF : 1.0);
+                const double own = (double)occ * tq;
+                const double capped = drain < T_DRAIN_MAX ? drain : T_DRAIN_MAX;
+                const double c = rounds + T_LAUNCH + (capped > own ? capped : own);
                 if (c < cost || t_forced_split == 1) { cost = c; p.ndp = full * slots; p.vq = w; }
                 break;
             }
@@ -276,7 +288,7 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
     if (static_ws) {
         // What the same call would use of a full-size workspace must fit the static array; then the plan
         // below, made for the array's size, is that same plan.
-        const Plan full = make_plan<T>(m, n, k, uplo, tab, nv, fast, WS_CNT_BYTES + WS_PART_BYTES);
+        const Plan full = make_plan<T>(m, n, k, uplo, tab, nv, fast, WS_CNT_BYTES + WS_PART_BYTES, is_n(tb) && !b_panel);
         if (full.nsplit > 1) {
             const VariantEntry<T> &e = tab[full.v];
             const int64_t tiles = tile_count(uplo, (int)((m + e.mt_m - 1) / e.mt_m), (int)((n + e.mt_n - 1) / e.mt_n),
@@ -291,7 +303,7 @@ int gemm_impl(char ta, char tb, int64_t m, int64_t n, int64_t k, T alpha, const 
         lwork = XGEMM_STATIC_SCRATCH_BYTES;
     }
     if (!work || (reinterpret_cast<uintptr_t>(work) & 15u)) lwork = 0;
-    const Plan plan = make_plan<T>(m, n, k, uplo, tab, nv, fast, lwork);
+    const Plan plan = make_plan<T>(m, n, k, uplo, tab, nv, fast, lwork, is_n(tb) && !b_panel);
     int v = plan.v;
     if (!fast)   // the element-wise fallback exists for the 64x64 tile only
         for (int i = 0; i < nv; ++i)

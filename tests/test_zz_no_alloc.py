@@ -34,9 +34,10 @@ def test_static_scratch_entry_matches_workspace_entry_on_calls_in_a_row():
     xg.xgemm_force_variant(-1)
     xg.xgemm_force_split(-1)
     rng = si.rng_for(97, 0)
-    # (shape, expected to split): 3072^3 uses the whole array (4 pieces x 64 tail tiles x 128 KiB), the next
-    # calls are smaller and find the previous call's partial sums and counters in the array
-    cases = [(("N", "N", 3072, 3072, 3072), True), (("N", "T", 768, 768, 2048), True),
+    # (shape, expected to split): 3072 x 3072 x 1000 uses the whole array (4 pieces x 64 tail tiles x 128 KiB; at
+    # this depth the tail cannot go to quarter tiles instead), the next calls are smaller and find the previous
+    # call's partial sums and counters in the array
+    cases = [(("N", "N", 3072, 3072, 1000), True), (("N", "T", 768, 768, 2048), True),
              (("T", "N", 3328, 2560, 2048), True), (("N", "N", 515, 259, 4100), True),
              (("N", "N", 1024, 1024, 512), False), (("T", "T", 300, 275, 83), False)]
     for (ta, tb, m, n, k), splits in cases:
