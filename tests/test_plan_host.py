@@ -102,3 +102,16 @@ def test_forcing_and_errors():
     assert xg.xgemm_plan("d", 3, 8, 8, 8, 0) == -2
     assert xg.xgemm_plan("d", 0, 0, 8, 8, 0) == -3
     assert xg.xgemm_plan("d", 0, 8, 8, 0, 0) == -5
+
+
+def test_picks_that_measurement_corrected():
+    """Three picks the planner got wrong until its model was corrected against the forced variants (each of these
+    was 6-15 % behind the best variant): a round of lone workgroups is priced per variant, and a quartered tail
+    costs one launch plus the longer of the first launch's drain and its own time."""
+    # 1280^3: 100 tiles of 128 x 128 or 200 of 128 x 64 would leave CUs idle or alone; 400 tiles of 64 x 64 win
+    v, pieces, whole = xg.xgemm_plan("d", 0, 1280, 1280, 1280, 0)
+    assert name("d", v) == "d_64x64x16_w2x2" and pieces == 1 and whole == 400
+    # 3072^3: one full round of 128 x 128 tiles and 64 tiles as quarter tiles, in both precisions
+    for prec in "ds":
+        v, pieces, whole = xg.xgemm_plan(prec, 0, 3072, 3072, 3072, 0)
+        assert name(prec, v) == f"{prec}_128x128x16_w2x2" and pieces == 1 and whole == 512
