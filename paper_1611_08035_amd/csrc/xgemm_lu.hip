@@ -11,7 +11,9 @@
 // to LEAF columns is factored by ONE workgroup (getf2_kernel): the search for the pivot is a
 // reduction inside the workgroup, so nothing in the library ever waits for another workgroup,
 // and a leaf costs one launch, not one per column; it carries its interchanges through all
-// columns of its panel.  After a panel its interchanges are applied to the columns on both
+// columns of its panel.  Two leaves side by side run without a launch between them: the left one
+// also solves for the block row of U above the right one, the right one applies the left one's
+// update as it loads.  After a panel its interchanges are applied to the columns on both
 // sides of it (laswp_kernel), the block row of U comes from a triangular solve and the rest
 // of the matrix is updated by one product of depth PANEL.
 #include "../../include/xgemm.h"
@@ -173,7 +175,7 @@ __device__ __forceinline__ void swap_batch(SwapLds<T, G, NTHR> &L, T *col, int t
 // column) and its column left as it is.  ipiv[j0 + c] receives the pivot's row + 1.
 template <typename T, int ROWS, int W, bool RESIDENT>
 __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m, int j0, int w, int c_lo, int c_hi,
-                                                        int *ipiv, int *info) {
+                                                        int *ipiv, int *info, int pre, int post) {
     __shared__ T s_val[2][LEAF_WAVES];
     __shared__ int s_row[2][LEAF_WAVES];
     __shared__ T s_cand[2][LEAF_WAVES][W];
@@ -183,14 +185,32 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
     constexpr int NONE = 0x7fffffff;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     T *const P = A + (int64_t)j0 * lda;          // column j0 of the matrix
+    __shared__ T s_pair[LEAF][LEAF];             // pre: the block row of U above this leaf; post: the leaf's own L11
     T a[ROWS][W];
     Cand<T> mine{T(-1), NONE};
+    // pre > 0 (resident leaves only): the `pre` columns left of this leaf are its factored left sibling, whose
+    // update of these columns is still due: rows j0 - pre .. j0 - 1 of these columns hold U12 (the sibling left it
+    // there, see post below) and every row from j0 on takes  a -= L21 U12  as it is loaded.
+    if (RESIDENT && W > 1 && pre > 0) {       // (leaves of one column are not paired: they have no register to spare)
+        if (tid < LEAF * LEAF) {
+            const int u = tid / LEAF, d = tid % LEAF;
+            s_pair[u][d] = (u < pre && d < w) ? A[(j0 - pre + u) + (int64_t)(j0 + d) * lda] : T(0);
+        }
+        __syncthreads();
+    }
     if (RESIDENT) {
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int i = j0 + tid + q * LEAF_NT;
 #pragma unroll
             for (int d = 0; d < W; ++d) a[q][d] = (i < m && d < w) ? P[i + (int64_t)d * lda] : T(0);
+            if (W > 1 && pre > 0 && i < m) {
+                for (int u = 0; u < pre; ++u) {
+                    const T l = P[i + (int64_t)(u - pre) * lda];
+#pragma unroll
+                    for (int d = 0; d < W; ++d) a[q][d] = a[q][d] - l * s_pair[u][d];
+                }
+            }
             if (i < m) {
                 const T v = abs_of(a[q][0]);
                 if (v > mine.val) { mine.val = v; mine.row = i; }
@@ -368,6 +388,32 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
         if (tid < 128 && x < outside) col = A + (int64_t)(c_lo + x + (c_lo + x >= j0 ? w : 0)) * lda;
         swap_batch<T, LEAF, 128>(s_swap, col, j0, s_piv, 0, w, tid);
     }
+    // post > 0 (resident leaves only): the `post` columns right of this leaf are its right sibling; their rows
+    // j0 .. j0 + w - 1 (already interchanged above) become the block row  U12 = L11^-1 A12  here, one thread per
+    // column, with L11 from the registers of the threads that own the leaf's first w rows, so that no solve has to
+    // be launched between the two leaves
+    if (RESIDENT && W > 1 && post > 0) {
+        __syncthreads();                              // s_pair may still be read as U12 by a slow wave of the load
+        if (tid < w) {
+#pragma unroll
+            for (int d = 0; d < W; ++d) s_pair[tid][d] = a[0][d];     // row j0 + tid is this thread's first row
+        }
+        __syncthreads();
+        if (tid < post) {
+            T *const x = A + j0 + (int64_t)(j0 + w + tid) * lda;
+            T u[LEAF];
+#pragma unroll
+            for (int t = 0; t < LEAF; ++t) u[t] = t < w ? x[t] : T(0);
+#pragma unroll
+            for (int t = 1; t < LEAF; ++t)
+#pragma unroll
+                for (int d = 0; d < t; ++d)
+                    if (t < w) u[t] = u[t] - s_pair[t][d] * u[d];
+#pragma unroll
+            for (int t = 1; t < LEAF; ++t)
+                if (t < w) x[t] = u[t];
+        }
+    }
     // the leaf back to memory
     if (RESIDENT) {
 #pragma unroll
@@ -424,29 +470,40 @@ template <typename T> struct Lu {
             if (rows_per_thread * wd <= leaf_elems<T>((int)wd)) return wd;
         return LEAF;
     }
-    template <int W> int leaf(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi, bool resident) const {
+    template <int W> int leaf(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi, bool resident, int pre, int post) const {
         const hipStream_t st = static_cast<hipStream_t>(stream);
         if (resident)
             hipLaunchKernelGGL((getf2_kernel<T, leaf_elems<T>(W) / W, W, true>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
-                               (int)w, (int)c_lo, (int)c_hi, ipiv, info);
+                               (int)w, (int)c_lo, (int)c_hi, ipiv, info, pre, post);
         else
             hipLaunchKernelGGL((getf2_kernel<T, leaf_elems<T>(W) / W, W, false>), dim3(1), dim3(LEAF_NT), 0, st, A, lda, (int)m, (int)j0,
-                               (int)w, (int)c_lo, (int)c_hi, ipiv, info);
+                               (int)w, (int)c_lo, (int)c_hi, ipiv, info, 0, 0);
         return (int)hipGetLastError();
+    }
+    bool resident_at(int64_t j0, int64_t lw) const { return ((m - j0 + LEAF_NT - 1) / LEAF_NT) * lw <= leaf_elems<T>((int)lw); }
+    int any_leaf(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi, int pre, int post) const {
+        const int64_t lw = leaf_width(j0);
+        const bool resident = resident_at(j0, lw);
+        switch (lw) {
+            case 8: return leaf<8>(j0, w, c_lo, c_hi, resident, pre, post);
+            case 4: return leaf<4>(j0, w, c_lo, c_hi, resident, pre, post);
+            case 2: return leaf<2>(j0, w, c_lo, c_hi, resident, pre, post);
+            default: return leaf<1>(j0, w, c_lo, c_hi, resident, pre, post);
+        }
     }
     int panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
         const int64_t lw = leaf_width(j0);
-        if (w <= lw) {
-            const bool resident = ((m - j0 + LEAF_NT - 1) / LEAF_NT) * lw <= leaf_elems<T>((int)lw);
-            switch (lw) {
-                case 8: return leaf<8>(j0, w, c_lo, c_hi, resident);
-                case 4: return leaf<4>(j0, w, c_lo, c_hi, resident);
-                case 2: return leaf<2>(j0, w, c_lo, c_hi, resident);
-                default: return leaf<1>(j0, w, c_lo, c_hi, resident);
-            }
-        }
+        if (w <= lw) return any_leaf(j0, w, c_lo, c_hi, 0, 0);
         const int64_t w1 = ((w / 2 + lw - 1) / lw) * lw, w2 = w - w1, j1 = j0 + w1;
         int rc;
+        // Two leaves side by side, both in registers: the left one leaves the block row of U for the right one
+        // behind (post), the right one applies the left one's update as it loads (pre), and neither the solve nor
+        // the product between them is launched.
+        const int64_t lw2 = leaf_width(j1);
+        if (lw > 1 && lw2 > 1 && w1 <= lw && w2 <= lw2 && resident_at(j0, lw) && resident_at(j1, lw2)) {
+            if ((rc = any_leaf(j0, w1, c_lo, c_hi, 0, (int)w2))) return rc;
+            return any_leaf(j1, w2, c_lo, c_hi, (int)w1, 0);
+        }
         if ((rc = panel(j0, w1, c_lo, c_hi))) return rc;
         T *const A11 = A + j0 + j0 * lda, *const A12 = A + j0 + j1 * lda;
         T *const A21 = A + j1 + j0 * lda, *const A22 = A + j1 + j1 * lda;
