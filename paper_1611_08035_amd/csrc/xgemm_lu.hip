@@ -34,7 +34,7 @@ constexpr int LEAF_NT = 512;     // its threads (two waves per SIMD, so that eac
 constexpr int LEAF_WAVES = LEAF_NT / 64;
 // elements of the leaf per thread, ROWS x W with W = 8, 4, 2 or 1 columns: what the registers of a lane hold
 // beside the rest of the kernel's state
-template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : 64; }
+template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : (w == 2 ? 56 : 64); }
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
 
@@ -199,18 +199,36 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
         __syncthreads();
     }
     if (RESIDENT) {
+        // all loads of the leaf are issued before anything looks at them
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int i = j0 + tid + q * LEAF_NT;
 #pragma unroll
             for (int d = 0; d < W; ++d) a[q][d] = (i < m && d < w) ? P[i + (int64_t)d * lda] : T(0);
-            if (W > 1 && pre > 0 && i < m) {
-                for (int u = 0; u < pre; ++u) {
-                    const T l = P[i + (int64_t)(u - pre) * lda];
+        }
+        if (W > 1 && pre > 0) {
+            // one column of the sibling's L at a time, HALF rows of a thread in flight together
+            constexpr int HALF = ROWS > 16 ? 8 : (ROWS + 1) / 2;
+            for (int u = 0; u < pre; ++u) {
+                const T *const lcol = P + (int64_t)(u - pre) * lda;
 #pragma unroll
-                    for (int d = 0; d < W; ++d) a[q][d] = a[q][d] - l * s_pair[u][d];
+                for (int h = 0; h < ROWS; h += HALF) {
+                    T l[HALF];
+#pragma unroll
+                    for (int q = h; q < h + HALF && q < ROWS; ++q) {
+                        const int i = j0 + tid + q * LEAF_NT;
+                        l[q - h] = i < m ? lcol[i] : T(0);
+                    }
+#pragma unroll
+                    for (int q = h; q < h + HALF && q < ROWS; ++q)
+#pragma unroll
+                        for (int d = 0; d < W; ++d) a[q][d] = a[q][d] - l[q - h] * s_pair[u][d];
                 }
             }
+        }
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int i = j0 + tid + q * LEAF_NT;
             if (i < m) {
                 const T v = abs_of(a[q][0]);
                 if (v > mine.val) { mine.val = v; mine.row = i; }
