@@ -39,6 +39,31 @@ template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
 
 template <typename T> __device__ __forceinline__ T abs_of(T x) { return x < T(0) ? -x : x; }
+
+// `count` elements from `base` on as a buffer: an element offset at or beyond count reads as zero and is not
+// written, so that the rows of a leaf past the end of the matrix need no branch (and no wait that a branch
+// per access brings with it).
+template <typename T> struct Rows {
+    __amdgpu_buffer_rsrc_t rsrc;
+    __device__ __forceinline__ Rows(T *base, int count)
+        : rsrc(__builtin_amdgcn_make_buffer_rsrc(base, 0, count > 0 ? count * (int)sizeof(T) : 0, 0x00020000)) {}
+    __device__ __forceinline__ T get(int at) const {
+        if constexpr (sizeof(T) == 8) {
+            typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+            return __builtin_bit_cast(T, (u32x2)__builtin_amdgcn_raw_buffer_load_b64(rsrc, at * (int)sizeof(T), 0, 0));
+        } else {
+            return __builtin_bit_cast(T, (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, at * (int)sizeof(T), 0, 0));
+        }
+    }
+    __device__ __forceinline__ void put(int at, T v) const {
+        if constexpr (sizeof(T) == 8) {
+            typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), rsrc, at * (int)sizeof(T), 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), rsrc, at * (int)sizeof(T), 0, 0);
+        }
+    }
+};
 // smallest magnitude whose reciprocal is finite and normal (LAPACK's safe minimum)
 template <typename T> struct RcpLimit;
 template <> struct RcpLimit<double> { static __device__ __forceinline__ double tiny() { return 2.2250738585072014e-308; } };
@@ -201,24 +226,21 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
     if (RESIDENT) {
         // all loads of the leaf are issued before anything looks at them
 #pragma unroll
-        for (int q = 0; q < ROWS; ++q) {
-            const int i = j0 + tid + q * LEAF_NT;
+        for (int d = 0; d < W; ++d) {
+            const Rows<T> col(P + j0 + (int64_t)d * lda, d < w ? m - j0 : 0);      // columns past w: all zeros
 #pragma unroll
-            for (int d = 0; d < W; ++d) a[q][d] = (i < m && d < w) ? P[i + (int64_t)d * lda] : T(0);
+            for (int q = 0; q < ROWS; ++q) a[q][d] = col.get(tid + q * LEAF_NT);
         }
         if (W > 1 && pre > 0) {
             // one column of the sibling's L at a time, HALF rows of a thread in flight together
             constexpr int HALF = ROWS > 16 ? 8 : (ROWS + 1) / 2;
             for (int u = 0; u < pre; ++u) {
-                const T *const lcol = P + (int64_t)(u - pre) * lda;
+                const Rows<T> lcol(P + j0 + (int64_t)(u - pre) * lda, m - j0);
 #pragma unroll
                 for (int h = 0; h < ROWS; h += HALF) {
                     T l[HALF];
 #pragma unroll
-                    for (int q = h; q < h + HALF && q < ROWS; ++q) {
-                        const int i = j0 + tid + q * LEAF_NT;
-                        l[q - h] = i < m ? lcol[i] : T(0);
-                    }
+                    for (int q = h; q < h + HALF && q < ROWS; ++q) l[q - h] = lcol.get(tid + q * LEAF_NT);
 #pragma unroll
                     for (int q = h; q < h + HALF && q < ROWS; ++q)
 #pragma unroll
@@ -432,16 +454,13 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
                 if (t < w) x[t] = u[t];
         }
     }
-    // the leaf back to memory
+    // the leaf back to memory, a column at a time
     if (RESIDENT) {
 #pragma unroll
-        for (int q = 0; q < ROWS; ++q) {
-            const int i = j0 + tid + q * LEAF_NT;
-            if (i < m) {
+        for (int d = 0; d < W; ++d) {
+            const Rows<T> col(P + j0 + (int64_t)d * lda, d < w ? m - j0 : 0);      // columns past w: nothing is written
 #pragma unroll
-                for (int d = 0; d < W; ++d)
-                    if (d < w) P[i + (int64_t)d * lda] = a[q][d];
-            }
+            for (int q = 0; q < ROWS; ++q) col.put(tid + q * LEAF_NT, a[q][d]);
         }
     }
 }
