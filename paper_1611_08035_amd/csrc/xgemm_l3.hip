@@ -503,7 +503,7 @@ __global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArg
     const bool live = !feeding && (blockIdx.x * WAVES + group) * MMA_RHS < a.nrhs;
     const int64_t xq = a.left ? a.ldx : 1, xs = a.left ? 1 : a.ldx;
     const T *const xcol = a.X + (int64_t)min(q, a.nrhs - 1) * xq;
-    T xr[2][KS];                                         // panel p in xr[p % 2]
+    T xr[3][KS];                                         // panel p in xr[p % 3]: asked for two panels before its use
     auto xfetch = [&](int p, int slot) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) xr[slot][ks] = xcol[(int64_t)min(p * PANEL + 4 * ks + lk, dim - 1) * xs];
@@ -568,6 +568,7 @@ __global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArg
         __syncthreads();
     } else {
         xfetch(0, 0);
+        xfetch(1, 1);
 #pragma unroll
         for (int t = 0; t < HT; ++t)
 #pragma unroll
@@ -583,7 +584,7 @@ __global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArg
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int sx = p * KS + ks;
-            const T xv = (4 * sx + lk < dim && q < a.nrhs) ? xr[p % 2][ks] : T(0);
+            const T xv = (4 * sx + lk < dim && q < a.nrhs) ? xr[p % 3][ks] : T(0);
 #pragma unroll
             for (int tt = 0; tt < HT; ++tt) {
                 const int t = H * HT + tt;
@@ -597,18 +598,19 @@ __global__ void __launch_bounds__(16 * 64) wide_product_kernel(const WideProdArg
     auto feed_step = [&](auto p_tag) {
         constexpr int p = decltype(p_tag)::value;
         if (p >= npan) return;                           // uniform over the workgroup
-        if (p + 1 < npan) {
-            constexpr int slot = (p + 1) % DEPTH;
-            stash(p + 1, slot);                          // into the half that nobody reads during this step
-            fetch(slot);                                 // panel p + 1 + DEPTH
-        }
+        // unconditional, also past the last panel (positions are clamped, such a panel is stored as zeros into the
+        // half that nobody reads any more): a fetch that might not have been issued would turn every wait for an
+        // older one into a wait for all loads
+        constexpr int slot = (p + 1) % DEPTH;
+        stash(p + 1, slot);                              // into the half that nobody reads during this step
+        fetch(slot);                                     // panel p + 1 + DEPTH
         __syncthreads();
     };
     auto multiply_step = [&](auto p_tag) {
         constexpr int p = decltype(p_tag)::value;
         if (p >= npan) return;                           // uniform over the workgroup
         if (live) {
-            xfetch(p + 1, (p + 1) % 2);
+            xfetch(p + 2, (p + 2) % 3);                  // positions are clamped into the block: past the last panel it re-reads the last row
             // Every tile of the wave's half takes part whatever the order, in straight-line code.  An
             // earlier form jumped around the tiles past the order, each jump straight after a tile's matrix
             // instruction and all to one block that copies accumulator registers; on that edge the compiler
