@@ -802,7 +802,64 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::OCC) gemm_kernel(const GemmArgs<
             }
     };
     // edge or diagonal tile: element by element under the bounds and triangle tests
+    // The elements are addressed from the tile's origin through a range-checked buffer: one that lies outside C or
+    // outside the triangle gets an offset beyond the range, reads as zero and is not written, so a row-block is
+    // one batch of loads and one batch of stores with no branch between them (a branch per element made the
+    // compiler wait for each element's round trip in turn).  Leading dimensions too large for 31-bit offsets
+    // inside a tile take the element-by-element way.
+    const bool c_in_range = (int64_t)g.ldc * (int64_t)(MT_N * sizeof(T)) < (int64_t)0x7fffffff;
     auto flush_edge = [&](int j, const typename M::acc_t (&a)[TM]) {
+        if (c_in_range) {
+            constexpr uint32_t OUTSIDE = 0x80000000u;
+            const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(g.C + (int64_t)n0 * g.ldc + m0, 0, (int)OUTSIDE, 0x00020000);
+            // RB accumulator registers (columns of C) at a time: at most 16 elements per lane in flight,
+            // so that the offsets and the old values never push a variant over its register budget
+            constexpr int RB = (16 / TM > 0) ? ((16 / TM < M::NR) ? 16 / TM : M::NR) : 1;
+            static_assert(M::NR % RB == 0, "row-blocks are flushed in whole batches");
+#pragma unroll
+            for (int r0 = 0; r0 < M::NR; r0 += RB) {
+                uint32_t off[RB][TM];
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    const int nn = c_n(j, r0 + r);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const int mm = mc + (i / VRM) * VRM * M::MI + (i % VRM);
+                        const int below = (g.uplo == 2) ? (n0 - m0) + nn - mm : (m0 - n0) + mm - nn;
+                        const bool ok = mm < m_lim && nn < n_lim && (g.uplo == 0 || below >= 0);
+                        off[r][i] = ok ? (uint32_t)(((int64_t)nn * g.ldc + mm) * (int64_t)sizeof(T)) : OUTSIDE;
+                    }
+                }
+                T cold[RB][TM];
+                if (use_c) {
+#pragma unroll
+                    for (int r = 0; r < RB; ++r)
+#pragma unroll
+                        for (int i = 0; i < TM; ++i) {
+                            if constexpr (sizeof(T) == 8) {
+                                typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                                cold[r][i] = __builtin_bit_cast(T, (u32x2)__builtin_amdgcn_raw_buffer_load_b64(rc, off[r][i], 0, 0));
+                            } else {
+                                cold[r][i] = __builtin_bit_cast(T, (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(rc, off[r][i], 0, 0));
+                            }
+                        }
+                }
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        T v = alpha * a[i][r0 + r];
+                        if (use_c) v += beta * cold[r][i];
+                        if constexpr (sizeof(T) == 8) {
+                            typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), rc, off[r][i], 0, 0);
+                        } else {
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), rc, off[r][i], 0, 0);
+                        }
+                    }
+            }
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < M::NR; ++r) {
             const int nn = c_n(j, r);
