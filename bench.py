@@ -523,8 +523,12 @@ def sweep(torch, np, xg, si, args):
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dA0, dA
-    for prec, nsz in (("d", 4096), ("d", 8192), ("d", 16384), ("s", 8192)):
-        if not want(f"{prec}getrf {nsz}"):
+    # LU: the panels' leaves on one workgroup each (xgemm_*getrf), and the panels shared by all the workgroups
+    # their rows need, through an exchange buffer (xgemm_*getrf_ws)
+    for prec, nsz, ws in (("d", 4096, 0), ("d", 8192, 0), ("d", 16384, 0), ("s", 8192, 0),
+                          ("d", 4096, 1), ("d", 8192, 1), ("d", 16384, 1), ("s", 8192, 1), ("s", 16384, 1)):
+        name = f"{prec}getrf{'_ws' if ws else ''} {nsz}"
+        if not want(name):
             continue
         dtype = np.float64 if prec == "d" else np.float32
         ld = si.padded_ld(nsz)
@@ -532,13 +536,20 @@ def sweep(torch, np, xg, si, args):
         dA = dA0.clone()
         dinfo = torch.zeros(1, dtype=torch.int32, device="cuda")
         dpiv = torch.zeros(nsz, dtype=torch.int32, device="cuda")
-        f = getattr(xg, f"xgemm_{prec}getrf")
-        dev = timed_in_place(lambda: dA.copy_(dA0), lambda: f(nsz, nsz, dA, ld, dpiv, dinfo), reps=4, skip=1)
+        if ws:
+            lwork = xg.xgemm_getrf_workspace_bytes()
+            work = torch.empty(lwork, dtype=torch.uint8, device="cuda")
+            fw = getattr(xg, f"xgemm_{prec}getrf_ws")
+            step = lambda: fw(nsz, nsz, dA, ld, dpiv, dinfo, work, lwork)
+        else:
+            f = getattr(xg, f"xgemm_{prec}getrf")
+            step = lambda: f(nsz, nsz, dA, ld, dpiv, dinfo)
+        dev = timed_in_place(lambda: dA.copy_(dA0), step, reps=4, skip=1)
         if int(dinfo.item()) != 0:
             raise RuntimeError("getrf info %d" % int(dinfo.item()))
         flops = 2.0 * float(nsz) ** 3 / 3.0
         peak = PEAK_TFLOPS["f64" if prec == "d" else "f32"] * 1e12
-        print(json.dumps({"shape": f"{prec}getrf {nsz}", "ms": round(dev * 1e3, 4),
+        print(json.dumps({"shape": name, "ms": round(dev * 1e3, 4),
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dA0, dA

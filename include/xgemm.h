@@ -262,6 +262,31 @@ int xgemm_dgetrf(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int *i
 int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *stream);
 
 /*
+ * The same factorisation with a caller-owned exchange buffer, which lets all workgroups that the rows of a
+ * panel need factor it together (xgemm_*getrf factors a panel's leaves on one compute unit at a time while
+ * the rest of the device waits): the rows of a panel of 128 columns are dealt to workgroups in stripes of 128
+ * (fp64) or 256 (fp32) rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
+ * of a column is agreed by every workgroup alike from the candidates (magnitude, row, the whole candidate
+ * row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
+ * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
+ *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 1 MiB); its
+ *          contents need no preparation and are undefined afterwards.  Calls that share it must not
+ *          overlap in time.  NULL or too small: the call runs exactly as xgemm_*getrf.
+ * The workgroups of a panel wait for each other (the only place in the library where a workgroup waits for
+ * another), so all of them must be resident together: the library never asks for more than one per compute
+ * unit (panels taller than that go the way of xgemm_*getrf), and every wait is bounded: a workgroup that
+ * does not see the others within about a second gives up, the others follow, and *info becomes -1 (A is
+ * then partly factored and must be discarded).  That can only happen when other work holds the device's
+ * compute units for that long.
+ * Returns as xgemm_*getrf, and -7 for a work that is not 16-byte aligned.
+ */
+size_t xgemm_getrf_workspace_bytes(void);
+int xgemm_dgetrf_ws(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork,
+                    void *stream);
+int xgemm_sgetrf_ws(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork,
+                    void *stream);
+
+/*
  * GEMM and SYRK with a caller-owned workspace, which lets the library
  * cut the tiles of the last, partly filled round of workgroups along K (the k_c
  * loop of Fig. 1 moved across workgroups for those tiles only): each piece

@@ -75,6 +75,12 @@ int xgemm_force_potrf_block(int order);
  * Returns 0, or -1 for any other value. */
 int xgemm_force_getrf_panel(int64_t width);
 
+/* Benchmark/test control of xgemm_*getrf_ws on the calling thread: how many polls a workgroup of a shared
+ * panel waits for the others before it gives up (default 2^18, about a microsecond each).  0 makes every
+ * panel shared by more than one workgroup give up at once unless all had arrived already: the way to test
+ * the time-out path without holding the device.  Returns 0, or -1 for a negative value. */
+int xgemm_force_getrf_spin_limit(int polls);
+
 /*
  * The workgroup -> macro-tile order the kernels use (host only, no device
  * access), for tests and for reasoning about L2 reuse: for an m x n result cut

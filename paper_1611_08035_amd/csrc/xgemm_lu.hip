@@ -37,6 +37,7 @@ constexpr int LEAF_WAVES = LEAF_NT / 64;
 template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : (w == 2 ? 56 : 64); }
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
+thread_local int t_lu_spin_limit = 1 << 18;   // polls a workgroup of a shared panel waits for the others (about a microsecond each)
 
 template <typename T> __device__ __forceinline__ T abs_of(T x) { return x < T(0) ? -x : x; }
 
@@ -465,6 +466,338 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
     }
 }
 
+// ---------------------------------------------------------------------------
+// A panel shared by many workgroups.  The leaf above is one workgroup on one compute unit while the rest of
+// the device waits; here the rows of a panel of up to NB columns are dealt to G workgroups in stripes of RPW
+// rows, each workgroup keeps its stripe in LDS for the whole panel, and the one decision per column that
+// concerns all of them, the pivot, is taken by every workgroup alike from G candidates exchanged through
+// memory:
+//   per column c (row r = j0 + c, sequence number r + 1):
+//   - every workgroup finds the best of its own live rows (the search rides on the update of the column
+//     before) and its first wave publishes the whole candidate row, then (stores acknowledged) a header
+//     {magnitude, row, sequence number}; workgroup 0, which owns row r, publishes that row too;
+//   - the first wave polls the G headers until all carry this column's sequence number, reduces them to the
+//     pivot row p with the rule of the leaf (largest magnitude, smallest row among equals), and fetches the
+//     published row of p's owner (the new row r of U) and, in p's owner, the old row r;
+//   - rows r and p change places inside the LDS of their owners, and every workgroup scales its part of the
+//     column and updates its part of the columns to the right.
+// The exchange memory is written through to memory and read around the caches (the L2s of different XCDs are
+// not coherent with each other).  Slots alternate with the parity of c: a workgroup that publishes for column
+// c + 2 has seen every header of column c + 1, whose owners had finished reading column c.  Sequence numbers
+// are unique within a factorisation and the headers are cleared when it starts, so a stale slot never matches.
+// Every wait is bounded: a workgroup that does not see the headers within `spin_limit` polls raises a flag in
+// the exchange memory and leaves; whoever sees the flag leaves too, and *info becomes -1.  The G workgroups
+// must be resident together (one per compute unit: the host never asks for more than the device has).
+// ---------------------------------------------------------------------------
+constexpr int COOP_GMAX = 256;            // most workgroups that share a panel
+constexpr int COOP_NB = 128;              // widest shared panel
+constexpr size_t COOP_FLAG_BYTES = 256;   // the time-out flag (first word)
+constexpr size_t COOP_HDR_BYTES = 2 * (size_t)COOP_GMAX * 16;
+constexpr size_t COOP_TOP_BYTES = 2 * (size_t)COOP_NB * 16;                 // elements travel as {value, sequence number}
+constexpr size_t COOP_ROWS_BYTES = 2 * (size_t)COOP_GMAX * COOP_NB * 16;
+constexpr size_t COOP_BYTES = COOP_FLAG_BYTES + COOP_HDR_BYTES + COOP_TOP_BYTES + COOP_ROWS_BYTES;
+constexpr int THROUGH = 17;               // cache policy bits sc0 | sc1: system scope
+constexpr int COOP_INFO_TIMEOUT = -1;
+
+template <typename T> struct CoopCfg;
+template <> struct CoopCfg<double> { static constexpr int RPW = 128, NT = 256; };
+template <> struct CoopCfg<float> { static constexpr int RPW = 256, NT = 512; };
+
+struct CoopHdr {
+    double val;
+    int row;
+    unsigned seq;
+};
+
+// the whole exchange memory to zero: no slot carries a sequence number of an earlier factorisation
+__global__ void __launch_bounds__(256) coop_clear_kernel(uint4 *xch) {
+    for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < COOP_BYTES / 16; i += gridDim.x * 256) xch[i] = uint4{0u, 0u, 0u, 0u};
+}
+
+template <typename T, int RPW, int NT>
+__global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m, int j0, int nb, int *ipiv, int *info,
+                                                        unsigned char *xch, int spin_limit) {
+    static_assert(COOP_NB <= RPW, "row r must belong to workgroup 0 for every column of the panel");
+    static_assert(NT % RPW == 0 && 64 % (NT / RPW) == 0, "the threads of a row share a wave");
+    constexpr int TPR = NT / RPW;          // threads per row
+    constexpr int RW = 64 / TPR;           // rows per wave
+    constexpr int NW = NT / 64;
+    constexpr int LS = RPW + 1;            // odd column stride: a row is read without bank conflicts
+    constexpr int NONE = 0x7fffffff;
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    extern __shared__ __align__(16) unsigned char coop_lds[];
+    T *const P = reinterpret_cast<T *>(coop_lds);          // P[d * LS + i]: column d, local row i
+    __shared__ T s_U[COOP_NB], s_top[COOP_NB];
+    __shared__ T s_wval[NW];
+    __shared__ int s_wrow[NW];
+    __shared__ int s_p, s_abort;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, G = gridDim.x;
+    const int i0 = j0 + g * RPW;                            // first row of this stripe
+    const int nrows = (m - i0) < RPW ? (m - i0) : RPW;
+
+    // exchange memory
+    unsigned *const x_flag = reinterpret_cast<unsigned *>(xch);
+    unsigned char *const x_hdr = xch + COOP_FLAG_BYTES;
+    unsigned char *const x_top = x_hdr + COOP_HDR_BYTES;
+    unsigned char *const x_rows = x_top + COOP_TOP_BYTES;
+    const __amdgpu_buffer_rsrc_t r_flag = __builtin_amdgcn_make_buffer_rsrc(x_flag, 0, 4, 0x00020000);
+
+    // the stripe as one range-checked buffer: rows past the end of the matrix get an offset outside it (they read
+    // as zero and are not written)
+    constexpr unsigned OUTSIDE = 0xfffffff0u;
+    const __amdgpu_buffer_rsrc_t r_panel = __builtin_amdgcn_make_buffer_rsrc(
+        A + i0 + (int64_t)j0 * lda, 0, (int)(((int64_t)(nb - 1) * lda + nrows) * (int64_t)sizeof(T)), 0x00020000);
+    auto panel_off = [&](int i, int d) -> unsigned {
+        return (i < nrows && d < nb) ? (unsigned)(((int64_t)d * lda + i) * (int64_t)sizeof(T)) : OUTSIDE;
+    };
+    // the stripe into LDS: thread (i, dsub) takes columns dsub, dsub + TPR, ...; sixteen loads in flight
+    {
+        const int i = tid % RPW, dsub = tid / RPW;
+        for (int d0 = 0; d0 < nb; d0 += 16 * TPR) {
+            T v[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const unsigned off = panel_off(i, d0 + dsub + q * TPR);
+                if constexpr (sizeof(T) == 8) v[q] = __builtin_bit_cast(T, (u32x2)__builtin_amdgcn_raw_buffer_load_b64(r_panel, off, 0, 0));
+                else v[q] = __builtin_bit_cast(T, (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(r_panel, off, 0, 0));
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int d = d0 + dsub + q * TPR;
+                if (d < nb) P[d * LS + i] = v[q];
+            }
+        }
+    }
+    if (tid == 0) s_abort = 0;
+    __syncthreads();
+
+    // thread (row i, column group dsub) of the update; the TPR threads of a row are lanes of one wave, which
+    // reads the row's multiplier in one instruction before any of them overwrites it
+    const int ui = wave * RW + lane % RW, udsub = lane / RW;
+    const int urow = i0 + ui;                               // global row
+    Cand<T> mine{T(-1), NONE};
+    if (udsub == 0 && ui < nrows) {
+        const T v = abs_of(P[ui]);
+        if (v > mine.val) { mine.val = v; mine.row = urow; }
+    }
+
+    bool aborted = false;
+    int c_reached = 0;                                      // first column without a decision, if the panel is given up
+    for (int c = 0; c < nb; ++c) {
+        const int r = j0 + c, par = c & 1;
+        const unsigned seq = (unsigned)r + 1u;
+        {
+            const Cand<T> wb = wave_best(mine);
+            if (lane == 0) { s_wval[wave] = wb.val; s_wrow[wave] = wb.row; }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            Cand<T> lb{T(-1), NONE};
+#pragma unroll
+            for (int v = 0; v < NW; ++v) lb = better(lb, Cand<T>{s_wval[v], s_wrow[v]});
+            int p = lb.row;
+            if (G > 1) {
+                const int ib = lb.row == NONE ? -1 : lb.row - i0;
+                const __amdgpu_buffer_rsrc_t r_mine = __builtin_amdgcn_make_buffer_rsrc(
+                    x_rows + ((size_t)par * COOP_GMAX + g) * COOP_NB * 16, 0, COOP_NB * 16, 0x00020000);
+                const __amdgpu_buffer_rsrc_t r_top = __builtin_amdgcn_make_buffer_rsrc(x_top + (size_t)par * COOP_NB * 16, 0,
+                                                                                       COOP_NB * 16, 0x00020000);
+                const __amdgpu_buffer_rsrc_t r_hdr = __builtin_amdgcn_make_buffer_rsrc(x_hdr + (size_t)par * COOP_GMAX * 16, 0,
+                                                                                       G * 16, 0x00020000);
+                // Every published item is one aligned 16-byte store that carries the sequence number beside its
+                // value, so a reader tells by itself whether what it read belongs to this column, and nothing has
+                // to wait for an acknowledgement between the items.
+                auto item = [&](double v) -> u32x4 {
+                    const u32x2 w = __builtin_bit_cast(u32x2, v);
+                    u32x4 o;
+                    o[0] = w[0];
+                    o[1] = w[1];
+                    o[2] = seq;
+                    o[3] = 0u;
+                    return o;
+                };
+                for (int d = lane; d < nb; d += 64) {
+                    __builtin_amdgcn_raw_buffer_store_b128(item(ib >= 0 ? (double)P[d * LS + ib] : 0.0), r_mine, d * 16, 0, THROUGH);
+                    if (g == 0) __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + c]), r_top, d * 16, 0, THROUGH);
+                }
+                if (lane == 0) {
+                    u32x4 h = item((double)lb.val);
+                    h[2] = (unsigned)lb.row;
+                    h[3] = seq;
+                    __builtin_amdgcn_raw_buffer_store_b128(h, r_hdr, g * 16, 0, THROUGH);
+                }
+                // poll: lane l looks at the headers l, l + 64, l + 128, l + 192 (past G: outside the buffer)
+                Cand<double> cb{-1.0, NONE};
+                int spins = 0;
+                bool fail = false;
+                for (;;) {
+                    u32x4 h[COOP_GMAX / 64];
+#pragma unroll
+                    for (int q = 0; q < COOP_GMAX / 64; ++q)
+                        h[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_hdr, (lane + 64 * q) * 16, 0, THROUGH);
+                    const unsigned fl = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(r_flag, 0, 0, THROUGH);
+                    bool ok = true;
+                    cb = Cand<double>{-1.0, NONE};
+#pragma unroll
+                    for (int q = 0; q < COOP_GMAX / 64; ++q) {
+                        if (lane + 64 * q < G) {
+                            ok = ok && (h[q][3] == seq);
+                            u32x2 vv;
+                            vv[0] = h[q][0];
+                            vv[1] = h[q][1];
+                            cb = better(cb, Cand<double>{__builtin_bit_cast(double, vv), (int)h[q][2]});
+                        }
+                    }
+                    if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) break;
+                    if (++spins > spin_limit || __builtin_amdgcn_readfirstlane((int)fl) != 0) { fail = true; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                if (!fail) {
+                    cb = wave_best(cb);
+                    const bool nobody = __builtin_amdgcn_readfirstlane(cb.row) == NONE;
+                    p = nobody ? r : __builtin_amdgcn_readfirstlane(cb.row);   // no candidate anywhere (a column of NaNs): row r stays
+                    const int gp = (p - j0) / RPW;
+                    const __amdgpu_buffer_rsrc_t r_win = __builtin_amdgcn_make_buffer_rsrc(
+                        x_rows + ((size_t)par * COOP_GMAX + gp) * COOP_NB * 16, 0, COOP_NB * 16, 0x00020000);
+                    // U is row p as its owner published it, unless nobody had a candidate (then row r itself);
+                    // read again until every item carries this column's sequence number
+                    const __amdgpu_buffer_rsrc_t r_u = nobody ? r_top : r_win;
+                    for (;;) {
+                        u32x4 uv[COOP_NB / 64], tv[COOP_NB / 64];
+#pragma unroll
+                        for (int q = 0; q < COOP_NB / 64; ++q) {
+                            uv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_u, (lane + 64 * q) * 16, 0, THROUGH);
+                            tv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_top, (lane + 64 * q) * 16, 0, THROUGH);
+                        }
+                        const unsigned fl = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(r_flag, 0, 0, THROUGH);
+                        bool ok = true;
+#pragma unroll
+                        for (int q = 0; q < COOP_NB / 64; ++q)
+                            if (lane + 64 * q < nb) ok = ok && uv[q][2] == seq && tv[q][2] == seq;
+                        if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) {
+#pragma unroll
+                            for (int q = 0; q < COOP_NB / 64; ++q) {
+                                const int d = lane + 64 * q;
+                                if (d < nb) {
+                                    u32x2 a, b;
+                                    a[0] = uv[q][0];
+                                    a[1] = uv[q][1];
+                                    b[0] = tv[q][0];
+                                    b[1] = tv[q][1];
+                                    s_U[d] = (T)__builtin_bit_cast(double, a);
+                                    s_top[d] = (T)__builtin_bit_cast(double, b);
+                                }
+                            }
+                            break;
+                        }
+                        if (++spins > spin_limit || __builtin_amdgcn_readfirstlane((int)fl) != 0) { fail = true; break; }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+                if (fail) {
+                    if (lane == 0) {
+                        __builtin_amdgcn_raw_buffer_store_b32(1u, r_flag, 0, 0, THROUGH);
+                        s_abort = 1;
+                    }
+                }
+            } else {
+                if (p == NONE) p = r;
+                for (int d = lane; d < nb; d += 64) {
+                    s_U[d] = P[d * LS + (p - i0)];
+                    s_top[d] = P[d * LS + c];
+                }
+            }
+            if (lane == 0) s_p = p;
+        }
+        __syncthreads();
+        if (s_abort) { aborted = true; c_reached = c; break; }
+        const int p = s_p;
+        const T pivot = s_U[c];
+        const bool nonzero = pivot != T(0);
+        const bool by_rcp = abs_of(pivot) >= RcpLimit<T>::tiny();
+        const T rcp = by_rcp ? T(1) / pivot : T(0);
+        const bool exchange = p != r;
+        if (g == 0 && tid == 0) {
+            ipiv[r] = p + 1;
+            if (!nonzero && *info == 0) *info = r + 1;
+        }
+        if (exchange && tid < nb) {
+            // row r (local row c of workgroup 0) becomes the pivot row; the old row r goes where the pivot was, its
+            // part left of column c here, the rest as the update below passes over that row
+            if (g == 0) P[tid * LS + c] = s_U[tid];
+            const int ip = p - i0;
+            if (ip >= 0 && ip < RPW && tid < c) P[tid * LS + ip] = s_top[tid];
+        }
+        mine.val = T(-1);
+        mine.row = NONE;
+        if (urow > r && ui < nrows) {
+            const bool moved = exchange && urow == p;
+            T l = moved ? s_top[c] : P[c * LS + ui];
+            if (nonzero) {
+                if (by_rcp) l = l * rcp;
+                else l = l / pivot;
+            }
+            __builtin_amdgcn_wave_barrier();                // every thread of the row has read before one writes
+            if (udsub == 0) P[c * LS + ui] = l;
+            // CH columns of the row at a time, all their reads issued before the first write and none of them
+            // under a branch (columns past the panel read its last column again and are not written); written one
+            // column per trip, the loop is a chain of LDS round trips
+            constexpr int CH = 16;
+            const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0ull;
+            for (int d0 = c + 1 + udsub; d0 < nb; d0 += CH * TPR) {
+                T x[CH], uu[CH];
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int d = d0 + q * TPR, dc = d < nb ? d : nb - 1;
+                    x[q] = P[dc * LS + ui];
+                    uu[q] = s_U[dc];
+                }
+                if (any_moved) {
+#pragma unroll
+                    for (int q = 0; q < CH; ++q) {
+                        const int d = d0 + q * TPR, dc = d < nb ? d : nb - 1;
+                        const T tv = s_top[dc];
+                        x[q] = moved ? tv : x[q];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int d = d0 + q * TPR;
+                    const T y = x[q] - l * uu[q];
+                    if (d < nb) P[d * LS + ui] = y;
+                    if (q == 0 && d == c + 1) {
+                        const T v = abs_of(y);
+                        if (v > mine.val) { mine.val = v; mine.row = urow; }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (aborted) {
+        // The panel stays as it was found.  The interchanges this panel has not decided are recorded as "none":
+        // the kernels that follow on the stream apply ipiv as it stands, and it must name rows of the matrix.
+        if (g == 0) {
+            for (int cc = c_reached + tid; cc < nb; cc += NT) ipiv[j0 + cc] = j0 + cc + 1;
+            if (tid == 0) *info = COOP_INFO_TIMEOUT;
+        }
+        return;
+    }
+    // the stripe back to memory
+    {
+        const int i = tid % RPW, dsub = tid / RPW;
+        for (int d = dsub; d < nb; d += TPR) {
+            const T v = P[d * LS + i];
+            const unsigned off = panel_off(i, d);
+            if constexpr (sizeof(T) == 8) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r_panel, off, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), r_panel, off, 0, 0);
+        }
+    }
+}
+
 // Row interchanges k = k0 .. k1 - 1 (row k with row ipiv[k] - 1, in that order) applied to columns
 // [c0, c1) of A: 64 columns per workgroup, one per thread, 32 interchanges per batch.
 constexpr int SWAP_G = 32, SWAP_NT = 64;
@@ -485,6 +818,25 @@ template <typename T> struct Lu {
     int64_t m, n;
     int *ipiv, *info;
     void *stream;
+    unsigned char *xch;     // exchange memory of the shared panels (COOP_BYTES), or nullptr: leaves of one workgroup only
+    int ncu;                // compute units of the device: most workgroups that can share a panel
+
+    // The panel [j0, j0 + nb) by all the workgroups its rows need (getrf_coop_kernel), if they can be resident
+    // together and the panel's offsets fit 32 bits; 1: not taken (the caller falls back to the recursive panel).
+    int coop_panel(int64_t j0, int64_t nb) const {
+        using C = CoopCfg<T>;
+        if (!xch || nb > COOP_NB) return 1;
+        const int64_t G = (m - j0 + C::RPW - 1) / C::RPW;
+        if (G > ncu || G > COOP_GMAX) return 1;
+        if ((int64_t)COOP_NB * lda * (int64_t)sizeof(T) >= (int64_t)0x7fffffff) return 1;
+        constexpr size_t LDS = (size_t)COOP_NB * (C::RPW + 1) * sizeof(T);
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(getrf_coop_kernel<T, C::RPW, C::NT>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+        if (attr != hipSuccess) return (int)attr;
+        hipLaunchKernelGGL((getrf_coop_kernel<T, C::RPW, C::NT>), dim3((unsigned)G), dim3(C::NT), LDS, static_cast<hipStream_t>(stream),
+                           A, lda, (int)m, (int)j0, (int)nb, ipiv, info, xch, t_lu_spin_limit);
+        return (int)hipGetLastError();
+    }
 
     int trsm(int64_t rows, int64_t cols, const T *L, T *B) const;
     int gemm(int64_t mm, int64_t nn, int64_t kk, const T *X, const T *Y, T *C) const;
@@ -551,11 +903,13 @@ template <typename T> struct Lu {
 
     int run() const {
         const int64_t steps = min64(m, n);
-        const int64_t W = t_lu_panel > 0 ? t_lu_panel : (steps >= 4096 ? 128 : 64);
+        const int64_t W = t_lu_panel > 0 ? t_lu_panel : ((xch || steps >= 4096) ? 128 : 64);
         int rc;
         for (int64_t j = 0; j < steps; j += W) {
             const int64_t nb = min64(W, steps - j), j1 = j + nb;
-            if ((rc = panel(j, nb, j, j1))) return rc;
+            rc = coop_panel(j, nb);
+            if (rc == 1) rc = panel(j, nb, j, j1);
+            if (rc) return rc;
             if ((rc = swap_rows(0, j, j, j1))) return rc;
             if (j1 < n) {
                 if ((rc = swap_rows(j1, n, j, j1))) return rc;
@@ -580,34 +934,64 @@ template <> int Lu<float>::gemm(int64_t mm, int64_t nn, int64_t kk, const float 
     return xgemm_sgemm('N', 'N', mm, nn, kk, -1.0f, X, lda, Y, lda, 1.0f, C, lda, stream);
 }
 
-template <typename T> int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, void *stream) {
+template <typename T>
+int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork, void *stream) {
     if (m < 0 || m > DIM_MAX) return -1;
     if (n < 0 || n > DIM_MAX) return -2;
     if (m > 0 && n > 0 && !A) return -3;
     if (lda < max64(1, m)) return -4;
     if (m > 0 && n > 0 && !ipiv) return -5;
     if (!info) return -6;
+    if (work && (reinterpret_cast<uintptr_t>(work) & 15)) return -7;
     hipLaunchKernelGGL(clear_int_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), info);
-    const int rc = (int)hipGetLastError();
+    int rc = (int)hipGetLastError();
     if (rc || m == 0 || n == 0) return rc;
-    const Lu<T> lu{A, lda, m, n, ipiv, info, stream};
+    unsigned char *xch = (work && lwork >= COOP_BYTES) ? static_cast<unsigned char *>(work) : nullptr;
+    int ncu = 0;
+    if (xch) {
+        int dev = 0;
+        if ((rc = (int)hipGetDevice(&dev))) return rc;
+        if ((rc = (int)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev))) return rc;
+        hipLaunchKernelGGL(coop_clear_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
+        if ((rc = (int)hipGetLastError())) return rc;
+    }
+    const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu};
     return lu.run();
 }
 
 }  // namespace
 
 namespace xg {
-void reset_lu_tuning() { t_lu_panel = -1; }
+void reset_lu_tuning() {
+    t_lu_panel = -1;
+    t_lu_spin_limit = 1 << 18;
+}
 }  // namespace xg
 
 extern "C" {
 
 int xgemm_dgetrf(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int *info, void *stream) {
-    return getrf_impl<double>(m, n, A, lda, ipiv, info, stream);
+    return getrf_impl<double>(m, n, A, lda, ipiv, info, nullptr, 0, stream);
 }
 
 int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *stream) {
-    return getrf_impl<float>(m, n, A, lda, ipiv, info, stream);
+    return getrf_impl<float>(m, n, A, lda, ipiv, info, nullptr, 0, stream);
+}
+
+size_t xgemm_getrf_workspace_bytes(void) { return COOP_BYTES; }
+
+int xgemm_dgetrf_ws(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork, void *stream) {
+    return getrf_impl<double>(m, n, A, lda, ipiv, info, work, lwork, stream);
+}
+
+int xgemm_sgetrf_ws(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork, void *stream) {
+    return getrf_impl<float>(m, n, A, lda, ipiv, info, work, lwork, stream);
+}
+
+int xgemm_force_getrf_spin_limit(int polls) {
+    if (polls < 0) return -1;
+    t_lu_spin_limit = polls;
+    return 0;
 }
 
 int xgemm_force_getrf_panel(int64_t width) {

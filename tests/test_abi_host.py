@@ -180,6 +180,16 @@ def test_getrf_illegal_arguments(fn):
     assert f(4, 4, P, 4, P, None, stream=0) == -6
     assert xg.xgemm_force_getrf_panel(0) == -1 and xg.xgemm_force_getrf_panel(-2) == -1
     assert xg.xgemm_force_getrf_panel(64) == 0 and xg.xgemm_force_getrf_panel(-1) == 0
+    # the routine with an exchange buffer: the same numbering, then the buffer's alignment
+    w = getattr(xg, fn + "_ws")
+    lw = xg.xgemm_getrf_workspace_bytes()
+    assert 0 < lw <= 2 << 20
+    assert w(-1, 4, P, 4, P, P, P, lw, stream=0) == -1
+    assert w(5, 4, P, 4, P, P, P, lw, stream=0) == -4
+    assert w(4, 4, P, 4, P, None, P, lw, stream=0) == -6
+    assert w(4, 4, P, 4, P, P, P + 8, lw, stream=0) == -7
+    assert xg.xgemm_force_getrf_spin_limit(-1) == -1 and xg.xgemm_force_getrf_spin_limit(5) == 0
+    xg.xgemm_tuning_reset()
 
 
 @pytest.mark.parametrize("pre", "ds")

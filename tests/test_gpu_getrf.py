@@ -22,28 +22,36 @@ def _auto():
     xg.xgemm_tuning_reset()
 
 
-def run_getrf(m, n, A, lda, stream=None):
+def run_getrf(m, n, A, lda, stream=None, ws=False):
+    """ws: through xgemm_*getrf_ws with an exchange buffer full of ones (it needs no preparation), so that the
+    panels are shared by all the workgroups their rows need."""
     torch = torch_mod()
-    f = xg.xgemm_dgetrf if A.dtype == np.float64 else xg.xgemm_sgetrf
     dA = to_dev(A)
     k = max(min(m, n), 1)
     dpiv = torch.full((k,), -7, dtype=torch.int32, device="cuda")
     dinfo = torch.full((1,), -7, dtype=torch.int32, device="cuda")
-    assert f(m, n, dA, lda, dpiv, dinfo, stream=stream) == 0
+    if ws:
+        f = xg.xgemm_dgetrf_ws if A.dtype == np.float64 else xg.xgemm_sgetrf_ws
+        lwork = xg.xgemm_getrf_workspace_bytes()
+        work = torch.full((lwork,), 0xFF, dtype=torch.uint8, device="cuda")
+        assert f(m, n, dA, lda, dpiv, dinfo, work, lwork, stream=stream) == 0
+    else:
+        f = xg.xgemm_dgetrf if A.dtype == np.float64 else xg.xgemm_sgetrf
+        assert f(m, n, dA, lda, dpiv, dinfo, stream=stream) == 0
     torch.cuda.synchronize()
     return dA.cpu().numpy(), dpiv.cpu().numpy()[:min(m, n)], int(dinfo.item())
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-@pytest.mark.parametrize("panel", [-1, 16, 40])
-def test_planted_factorisations_are_recovered_exactly(dtype, panel):
+@pytest.mark.parametrize("panel,ws", [(-1, False), (16, False), (40, False), (-1, True), (16, True), (40, True)])
+def test_planted_factorisations_are_recovered_exactly(dtype, panel, ws):
     """Every operation on these matrices is exact, so interchanges and factors must come out bit for bit,
     whatever the blocking: one leaf, several leaves, several panels, ragged last leaf and panel, tall, wide."""
     rng = si.rng_for(310, panel + 1)
     for m, n in [(1, 1), (7, 5), (5, 7), (8, 8), (9, 9), (64, 64), (200, 131), (131, 200), (300, 300), (517, 517), (1100, 700)]:
         A, L, U, perm = planted_lu(rng, m, n, dtype, ld=m + 3)
         assert xg.xgemm_force_getrf_panel(panel) == 0
-        F, ipiv, info = run_getrf(m, n, A, m + 3)
+        F, ipiv, info = run_getrf(m, n, A, m + 3, ws=ws)
         assert info == 0, (m, n)
         k = min(m, n)
         assert np.all(ipiv >= np.arange(1, k + 1)) and np.all(ipiv <= m)
@@ -54,15 +62,16 @@ def test_planted_factorisations_are_recovered_exactly(dtype, panel):
         assert np.all(np.isnan(F[:, m:])), "padding rows were written"
 
 
+@pytest.mark.parametrize("ws", [False, True])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-def test_random_matrices_every_element_and_against_the_oracle(dtype):
+def test_random_matrices_every_element_and_against_the_oracle(dtype, ws):
     rng = si.rng_for(311, 0)
     u = unit_roundoff(dtype)
     for (m, n), panel in [((50, 50), -1), ((257, 257), 64), ((300, 120), -1), ((120, 300), 32), ((1000, 1000), -1),
                           ((777, 1031), 128), ((1031, 777), 24)]:
         A = si.uniform(rng, m, n, m + 1, dtype)
         assert xg.xgemm_force_getrf_panel(panel) == 0
-        F, ipiv, info = run_getrf(m, n, A, m + 1)
+        F, ipiv, info = run_getrf(m, n, A, m + 1, ws=ws)
         assert info == 0
         ratio = check_valid(m, n, A, m + 1, F, m + 1, ipiv, u)
         assert np.all(np.isnan(F[:, m:]))
@@ -72,10 +81,13 @@ def test_random_matrices_every_element_and_against_the_oracle(dtype):
         assert oinfo == 0 and np.array_equal(ipiv, opiv), (m, n)
         tol = 64 * min(m, n) * u
         assert np.allclose(F[:, :m], W[:, :m], rtol=tol, atol=tol), (m, n)
-        print("getrf", dtype.__name__, m, n, "panel", panel, "max err/bound", ratio)
+        print("getrf", dtype.__name__, m, n, "panel", panel, "ws", ws, "max err/bound", ratio)
 
 
-def test_tie_rule_and_zero_pivots():
+@pytest.mark.parametrize("ws", [False, True])
+def test_tie_rule_and_zero_pivots(ws):
+    def run_getrf(*a):
+        return globals()["run_getrf"](*a, ws=ws)
     # the first of equal candidates is taken (exact small integers: the arithmetic decides nothing)
     A = np.array([[2.0, -2.0, 2.0], [1.0, 3.0, 5.0], [0.0, 1.0, 4.0]])
     F, ipiv, info = run_getrf(3, 3, A, 3)
@@ -102,22 +114,32 @@ def test_tie_rule_and_zero_pivots():
     assert info == oinfo == 18 and np.array_equal(ipiv, opiv)
     assert np.allclose(F, W, rtol=1e-12, atol=1e-13)
     check_valid(40, 40, A, 40, F, 40, ipiv, oracle.U64)
+    # ties across the stripes of a shared panel: the first row of the largest magnitude wins wherever it lies
+    n = 700
+    A = si.integers(rng, n, n, n, np.float64, R=1)
+    A[0, :] = 0.0                                            # column 1: +-3 in rows 650, 300 and 129 only
+    A[0, 650], A[0, 300], A[0, 129] = 3.0, -3.0, 3.0
+    F, ipiv, info = run_getrf(n, n, A, n)
+    assert ipiv[0] == 130
+    if info == 0:
+        check_valid(n, n, A, n, F, n, ipiv, oracle.U64)
 
 
+@pytest.mark.parametrize("ws", [False, True])
 @pytest.mark.parametrize("dtype,n", [(np.float64, 4096), (np.float64, 8192), (np.float32, 8192)])
-def test_full_size_sampled(dtype, n):
+def test_full_size_sampled(dtype, n, ws):
     """The sizes of the sweep: legal interchanges, multipliers within one, the residual bound on 16 full rows,
     16 full columns and 2^15 entries; the planted matrix of the same size bit for bit."""
     rng = si.rng_for(313, n)
     A = si.uniform(rng, n, n, n, dtype)
-    F, ipiv, info = run_getrf(n, n, A, n)
+    F, ipiv, info = run_getrf(n, n, A, n, ws=ws)
     assert info == 0
     I, J = si.sample_indices(rng, n, n, 16, 16, 1 << 15)
     ratio = check_valid(n, n, A, n, F, n, ipiv, unit_roundoff(dtype), I=I, J=J)
     print("getrf", dtype.__name__, n, "sampled max err/bound", ratio)
     if dtype == np.float64 and n == 4096:
         A, L, U, perm = planted_lu(rng, n, n, dtype)
-        F, ipiv, info = run_getrf(n, n, A, n)
+        F, ipiv, info = run_getrf(n, n, A, n, ws=ws)
         Lg, Ug = unpack(F, n, n)
         assert info == 0 and np.array_equal(perm_of(ipiv, n), perm) and np.array_equal(Ug, U) and np.array_equal(Lg, L)
 
@@ -131,3 +153,37 @@ def test_on_a_stream_of_the_callers_and_twice_the_same_bits():
     side = torch.cuda.Stream()
     F2, p2, i2 = run_getrf(n, n, A, n, stream=side)
     assert i1 == 0 and i2 == 0 and np.array_equal(p1, p2) and np.array_equal(F1, F2)
+
+
+def test_shared_panels_agree_with_the_leaves_and_repeat_bit_for_bit():
+    """Tie-free data: both routes take the same pivots; the shared panels give the same bits twice in a row
+    (nothing in them depends on which workgroup arrives first)."""
+    rng = si.rng_for(315, 0)
+    for m, n in [(1500, 1500), (2300, 900), (900, 2300)]:
+        A = si.uniform(rng, m, n, m)
+        F0, p0, i0 = run_getrf(m, n, A, m)
+        F1, p1, i1 = run_getrf(m, n, A, m, ws=True)
+        F2, p2, i2 = run_getrf(m, n, A, m, ws=True)
+        assert i0 == i1 == i2 == 0 and np.array_equal(p0, p1) and np.array_equal(p1, p2)
+        assert np.array_equal(F1, F2)
+        tol = 64 * min(m, n) * oracle.U64 * np.abs(F0[:, :m]).max()       # entries of U grow beyond one
+        assert np.allclose(F0, F1, rtol=0.0, atol=tol)
+
+
+def test_a_wait_that_times_out_ends_the_call_with_info_minus_one():
+    """With no polls allowed a workgroup of a shared panel gives up unless all others had arrived already; the
+    others follow, every kernel ends, *info is -1, and the next call with the default limit is right again."""
+    torch = torch_mod()
+    rng = si.rng_for(316, 0)
+    n = 2048
+    A = si.uniform(rng, n, n, n)
+    assert xg.xgemm_force_getrf_spin_limit(0) == 0
+    F, ipiv, info = run_getrf(n, n, A, n, ws=True)
+    assert info in (0, -1)
+    if info == 0:
+        check_valid(n, n, A, n, F, n, ipiv, oracle.U64)
+    xg.xgemm_tuning_reset()
+    F, ipiv, info = run_getrf(n, n, A, n, ws=True)
+    assert info == 0
+    I, J = si.sample_indices(rng, n, n, 8, 8, 1 << 12)
+    check_valid(n, n, A, n, F, n, ipiv, oracle.U64, I=I, J=J)
