@@ -500,7 +500,7 @@ constexpr int THROUGH = 17;               // cache policy bits sc0 | sc1: system
 constexpr int COOP_INFO_TIMEOUT = -1;
 
 template <typename T> struct CoopCfg;
-template <> struct CoopCfg<double> { static constexpr int RPW = 128, NT = 256; };
+template <> struct CoopCfg<double> { static constexpr int RPW = 128, NT = 512; };
 template <> struct CoopCfg<float> { static constexpr int RPW = 256, NT = 512; };
 
 struct CoopHdr {
@@ -747,13 +747,15 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
             // column per trip, the loop is a chain of LDS round trips
             constexpr int CH = 16;
             const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0ull;
+            const int e_last = (nb - 1) * LS + ui;           // the panel's last column: what columns past it read instead
             for (int d0 = c + 1 + udsub; d0 < nb; d0 += CH * TPR) {
                 T x[CH], uu[CH];
+                const int e0 = d0 * LS + ui;
 #pragma unroll
                 for (int q = 0; q < CH; ++q) {
-                    const int d = d0 + q * TPR, dc = d < nb ? d : nb - 1;
-                    x[q] = P[dc * LS + ui];
-                    uu[q] = s_U[dc];
+                    const int e = e0 + q * (TPR * LS), dq = d0 + q * TPR;
+                    x[q] = P[e < e_last ? e : e_last];
+                    uu[q] = s_U[dq < nb ? dq : nb - 1];
                 }
                 if (any_moved) {
 #pragma unroll
