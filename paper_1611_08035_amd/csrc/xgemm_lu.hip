@@ -471,57 +471,56 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
 // the device waits; here the rows of a panel of up to NB columns are dealt to G workgroups in stripes of RPW
 // rows, each workgroup keeps its stripe in LDS for the whole panel, and the one decision per column that
 // concerns all of them, the pivot, is taken by every workgroup alike from G candidates exchanged through
-// memory:
-//   per column c (row r = j0 + c, sequence number r + 1):
-//   - every workgroup finds the best of its own live rows (the search rides on the update of the column
-//     before) and its first wave publishes the whole candidate row, then (stores acknowledged) a header
-//     {magnitude, row, sequence number}; workgroup 0, which owns row r, publishes that row too;
-//   - the first wave polls the G headers until all carry this column's sequence number, reduces them to the
-//     pivot row p with the rule of the leaf (largest magnitude, smallest row among equals), and fetches the
-//     published row of p's owner (the new row r of U) and, in p's owner, the old row r;
-//   - rows r and p change places inside the LDS of their owners, and every workgroup scales its part of the
-//     column and updates its part of the columns to the right.
-// The exchange memory is written through to memory and read around the caches (the L2s of different XCDs are
-// not coherent with each other).  Slots alternate with the parity of c: a workgroup that publishes for column
-// c + 2 has seen every header of column c + 1, whose owners had finished reading column c.  Sequence numbers
-// are unique within a factorisation and the headers are cleared when it starts, so a stale slot never matches.
-// Every wait is bounded: a workgroup that does not see the headers within `spin_limit` polls raises a flag in
-// the exchange memory and leaves; whoever sees the flag leaves too, and *info becomes -1.  The G workgroups
-// must be resident together (one per compute unit: the host never asks for more than the device has).
+// memory.  A workgroup has RPW * TPR computing threads (TPR threads per row, lanes of one wave) and one more
+// wave, the communicator, that talks to the other workgroups while the computing waves work.  Column c
+// (row r = j0 + c, sequence number r + 1) goes through three barriers:
+//   - the computing waves reduce their candidates for column c (largest magnitude, smallest row among equals;
+//     found when column c was last updated) to one per wave;                                        barrier A
+//   - the communicator publishes the workgroup's candidate {magnitude, row, sequence number} and polls the G
+//     headers until all carry this column's number, which gives the pivot row p to every workgroup alike;
+//     meanwhile the computing waves bring the columns right of c up to date with the pivot row of column
+//     c - 1 (that update lags one column behind, so that it runs while the headers travel);           barrier B
+//   - the stripe is now up to date: p's owner publishes row p, workgroup 0 (which owns row r) publishes row r,
+//     every communicator fetches both into LDS;                                                    barrier C
+//   - the computing waves exchange the two rows inside the stripes that hold them, scale column c, update
+//     column c + 1 alone and look for its largest entry: the candidates of the next column.
+// Every published item is one aligned 16-byte store that carries the column's sequence number beside its
+// value; a reader tells by itself whether what it read belongs to this column, so nothing waits for an
+// acknowledgement.  The exchange memory is written through to memory and read around the caches (the L2s of
+// different XCDs are not coherent with each other).  Slots alternate with the parity of c: whoever publishes
+// for column c + 2 has seen every header of column c + 1, whose owners had finished reading column c.
+// Sequence numbers are unique within a factorisation and the exchange memory is cleared when it starts, so a
+// stale slot never matches.  Every wait is bounded: a communicator that does not see what it waits for
+// within `spin_limit` polls raises a flag in the exchange memory and gives up; whoever sees the flag gives up
+// too, and *info becomes -1.  The G workgroups must be resident together (one per compute unit: the host
+// never asks for more than the device has).
 // ---------------------------------------------------------------------------
 constexpr int COOP_GMAX = 256;            // most workgroups that share a panel
 constexpr int COOP_NB = 128;              // widest shared panel
 constexpr size_t COOP_FLAG_BYTES = 256;   // the time-out flag (first word)
 constexpr size_t COOP_HDR_BYTES = 2 * (size_t)COOP_GMAX * 16;
-constexpr size_t COOP_TOP_BYTES = 2 * (size_t)COOP_NB * 16;                 // elements travel as {value, sequence number}
-constexpr size_t COOP_ROWS_BYTES = 2 * (size_t)COOP_GMAX * COOP_NB * 16;
-constexpr size_t COOP_BYTES = COOP_FLAG_BYTES + COOP_HDR_BYTES + COOP_TOP_BYTES + COOP_ROWS_BYTES;
+constexpr size_t COOP_ROW_BYTES = 2 * (size_t)COOP_NB * 16;                 // elements travel as {value, sequence number}
+constexpr size_t COOP_BYTES = COOP_FLAG_BYTES + COOP_HDR_BYTES + 2 * COOP_ROW_BYTES;   // flag, headers, pivot row, row r
 constexpr int THROUGH = 17;               // cache policy bits sc0 | sc1: system scope
 constexpr int COOP_INFO_TIMEOUT = -1;
 
 template <typename T> struct CoopCfg;
-template <> struct CoopCfg<double> { static constexpr int RPW = 128, NT = 512; };
-template <> struct CoopCfg<float> { static constexpr int RPW = 256, NT = 512; };
-
-struct CoopHdr {
-    double val;
-    int row;
-    unsigned seq;
-};
+template <> struct CoopCfg<double> { static constexpr int RPW = 128, TPR = 4; };
+template <> struct CoopCfg<float> { static constexpr int RPW = 256, TPR = 2; };
 
 // the whole exchange memory to zero: no slot carries a sequence number of an earlier factorisation
 __global__ void __launch_bounds__(256) coop_clear_kernel(uint4 *xch) {
-    for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < COOP_BYTES / 16; i += gridDim.x * 256) xch[i] = uint4{0u, 0u, 0u, 0u};
+    for (unsigned i = threadIdx.x; i < COOP_BYTES / 16; i += 256) xch[i] = uint4{0u, 0u, 0u, 0u};
 }
 
-template <typename T, int RPW, int NT>
-__global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m, int j0, int nb, int *ipiv, int *info,
-                                                        unsigned char *xch, int spin_limit) {
+template <typename T, int RPW, int TPR>
+__global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_t lda, int m, int j0, int nb, int *ipiv, int *info,
+                                                                    unsigned char *xch, int spin_limit) {
     static_assert(COOP_NB <= RPW, "row r must belong to workgroup 0 for every column of the panel");
-    static_assert(NT % RPW == 0 && 64 % (NT / RPW) == 0, "the threads of a row share a wave");
-    constexpr int TPR = NT / RPW;          // threads per row
+    static_assert(64 % TPR == 0, "the threads of a row share a wave");
+    constexpr int NTC = RPW * TPR;         // computing threads
+    constexpr int NWC = NTC / 64;          // computing waves; wave NWC is the communicator
     constexpr int RW = 64 / TPR;           // rows per wave
-    constexpr int NW = NT / 64;
     constexpr int LS = RPW + 1;            // odd column stride: a row is read without bank conflicts
     constexpr int NONE = 0x7fffffff;
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -529,21 +528,21 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
     extern __shared__ __align__(16) unsigned char coop_lds[];
     T *const P = reinterpret_cast<T *>(coop_lds);          // P[d * LS + i]: column d, local row i
     __shared__ T s_U[COOP_NB], s_top[COOP_NB];
-    __shared__ T s_wval[NW];
-    __shared__ int s_wrow[NW];
+    __shared__ T s_wval[NWC];
+    __shared__ int s_wrow[NWC];
     __shared__ int s_p, s_abort;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool comm = wave == NWC;
     const int g = blockIdx.x, G = gridDim.x;
     const int i0 = j0 + g * RPW;                            // first row of this stripe
     const int nrows = (m - i0) < RPW ? (m - i0) : RPW;
 
     // exchange memory
-    unsigned *const x_flag = reinterpret_cast<unsigned *>(xch);
     unsigned char *const x_hdr = xch + COOP_FLAG_BYTES;
-    unsigned char *const x_top = x_hdr + COOP_HDR_BYTES;
-    unsigned char *const x_rows = x_top + COOP_TOP_BYTES;
-    const __amdgpu_buffer_rsrc_t r_flag = __builtin_amdgcn_make_buffer_rsrc(x_flag, 0, 4, 0x00020000);
+    unsigned char *const x_win = x_hdr + COOP_HDR_BYTES;
+    unsigned char *const x_top = x_win + COOP_ROW_BYTES;
+    const __amdgpu_buffer_rsrc_t r_flag = __builtin_amdgcn_make_buffer_rsrc(xch, 0, 4, 0x00020000);
 
     // the stripe as one range-checked buffer: rows past the end of the matrix get an offset outside it (they read
     // as zero and are not written)
@@ -554,7 +553,7 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
         return (i < nrows && d < nb) ? (unsigned)(((int64_t)d * lda + i) * (int64_t)sizeof(T)) : OUTSIDE;
     };
     // the stripe into LDS: thread (i, dsub) takes columns dsub, dsub + TPR, ...; sixteen loads in flight
-    {
+    if (!comm) {
         const int i = tid % RPW, dsub = tid / RPW;
         for (int d0 = 0; d0 < nb; d0 += 16 * TPR) {
             T v[16];
@@ -574,55 +573,47 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
     if (tid == 0) s_abort = 0;
     __syncthreads();
 
-    // thread (row i, column group dsub) of the update; the TPR threads of a row are lanes of one wave, which
-    // reads the row's multiplier in one instruction before any of them overwrites it
+    // computing thread (row ui, column group udsub); the TPR threads of a row are lanes of one wave, which reads
+    // the row's multiplier in one instruction before any of them overwrites it
     const int ui = wave * RW + lane % RW, udsub = lane / RW;
     const int urow = i0 + ui;                               // global row
+    const bool has_row = !comm && ui < nrows;
     Cand<T> mine{T(-1), NONE};
-    if (udsub == 0 && ui < nrows) {
+    if (has_row && udsub == 0) {
         const T v = abs_of(P[ui]);
         if (v > mine.val) { mine.val = v; mine.row = urow; }
     }
+    T l_lag = T(0);                                         // this row's multiplier of the column before: its update is due
 
     bool aborted = false;
     int c_reached = 0;                                      // first column without a decision, if the panel is given up
     for (int c = 0; c < nb; ++c) {
         const int r = j0 + c, par = c & 1;
         const unsigned seq = (unsigned)r + 1u;
-        {
+        if (!comm) {
             const Cand<T> wb = wave_best(mine);
             if (lane == 0) { s_wval[wave] = wb.val; s_wrow[wave] = wb.row; }
         }
-        __syncthreads();
-        if (wave == 0) {
+        __syncthreads();                                    // A: the waves' candidates for column c
+        int p = r;
+        int spins = 0;
+        bool fail = false;
+        auto item = [&](double v) -> u32x4 {
+            const u32x2 w = __builtin_bit_cast(u32x2, v);
+            u32x4 o;
+            o[0] = w[0];
+            o[1] = w[1];
+            o[2] = seq;
+            o[3] = 0u;
+            return o;
+        };
+        if (comm) {
             Cand<T> lb{T(-1), NONE};
 #pragma unroll
-            for (int v = 0; v < NW; ++v) lb = better(lb, Cand<T>{s_wval[v], s_wrow[v]});
-            int p = lb.row;
+            for (int v = 0; v < NWC; ++v) lb = better(lb, Cand<T>{s_wval[v], s_wrow[v]});
             if (G > 1) {
-                const int ib = lb.row == NONE ? -1 : lb.row - i0;
-                const __amdgpu_buffer_rsrc_t r_mine = __builtin_amdgcn_make_buffer_rsrc(
-                    x_rows + ((size_t)par * COOP_GMAX + g) * COOP_NB * 16, 0, COOP_NB * 16, 0x00020000);
-                const __amdgpu_buffer_rsrc_t r_top = __builtin_amdgcn_make_buffer_rsrc(x_top + (size_t)par * COOP_NB * 16, 0,
-                                                                                       COOP_NB * 16, 0x00020000);
                 const __amdgpu_buffer_rsrc_t r_hdr = __builtin_amdgcn_make_buffer_rsrc(x_hdr + (size_t)par * COOP_GMAX * 16, 0,
                                                                                        G * 16, 0x00020000);
-                // Every published item is one aligned 16-byte store that carries the sequence number beside its
-                // value, so a reader tells by itself whether what it read belongs to this column, and nothing has
-                // to wait for an acknowledgement between the items.
-                auto item = [&](double v) -> u32x4 {
-                    const u32x2 w = __builtin_bit_cast(u32x2, v);
-                    u32x4 o;
-                    o[0] = w[0];
-                    o[1] = w[1];
-                    o[2] = seq;
-                    o[3] = 0u;
-                    return o;
-                };
-                for (int d = lane; d < nb; d += 64) {
-                    __builtin_amdgcn_raw_buffer_store_b128(item(ib >= 0 ? (double)P[d * LS + ib] : 0.0), r_mine, d * 16, 0, THROUGH);
-                    if (g == 0) __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + c]), r_top, d * 16, 0, THROUGH);
-                }
                 if (lane == 0) {
                     u32x4 h = item((double)lb.val);
                     h[2] = (unsigned)lb.row;
@@ -631,8 +622,6 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
                 }
                 // poll: lane l looks at the headers l, l + 64, l + 128, l + 192 (past G: outside the buffer)
                 Cand<double> cb{-1.0, NONE};
-                int spins = 0;
-                bool fail = false;
                 for (;;) {
                     u32x4 h[COOP_GMAX / 64];
 #pragma unroll
@@ -657,19 +646,57 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
                 }
                 if (!fail) {
                     cb = wave_best(cb);
-                    const bool nobody = __builtin_amdgcn_readfirstlane(cb.row) == NONE;
-                    p = nobody ? r : __builtin_amdgcn_readfirstlane(cb.row);   // no candidate anywhere (a column of NaNs): row r stays
-                    const int gp = (p - j0) / RPW;
-                    const __amdgpu_buffer_rsrc_t r_win = __builtin_amdgcn_make_buffer_rsrc(
-                        x_rows + ((size_t)par * COOP_GMAX + gp) * COOP_NB * 16, 0, COOP_NB * 16, 0x00020000);
-                    // U is row p as its owner published it, unless nobody had a candidate (then row r itself);
-                    // read again until every item carries this column's sequence number
-                    const __amdgpu_buffer_rsrc_t r_u = nobody ? r_top : r_win;
+                    const int best_row = __builtin_amdgcn_readfirstlane(cb.row);
+                    p = best_row == NONE ? r : best_row;    // no candidate anywhere (a column of NaNs): row r stays
+                }
+            } else {
+                p = lb.row == NONE ? r : __builtin_amdgcn_readfirstlane(lb.row);
+            }
+        } else if (c > 0 && has_row && urow >= r) {
+            // the update that lags: columns right of c take the pivot row of column c - 1 (still in s_U), CH columns
+            // of the row at a time, all their reads issued before the first write and none of them under a branch
+            // (columns past the panel read its last column again and are not written)
+            constexpr int CH = 16;
+            const int e_last = (nb - 1) * LS + ui;
+            for (int d0 = c + 1 + udsub; d0 < nb; d0 += CH * TPR) {
+                T x[CH], uu[CH];
+                const int e0 = d0 * LS + ui;
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int e = e0 + q * (TPR * LS), dq = d0 + q * TPR;
+                    x[q] = P[e < e_last ? e : e_last];
+                    uu[q] = s_U[dq < nb ? dq : nb - 1];
+                }
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int d = d0 + q * TPR;
+                    if (d < nb) P[d * LS + ui] = x[q] - l_lag * uu[q];
+                }
+            }
+        }
+        __syncthreads();                                    // B: the stripe is up to date with column c - 1; p is known
+        if (comm) {
+            if (!fail) {
+                if (G > 1) {
+                    const __amdgpu_buffer_rsrc_t r_win = __builtin_amdgcn_make_buffer_rsrc(x_win + (size_t)par * COOP_NB * 16, 0,
+                                                                                           COOP_NB * 16, 0x00020000);
+                    const __amdgpu_buffer_rsrc_t r_top = __builtin_amdgcn_make_buffer_rsrc(x_top + (size_t)par * COOP_NB * 16, 0,
+                                                                                           COOP_NB * 16, 0x00020000);
+                    const int ip = p - i0;
+                    if (ip >= 0 && ip < RPW) {
+                        for (int d = lane; d < nb; d += 64)
+                            __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + ip]), r_win, d * 16, 0, THROUGH);
+                    }
+                    if (g == 0) {
+                        for (int d = lane; d < nb; d += 64)
+                            __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + c]), r_top, d * 16, 0, THROUGH);
+                    }
+                    // both rows, read again until every item carries this column's sequence number
                     for (;;) {
                         u32x4 uv[COOP_NB / 64], tv[COOP_NB / 64];
 #pragma unroll
                         for (int q = 0; q < COOP_NB / 64; ++q) {
-                            uv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_u, (lane + 64 * q) * 16, 0, THROUGH);
+                            uv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_win, (lane + 64 * q) * 16, 0, THROUGH);
                             tv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_top, (lane + 64 * q) * 16, 0, THROUGH);
                         }
                         const unsigned fl = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(r_flag, 0, 0, THROUGH);
@@ -682,13 +709,13 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
                             for (int q = 0; q < COOP_NB / 64; ++q) {
                                 const int d = lane + 64 * q;
                                 if (d < nb) {
-                                    u32x2 a, b;
-                                    a[0] = uv[q][0];
-                                    a[1] = uv[q][1];
-                                    b[0] = tv[q][0];
-                                    b[1] = tv[q][1];
-                                    s_U[d] = (T)__builtin_bit_cast(double, a);
-                                    s_top[d] = (T)__builtin_bit_cast(double, b);
+                                    u32x2 ua, ta;
+                                    ua[0] = uv[q][0];
+                                    ua[1] = uv[q][1];
+                                    ta[0] = tv[q][0];
+                                    ta[1] = tv[q][1];
+                                    s_U[d] = (T)__builtin_bit_cast(double, ua);
+                                    s_top[d] = (T)__builtin_bit_cast(double, ta);
                                 }
                             }
                             break;
@@ -696,25 +723,25 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
                         if (++spins > spin_limit || __builtin_amdgcn_readfirstlane((int)fl) != 0) { fail = true; break; }
                         __builtin_amdgcn_s_sleep(1);
                     }
-                }
-                if (fail) {
-                    if (lane == 0) {
-                        __builtin_amdgcn_raw_buffer_store_b32(1u, r_flag, 0, 0, THROUGH);
-                        s_abort = 1;
+                } else {
+                    for (int d = lane; d < nb; d += 64) {
+                        s_U[d] = P[d * LS + (p - i0)];
+                        s_top[d] = P[d * LS + c];
                     }
                 }
-            } else {
-                if (p == NONE) p = r;
-                for (int d = lane; d < nb; d += 64) {
-                    s_U[d] = P[d * LS + (p - i0)];
-                    s_top[d] = P[d * LS + c];
-                }
             }
-            if (lane == 0) s_p = p;
+            if (lane == 0) {
+                if (fail) {
+                    __builtin_amdgcn_raw_buffer_store_b32(1u, r_flag, 0, 0, THROUGH);
+                    s_abort = 1;
+                }
+                s_p = p;
+            }
         }
-        __syncthreads();
+        __syncthreads();                                    // C: pivot row and row r in LDS
         if (s_abort) { aborted = true; c_reached = c; break; }
-        const int p = s_p;
+        if (comm) continue;
+        p = s_p;
         const T pivot = s_U[c];
         const bool nonzero = pivot != T(0);
         const bool by_rcp = abs_of(pivot) >= RcpLimit<T>::tiny();
@@ -725,55 +752,32 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
             if (!nonzero && *info == 0) *info = r + 1;
         }
         if (exchange && tid < nb) {
-            // row r (local row c of workgroup 0) becomes the pivot row; the old row r goes where the pivot was, its
-            // part left of column c here, the rest as the update below passes over that row
+            // row r (local row c of workgroup 0) becomes the pivot row; the old row r goes where the pivot was,
+            // except in columns c and c + 1, which the owners of that row take from s_top below
             if (g == 0) P[tid * LS + c] = s_U[tid];
             const int ip = p - i0;
-            if (ip >= 0 && ip < RPW && tid < c) P[tid * LS + ip] = s_top[tid];
+            if (ip >= 0 && ip < RPW && tid != c && tid != c + 1) P[tid * LS + ip] = s_top[tid];
         }
         mine.val = T(-1);
         mine.row = NONE;
-        if (urow > r && ui < nrows) {
+        if (has_row && urow > r) {
             const bool moved = exchange && urow == p;
             T l = moved ? s_top[c] : P[c * LS + ui];
+            T x1 = T(0);
+            if (c + 1 < nb) x1 = moved ? s_top[c + 1] : P[(c + 1) * LS + ui];
             if (nonzero) {
                 if (by_rcp) l = l * rcp;
                 else l = l / pivot;
             }
+            l_lag = l;
             __builtin_amdgcn_wave_barrier();                // every thread of the row has read before one writes
-            if (udsub == 0) P[c * LS + ui] = l;
-            // CH columns of the row at a time, all their reads issued before the first write and none of them
-            // under a branch (columns past the panel read its last column again and are not written); written one
-            // column per trip, the loop is a chain of LDS round trips
-            constexpr int CH = 16;
-            const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0ull;
-            const int e_last = (nb - 1) * LS + ui;           // the panel's last column: what columns past it read instead
-            for (int d0 = c + 1 + udsub; d0 < nb; d0 += CH * TPR) {
-                T x[CH], uu[CH];
-                const int e0 = d0 * LS + ui;
-#pragma unroll
-                for (int q = 0; q < CH; ++q) {
-                    const int e = e0 + q * (TPR * LS), dq = d0 + q * TPR;
-                    x[q] = P[e < e_last ? e : e_last];
-                    uu[q] = s_U[dq < nb ? dq : nb - 1];
-                }
-                if (any_moved) {
-#pragma unroll
-                    for (int q = 0; q < CH; ++q) {
-                        const int d = d0 + q * TPR, dc = d < nb ? d : nb - 1;
-                        const T tv = s_top[dc];
-                        x[q] = moved ? tv : x[q];
-                    }
-                }
-#pragma unroll
-                for (int q = 0; q < CH; ++q) {
-                    const int d = d0 + q * TPR;
-                    const T y = x[q] - l * uu[q];
-                    if (d < nb) P[d * LS + ui] = y;
-                    if (q == 0 && d == c + 1) {
-                        const T v = abs_of(y);
-                        if (v > mine.val) { mine.val = v; mine.row = urow; }
-                    }
+            if (udsub == 0) {
+                P[c * LS + ui] = l;
+                if (c + 1 < nb) {
+                    const T y = x1 - l * s_U[c + 1];
+                    P[(c + 1) * LS + ui] = y;
+                    const T v = abs_of(y);
+                    if (v > mine.val) { mine.val = v; mine.row = urow; }
                 }
             }
         }
@@ -783,13 +787,13 @@ __global__ void __launch_bounds__(NT) getrf_coop_kernel(T *A, int64_t lda, int m
         // The panel stays as it was found.  The interchanges this panel has not decided are recorded as "none":
         // the kernels that follow on the stream apply ipiv as it stands, and it must name rows of the matrix.
         if (g == 0) {
-            for (int cc = c_reached + tid; cc < nb; cc += NT) ipiv[j0 + cc] = j0 + cc + 1;
+            for (int cc = c_reached + tid; cc < nb; cc += NTC + 64) ipiv[j0 + cc] = j0 + cc + 1;
             if (tid == 0) *info = COOP_INFO_TIMEOUT;
         }
         return;
     }
     // the stripe back to memory
-    {
+    if (!comm) {
         const int i = tid % RPW, dsub = tid / RPW;
         for (int d = dsub; d < nb; d += TPR) {
             const T v = P[d * LS + i];
@@ -832,10 +836,10 @@ template <typename T> struct Lu {
         if (G > ncu || G > COOP_GMAX) return 1;
         if ((int64_t)COOP_NB * lda * (int64_t)sizeof(T) >= (int64_t)0x7fffffff) return 1;
         constexpr size_t LDS = (size_t)COOP_NB * (C::RPW + 1) * sizeof(T);
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(getrf_coop_kernel<T, C::RPW, C::NT>),
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(getrf_coop_kernel<T, C::RPW, C::TPR>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
         if (attr != hipSuccess) return (int)attr;
-        hipLaunchKernelGGL((getrf_coop_kernel<T, C::RPW, C::NT>), dim3((unsigned)G), dim3(C::NT), LDS, static_cast<hipStream_t>(stream),
+        hipLaunchKernelGGL((getrf_coop_kernel<T, C::RPW, C::TPR>), dim3((unsigned)G), dim3(C::RPW * C::TPR + 64), LDS, static_cast<hipStream_t>(stream),
                            A, lda, (int)m, (int)j0, (int)nb, ipiv, info, xch, t_lu_spin_limit);
         return (int)hipGetLastError();
     }
@@ -954,7 +958,7 @@ int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, vo
         int dev = 0;
         if ((rc = (int)hipGetDevice(&dev))) return rc;
         if ((rc = (int)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev))) return rc;
-        hipLaunchKernelGGL(coop_clear_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
+        hipLaunchKernelGGL(coop_clear_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
         if ((rc = (int)hipGetLastError())) return rc;
     }
     const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu};
