@@ -269,7 +269,7 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * of a column is agreed by every workgroup alike from the candidates (magnitude, row, the whole candidate
  * row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
  * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
- *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 1 MiB); its
+ *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 16 KiB); its
  *          contents need no preparation and are undefined afterwards.  Calls that share it must not
  *          overlap in time.  NULL or too small: the call runs exactly as xgemm_*getrf.
  * The workgroups of a panel wait for each other (the only place in the library where a workgroup waits for

@@ -530,7 +530,8 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
     __shared__ T s_U[COOP_NB], s_top[COOP_NB];
     __shared__ T s_wval[NWC];
     __shared__ int s_wrow[NWC];
-    __shared__ int s_p, s_abort;
+    __shared__ int s_p, s_abort, s_how;                     // s_how: 0 pivot is zero, 1 scale by s_rcp, 2 divide
+    __shared__ T s_rcp;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool comm = wave == NWC;
@@ -656,11 +657,12 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
             // the update that lags: columns right of c take the pivot row of column c - 1 (still in s_U), CH columns
             // of the row at a time, all their reads issued before the first write and none of them under a branch
             // (columns past the panel read its last column again and are not written)
-            constexpr int CH = 16;
             const int e_last = (nb - 1) * LS + ui;
-            for (int d0 = c + 1 + udsub; d0 < nb; d0 += CH * TPR) {
+            // one piece: CH columns of the row per thread (CH * TPR columns of the panel from dbase on)
+            auto piece = [&](auto ch_tag, int dbase) {
+                constexpr int CH = decltype(ch_tag)::value;
+                const int d0 = dbase + udsub, e0 = d0 * LS + ui;
                 T x[CH], uu[CH];
-                const int e0 = d0 * LS + ui;
 #pragma unroll
                 for (int q = 0; q < CH; ++q) {
                     const int e = e0 + q * (TPR * LS), dq = d0 + q * TPR;
@@ -672,7 +674,13 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                     const int d = d0 + q * TPR;
                     if (d < nb) P[d * LS + ui] = x[q] - l_lag * uu[q];
                 }
-            }
+            };
+            // pieces of 16 columns per thread, the last one of 8 or 4 where that covers what is left, so that the
+            // last trip does not pay for columns that are not there
+            int dbase = c + 1;
+            for (; nb - dbase > 8 * TPR; dbase += 16 * TPR) piece(std::integral_constant<int, 16>{}, dbase);
+            if (nb - dbase > 4 * TPR) piece(std::integral_constant<int, 8>{}, dbase);
+            else if (nb - dbase > 0) piece(std::integral_constant<int, 4>{}, dbase);
         }
         __syncthreads();                                    // B: the stripe is up to date with column c - 1; p is known
         if (comm) {
@@ -730,27 +738,36 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                     }
                 }
             }
-            if (lane == 0) {
-                if (fail) {
+            if (fail) {
+                if (lane == 0) {
                     __builtin_amdgcn_raw_buffer_store_b32(1u, r_flag, 0, 0, THROUGH);
                     s_abort = 1;
                 }
-                s_p = p;
+            } else {
+                // what every computing thread needs of the pivot, worked out once: the column is scaled by the
+                // pivot's reciprocal as LAPACK does (one division per column; |a| <= |pivot| still gives
+                // |a * (1 / pivot)| <= 1 after rounding) unless the reciprocal would overflow
+                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): this wave's writes of s_U have landed
+                const T pivot = s_U[c];
+                const bool nonzero = pivot != T(0), by_rcp = abs_of(pivot) >= RcpLimit<T>::tiny();
+                if (lane == 0) {
+                    s_p = p;
+                    s_how = !nonzero ? 0 : (by_rcp ? 1 : 2);
+                    s_rcp = by_rcp ? T(1) / pivot : pivot;
+                    if (g == 0) {
+                        ipiv[r] = p + 1;
+                        if (!nonzero && *info == 0) *info = r + 1;
+                    }
+                }
             }
         }
         __syncthreads();                                    // C: pivot row and row r in LDS
         if (s_abort) { aborted = true; c_reached = c; break; }
         if (comm) continue;
         p = s_p;
-        const T pivot = s_U[c];
-        const bool nonzero = pivot != T(0);
-        const bool by_rcp = abs_of(pivot) >= RcpLimit<T>::tiny();
-        const T rcp = by_rcp ? T(1) / pivot : T(0);
+        const int how = s_how;
+        const T rcp = s_rcp;                                // the reciprocal, or the pivot itself where that would overflow
         const bool exchange = p != r;
-        if (g == 0 && tid == 0) {
-            ipiv[r] = p + 1;
-            if (!nonzero && *info == 0) *info = r + 1;
-        }
         if (exchange && tid < nb) {
             // row r (local row c of workgroup 0) becomes the pivot row; the old row r goes where the pivot was,
             // except in columns c and c + 1, which the owners of that row take from s_top below
@@ -765,10 +782,8 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
             T l = moved ? s_top[c] : P[c * LS + ui];
             T x1 = T(0);
             if (c + 1 < nb) x1 = moved ? s_top[c + 1] : P[(c + 1) * LS + ui];
-            if (nonzero) {
-                if (by_rcp) l = l * rcp;
-                else l = l / pivot;
-            }
+            if (how == 1) l = l * rcp;
+            else if (how == 2) l = l / rcp;
             l_lag = l;
             __builtin_amdgcn_wave_barrier();                // every thread of the row has read before one writes
             if (udsub == 0) {
