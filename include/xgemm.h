@@ -266,8 +266,8 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * panel need factor it together (xgemm_*getrf factors a panel's leaves on one compute unit at a time while
  * the rest of the device waits): the rows of a panel of 128 columns are dealt to workgroups in stripes of 128
  * (fp64) or 256 (fp32) rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
- * of a column is agreed by every workgroup alike from the candidates (magnitude, row, the whole candidate
- * row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
+ * of a column is agreed by every workgroup alike from the candidates (magnitude and row) that all of them
+ * publish in `work`, where the pivot's owner then leaves the pivot row for the others.  Same semantics, same pivot rule and the same statement about the
  * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
  *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 16 KiB); its
  *          contents need no preparation and are undefined afterwards.  Calls that share it must not
@@ -275,7 +275,7 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * The workgroups of a panel wait for each other (the only place in the library where a workgroup waits for
  * another), so all of them must be resident together: the library never asks for more than one per compute
  * unit (panels taller than that go the way of xgemm_*getrf), and every wait is bounded: a workgroup that
- * does not see the others within about a second gives up, the others follow, and *info becomes -1 (A is
+ * does not see the others within a few tenths of a second gives up, the others follow, and *info becomes -1 (A is
  * then partly factored and must be discarded).  That can only happen when other work holds the device's
  * compute units for that long.
  * Returns as xgemm_*getrf, and -7 for a work that is not 16-byte aligned.
