@@ -81,6 +81,12 @@ int xgemm_force_getrf_panel(int64_t width);
  * the time-out path without holding the device.  Returns 0, or -1 for a negative value. */
 int xgemm_force_getrf_spin_limit(int polls);
 
+/* Benchmark control of xgemm_*getrf_ws on the calling thread: how long a workgroup of a shared panel waits
+ * after publishing before it first looks for the others' headers resp. for the pivot row, in sleeps of 64
+ * clocks (0 .. 1024 each; defaults 18 and 13, about the time a published item takes to become visible to
+ * another workgroup).  Returns 0, or -1 for a value out of range. */
+int xgemm_force_getrf_poll_delay(int header_sleeps, int row_sleeps);
+
 /*
  * The workgroup -> macro-tile order the kernels use (host only, no device
  * access), for tests and for reasoning about L2 reuse: for an m x n result cut

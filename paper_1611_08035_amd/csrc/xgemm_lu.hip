@@ -37,6 +37,11 @@ constexpr int LEAF_WAVES = LEAF_NT / 64;
 template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : (w == 2 ? 56 : 64); }
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
+// First look of a poll put off by this many 64-clock sleeps: what a published item takes to become visible to a
+// load that another workgroup issues (a look that comes too early costs a whole round trip more; swept on the
+// device, flat between 16 and 20 for the headers and between 10 and 16 for the rows).
+constexpr int LU_HDR_DELAY = 18, LU_ROW_DELAY = 13;
+thread_local int t_lu_hdr_delay = LU_HDR_DELAY, t_lu_row_delay = LU_ROW_DELAY;
 thread_local int t_lu_spin_limit = 1 << 18;   // polls a workgroup of a shared panel waits for the others (about a microsecond each)
 
 template <typename T> __device__ __forceinline__ T abs_of(T x) { return x < T(0) ? -x : x; }
@@ -515,7 +520,7 @@ __global__ void __launch_bounds__(256) coop_clear_kernel(uint4 *xch) {
 
 template <typename T, int RPW, int TPR>
 __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_t lda, int m, int j0, int nb, int *ipiv, int *info,
-                                                                    unsigned char *xch, int spin_limit) {
+                                                                    unsigned char *xch, int spin_limit, int hdr_delay, int row_delay) {
     static_assert(COOP_NB <= RPW, "row r must belong to workgroup 0 for every column of the panel");
     static_assert(64 % TPR == 0, "the threads of a row share a wave");
     constexpr int NTC = RPW * TPR;         // computing threads
@@ -621,7 +626,10 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                     h[3] = seq;
                     __builtin_amdgcn_raw_buffer_store_b128(h, r_hdr, g * 16, 0, THROUGH);
                 }
-                // poll: lane l looks at the headers l, l + 64, l + 128, l + 192 (past G: outside the buffer)
+                // poll: lane l looks at the headers l, l + 64, l + 128, l + 192 (past G: outside the buffer).  The first
+                // look is put off by the time a published item takes to become visible: a look that comes too early
+                // costs a whole round trip more
+                for (int w = 0; w < hdr_delay; ++w) __builtin_amdgcn_s_sleep(1);
                 Cand<double> cb{-1.0, NONE};
                 for (;;) {
                     u32x4 h[COOP_GMAX / 64];
@@ -700,6 +708,7 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                             __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + c]), r_top, d * 16, 0, THROUGH);
                     }
                     // both rows, read again until every item carries this column's sequence number
+                    for (int w = 0; w < row_delay; ++w) __builtin_amdgcn_s_sleep(1);
                     for (;;) {
                         u32x4 uv[COOP_NB / 64], tv[COOP_NB / 64];
 #pragma unroll
@@ -855,7 +864,7 @@ template <typename T> struct Lu {
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
         if (attr != hipSuccess) return (int)attr;
         hipLaunchKernelGGL((getrf_coop_kernel<T, C::RPW, C::TPR>), dim3((unsigned)G), dim3(C::RPW * C::TPR + 64), LDS, static_cast<hipStream_t>(stream),
-                           A, lda, (int)m, (int)j0, (int)nb, ipiv, info, xch, t_lu_spin_limit);
+                           A, lda, (int)m, (int)j0, (int)nb, ipiv, info, xch, t_lu_spin_limit, t_lu_hdr_delay, t_lu_row_delay);
         return (int)hipGetLastError();
     }
 
@@ -986,6 +995,8 @@ namespace xg {
 void reset_lu_tuning() {
     t_lu_panel = -1;
     t_lu_spin_limit = 1 << 18;
+    t_lu_hdr_delay = LU_HDR_DELAY;
+    t_lu_row_delay = LU_ROW_DELAY;
 }
 }  // namespace xg
 
@@ -1007,6 +1018,13 @@ int xgemm_dgetrf_ws(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int
 
 int xgemm_sgetrf_ws(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork, void *stream) {
     return getrf_impl<float>(m, n, A, lda, ipiv, info, work, lwork, stream);
+}
+
+int xgemm_force_getrf_poll_delay(int header_sleeps, int row_sleeps) {
+    if (header_sleeps < 0 || row_sleeps < 0 || header_sleeps > 1024 || row_sleeps > 1024) return -1;
+    t_lu_hdr_delay = header_sleeps;
+    t_lu_row_delay = row_sleeps;
+    return 0;
 }
 
 int xgemm_force_getrf_spin_limit(int polls) {

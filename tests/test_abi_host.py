@@ -189,6 +189,8 @@ def test_getrf_illegal_arguments(fn):
     assert w(4, 4, P, 4, P, None, P, lw, stream=0) == -6
     assert w(4, 4, P, 4, P, P, P + 8, lw, stream=0) == -7
     assert xg.xgemm_force_getrf_spin_limit(-1) == -1 and xg.xgemm_force_getrf_spin_limit(5) == 0
+    assert xg.xgemm_force_getrf_poll_delay(-1, 0) == -1 and xg.xgemm_force_getrf_poll_delay(0, 2000) == -1
+    assert xg.xgemm_force_getrf_poll_delay(4, 4) == 0
     xg.xgemm_tuning_reset()
 
 
