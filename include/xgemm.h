@@ -277,7 +277,9 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * unit (panels taller than that go the way of xgemm_*getrf), and every wait is bounded: a workgroup that
  * does not see the others within a few tenths of a second gives up, the others follow, and *info becomes -1 (A is
  * then partly factored and must be discarded).  That can only happen when other work holds the device's
- * compute units for that long.
+ * compute units for that long; two such factorisations running at the same time on one device (different
+ * streams, different buffers) can each hold the compute units the other waits for and both time out: run
+ * them one after the other.
  * Returns as xgemm_*getrf, and -7 for a work that is not 16-byte aligned.
  */
 size_t xgemm_getrf_workspace_bytes(void);
