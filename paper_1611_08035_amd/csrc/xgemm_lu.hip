@@ -584,23 +584,32 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
     const int ui = wave * RW + lane % RW, udsub = lane / RW;
     const int urow = i0 + ui;                               // global row
     const bool has_row = !comm && ui < nrows;
-    Cand<T> mine{T(-1), NONE};
-    if (has_row && udsub == 0) {
-        const T v = abs_of(P[ui]);
-        if (v > mine.val) { mine.val = v; mine.row = urow; }
+    // The communicator's own view of the stripe: rows lane, lane + 64, ... (RPW / 64 of them).  It finds the
+    // candidates of a column itself, from what the column will hold once the pivot before is applied, with the
+    // very operations the computing waves use (scaled() and eliminated() below), so that the magnitudes it
+    // compares are those of the entries that get stored.
+    constexpr int CR = RPW / 64;
+    auto scaled = [](T x, int how, T rcp) -> T { return how == 1 ? x * rcp : (how == 2 ? x / rcp : x); };
+    auto eliminated = [](T x, T l, T u) -> T {
+        if constexpr (sizeof(T) == 8) return __builtin_fma(-l, u, x);
+        else return __builtin_fmaf(-l, u, x);
+    };
+    Cand<T> lb{T(-1), NONE};                                // communicator: the stripe's candidate for the column at hand
+    if (comm) {
+        Cand<T> mine{T(-1), NONE};
+#pragma unroll
+        for (int k = 0; k < CR; ++k) {
+            const int i = lane + 64 * k;
+            if (i < nrows) mine = better(mine, Cand<T>{abs_of(P[i]), i0 + i});
+        }
+        lb = wave_best(mine);
     }
-    T l_lag = T(0);                                         // this row's multiplier of the column before: its update is due
 
     bool aborted = false;
     int c_reached = 0;                                      // first column without a decision, if the panel is given up
     for (int c = 0; c < nb; ++c) {
         const int r = j0 + c, par = c & 1;
         const unsigned seq = (unsigned)r + 1u;
-        if (!comm) {
-            const Cand<T> wb = wave_best(mine);
-            if (lane == 0) { s_wval[wave] = wb.val; s_wrow[wave] = wb.row; }
-        }
-        __syncthreads();                                    // A: the waves' candidates for column c
         int p = r;
         int spins = 0;
         bool fail = false;
@@ -614,9 +623,6 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
             return o;
         };
         if (comm) {
-            Cand<T> lb{T(-1), NONE};
-#pragma unroll
-            for (int v = 0; v < NWC; ++v) lb = better(lb, Cand<T>{s_wval[v], s_wrow[v]});
             if (G > 1) {
                 const __amdgpu_buffer_rsrc_t r_hdr = __builtin_amdgcn_make_buffer_rsrc(x_hdr + (size_t)par * COOP_GMAX * 16, 0,
                                                                                        G * 16, 0x00020000);
@@ -661,34 +667,6 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
             } else {
                 p = lb.row == NONE ? r : __builtin_amdgcn_readfirstlane(lb.row);
             }
-        } else if (c > 0 && has_row && urow >= r) {
-            // the update that lags: columns right of c take the pivot row of column c - 1 (still in s_U), CH columns
-            // of the row at a time, all their reads issued before the first write and none of them under a branch
-            // (columns past the panel read its last column again and are not written)
-            const int e_last = (nb - 1) * LS + ui;
-            // one piece: CH columns of the row per thread (CH * TPR columns of the panel from dbase on)
-            auto piece = [&](auto ch_tag, int dbase) {
-                constexpr int CH = decltype(ch_tag)::value;
-                const int d0 = dbase + udsub, e0 = d0 * LS + ui;
-                T x[CH], uu[CH];
-#pragma unroll
-                for (int q = 0; q < CH; ++q) {
-                    const int e = e0 + q * (TPR * LS), dq = d0 + q * TPR;
-                    x[q] = P[e < e_last ? e : e_last];
-                    uu[q] = s_U[dq < nb ? dq : nb - 1];
-                }
-#pragma unroll
-                for (int q = 0; q < CH; ++q) {
-                    const int d = d0 + q * TPR;
-                    if (d < nb) P[d * LS + ui] = x[q] - l_lag * uu[q];
-                }
-            };
-            // pieces of 16 columns per thread, the last one of 8 or 4 where that covers what is left, so that the
-            // last trip does not pay for columns that are not there
-            int dbase = c + 1;
-            for (; nb - dbase > 8 * TPR; dbase += 16 * TPR) piece(std::integral_constant<int, 16>{}, dbase);
-            if (nb - dbase > 4 * TPR) piece(std::integral_constant<int, 8>{}, dbase);
-            else if (nb - dbase > 0) piece(std::integral_constant<int, 4>{}, dbase);
         }
         __syncthreads();                                    // B: the stripe is up to date with column c - 1; p is known
         if (comm) {
@@ -756,54 +734,95 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                 // what every computing thread needs of the pivot, worked out once: the column is scaled by the
                 // pivot's reciprocal as LAPACK does (one division per column; |a| <= |pivot| still gives
                 // |a * (1 / pivot)| <= 1 after rounding) unless the reciprocal would overflow
-                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): this wave's writes of s_U have landed
+                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): this wave's writes of s_U and s_top have landed
                 const T pivot = s_U[c];
                 const bool nonzero = pivot != T(0), by_rcp = abs_of(pivot) >= RcpLimit<T>::tiny();
+                const int how = !nonzero ? 0 : (by_rcp ? 1 : 2);
+                const T rcp = by_rcp ? T(1) / pivot : pivot;
                 if (lane == 0) {
                     s_p = p;
-                    s_how = !nonzero ? 0 : (by_rcp ? 1 : 2);
-                    s_rcp = by_rcp ? T(1) / pivot : pivot;
+                    s_how = how;
+                    s_rcp = rcp;
                     if (g == 0) {
                         ipiv[r] = p + 1;
                         if (!nonzero && *info == 0) *info = r + 1;
                     }
                 }
+                // the candidates of column c + 1: what its entries below row r will be once this pivot is applied
+                // (the row that takes the old row r is read from s_top, as the computing waves will do)
+                Cand<T> mine{T(-1), NONE};
+                if (c + 1 < nb) {
+                    const T u1 = s_U[c + 1], t0 = s_top[c], t1 = s_top[c + 1];
+#pragma unroll
+                    for (int k = 0; k < CR; ++k) {
+                        const int i = lane + 64 * k, row = i0 + i;
+                        if (i < nrows && row > r) {
+                            const bool moved = row == p;    // p != r here: row > r
+                            const T xc = moved ? t0 : P[c * LS + i], x1 = moved ? t1 : P[(c + 1) * LS + i];
+                            const T y = eliminated(x1, scaled(xc, how, rcp), u1);
+                            mine = better(mine, Cand<T>{abs_of(y), row});
+                        }
+                    }
+                }
+                lb = wave_best(mine);
             }
         }
-        __syncthreads();                                    // C: pivot row and row r in LDS
+        __syncthreads();                                    // C: pivot row and row r in LDS, what to do with them known
         if (s_abort) { aborted = true; c_reached = c; break; }
         if (comm) continue;
+        // the computing waves apply the pivot: the two rows change places, the column is scaled, the columns on its
+        // right are updated; the communicator is already exchanging the candidates of the next column
         p = s_p;
         const int how = s_how;
         const T rcp = s_rcp;                                // the reciprocal, or the pivot itself where that would overflow
         const bool exchange = p != r;
         if (exchange && tid < nb) {
-            // row r (local row c of workgroup 0) becomes the pivot row; the old row r goes where the pivot was,
-            // except in columns c and c + 1, which the owners of that row take from s_top below
+            // row r (local row c of workgroup 0) becomes the pivot row; the old row r goes where the pivot was: its
+            // part left of column c here, the rest as the update below passes over that row
             if (g == 0) P[tid * LS + c] = s_U[tid];
             const int ip = p - i0;
-            if (ip >= 0 && ip < RPW && tid != c && tid != c + 1) P[tid * LS + ip] = s_top[tid];
+            if (ip >= 0 && ip < RPW && tid < c) P[tid * LS + ip] = s_top[tid];
         }
-        mine.val = T(-1);
-        mine.row = NONE;
         if (has_row && urow > r) {
             const bool moved = exchange && urow == p;
-            T l = moved ? s_top[c] : P[c * LS + ui];
-            T x1 = T(0);
-            if (c + 1 < nb) x1 = moved ? s_top[c + 1] : P[(c + 1) * LS + ui];
-            if (how == 1) l = l * rcp;
-            else if (how == 2) l = l / rcp;
-            l_lag = l;
+            const T l = scaled(moved ? s_top[c] : P[c * LS + ui], how, rcp);
             __builtin_amdgcn_wave_barrier();                // every thread of the row has read before one writes
-            if (udsub == 0) {
-                P[c * LS + ui] = l;
-                if (c + 1 < nb) {
-                    const T y = x1 - l * s_U[c + 1];
-                    P[(c + 1) * LS + ui] = y;
-                    const T v = abs_of(y);
-                    if (v > mine.val) { mine.val = v; mine.row = urow; }
+            if (udsub == 0) P[c * LS + ui] = l;
+            const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0ull;
+            const int e_last = (nb - 1) * LS + ui;
+            // one piece: CH columns of the row per thread (CH * TPR columns of the panel from dbase on), all their
+            // reads issued before the first write and none of them under a branch (columns past the panel read its
+            // last column again and are not written)
+            auto piece = [&](auto ch_tag, int dbase) {
+                constexpr int CH = decltype(ch_tag)::value;
+                const int d0 = dbase + udsub, e0 = d0 * LS + ui;
+                T x[CH], uu[CH];
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int e = e0 + q * (TPR * LS), dq = d0 + q * TPR;
+                    x[q] = P[e < e_last ? e : e_last];
+                    uu[q] = s_U[dq < nb ? dq : nb - 1];
                 }
-            }
+                if (any_moved) {
+#pragma unroll
+                    for (int q = 0; q < CH; ++q) {
+                        const int dq = d0 + q * TPR;
+                        const T tv = s_top[dq < nb ? dq : nb - 1];
+                        x[q] = moved ? tv : x[q];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int d = d0 + q * TPR;
+                    if (d < nb) P[d * LS + ui] = eliminated(x[q], l, uu[q]);
+                }
+            };
+            // pieces of 16 columns per thread, the last one of 8 or 4 where that covers what is left, so that the
+            // last trip does not pay for columns that are not there
+            int dbase = c + 1;
+            for (; nb - dbase > 8 * TPR; dbase += 16 * TPR) piece(std::integral_constant<int, 16>{}, dbase);
+            if (nb - dbase > 4 * TPR) piece(std::integral_constant<int, 8>{}, dbase);
+            else if (nb - dbase > 0) piece(std::integral_constant<int, 4>{}, dbase);
         }
     }
     __syncthreads();
