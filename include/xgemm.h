@@ -265,7 +265,7 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * The same factorisation with a caller-owned exchange buffer, which lets all workgroups that the rows of a
  * panel need factor it together (xgemm_*getrf factors a panel's leaves on one compute unit at a time while
  * the rest of the device waits): the rows of a panel of 128 columns are dealt to workgroups in stripes of 128
- * (fp64) or 256 (fp32) rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
+ * rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
  * of a column is agreed by every workgroup alike from the candidates (magnitude and row) that all of them
  * publish in `work`, where the pivot's owner then leaves the pivot row for the others.  Same semantics, same pivot rule and the same statement about the
  * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.

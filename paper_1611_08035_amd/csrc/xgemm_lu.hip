@@ -511,7 +511,7 @@ constexpr int COOP_INFO_TIMEOUT = -1;
 
 template <typename T> struct CoopCfg;
 template <> struct CoopCfg<double> { static constexpr int RPW = 128, TPR = 4; };
-template <> struct CoopCfg<float> { static constexpr int RPW = 256, TPR = 2; };
+template <> struct CoopCfg<float> { static constexpr int RPW = 128, TPR = 4; };
 
 // the whole exchange memory to zero: no slot carries a sequence number of an earlier factorisation
 __global__ void __launch_bounds__(256) coop_clear_kernel(uint4 *xch) {
