@@ -266,10 +266,10 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * panel need factor it together (xgemm_*getrf factors a panel's leaves on one compute unit at a time while
  * the rest of the device waits): the rows of a panel of 128 columns are dealt to workgroups in stripes of 128
  * rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
- * of a column is agreed by every workgroup alike from the candidates (magnitude and row) that all of them
- * publish in `work`, where the pivot's owner then leaves the pivot row for the others.  Same semantics, same pivot rule and the same statement about the
+ * of a column is agreed by every workgroup alike from the candidates (magnitude, row and the whole
+ * candidate row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
  * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
- *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 16 KiB); its
+ *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 1 MiB); its
  *          contents need no preparation and are undefined afterwards.  Calls that share it must not
  *          overlap in time.  NULL or too small: the call runs exactly as xgemm_*getrf.
  * The workgroups of a panel wait for each other (the only place in the library where a workgroup waits for

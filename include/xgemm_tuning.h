@@ -83,8 +83,7 @@ int xgemm_force_getrf_spin_limit(int polls);
 
 /* Benchmark control of xgemm_*getrf_ws on the calling thread: how long a workgroup of a shared panel waits
  * after publishing before it first looks for the others' headers resp. for the pivot row, in sleeps of 64
- * clocks (0 .. 1024 each; defaults 18 and 13, about the time a published item takes to become visible to
- * another workgroup).  Returns 0, or -1 for a value out of range. */
+ * clocks (0 .. 1024 each; default 0 for both: the items are published well ahead of the first look).  Returns 0, or -1 for a value out of range. */
 int xgemm_force_getrf_poll_delay(int header_sleeps, int row_sleeps);
 
 /*

@@ -37,10 +37,10 @@ constexpr int LEAF_WAVES = LEAF_NT / 64;
 template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : (w == 2 ? 56 : 64); }
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
-// First look of a poll put off by this many 64-clock sleeps: what a published item takes to become visible to a
-// load that another workgroup issues (a look that comes too early costs a whole round trip more; swept on the
-// device, flat between 16 and 20 for the headers and between 10 and 16 for the rows).
-constexpr int LU_HDR_DELAY = 18, LU_ROW_DELAY = 13;
+// First look of a poll put off by this many 64-clock sleeps.  While headers and rows were published right before
+// they were polled for, a look that came too early cost a whole round trip more and 18 resp. 13 sleeps paid
+// (52.5 -> 48.1 ms at 8192); since both are published a barrier ahead of the poll, no delay is best.
+constexpr int LU_HDR_DELAY = 0, LU_ROW_DELAY = 0;
 thread_local int t_lu_hdr_delay = LU_HDR_DELAY, t_lu_row_delay = LU_ROW_DELAY;
 thread_local int t_lu_spin_limit = 1 << 18;   // polls a workgroup of a shared panel waits for the others (about a microsecond each)
 
@@ -477,23 +477,29 @@ __global__ void __launch_bounds__(LEAF_NT) getf2_kernel(T *A, int64_t lda, int m
 // rows, each workgroup keeps its stripe in LDS for the whole panel, and the one decision per column that
 // concerns all of them, the pivot, is taken by every workgroup alike from G candidates exchanged through
 // memory.  A workgroup has RPW * TPR computing threads (TPR threads per row, lanes of one wave) and one more
-// wave, the communicator, that talks to the other workgroups while the computing waves work.  Column c
-// (row r = j0 + c, sequence number r + 1) goes through three barriers:
-//   - the computing waves reduce their candidates for column c (largest magnitude, smallest row among equals;
-//     found when column c was last updated) to one per wave;                                        barrier A
-//   - the communicator publishes the workgroup's candidate {magnitude, row, sequence number} and polls the G
-//     headers until all carry this column's number, which gives the pivot row p to every workgroup alike;
-//     meanwhile the computing waves bring the columns right of c up to date with the pivot row of column
-//     c - 1 (that update lags one column behind, so that it runs while the headers travel);           barrier B
-//   - the stripe is now up to date: p's owner publishes row p, workgroup 0 (which owns row r) publishes row r,
-//     every communicator fetches both into LDS;                                                    barrier C
-//   - the computing waves exchange the two rows inside the stripes that hold them, scale column c, update
-//     column c + 1 alone and look for its largest entry: the candidates of the next column.
+// wave, the communicator, that talks to the other workgroups while the computing waves work.  For column c
+// (row r = j0 + c, sequence number r + 1):
+//   - the communicator polls the G headers {magnitude, row, sequence number} of column c until all carry
+//     this column's number, which gives the pivot row p to every workgroup alike (largest magnitude, smallest
+//     row among equals), and fetches the row that p's owner published with its header and the row r that
+//     workgroup 0 published, into LDS; meanwhile the computing waves are still applying the pivot of column
+//     c - 1 to their stripe;                                                                        barrier B
+//   - the stripe is up to date with column c - 1.  The communicator works out what all threads need of the
+//     pivot (how to scale, the reciprocal), writes ipiv and info (workgroup 0), and then, for column c + 1,
+//     from what the stripe WILL hold once pivot c is applied (computed with the very operations the computing
+//     waves use, scaled() and eliminated(), so that the magnitudes it compares are those of the entries that
+//     get stored): the stripe's candidate, which it publishes at once, then the candidate's whole row and
+//     (workgroup 0) the row that will be row r + 1, which it publishes too;                          barrier C
+//   - the computing waves apply pivot c: rows r and p change places inside the stripes that hold them, the
+//     column is scaled, the columns on its right are updated, while the communicator is already polling
+//     for column c + 1.
+// So a column costs the other workgroups' store-to-load latency once (header and row travel together) plus
+// what the communicator computes between the barriers, and the update of the stripe runs beside the exchange.
 // Every published item is one aligned 16-byte store that carries the column's sequence number beside its
 // value; a reader tells by itself whether what it read belongs to this column, so nothing waits for an
 // acknowledgement.  The exchange memory is written through to memory and read around the caches (the L2s of
 // different XCDs are not coherent with each other).  Slots alternate with the parity of c: whoever publishes
-// for column c + 2 has seen every header of column c + 1, whose owners had finished reading column c.
+// for column c + 1 has seen every header of column c, whose owners had finished reading column c - 1.
 // Sequence numbers are unique within a factorisation and the exchange memory is cleared when it starts, so a
 // stale slot never matches.  Every wait is bounded: a communicator that does not see what it waits for
 // within `spin_limit` polls raises a flag in the exchange memory and gives up; whoever sees the flag gives up
@@ -505,7 +511,7 @@ constexpr int COOP_NB = 128;              // widest shared panel
 constexpr size_t COOP_FLAG_BYTES = 256;   // the time-out flag (first word)
 constexpr size_t COOP_HDR_BYTES = 2 * (size_t)COOP_GMAX * 16;
 constexpr size_t COOP_ROW_BYTES = 2 * (size_t)COOP_NB * 16;                 // elements travel as {value, sequence number}
-constexpr size_t COOP_BYTES = COOP_FLAG_BYTES + COOP_HDR_BYTES + 2 * COOP_ROW_BYTES;   // flag, headers, pivot row, row r
+constexpr size_t COOP_BYTES = COOP_FLAG_BYTES + COOP_HDR_BYTES + (COOP_GMAX + 1) * COOP_ROW_BYTES;   // flag, headers, a candidate row per workgroup, row r
 constexpr int THROUGH = 17;               // cache policy bits sc0 | sc1: system scope
 constexpr int COOP_INFO_TIMEOUT = -1;
 
@@ -515,7 +521,7 @@ template <> struct CoopCfg<float> { static constexpr int RPW = 128, TPR = 4; };
 
 // the whole exchange memory to zero: no slot carries a sequence number of an earlier factorisation
 __global__ void __launch_bounds__(256) coop_clear_kernel(uint4 *xch) {
-    for (unsigned i = threadIdx.x; i < COOP_BYTES / 16; i += 256) xch[i] = uint4{0u, 0u, 0u, 0u};
+    for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < COOP_BYTES / 16; i += gridDim.x * 256) xch[i] = uint4{0u, 0u, 0u, 0u};
 }
 
 template <typename T, int RPW, int TPR>
@@ -532,9 +538,7 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     extern __shared__ __align__(16) unsigned char coop_lds[];
     T *const P = reinterpret_cast<T *>(coop_lds);          // P[d * LS + i]: column d, local row i
-    __shared__ T s_U[COOP_NB], s_top[COOP_NB];
-    __shared__ T s_wval[NWC];
-    __shared__ int s_wrow[NWC];
+    __shared__ T s_Ub[2][COOP_NB], s_topb[2][COOP_NB];      // pivot row and old row r, by the parity of the column
     __shared__ int s_p, s_abort, s_how;                     // s_how: 0 pivot is zero, 1 scale by s_rcp, 2 divide
     __shared__ T s_rcp;
 
@@ -546,8 +550,8 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
 
     // exchange memory
     unsigned char *const x_hdr = xch + COOP_FLAG_BYTES;
-    unsigned char *const x_win = x_hdr + COOP_HDR_BYTES;
-    unsigned char *const x_top = x_win + COOP_ROW_BYTES;
+    unsigned char *const x_top = x_hdr + COOP_HDR_BYTES;                   // [parity][column]
+    unsigned char *const x_rows = x_top + COOP_ROW_BYTES;                  // [workgroup][parity][column]
     const __amdgpu_buffer_rsrc_t r_flag = __builtin_amdgcn_make_buffer_rsrc(xch, 0, 4, 0x00020000);
 
     // the stripe as one range-checked buffer: rows past the end of the matrix get an offset outside it (they read
@@ -594,7 +598,40 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
         if constexpr (sizeof(T) == 8) return __builtin_fma(-l, u, x);
         else return __builtin_fmaf(-l, u, x);
     };
-    Cand<T> lb{T(-1), NONE};                                // communicator: the stripe's candidate for the column at hand
+    // The communicator publishes, for the column that comes next, the stripe's candidate {magnitude, row, sequence
+    // number}, the candidate's whole row and (workgroup 0) the row that will be row r, all as they will be once the
+    // pivot at hand is applied: it works them out itself while the computing waves have not started on that pivot.
+    // rowv / topv: this lane's two elements (columns lane and lane + 64) of those rows.
+    Cand<T> lb{T(-1), NONE};
+    T rowv[COOP_NB / 64], topv[COOP_NB / 64];
+    auto publish = [&](int cn, bool header, bool rows) {    // for column cn: the header first, the rows when they are worked out
+        if (G == 1) return;
+        const int parn = cn & 1;
+        const unsigned seqn = (unsigned)(j0 + cn) + 1u;
+        auto item = [&](double v, unsigned w2, unsigned w3) -> u32x4 {
+            const u32x2 w = __builtin_bit_cast(u32x2, v);
+            u32x4 o;
+            o[0] = w[0];
+            o[1] = w[1];
+            o[2] = w2;
+            o[3] = w3;
+            return o;
+        };
+        const __amdgpu_buffer_rsrc_t r_hdr = __builtin_amdgcn_make_buffer_rsrc(x_hdr + (size_t)parn * COOP_GMAX * 16, 0, G * 16, 0x00020000);
+        const __amdgpu_buffer_rsrc_t r_mine = __builtin_amdgcn_make_buffer_rsrc(x_rows + ((size_t)g * 2 + parn) * COOP_NB * 16, 0,
+                                                                                COOP_NB * 16, 0x00020000);
+        const __amdgpu_buffer_rsrc_t r_top = __builtin_amdgcn_make_buffer_rsrc(x_top + (size_t)parn * COOP_NB * 16, 0, COOP_NB * 16,
+                                                                               0x00020000);
+        if (header && lane == 0) __builtin_amdgcn_raw_buffer_store_b128(item((double)lb.val, (unsigned)lb.row, seqn), r_hdr, g * 16, 0, THROUGH);
+#pragma unroll
+        for (int q = 0; q < COOP_NB / 64; ++q) {
+            const int d = lane + 64 * q;
+            if (rows && d < nb) {
+                __builtin_amdgcn_raw_buffer_store_b128(item((double)rowv[q], seqn, 0u), r_mine, d * 16, 0, THROUGH);
+                if (g == 0) __builtin_amdgcn_raw_buffer_store_b128(item((double)topv[q], seqn, 0u), r_top, d * 16, 0, THROUGH);
+            }
+        }
+    };
     if (comm) {
         Cand<T> mine{T(-1), NONE};
 #pragma unroll
@@ -603,6 +640,14 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
             if (i < nrows) mine = better(mine, Cand<T>{abs_of(P[i]), i0 + i});
         }
         lb = wave_best(mine);
+        const int ib = lb.row == NONE ? -1 : lb.row - i0;
+#pragma unroll
+        for (int q = 0; q < COOP_NB / 64; ++q) {
+            const int d = lane + 64 * q;
+            rowv[q] = (ib >= 0 && d < nb) ? P[d * LS + ib] : T(0);
+            topv[q] = d < nb ? P[d * LS] : T(0);
+        }
+        publish(0, true, true);
     }
 
     bool aborted = false;
@@ -610,28 +655,14 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
     for (int c = 0; c < nb; ++c) {
         const int r = j0 + c, par = c & 1;
         const unsigned seq = (unsigned)r + 1u;
+        T *const s_U = s_Ub[par], *const s_top = s_topb[par];
         int p = r;
         int spins = 0;
         bool fail = false;
-        auto item = [&](double v) -> u32x4 {
-            const u32x2 w = __builtin_bit_cast(u32x2, v);
-            u32x4 o;
-            o[0] = w[0];
-            o[1] = w[1];
-            o[2] = seq;
-            o[3] = 0u;
-            return o;
-        };
         if (comm) {
             if (G > 1) {
                 const __amdgpu_buffer_rsrc_t r_hdr = __builtin_amdgcn_make_buffer_rsrc(x_hdr + (size_t)par * COOP_GMAX * 16, 0,
                                                                                        G * 16, 0x00020000);
-                if (lane == 0) {
-                    u32x4 h = item((double)lb.val);
-                    h[2] = (unsigned)lb.row;
-                    h[3] = seq;
-                    __builtin_amdgcn_raw_buffer_store_b128(h, r_hdr, g * 16, 0, THROUGH);
-                }
                 // poll: lane l looks at the headers l, l + 64, l + 128, l + 192 (past G: outside the buffer).  The first
                 // look is put off by the time a published item takes to become visible: a look that comes too early
                 // costs a whole round trip more
@@ -662,36 +693,22 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                 if (!fail) {
                     cb = wave_best(cb);
                     const int best_row = __builtin_amdgcn_readfirstlane(cb.row);
-                    p = best_row == NONE ? r : best_row;    // no candidate anywhere (a column of NaNs): row r stays
-                }
-            } else {
-                p = lb.row == NONE ? r : __builtin_amdgcn_readfirstlane(lb.row);
-            }
-        }
-        __syncthreads();                                    // B: the stripe is up to date with column c - 1; p is known
-        if (comm) {
-            if (!fail) {
-                if (G > 1) {
-                    const __amdgpu_buffer_rsrc_t r_win = __builtin_amdgcn_make_buffer_rsrc(x_win + (size_t)par * COOP_NB * 16, 0,
+                    const bool nobody = best_row == NONE;   // no candidate anywhere (a column of NaNs): row r stays
+                    p = nobody ? r : best_row;
+                    const int gp = (p - j0) / RPW;
+                    const __amdgpu_buffer_rsrc_t r_win = __builtin_amdgcn_make_buffer_rsrc(x_rows + ((size_t)gp * 2 + par) * COOP_NB * 16, 0,
                                                                                            COOP_NB * 16, 0x00020000);
                     const __amdgpu_buffer_rsrc_t r_top = __builtin_amdgcn_make_buffer_rsrc(x_top + (size_t)par * COOP_NB * 16, 0,
                                                                                            COOP_NB * 16, 0x00020000);
-                    const int ip = p - i0;
-                    if (ip >= 0 && ip < RPW) {
-                        for (int d = lane; d < nb; d += 64)
-                            __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + ip]), r_win, d * 16, 0, THROUGH);
-                    }
-                    if (g == 0) {
-                        for (int d = lane; d < nb; d += 64)
-                            __builtin_amdgcn_raw_buffer_store_b128(item((double)P[d * LS + c]), r_top, d * 16, 0, THROUGH);
-                    }
-                    // both rows, read again until every item carries this column's sequence number
+                    const __amdgpu_buffer_rsrc_t r_u = nobody ? r_top : r_win;
+                    // the pivot's row as its owner published it with its header, and row r: read again until every
+                    // item carries this column's sequence number
                     for (int w = 0; w < row_delay; ++w) __builtin_amdgcn_s_sleep(1);
                     for (;;) {
                         u32x4 uv[COOP_NB / 64], tv[COOP_NB / 64];
 #pragma unroll
                         for (int q = 0; q < COOP_NB / 64; ++q) {
-                            uv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_win, (lane + 64 * q) * 16, 0, THROUGH);
+                            uv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_u, (lane + 64 * q) * 16, 0, THROUGH);
                             tv[q] = (u32x4)__builtin_amdgcn_raw_buffer_load_b128(r_top, (lane + 64 * q) * 16, 0, THROUGH);
                         }
                         const unsigned fl = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(r_flag, 0, 0, THROUGH);
@@ -718,13 +735,22 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                         if (++spins > spin_limit || __builtin_amdgcn_readfirstlane((int)fl) != 0) { fail = true; break; }
                         __builtin_amdgcn_s_sleep(1);
                     }
-                } else {
-                    for (int d = lane; d < nb; d += 64) {
-                        s_U[d] = P[d * LS + (p - i0)];
-                        s_top[d] = P[d * LS + c];
+                }
+            } else {
+                // one workgroup: its own candidate is the pivot, the rows are in this wave's registers
+                p = lb.row == NONE ? r : __builtin_amdgcn_readfirstlane(lb.row);
+#pragma unroll
+                for (int q = 0; q < COOP_NB / 64; ++q) {
+                    const int d = lane + 64 * q;
+                    if (d < nb) {
+                        s_U[d] = lb.row == NONE ? topv[q] : rowv[q];
+                        s_top[d] = topv[q];
                     }
                 }
             }
+        }
+        __syncthreads();                                    // B: the stripe is up to date with column c - 1
+        if (comm) {
             if (fail) {
                 if (lane == 0) {
                     __builtin_amdgcn_raw_buffer_store_b32(1u, r_flag, 0, 0, THROUGH);
@@ -748,23 +774,35 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                         if (!nonzero && *info == 0) *info = r + 1;
                     }
                 }
-                // the candidates of column c + 1: what its entries below row r will be once this pivot is applied
-                // (the row that takes the old row r is read from s_top, as the computing waves will do)
-                Cand<T> mine{T(-1), NONE};
                 if (c + 1 < nb) {
-                    const T u1 = s_U[c + 1], t0 = s_top[c], t1 = s_top[c + 1];
+                    // A row of the stripe as it will be once this pivot is applied, in column d (the row that takes
+                    // the old row r is read from s_top, as the computing waves will do).
+                    const T t0 = s_top[c];
+                    auto after = [&](int i, int d) -> T {
+                        const bool moved = i0 + i == p && p != r;
+                        const T xd = moved ? s_top[d] : P[d * LS + i];
+                        if (d < c) return xd;
+                        const T l = scaled(moved ? t0 : P[c * LS + i], how, rcp);
+                        return d == c ? l : eliminated(xd, l, s_U[d]);
+                    };
+                    // the candidates of column c + 1 among the rows below row r
+                    Cand<T> mine{T(-1), NONE};
 #pragma unroll
                     for (int k = 0; k < CR; ++k) {
                         const int i = lane + 64 * k, row = i0 + i;
-                        if (i < nrows && row > r) {
-                            const bool moved = row == p;    // p != r here: row > r
-                            const T xc = moved ? t0 : P[c * LS + i], x1 = moved ? t1 : P[(c + 1) * LS + i];
-                            const T y = eliminated(x1, scaled(xc, how, rcp), u1);
-                            mine = better(mine, Cand<T>{abs_of(y), row});
-                        }
+                        if (i < nrows && row > r) mine = better(mine, Cand<T>{abs_of(after(i, c + 1)), row});
                     }
+                    lb = wave_best(mine);
+                    publish(c + 1, true, false);
+                    const int ib = lb.row == NONE ? -1 : __builtin_amdgcn_readfirstlane(lb.row) - i0;
+#pragma unroll
+                    for (int q = 0; q < COOP_NB / 64; ++q) {
+                        const int d = lane + 64 * q;
+                        rowv[q] = (ib >= 0 && d < nb) ? after(ib, d) : T(0);
+                        topv[q] = (g == 0 && d < nb) ? after(c + 1, d) : T(0);       // row r + 1 is local row c + 1 of workgroup 0
+                    }
+                    publish(c + 1, false, true);
                 }
-                lb = wave_best(mine);
             }
         }
         __syncthreads();                                    // C: pivot row and row r in LDS, what to do with them known
@@ -1001,7 +1039,7 @@ int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, vo
         int dev = 0;
         if ((rc = (int)hipGetDevice(&dev))) return rc;
         if ((rc = (int)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev))) return rc;
-        hipLaunchKernelGGL(coop_clear_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
+        hipLaunchKernelGGL(coop_clear_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
         if ((rc = (int)hipGetLastError())) return rc;
     }
     const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu};
