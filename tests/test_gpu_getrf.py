@@ -187,3 +187,25 @@ def test_a_wait_that_times_out_ends_the_call_with_info_minus_one():
     assert info == 0
     I, J = si.sample_indices(rng, n, n, 8, 8, 1 << 12)
     check_valid(n, n, A, n, F, n, ipiv, oracle.U64, I=I, J=J)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_tall_panels_up_to_one_workgroup_per_compute_unit_and_beyond(dtype):
+    """Shared panels of 157, 256 (every compute unit of the device holds a stripe) and 258 stripes (more than
+    the device has compute units: that panel goes the way of the leaves, the later ones are shared again):
+    in fp64 the same interchanges as the oracle and the factors to rounding; the validity statement on sampled
+    rows and columns."""
+    u = unit_roundoff(dtype)
+    for m, n in [(20000, 200), (32768, 130), (33000, 260)]:
+        rng = si.rng_for(317, m)
+        A = si.uniform(rng, m, n, m, dtype)
+        F, ipiv, info = run_getrf(m, n, A, m, ws=True)
+        assert info == 0
+        if dtype == np.float64:       # (in fp32 the two largest of 33000 entries are within a rounding often enough)
+            W = A.copy()
+            oinfo, opiv = oracle.getrf(m, n, W, m)
+            assert oinfo == 0 and np.array_equal(ipiv, opiv), (m, n)
+            tol = 64 * n * u * max(1.0, float(np.abs(W).max()))
+            assert np.allclose(F, W, rtol=0.0, atol=tol), (m, n)
+        I, J = si.sample_indices(rng, m, n, 8, 8, 1 << 12)
+        check_valid(m, n, A, m, F, m, ipiv, u, I=I, J=J)
