@@ -886,15 +886,17 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
 }
 
 // Row interchanges k = k0 .. k1 - 1 (row k with row ipiv[k] - 1, in that order) applied to columns
-// [c0, c1) of A: 64 columns per workgroup, one per thread, 32 interchanges per batch.
-constexpr int SWAP_G = 32, SWAP_NT = 64;
+// [c0, c1) of A: 32 columns per workgroup of one wave, one per thread (twice the workgroups of 64 columns each, so
+// that every compute unit has one: the accesses are scattered lines, and the more units ask the better), 32
+// interchanges per batch.
+constexpr int SWAP_G = 32, SWAP_NT = 64, SWAP_COLS = 32;   // a wave per workgroup (its lanes are the slots of a batch), SWAP_COLS columns
 template <typename T>
 __global__ void __launch_bounds__(SWAP_NT) laswp_kernel(T *A, int64_t lda, int c0, int c1, int k0, int k1, const int *ipiv) {
-    __shared__ SwapLds<T, SWAP_G, SWAP_NT> s_swap;
-    const int tid = threadIdx.x, c = c0 + blockIdx.x * SWAP_NT + tid;
+    __shared__ SwapLds<T, SWAP_G, SWAP_COLS> s_swap;
+    const int tid = threadIdx.x, c = tid < SWAP_COLS ? c0 + blockIdx.x * SWAP_COLS + tid : c1;
     T *const col = c < c1 ? A + (int64_t)c * lda : nullptr;
     for (int k = k0; k < k1; k += SWAP_G)
-        swap_batch<T, SWAP_G, SWAP_NT>(s_swap, col, k, ipiv + k, -1, (k1 - k) < SWAP_G ? (k1 - k) : SWAP_G, tid);
+        swap_batch<T, SWAP_G, SWAP_COLS>(s_swap, col, k, ipiv + k, -1, (k1 - k) < SWAP_G ? (k1 - k) : SWAP_G, tid);
 }
 
 __global__ void clear_int_kernel(int *p) { *p = 0; }
@@ -930,7 +932,7 @@ template <typename T> struct Lu {
 
     int swap_rows(int64_t c0, int64_t c1, int64_t k0, int64_t k1) const {
         if (c1 <= c0 || k1 <= k0) return 0;
-        hipLaunchKernelGGL(laswp_kernel<T>, dim3((unsigned)((c1 - c0 + SWAP_NT - 1) / SWAP_NT)), dim3(SWAP_NT), 0,
+        hipLaunchKernelGGL(laswp_kernel<T>, dim3((unsigned)((c1 - c0 + SWAP_COLS - 1) / SWAP_COLS)), dim3(SWAP_NT), 0,
                            static_cast<hipStream_t>(stream), A, lda, (int)c0, (int)c1, (int)k0, (int)k1, ipiv);
         return (int)hipGetLastError();
     }
