@@ -61,3 +61,41 @@ def test_captured_chain_replays_bit_identically():
         assert torch.equal(C, want_C) and torch.equal(S, want_S), f"replay {rep} differs from the eager run"
         assert int(info.item()) == 0
         del scratch
+
+
+def test_captured_lu_with_shared_panels_replays_bit_identically():
+    """xgemm_dgetrf_ws enqueues kernels only (the exchange buffer is cleared by a kernel, the workgroups of a
+    panel wait for each other inside one kernel), so it can be captured too; every replay gives the eager bits."""
+    torch = torch_mod()
+    xg.xgemm_tuning_reset()
+    rng = si.rng_for(191, 0)
+    n = 1100
+    A0 = to_dev(si.uniform(rng, n, n))
+    A = A0.clone()
+    piv = torch.zeros(n, dtype=torch.int32, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    lw = xg.xgemm_getrf_workspace_bytes()
+    work = torch.empty(lw, dtype=torch.uint8, device="cuda")
+
+    def step():
+        assert xg.xgemm_dgetrf_ws(n, n, A, n, piv, info, work, lw) == 0
+
+    step()
+    torch.cuda.synchronize()
+    want_A, want_piv = A.clone(), piv.clone()
+    assert int(info.item()) == 0
+    graph = torch.cuda.CUDAGraph()
+    A.copy_(A0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        A.copy_(A0)
+        piv.fill_(-3)
+        info.fill_(7)
+        work.fill_(rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(A, want_A) and torch.equal(piv, want_piv), f"replay {rep} differs from the eager run"
+        assert int(info.item()) == 0
