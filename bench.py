@@ -526,7 +526,7 @@ def sweep(torch, np, xg, si, args):
     # LU: the panels' leaves on one workgroup each (xgemm_*getrf), and the panels shared by all the workgroups
     # their rows need, through an exchange buffer (xgemm_*getrf_ws)
     for prec, nsz, ws in (("d", 4096, 0), ("d", 8192, 0), ("d", 16384, 0), ("s", 8192, 0),
-                          ("d", 4096, 1), ("d", 8192, 1), ("d", 16384, 1), ("s", 8192, 1), ("s", 16384, 1)):
+                          ("d", 4096, 1), ("d", 8192, 1), ("d", 16384, 1), ("d", 32768, 1), ("s", 8192, 1), ("s", 16384, 1)):
         name = f"{prec}getrf{'_ws' if ws else ''} {nsz}"
         if not want(name):
             continue

@@ -268,7 +268,9 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
  * of a column is agreed by every workgroup alike from the candidates (magnitude, row and the whole
  * candidate row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
- * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
+ * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.  The matrix is not swept
+ * in panels here but halved recursively as a whole down to shared panels of 128 columns (deepest products,
+ * interchanges applied to as few columns as possible), unless it has more rows than shared panels can hold.
  *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 1 MiB); its
  *          contents need no preparation and are undefined afterwards.  Calls that share it must not
  *          overlap in time.  NULL or too small: the call runs exactly as xgemm_*getrf.

@@ -970,10 +970,28 @@ template <typename T> struct Lu {
         }
     }
     int panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
+        int rc;
+        if (xch) {
+            // with exchange memory the leaves of the halving are shared panels of up to COOP_NB columns; such a leaf
+            // leaves its interchanges to be applied to the other columns of the enclosing panel here
+            if (w <= COOP_NB) {
+                rc = coop_panel(j0, w);
+                if (rc == 0) {
+                    if ((rc = swap_rows(c_lo, j0, j0, j0 + w))) return rc;
+                    return swap_rows(j0 + w, c_hi, j0, j0 + w);
+                }
+                if (rc != 1) return rc;       // 1: not taken (too tall); the leaves of one workgroup below
+            } else {
+                const int64_t w1 = ((w / 2 + COOP_NB - 1) / COOP_NB) * COOP_NB, w2 = w - w1, j1 = j0 + w1;
+                if ((rc = panel(j0, w1, c_lo, c_hi))) return rc;
+                if ((rc = trsm(w1, w2, A + j0 + j0 * lda, A + j0 + j1 * lda))) return rc;
+                if (m > j1 && (rc = gemm(m - j1, w2, w1, A + j1 + j0 * lda, A + j0 + j1 * lda, A + j1 + j1 * lda))) return rc;
+                return panel(j1, w2, c_lo, c_hi);
+            }
+        }
         const int64_t lw = leaf_width(j0);
         if (w <= lw) return any_leaf(j0, w, c_lo, c_hi, 0, 0);
         const int64_t w1 = ((w / 2 + lw - 1) / lw) * lw, w2 = w - w1, j1 = j0 + w1;
-        int rc;
         // Two leaves side by side, both in registers: the left one leaves the block row of U for the right one
         // behind (post), the right one applies the left one's update as it loads (pre), and neither the solve nor
         // the product between them is launched.
@@ -992,13 +1010,17 @@ template <typename T> struct Lu {
 
     int run() const {
         const int64_t steps = min64(m, n);
-        const int64_t W = t_lu_panel > 0 ? t_lu_panel : ((xch || steps >= 4096) ? 128 : 64);
+        // With exchange memory the whole matrix is one panel, halved down to shared panels of COOP_NB columns: the
+        // products between the halves are as deep as they can be and interchanges are applied level by level to as few
+        // columns as possible (dgetrf_ws 16384 139 -> 127 ms, 32768 677 -> 521 against a sweep over panels of 128
+        // columns; no difference at 8192).  Only a matrix too tall for shared panels from its first column on is swept,
+        // because leaves of one workgroup carry their interchanges through their whole panel.
+        const bool all_shared = xch && m <= (int64_t)ncu * CoopCfg<T>::RPW && m <= (int64_t)COOP_GMAX * CoopCfg<T>::RPW;
+        const int64_t W = t_lu_panel > 0 ? t_lu_panel : (all_shared ? max64(steps, 1) : ((xch || steps >= 4096) ? 128 : 64));
         int rc;
         for (int64_t j = 0; j < steps; j += W) {
             const int64_t nb = min64(W, steps - j), j1 = j + nb;
-            rc = coop_panel(j, nb);
-            if (rc == 1) rc = panel(j, nb, j, j1);
-            if (rc) return rc;
+            if ((rc = panel(j, nb, j, j1))) return rc;
             if ((rc = swap_rows(0, j, j, j1))) return rc;
             if (j1 < n) {
                 if ((rc = swap_rows(j1, n, j, j1))) return rc;
