@@ -249,11 +249,9 @@ int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *s
  * 1-based: at step j, row j changed places with row ipiv[j] >= j; the pivot of a column is
  * the first of its entries of largest magnitude.  `info` (DEVICE int, written on the
  * stream): 0, or j > 0 if U(j,j) is exactly zero (the first such j; the factorisation is
- * completed all the same, as in LAPACK).  Right-looking over panels of 64 or 128 columns;
- * a panel is halved recursively onto xgemm_*trsm and xgemm_*gemm, its leaves of 8 columns
- * are factored by one workgroup each; interchanges are applied to the rest of the rows by
- * a kernel of their own, the block row of U comes from xgemm_*trsm and the trailing
- * matrix from one xgemm_*gemm of the panel's depth.  Every multiplier satisfies
+ * completed all the same, as in LAPACK).  The matrix is halved recursively by columns onto
+ * xgemm_*trsm and xgemm_*gemm down to leaves of 8 columns, which are factored by one
+ * workgroup each; interchanges are applied to the other columns by a kernel of their own.  Every multiplier satisfies
  * |L(i,j)| <= 1 and the factors satisfy |P A - L U| <= 4 min(m,n) u |L| |U| element by
  * element.  Returns 0, -i for an illegal argument (m 1, n 2, A 3, lda 4, ipiv 5, info 6)
  * or a hipError_t.  flops: m n^2 - n^3 / 3 for m >= n (2 n^3 / 3 when square).
@@ -268,9 +266,7 @@ int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *in
  * rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
  * of a column is agreed by every workgroup alike from the candidates (magnitude, row and the whole
  * candidate row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
- * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.  The matrix is not swept
- * in panels here but halved recursively as a whole down to shared panels of 128 columns (deepest products,
- * interchanges applied to as few columns as possible), unless it has more rows than shared panels can hold.
+ * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
  *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 1 MiB); its
  *          contents need no preparation and are undefined afterwards.  Calls that share it must not
  *          overlap in time.  NULL or too small: the call runs exactly as xgemm_*getrf.

@@ -4,18 +4,18 @@
 //     P A = L U,   A m x n,  L unit lower trapezoidal, U upper trapezoidal, both in place;
 //     ipiv[j] (1-based) is the row that was interchanged with row j at step j.
 //
-// Organisation.  The matrix is swept right-looking in panels of PANEL columns.  A panel is
-// factored recursively by halving its columns (left half; interchanges, triangular solve and
-// product for the right half; right half; interchanges for the left half), so that all
-// arithmetic of a panel except its leaves runs in the solve and product kernels.  A leaf of up
-// to LEAF columns is factored by ONE workgroup (getf2_kernel): the search for the pivot is a
-// reduction inside the workgroup, so nothing in the library ever waits for another workgroup,
-// and a leaf costs one launch, not one per column; it carries its interchanges through all
-// columns of its panel.  Two leaves side by side run without a launch between them: the left one
-// also solves for the block row of U above the right one, the right one applies the left one's
-// update as it loads.  After a panel its interchanges are applied to the columns on both
-// sides of it (laswp_kernel), the block row of U comes from a triangular solve and the rest
-// of the matrix is updated by one product of depth PANEL.
+// Organisation.  The matrix is halved recursively by columns (left half; triangular solve and product
+// for the right half; right half), so that all arithmetic except that of the base panels runs in the
+// solve and product kernels at the greatest depth there is.  A base panel (at most 128 columns) is
+//   - with a caller's exchange buffer (xgemm_*getrf_ws): factored by all the workgroups its rows need
+//     at once, each holding a stripe of rows in LDS, the pivot of a column agreed through the buffer
+//     (getrf_coop_kernel; the only kernel of the library in which a workgroup waits for another);
+//   - without: halved further down to leaves of up to LEAF columns, each factored by ONE workgroup
+//     (getf2_kernel): the search for the pivot is a reduction inside the workgroup, a leaf costs one
+//     launch, not one per column, and carries its interchanges through the columns of its base panel.
+//     Two leaves side by side run without a launch between them: the left one also solves for the
+//     block row of U above the right one, the right one applies the left one's update as it loads.
+// A base panel's interchanges are applied to the other columns of every enclosing half by laswp_kernel.
 #include "../../include/xgemm.h"
 #include "../../include/xgemm_tuning.h"
 
@@ -969,26 +969,29 @@ template <typename T> struct Lu {
             default: return leaf<1>(j0, w, c_lo, c_hi, resident, pre, post);
         }
     }
+    // Columns [j0, j0 + w) inside the enclosing panel [c_lo, c_hi): halved down to base panels of at most `base`
+    // columns; a base panel is shared by all the workgroups its rows need where there is exchange memory and it is
+    // not too tall, else halved further down to leaves of one workgroup, and its interchanges are then applied to
+    // the other columns of the enclosing panel by laswp_kernel (a leaf carries its interchanges only through its
+    // own base panel: carried through a wide panel they cost more than everything else).
+    int64_t base;
     int panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
         int rc;
-        if (xch) {
-            // with exchange memory the leaves of the halving are shared panels of up to COOP_NB columns; such a leaf
-            // leaves its interchanges to be applied to the other columns of the enclosing panel here
-            if (w <= COOP_NB) {
-                rc = coop_panel(j0, w);
-                if (rc == 0) {
-                    if ((rc = swap_rows(c_lo, j0, j0, j0 + w))) return rc;
-                    return swap_rows(j0 + w, c_hi, j0, j0 + w);
-                }
-                if (rc != 1) return rc;       // 1: not taken (too tall); the leaves of one workgroup below
-            } else {
-                const int64_t w1 = ((w / 2 + COOP_NB - 1) / COOP_NB) * COOP_NB, w2 = w - w1, j1 = j0 + w1;
-                if ((rc = panel(j0, w1, c_lo, c_hi))) return rc;
-                if ((rc = trsm(w1, w2, A + j0 + j0 * lda, A + j0 + j1 * lda))) return rc;
-                if (m > j1 && (rc = gemm(m - j1, w2, w1, A + j1 + j0 * lda, A + j0 + j1 * lda, A + j1 + j1 * lda))) return rc;
-                return panel(j1, w2, c_lo, c_hi);
-            }
+        if (w <= base) {
+            rc = coop_panel(j0, w);
+            if (rc == 1) rc = leaf_panel(j0, w, j0, j0 + w);
+            if (rc) return rc;
+            if ((rc = swap_rows(c_lo, j0, j0, j0 + w))) return rc;
+            return swap_rows(j0 + w, c_hi, j0, j0 + w);
         }
+        const int64_t w1 = ((w / 2 + base - 1) / base) * base, w2 = w - w1, j1 = j0 + w1;
+        if ((rc = panel(j0, w1, c_lo, c_hi))) return rc;
+        if ((rc = trsm(w1, w2, A + j0 + j0 * lda, A + j0 + j1 * lda))) return rc;
+        if (m > j1 && (rc = gemm(m - j1, w2, w1, A + j1 + j0 * lda, A + j0 + j1 * lda, A + j1 + j1 * lda))) return rc;
+        return panel(j1, w2, c_lo, c_hi);
+    }
+    int leaf_panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
+        int rc;
         const int64_t lw = leaf_width(j0);
         if (w <= lw) return any_leaf(j0, w, c_lo, c_hi, 0, 0);
         const int64_t w1 = ((w / 2 + lw - 1) / lw) * lw, w2 = w - w1, j1 = j0 + w1;
@@ -1000,23 +1003,21 @@ template <typename T> struct Lu {
             if ((rc = any_leaf(j0, w1, c_lo, c_hi, 0, (int)w2))) return rc;
             return any_leaf(j1, w2, c_lo, c_hi, (int)w1, 0);
         }
-        if ((rc = panel(j0, w1, c_lo, c_hi))) return rc;
+        if ((rc = leaf_panel(j0, w1, c_lo, c_hi))) return rc;
         T *const A11 = A + j0 + j0 * lda, *const A12 = A + j0 + j1 * lda;
         T *const A21 = A + j1 + j0 * lda, *const A22 = A + j1 + j1 * lda;
         if ((rc = trsm(w1, w2, A11, A12))) return rc;
         if (m > j1 && (rc = gemm(m - j1, w2, w1, A21, A12, A22))) return rc;
-        return panel(j1, w2, c_lo, c_hi);
+        return leaf_panel(j1, w2, c_lo, c_hi);
     }
 
     int run() const {
         const int64_t steps = min64(m, n);
-        // With exchange memory the whole matrix is one panel, halved down to shared panels of COOP_NB columns: the
-        // products between the halves are as deep as they can be and interchanges are applied level by level to as few
-        // columns as possible (dgetrf_ws 16384 139 -> 127 ms, 32768 677 -> 521 against a sweep over panels of 128
-        // columns; no difference at 8192).  Only a matrix too tall for shared panels from its first column on is swept,
-        // because leaves of one workgroup carry their interchanges through their whole panel.
-        const bool all_shared = xch && m <= (int64_t)ncu * CoopCfg<T>::RPW && m <= (int64_t)COOP_GMAX * CoopCfg<T>::RPW;
-        const int64_t W = t_lu_panel > 0 ? t_lu_panel : (all_shared ? max64(steps, 1) : ((xch || steps >= 4096) ? 128 : 64));
+        // The whole matrix is one panel, halved down to base panels: the products between the halves are as deep as they
+        // can be and interchanges are applied level by level to as few columns as possible (against a sweep over panels
+        // of 128 columns: dgetrf_ws 16384 139 -> 127 ms, 32768 677 -> 521; dgetrf 16384 311 -> 296; no difference at
+        // 8192).  A forced width W sweeps over panels of W columns, each halved the same way.
+        const int64_t W = t_lu_panel > 0 ? t_lu_panel : max64(steps, 1);
         int rc;
         for (int64_t j = 0; j < steps; j += W) {
             const int64_t nb = min64(W, steps - j), j1 = j + nb;
@@ -1066,7 +1067,8 @@ int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, vo
         hipLaunchKernelGGL(coop_clear_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
         if ((rc = (int)hipGetLastError())) return rc;
     }
-    const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu};
+    const int64_t steps = min64(m, n), base_default = (xch || steps >= 4096) ? 128 : 64;
+    const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu, t_lu_panel > 0 ? min64(t_lu_panel, base_default) : base_default};
     return lu.run();
 }
 
