@@ -775,31 +775,52 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                     }
                 }
                 if (c + 1 < nb) {
-                    // A row of the stripe as it will be once this pivot is applied, in column d (the row that takes
-                    // the old row r is read from s_top, as the computing waves will do).
-                    const T t0 = s_top[c];
-                    auto after = [&](int i, int d) -> T {
-                        const bool moved = i0 + i == p && p != r;
-                        const T xd = moved ? s_top[d] : P[d * LS + i];
-                        if (d < c) return xd;
-                        const T l = scaled(moved ? t0 : P[c * LS + i], how, rcp);
-                        return d == c ? l : eliminated(xd, l, s_U[d]);
-                    };
+                    // What the stripe will hold once this pivot is applied (the row that takes the old row r is read
+                    // from s_top, as the computing waves will do).  Everything a step needs from LDS is asked for in
+                    // one batch and chosen from afterwards: written with a branch per case this wave made eight LDS
+                    // round trips in a row here, and all other waves of all workgroups wait for it.
+                    const bool exch = p != r;
+                    T xc[CR], x1[CR];
+#pragma unroll
+                    for (int k = 0; k < CR; ++k) {
+                        xc[k] = P[c * LS + lane + 64 * k];
+                        x1[k] = P[(c + 1) * LS + lane + 64 * k];
+                    }
+                    const T u1 = s_U[c + 1], t0 = s_top[c], t1 = s_top[c + 1];
                     // the candidates of column c + 1 among the rows below row r
                     Cand<T> mine{T(-1), NONE};
 #pragma unroll
                     for (int k = 0; k < CR; ++k) {
                         const int i = lane + 64 * k, row = i0 + i;
-                        if (i < nrows && row > r) mine = better(mine, Cand<T>{abs_of(after(i, c + 1)), row});
+                        const bool moved = exch && row == p;
+                        const T y = eliminated(moved ? t1 : x1[k], scaled(moved ? t0 : xc[k], how, rcp), u1);
+                        if (i < nrows && row > r) mine = better(mine, Cand<T>{abs_of(y), row});
                     }
                     lb = wave_best(mine);
                     publish(c + 1, true, false);
+                    // the candidate's row and (workgroup 0) row r + 1, local row c + 1, both as they will be
                     const int ib = lb.row == NONE ? -1 : __builtin_amdgcn_readfirstlane(lb.row) - i0;
+                    const int ibs = ib >= 0 ? ib : 0, it = c + 1;
+                    T pr[COOP_NB / 64], pt[COOP_NB / 64], su[COOP_NB / 64], st[COOP_NB / 64];
+#pragma unroll
+                    for (int q = 0; q < COOP_NB / 64; ++q) {
+                        const int d = lane + 64 * q, dq = d < nb ? d : nb - 1;
+                        pr[q] = P[dq * LS + ibs];
+                        pt[q] = P[dq * LS + it];
+                        su[q] = s_U[dq];
+                        st[q] = s_top[dq];
+                    }
+                    const bool moved_b = exch && i0 + ibs == p, moved_t = exch && i0 + it == p;
+                    const T l_b = scaled(moved_b ? t0 : P[c * LS + ibs], how, rcp);
+                    const T l_t = scaled(moved_t ? t0 : P[c * LS + it], how, rcp);
 #pragma unroll
                     for (int q = 0; q < COOP_NB / 64; ++q) {
                         const int d = lane + 64 * q;
-                        rowv[q] = (ib >= 0 && d < nb) ? after(ib, d) : T(0);
-                        topv[q] = (g == 0 && d < nb) ? after(c + 1, d) : T(0);       // row r + 1 is local row c + 1 of workgroup 0
+                        const T xb = moved_b ? st[q] : pr[q], xt = moved_t ? st[q] : pt[q];
+                        const T vb = d < c ? xb : (d == c ? l_b : eliminated(xb, l_b, su[q]));
+                        const T vt = d < c ? xt : (d == c ? l_t : eliminated(xt, l_t, su[q]));
+                        rowv[q] = (ib >= 0 && d < nb) ? vb : T(0);
+                        topv[q] = (g == 0 && d < nb) ? vt : T(0);
                     }
                     publish(c + 1, false, true);
                 }
