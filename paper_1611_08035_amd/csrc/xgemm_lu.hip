@@ -761,7 +761,29 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                 // pivot's reciprocal as LAPACK does (one division per column; |a| <= |pivot| still gives
                 // |a * (1 / pivot)| <= 1 after rounding) unless the reciprocal would overflow
                 __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): this wave's writes of s_U and s_top have landed
+                // Everything the steps below need from LDS that does not depend on their results is asked for here,
+                // in one batch with the pivot, and chosen from afterwards: written with a branch per case this wave
+                // made eight LDS round trips in a row, and all other waves of all workgroups wait for it.
+                const bool more = c + 1 < nb;               // there is a next column
+                const int cn = more ? c + 1 : c, it = cn;   // row r + 1 is local row c + 1 of workgroup 0
                 const T pivot = s_U[c];
+                T xc[CR], x1[CR], pt[COOP_NB / 64], su[COOP_NB / 64], st[COOP_NB / 64];
+#pragma unroll
+                for (int k = 0; k < CR; ++k) {
+                    xc[k] = P[c * LS + lane + 64 * k];
+                    x1[k] = P[cn * LS + lane + 64 * k];
+                }
+                const T u1 = s_U[cn], t0 = s_top[c], t1 = s_top[cn], lt_raw = P[c * LS + it];
+#pragma unroll
+                for (int q = 0; q < COOP_NB / 64; ++q) {
+                    const int d = lane + 64 * q, dq = d < nb ? d : nb - 1;
+                    pt[q] = P[dq * LS + it];
+                    su[q] = s_U[dq];
+                    st[q] = s_top[dq];
+                }
+                // what every computing thread needs of the pivot, worked out once: the column is scaled by the
+                // pivot's reciprocal as LAPACK does (one division per column; |a| <= |pivot| still gives
+                // |a * (1 / pivot)| <= 1 after rounding) unless the reciprocal would overflow
                 const bool nonzero = pivot != T(0), by_rcp = abs_of(pivot) >= RcpLimit<T>::tiny();
                 const int how = !nonzero ? 0 : (by_rcp ? 1 : 2);
                 const T rcp = by_rcp ? T(1) / pivot : pivot;
@@ -774,20 +796,11 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                         if (!nonzero && *info == 0) *info = r + 1;
                     }
                 }
-                if (c + 1 < nb) {
+                if (more) {
                     // What the stripe will hold once this pivot is applied (the row that takes the old row r is read
-                    // from s_top, as the computing waves will do).  Everything a step needs from LDS is asked for in
-                    // one batch and chosen from afterwards: written with a branch per case this wave made eight LDS
-                    // round trips in a row here, and all other waves of all workgroups wait for it.
+                    // from s_top, as the computing waves will do): the candidates of column c + 1 among the rows
+                    // below row r
                     const bool exch = p != r;
-                    T xc[CR], x1[CR];
-#pragma unroll
-                    for (int k = 0; k < CR; ++k) {
-                        xc[k] = P[c * LS + lane + 64 * k];
-                        x1[k] = P[(c + 1) * LS + lane + 64 * k];
-                    }
-                    const T u1 = s_U[c + 1], t0 = s_top[c], t1 = s_top[c + 1];
-                    // the candidates of column c + 1 among the rows below row r
                     Cand<T> mine{T(-1), NONE};
 #pragma unroll
                     for (int k = 0; k < CR; ++k) {
@@ -798,21 +811,18 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                     }
                     lb = wave_best(mine);
                     publish(c + 1, true, false);
-                    // the candidate's row and (workgroup 0) row r + 1, local row c + 1, both as they will be
+                    // the candidate's row and (workgroup 0) row r + 1, both as they will be
                     const int ib = lb.row == NONE ? -1 : __builtin_amdgcn_readfirstlane(lb.row) - i0;
-                    const int ibs = ib >= 0 ? ib : 0, it = c + 1;
-                    T pr[COOP_NB / 64], pt[COOP_NB / 64], su[COOP_NB / 64], st[COOP_NB / 64];
+                    const int ibs = ib >= 0 ? ib : 0;
+                    T pr[COOP_NB / 64];
 #pragma unroll
                     for (int q = 0; q < COOP_NB / 64; ++q) {
                         const int d = lane + 64 * q, dq = d < nb ? d : nb - 1;
                         pr[q] = P[dq * LS + ibs];
-                        pt[q] = P[dq * LS + it];
-                        su[q] = s_U[dq];
-                        st[q] = s_top[dq];
                     }
                     const bool moved_b = exch && i0 + ibs == p, moved_t = exch && i0 + it == p;
                     const T l_b = scaled(moved_b ? t0 : P[c * LS + ibs], how, rcp);
-                    const T l_t = scaled(moved_t ? t0 : P[c * LS + it], how, rcp);
+                    const T l_t = scaled(moved_t ? t0 : lt_raw, how, rcp);
 #pragma unroll
                     for (int q = 0; q < COOP_NB / 64; ++q) {
                         const int d = lane + 64 * q;
