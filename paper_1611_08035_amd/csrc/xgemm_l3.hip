@@ -1496,7 +1496,7 @@ constexpr int64_t HALVE = -2;
 template <typename T> int64_t potrf_panel(int64_t n) {
     if (t_potrf_panel >= 0) return t_potrf_panel;
     if (n < 3072) return 0;
-    if (n <= 16384) return 256;
+    if (n <= 16384) return (sizeof(T) == 8 && n >= 12288) ? 512 : 256;   // fp64 16384: 33.8 ms with 256, 32.3 with 512; 12288: 17.0, 16.8
     return sizeof(T) == 8 ? HALVE : 512;
 }
 
