@@ -523,11 +523,13 @@ def sweep(torch, np, xg, si, args):
                           "GFLOP/s": round(flops / dev / 1e9, 1), "frac_of_mfma_peak": round(flops / dev / peak, 4)}),
               file=sys.stderr, flush=True)
         del dA0, dA
-    # LU: the panels' leaves on one workgroup each (xgemm_*getrf), and the panels shared by all the workgroups
-    # their rows need, through an exchange buffer (xgemm_*getrf_ws)
-    for prec, nsz, ws in (("d", 4096, 0), ("d", 8192, 0), ("d", 16384, 0), ("s", 8192, 0),
-                          ("d", 4096, 1), ("d", 8192, 1), ("d", 16384, 1), ("d", 32768, 1), ("s", 8192, 1), ("s", 16384, 1)):
-        name = f"{prec}getrf{'_ws' if ws else ''} {nsz}"
+    # LU: xgemm_*getrf (base panels shared by all the workgroups their rows need, through the library's own
+    # exchange buffer), the same through a caller's buffer (xgemm_*getrf_ws), and held to the leaves of one
+    # workgroup each (what a captured call without a buffer gets)
+    for prec, nsz, ws in (("d", 4096, 0), ("d", 8192, 0), ("d", 16384, 0), ("d", 32768, 0), ("s", 8192, 0), ("s", 16384, 0),
+                          ("d", 8192, 1), ("d", 16384, 1), ("s", 8192, 1),
+                          ("d", 4096, 2), ("d", 8192, 2), ("d", 16384, 2), ("s", 8192, 2)):
+        name = f"{prec}getrf{('', '_ws', ' (leaves only)')[ws]} {nsz}"
         if not want(name):
             continue
         dtype = np.float64 if prec == "d" else np.float32
@@ -536,7 +538,8 @@ def sweep(torch, np, xg, si, args):
         dA = dA0.clone()
         dinfo = torch.zeros(1, dtype=torch.int32, device="cuda")
         dpiv = torch.zeros(nsz, dtype=torch.int32, device="cuda")
-        if ws:
+        xg.xgemm_force_getrf_shared(0 if ws == 2 else -1)
+        if ws == 1:
             lwork = xg.xgemm_getrf_workspace_bytes()
             work = torch.empty(lwork, dtype=torch.uint8, device="cuda")
             fw = getattr(xg, f"xgemm_{prec}getrf_ws")
@@ -545,6 +548,7 @@ def sweep(torch, np, xg, si, args):
             f = getattr(xg, f"xgemm_{prec}getrf")
             step = lambda: f(nsz, nsz, dA, ld, dpiv, dinfo)
         dev = timed_in_place(lambda: dA.copy_(dA0), step, reps=4, skip=1)
+        xg.xgemm_force_getrf_shared(-1)
         if int(dinfo.item()) != 0:
             raise RuntimeError("getrf info %d" % int(dinfo.item()))
         flops = 2.0 * float(nsz) ** 3 / 3.0

@@ -35,6 +35,9 @@
  *       . per thread and device, two streams and 23 events that xgemm_*potrf
  *         creates on its first look-ahead sweep and keeps for later calls
  *         (xgemm_release_thread_resources() destroys them);
+ *       . per process and device: the exchange buffer (about 1 MiB) and the event
+ *         that xgemm_*getrf allocates on its first call outside a capture and keeps,
+ *         and a lock held while such a call enqueues its kernels;
  *       . per process and device, read once: the number of compute units, the
  *         address of the static scratch of xgemm_dgemm_static, and which kernels
  *         have been granted more than 64 KiB of LDS;
@@ -249,35 +252,47 @@ int xgemm_spotrf(char uplo, int64_t n, float *A, int64_t lda, int *info, void *s
  * 1-based: at step j, row j changed places with row ipiv[j] >= j; the pivot of a column is
  * the first of its entries of largest magnitude.  `info` (DEVICE int, written on the
  * stream): 0, or j > 0 if U(j,j) is exactly zero (the first such j; the factorisation is
- * completed all the same, as in LAPACK).  The matrix is halved recursively by columns onto
- * xgemm_*trsm and xgemm_*gemm down to leaves of 8 columns, which are factored by one
- * workgroup each; interchanges are applied to the other columns by a kernel of their own.  Every multiplier satisfies
- * |L(i,j)| <= 1 and the factors satisfy |P A - L U| <= 4 min(m,n) u |L| |U| element by
- * element.  Returns 0, -i for an illegal argument (m 1, n 2, A 3, lda 4, ipiv 5, info 6)
+ * completed all the same, as in LAPACK).  Every multiplier satisfies |L(i,j)| <= 1 and the
+ * factors satisfy |P A - L U| <= 4 min(m,n) u |L| |U| element by element.
+ *
+ * How it runs.  The matrix is halved recursively by columns onto xgemm_*trsm and xgemm_*gemm
+ * down to base panels of 128 columns; a base panel's interchanges are applied to the other
+ * columns by a kernel of their own.  A base panel is factored by all the workgroups its rows
+ * need at once: its rows are dealt to workgroups in stripes of 128, each stripe stays in the
+ * LDS of its workgroup for the whole panel, and the pivot of a column is agreed by every
+ * workgroup alike from the candidates (value, row and the whole candidate row) that all of
+ * them publish in an exchange buffer.  That buffer (about 1 MiB) is one per device, allocated
+ * by the first call that needs it and kept for the life of the process.
+ * The workgroups of such a panel wait for each other (the only place in the library where a
+ * workgroup waits for another), so all of them must be resident together: the library never
+ * asks for more than one per compute unit, and it orders every factorisation of this kind on
+ * a device behind the one before it, whichever host thread and stream it comes from (an
+ * event; calls on different streams therefore do not overlap each other).  Every wait is
+ * bounded: a workgroup that does not see the others within a few tenths of a second gives
+ * up, the others follow, and *info becomes -1 (A is then partly factored and must be
+ * discarded); that can only happen when other work holds the device's compute units for
+ * that long.
+ * Where that cannot be done (the stream is being captured, where nothing may be allocated and
+ * no event of the library's waited for; a panel of more than 128 rows per compute unit of the
+ * device; the allocation failed) a base panel is halved further down to leaves of 8 columns
+ * that one workgroup each factors on its own, as every panel of at most 128 rows is anyway.
+ * Returns 0, -i for an illegal argument (m 1, n 2, A 3, lda 4, ipiv 5, info 6)
  * or a hipError_t.  flops: m n^2 - n^3 / 3 for m >= n (2 n^3 / 3 when square).
  */
 int xgemm_dgetrf(int64_t m, int64_t n, double *A, int64_t lda, int *ipiv, int *info, void *stream);
 int xgemm_sgetrf(int64_t m, int64_t n, float *A, int64_t lda, int *ipiv, int *info, void *stream);
 
 /*
- * The same factorisation with a caller-owned exchange buffer, which lets all workgroups that the rows of a
- * panel need factor it together (xgemm_*getrf factors a panel's leaves on one compute unit at a time while
- * the rest of the device waits): the rows of a panel of 128 columns are dealt to workgroups in stripes of 128
- * rows, each stripe stays in the LDS of its workgroup for the whole panel, and the pivot
- * of a column is agreed by every workgroup alike from the candidates (magnitude, row and the whole
- * candidate row) that all of them publish in `work`.  Same semantics, same pivot rule and the same statement about the
- * factors as xgemm_*getrf; the factors may differ from its factors in the last bits.
+ * The same factorisation with a caller-owned exchange buffer: for callers that keep device memory
+ * under their own control, and the only way to get shared panels into a captured graph.
  *   work : device buffer, 16-byte aligned, lwork >= xgemm_getrf_workspace_bytes() (about 1 MiB); its
  *          contents need no preparation and are undefined afterwards.  Calls that share it must not
  *          overlap in time.  NULL or too small: the call runs exactly as xgemm_*getrf.
- * The workgroups of a panel wait for each other (the only place in the library where a workgroup waits for
- * another), so all of them must be resident together: the library never asks for more than one per compute
- * unit (panels taller than that go the way of xgemm_*getrf), and every wait is bounded: a workgroup that
- * does not see the others within a few tenths of a second gives up, the others follow, and *info becomes -1 (A is
- * then partly factored and must be discarded).  That can only happen when other work holds the device's
- * compute units for that long; two such factorisations running at the same time on one device (different
- * streams, different buffers) can each hold the compute units the other waits for and both time out: run
- * them one after the other.
+ * Outside a capture these calls take part in the order described above.  A captured call cannot (it may
+ * not wait for an event recorded outside its capture): two factorisations with shared panels that run at
+ * the same time on one device can each hold the compute units the other waits for and both time out, so
+ * a graph that holds one must not be replayed beside another such factorisation.
+ * Same semantics, same pivot rule, same bits as xgemm_*getrf where that uses shared panels too.
  * Returns as xgemm_*getrf, and -7 for a work that is not 16-byte aligned.
  */
 size_t xgemm_getrf_workspace_bytes(void);

@@ -75,6 +75,12 @@ int xgemm_force_potrf_block(int order);
  * Returns 0, or -1 for any other value. */
 int xgemm_force_getrf_panel(int64_t width);
 
+/* Benchmark/test control of xgemm_*getrf and xgemm_*getrf_ws on the calling thread: -1 (default) base panels
+ * are held in LDS and shared by all the workgroups their rows need wherever that is possible; 0: only the
+ * leaves of one workgroup each (the route that a captured call without an exchange buffer takes for panels of
+ * more than 128 rows).  Returns 0, or -1 for any other value. */
+int xgemm_force_getrf_shared(int mode);
+
 /* Benchmark/test control of xgemm_*getrf_ws on the calling thread: how many polls a workgroup of a shared
  * panel waits for the others before it gives up (default 2^18, about a microsecond each).  0 makes every
  * panel shared by more than one workgroup give up at once unless all had arrived already: the way to test

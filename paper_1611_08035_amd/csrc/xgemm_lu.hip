@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 namespace {
@@ -37,6 +38,7 @@ constexpr int LEAF_WAVES = LEAF_NT / 64;
 template <typename T> constexpr int leaf_elems(int w) { return sizeof(T) == 8 ? (w == 2 ? 40 : 48) : (w == 2 ? 56 : 64); }
 
 thread_local int64_t t_lu_panel = -1;   // -1: by the order; W > 0: panels of W columns
+thread_local int t_lu_shared = -1;       // -1: shared panels wherever they can be used; 0: leaves of one workgroup only
 // First look of a poll put off by this many 64-clock sleeps.  While headers and rows were published right before
 // they were polled for, a look that came too early cost a whole round trip more and 18 resp. 13 sleeps paid
 // (52.5 -> 48.1 ms at 8192); since both are published a barrier ahead of the poll, no delay is best.
@@ -938,16 +940,16 @@ template <typename T> struct Lu {
     int64_t m, n;
     int *ipiv, *info;
     void *stream;
-    unsigned char *xch;     // exchange memory of the shared panels (COOP_BYTES), or nullptr: leaves of one workgroup only
+    unsigned char *xch;     // exchange memory of the shared panels (COOP_BYTES), or nullptr: no panel of several workgroups
     int ncu;                // compute units of the device: most workgroups that can share a panel
 
     // The panel [j0, j0 + nb) by all the workgroups its rows need (getrf_coop_kernel), if they can be resident
     // together and the panel's offsets fit 32 bits; 1: not taken (the caller falls back to the recursive panel).
     int coop_panel(int64_t j0, int64_t nb) const {
         using C = CoopCfg<T>;
-        if (!xch || nb > COOP_NB) return 1;
+        if (!shared || nb > COOP_NB) return 1;
         const int64_t G = (m - j0 + C::RPW - 1) / C::RPW;
-        if (G > ncu || G > COOP_GMAX) return 1;
+        if (G > 1 && (!xch || G > ncu || G > COOP_GMAX)) return 1;      // one workgroup waits for nobody and exchanges nothing
         if ((int64_t)COOP_NB * lda * (int64_t)sizeof(T) >= (int64_t)0x7fffffff) return 1;
         constexpr size_t LDS = (size_t)COOP_NB * (C::RPW + 1) * sizeof(T);
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(getrf_coop_kernel<T, C::RPW, C::TPR>),
@@ -1006,6 +1008,7 @@ template <typename T> struct Lu {
     // the other columns of the enclosing panel by laswp_kernel (a leaf carries its interchanges only through its
     // own base panel: carried through a wide panel they cost more than everything else).
     int64_t base;
+    bool shared;            // base panels in LDS (getrf_coop_kernel) where they can be; false: leaves of one workgroup only
     int panel(int64_t j0, int64_t w, int64_t c_lo, int64_t c_hi) const {
         int rc;
         if (w <= base) {
@@ -1077,6 +1080,17 @@ template <> int Lu<float>::gemm(int64_t mm, int64_t nn, int64_t kk, const float 
     return xgemm_sgemm('N', 'N', mm, nn, kk, -1.0f, X, lda, Y, lda, 1.0f, C, lda, stream);
 }
 
+// Per process and device: what orders the factorisations with shared panels, and the exchange buffer of those
+// that bring none.
+struct SharedPanels {
+    static constexpr int MAX_DEV = 64;
+    std::mutex mu;
+    unsigned char *buf = nullptr;
+    hipEvent_t done = nullptr;
+    bool used = false, alloc_failed = false;
+};
+SharedPanels g_shared_panels[SharedPanels::MAX_DEV];
+
 template <typename T>
 int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, void *work, size_t lwork, void *stream) {
     if (m < 0 || m > DIM_MAX) return -1;
@@ -1089,18 +1103,58 @@ int getrf_impl(int64_t m, int64_t n, T *A, int64_t lda, int *ipiv, int *info, vo
     hipLaunchKernelGGL(clear_int_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), info);
     int rc = (int)hipGetLastError();
     if (rc || m == 0 || n == 0) return rc;
-    unsigned char *xch = (work && lwork >= COOP_BYTES) ? static_cast<unsigned char *>(work) : nullptr;
-    int ncu = 0;
+    // Panels shared by several workgroups need exchange memory: the caller's, else one buffer per device that
+    // the library allocates the first time it is needed (never while the stream is being captured: then, and if
+    // the allocation fails, only panels of a single workgroup and the leaves are used).  Workgroups of a shared
+    // panel wait for each other, and two factorisations whose panels cannot all be resident together could each
+    // hold the compute units the other waits for; so every factorisation with shared panels on a device is
+    // ordered behind the one before it, whichever thread and stream it comes from (an event recorded at the end
+    // of each, waited for at the start of the next, both under a lock that is held while the kernels are
+    // enqueued).  A captured call can take no part in that order: it is up to the caller there.
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if ((rc = (int)hipStreamIsCapturing(st, &capturing))) return rc;
+    const bool captured = capturing != hipStreamCaptureStatusNone;
+    const bool want_shared = t_lu_shared != 0;
+    unsigned char *xch = (want_shared && work && lwork >= COOP_BYTES) ? static_cast<unsigned char *>(work) : nullptr;
+    int dev = 0, ncu = 0;
+    if ((rc = (int)hipGetDevice(&dev))) return rc;
+    if ((rc = (int)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev))) return rc;
+    SharedPanels *sp = (want_shared && !captured && dev >= 0 && dev < SharedPanels::MAX_DEV) ? &g_shared_panels[dev] : nullptr;
+    std::unique_lock<std::mutex> order;
+    if (sp) {
+        order = std::unique_lock<std::mutex>(sp->mu);
+        if (!sp->done && hipEventCreateWithFlags(&sp->done, hipEventDisableTiming) != hipSuccess) sp->done = nullptr;
+        if (!sp->done) {
+            (void)hipGetLastError();
+            order.unlock();
+            sp = nullptr;
+            if (!captured) xch = nullptr;             // without the order no shared panels outside a capture
+        } else {
+            if (!xch) {
+                if (!sp->buf && !sp->alloc_failed && hipMalloc(reinterpret_cast<void **>(&sp->buf), COOP_BYTES) != hipSuccess) {
+                    (void)hipGetLastError();
+                    sp->buf = nullptr;
+                    sp->alloc_failed = true;
+                }
+                xch = sp->buf;
+            }
+            if (xch && sp->used && (rc = (int)hipStreamWaitEvent(st, sp->done, 0))) return rc;
+        }
+    }
     if (xch) {
-        int dev = 0;
-        if ((rc = (int)hipGetDevice(&dev))) return rc;
-        if ((rc = (int)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev))) return rc;
-        hipLaunchKernelGGL(coop_clear_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream), reinterpret_cast<uint4 *>(xch));
+        hipLaunchKernelGGL(coop_clear_kernel, dim3(64), dim3(256), 0, st, reinterpret_cast<uint4 *>(xch));
         if ((rc = (int)hipGetLastError())) return rc;
     }
-    const int64_t steps = min64(m, n), base_default = (xch || steps >= 4096) ? 128 : 64;
-    const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu, t_lu_panel > 0 ? min64(t_lu_panel, base_default) : base_default};
-    return lu.run();
+    const int64_t steps = min64(m, n), base_default = (want_shared || steps >= 4096) ? 128 : 64;
+    const Lu<T> lu{A, lda, m, n, ipiv, info, stream, xch, ncu, t_lu_panel > 0 ? min64(t_lu_panel, base_default) : base_default, want_shared};
+    rc = lu.run();
+    if (sp && xch) {
+        const int rec = (int)hipEventRecord(sp->done, st);
+        sp->used = sp->used || rec == 0;
+        if (!rc) rc = rec;
+    }
+    return rc;
 }
 
 }  // namespace
@@ -1109,6 +1163,7 @@ namespace xg {
 void reset_lu_tuning() {
     t_lu_panel = -1;
     t_lu_spin_limit = 1 << 18;
+    t_lu_shared = -1;
     t_lu_hdr_delay = LU_HDR_DELAY;
     t_lu_row_delay = LU_ROW_DELAY;
 }
@@ -1138,6 +1193,12 @@ int xgemm_force_getrf_poll_delay(int header_sleeps, int row_sleeps) {
     if (header_sleeps < 0 || row_sleeps < 0 || header_sleeps > 1024 || row_sleeps > 1024) return -1;
     t_lu_hdr_delay = header_sleeps;
     t_lu_row_delay = row_sleeps;
+    return 0;
+}
+
+int xgemm_force_getrf_shared(int mode) {
+    if (mode != -1 && mode != 0) return -1;
+    t_lu_shared = mode;
     return 0;
 }
 

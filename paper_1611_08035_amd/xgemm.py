@@ -21,7 +21,7 @@ EXPORTS = [
     "xgemm_workspace_bytes", "xgemm_workspace_init", "xgemm_dgemm_ws", "xgemm_sgemm_ws", "xgemm_dsyrk_ws",
     "xgemm_ssyrk_ws", "xgemm_force_split", "xgemm_last_split", "xgemm_plan", "xgemm_dtrsm", "xgemm_strsm", "xgemm_dtrmm", "xgemm_strmm", "xgemm_dsyr2k", "xgemm_ssyr2k", "xgemm_dsymm",
     "xgemm_ssymm", "xgemm_zgemm", "xgemm_zgemm_workbytes", "xgemm_dpotrf", "xgemm_spotrf", "xgemm_latency_probe",
-    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_model_enumerate", "xgemm_model_efficiency", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_dgetrf_ws", "xgemm_sgetrf_ws", "xgemm_getrf_workspace_bytes", "xgemm_force_getrf_spin_limit", "xgemm_force_getrf_poll_delay", "xgemm_pack_elems", "xgemm_dpack_a", "xgemm_dpack_b", "xgemm_spack_a", "xgemm_spack_b", "xgemm_dgemm_packed", "xgemm_sgemm_packed", "xgemm_release_thread_resources",
+    "xgemm_force_potrf_panel", "xgemm_force_potrf_block", "xgemm_dgemm_static", "xgemm_tuning_reset", "xgemm_model_enumerate", "xgemm_model_efficiency", "xgemm_dgetrf", "xgemm_sgetrf", "xgemm_force_getrf_panel", "xgemm_dgetrf_ws", "xgemm_sgetrf_ws", "xgemm_getrf_workspace_bytes", "xgemm_force_getrf_spin_limit", "xgemm_force_getrf_poll_delay", "xgemm_force_getrf_shared", "xgemm_pack_elems", "xgemm_dpack_a", "xgemm_dpack_b", "xgemm_spack_a", "xgemm_spack_b", "xgemm_dgemm_packed", "xgemm_sgemm_packed", "xgemm_release_thread_resources",
 ]
 
 
@@ -99,6 +99,8 @@ def lib():
         f.argtypes = [_i64, _i64, _p, _i64, _p, _p, _p, ctypes.c_size_t, _p]
     L.xgemm_getrf_workspace_bytes.restype = ctypes.c_size_t
     L.xgemm_getrf_workspace_bytes.argtypes = []
+    L.xgemm_force_getrf_shared.restype = ctypes.c_int
+    L.xgemm_force_getrf_shared.argtypes = [ctypes.c_int]
     L.xgemm_force_getrf_poll_delay.restype = ctypes.c_int
     L.xgemm_force_getrf_poll_delay.argtypes = [ctypes.c_int, ctypes.c_int]
     L.xgemm_force_getrf_spin_limit.restype = ctypes.c_int
@@ -256,6 +258,10 @@ def xgemm_dgetrf_ws(m, n, A, lda, ipiv, info, work, lwork, stream=None) -> int:
 
 def xgemm_sgetrf_ws(m, n, A, lda, ipiv, info, work, lwork, stream=None) -> int:
     return int(lib().xgemm_sgetrf_ws(m, n, _ptr(A), lda, _ptr(ipiv), _ptr(info), _ptr(work), lwork, _stream(stream)))
+
+
+def xgemm_force_getrf_shared(mode) -> int:
+    return int(lib().xgemm_force_getrf_shared(int(mode)))
 
 
 def xgemm_force_getrf_poll_delay(header_sleeps, row_sleeps) -> int:

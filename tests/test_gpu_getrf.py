@@ -23,27 +23,31 @@ def _auto():
 
 
 def run_getrf(m, n, A, lda, stream=None, ws=False):
-    """ws: through xgemm_*getrf_ws with an exchange buffer full of ones (it needs no preparation), so that the
-    panels are shared by all the workgroups their rows need."""
+    """ws False: xgemm_*getrf held to the leaves of one workgroup each (the route of a captured call);
+    ws True: through xgemm_*getrf_ws with an exchange buffer full of ones (it needs no preparation), so that
+    the panels are shared by all the workgroups their rows need; ws "auto": xgemm_*getrf as it comes (shared
+    panels through the library's own exchange buffer)."""
     torch = torch_mod()
     dA = to_dev(A)
     k = max(min(m, n), 1)
     dpiv = torch.full((k,), -7, dtype=torch.int32, device="cuda")
     dinfo = torch.full((1,), -7, dtype=torch.int32, device="cuda")
-    if ws:
+    if ws is True:
         f = xg.xgemm_dgetrf_ws if A.dtype == np.float64 else xg.xgemm_sgetrf_ws
         lwork = xg.xgemm_getrf_workspace_bytes()
         work = torch.full((lwork,), 0xFF, dtype=torch.uint8, device="cuda")
         assert f(m, n, dA, lda, dpiv, dinfo, work, lwork, stream=stream) == 0
     else:
+        assert xg.xgemm_force_getrf_shared(-1 if ws == "auto" else 0) == 0
         f = xg.xgemm_dgetrf if A.dtype == np.float64 else xg.xgemm_sgetrf
         assert f(m, n, dA, lda, dpiv, dinfo, stream=stream) == 0
+        assert xg.xgemm_force_getrf_shared(-1) == 0
     torch.cuda.synchronize()
     return dA.cpu().numpy(), dpiv.cpu().numpy()[:min(m, n)], int(dinfo.item())
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-@pytest.mark.parametrize("panel,ws", [(-1, False), (16, False), (40, False), (-1, True), (16, True), (40, True)])
+@pytest.mark.parametrize("panel,ws", [(-1, False), (16, False), (40, False), (-1, True), (16, True), (40, True), (-1, "auto"), (40, "auto")])
 def test_planted_factorisations_are_recovered_exactly(dtype, panel, ws):
     """Every operation on these matrices is exact, so interchanges and factors must come out bit for bit,
     whatever the blocking: one leaf, several leaves, several panels, ragged last leaf and panel, tall, wide."""
@@ -62,7 +66,7 @@ def test_planted_factorisations_are_recovered_exactly(dtype, panel, ws):
         assert np.all(np.isnan(F[:, m:])), "padding rows were written"
 
 
-@pytest.mark.parametrize("ws", [False, True])
+@pytest.mark.parametrize("ws", [False, True, "auto"])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_random_matrices_every_element_and_against_the_oracle(dtype, ws):
     rng = si.rng_for(311, 0)
@@ -84,7 +88,7 @@ def test_random_matrices_every_element_and_against_the_oracle(dtype, ws):
         print("getrf", dtype.__name__, m, n, "panel", panel, "ws", ws, "max err/bound", ratio)
 
 
-@pytest.mark.parametrize("ws", [False, True])
+@pytest.mark.parametrize("ws", [False, True, "auto"])
 def test_tie_rule_and_zero_pivots(ws):
     def run_getrf(*a):
         return globals()["run_getrf"](*a, ws=ws)
@@ -125,7 +129,7 @@ def test_tie_rule_and_zero_pivots(ws):
         check_valid(n, n, A, n, F, n, ipiv, oracle.U64)
 
 
-@pytest.mark.parametrize("ws", [False, True])
+@pytest.mark.parametrize("ws", [False, True, "auto"])
 @pytest.mark.parametrize("dtype,n", [(np.float64, 4096), (np.float64, 8192), (np.float32, 8192)])
 def test_full_size_sampled(dtype, n, ws):
     """The sizes of the sweep: legal interchanges, multipliers within one, the residual bound on 16 full rows,
@@ -149,10 +153,11 @@ def test_on_a_stream_of_the_callers_and_twice_the_same_bits():
     rng = si.rng_for(314, 0)
     n = 900
     A = si.uniform(rng, n, n, n)
-    F1, p1, i1 = run_getrf(n, n, A, n)
     side = torch.cuda.Stream()
-    F2, p2, i2 = run_getrf(n, n, A, n, stream=side)
-    assert i1 == 0 and i2 == 0 and np.array_equal(p1, p2) and np.array_equal(F1, F2)
+    for ws in (False, "auto"):
+        F1, p1, i1 = run_getrf(n, n, A, n, ws=ws)
+        F2, p2, i2 = run_getrf(n, n, A, n, stream=side, ws=ws)
+        assert i1 == 0 and i2 == 0 and np.array_equal(p1, p2) and np.array_equal(F1, F2)
 
 
 def test_shared_panels_agree_with_the_leaves_and_repeat_bit_for_bit():
@@ -209,3 +214,30 @@ def test_tall_panels_up_to_one_workgroup_per_compute_unit_and_beyond(dtype):
             assert np.allclose(F, W, rtol=0.0, atol=tol), (m, n)
         I, J = si.sample_indices(rng, m, n, 8, 8, 1 << 12)
         check_valid(m, n, A, m, F, m, ipiv, u, I=I, J=J)
+
+
+def test_factorisations_on_two_streams_at_once_are_ordered_by_the_library():
+    """Two factorisations with shared panels enqueued back to back on two streams, each with panels of 40 or
+    more workgroups, and a third through the caller's own buffer: the library orders them on the device (their
+    workgroups wait for each other, so they must not compete for compute units), and all three give the bits
+    of a factorisation that ran alone."""
+    torch = torch_mod()
+    rng = si.rng_for(318, 0)
+    n = 5200
+    A = si.uniform(rng, n, n, n)
+    want, wpiv, winfo = run_getrf(n, n, A, n, ws="auto")
+    assert winfo == 0
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    dAs = [to_dev(A) for _ in range(3)]
+    pivs = [torch.zeros(n, dtype=torch.int32, device="cuda") for _ in range(3)]
+    infos = [torch.full((1,), -7, dtype=torch.int32, device="cuda") for _ in range(3)]
+    lw = xg.xgemm_getrf_workspace_bytes()
+    work = torch.empty(lw, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    assert xg.xgemm_dgetrf(n, n, dAs[0], n, pivs[0], infos[0], stream=streams[0]) == 0
+    assert xg.xgemm_dgetrf(n, n, dAs[1], n, pivs[1], infos[1], stream=streams[1]) == 0
+    assert xg.xgemm_dgetrf_ws(n, n, dAs[2], n, pivs[2], infos[2], work, lw, stream=streams[2]) == 0
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert int(infos[k].item()) == 0
+        assert np.array_equal(pivs[k].cpu().numpy(), wpiv) and np.array_equal(dAs[k].cpu().numpy(), want), k
