@@ -17,7 +17,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work; they do not synchronise.  All work goes to `stream`
  *     (xgemm_*potrf may also use streams of the library's between a fork from
- *     and a join to `stream`, see there).
+ *     and a join to `stream`, see there; the first xgemm_*getrf of a process on
+ *     a device outside a stream capture allocates an exchange buffer, which may
+ *     synchronise the device that once).
  *   - trans is one of N n T t C c.  For the real routines C means T.
  *   - beta == 0: C is write-only; whatever it held (NaN, Inf) is overwritten.
  *     alpha == 0 or k == 0: A and B are not read (and may be NULL).
