@@ -99,3 +99,38 @@ def test_captured_lu_with_shared_panels_replays_bit_identically():
         torch.cuda.synchronize()
         assert torch.equal(A, want_A) and torch.equal(piv, want_piv), f"replay {rep} differs from the eager run"
         assert int(info.item()) == 0
+
+
+def test_captured_plain_lu_allocates_nothing_and_replays_bit_identically():
+    """Under capture xgemm_dgetrf may neither allocate its exchange buffer nor wait for the library's event:
+    panels of more than 128 rows go to the leaves of one workgroup each, the others stay in LDS.  The capture
+    succeeds, every replay gives the same bits, and they are a valid factorisation."""
+    import oracle
+    from lu_util import check_valid
+    torch = torch_mod()
+    xg.xgemm_tuning_reset()
+    rng = si.rng_for(192, 0)
+    n = 700
+    A_host = si.uniform(rng, n, n)
+    A0 = to_dev(A_host)
+    A = A0.clone()
+    piv = torch.zeros(n, dtype=torch.int32, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        assert xg.xgemm_dgetrf(n, n, A, n, piv, info) == 0
+    first = None
+    for rep in range(3):
+        A.copy_(A0)
+        piv.fill_(-3)
+        info.fill_(7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(info.item()) == 0
+        got = (A.clone(), piv.clone())
+        if first is None:
+            first = got
+        assert torch.equal(got[0], first[0]) and torch.equal(got[1], first[1]), f"replay {rep} differs from the first"
+    check_valid(n, n, A_host, n, first[0].cpu().numpy(), n, first[1].cpu().numpy(), oracle.U64)
