@@ -7,14 +7,18 @@
 // Organisation.  The matrix is halved recursively by columns (left half; triangular solve and product
 // for the right half; right half), so that all arithmetic except that of the base panels runs in the
 // solve and product kernels at the greatest depth there is.  A base panel (at most 128 columns) is
-//   - with a caller's exchange buffer (xgemm_*getrf_ws): factored by all the workgroups its rows need
-//     at once, each holding a stripe of rows in LDS, the pivot of a column agreed through the buffer
-//     (getrf_coop_kernel; the only kernel of the library in which a workgroup waits for another);
-//   - without: halved further down to leaves of up to LEAF columns, each factored by ONE workgroup
-//     (getf2_kernel): the search for the pivot is a reduction inside the workgroup, a leaf costs one
-//     launch, not one per column, and carries its interchanges through the columns of its base panel.
-//     Two leaves side by side run without a launch between them: the left one also solves for the
-//     block row of U above the right one, the right one applies the left one's update as it loads.
+//   - where exchange memory is at hand (the caller's, xgemm_*getrf_ws, or the buffer the library allocates
+//     per device on the first call outside a stream capture) or the panel has at most 128 rows: factored by
+//     all the workgroups its rows need at once, each holding a stripe of rows in LDS, the pivot of a column
+//     agreed through the exchange memory (getrf_coop_kernel; the only kernel of the library in which a
+//     workgroup waits for another, which is why such factorisations are ordered one behind the other on a
+//     device, see getrf_impl);
+//   - otherwise (a captured call without a buffer, a panel taller than the device has compute units for):
+//     halved further down to leaves of up to LEAF columns, each factored by ONE workgroup (getf2_kernel):
+//     the search for the pivot is a reduction inside the workgroup, a leaf costs one launch, not one per
+//     column, and carries its interchanges through the columns of its base panel.  Two leaves side by side
+//     run without a launch between them: the left one also solves for the block row of U above the right
+//     one, the right one applies the left one's update as it loads.
 // A base panel's interchanges are applied to the other columns of every enclosing half by laswp_kernel.
 #include "../../include/xgemm.h"
 #include "../../include/xgemm_tuning.h"
