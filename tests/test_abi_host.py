@@ -191,6 +191,7 @@ def test_getrf_illegal_arguments(fn):
     assert xg.xgemm_force_getrf_spin_limit(-1) == -1 and xg.xgemm_force_getrf_spin_limit(5) == 0
     assert xg.xgemm_force_getrf_poll_delay(-1, 0) == -1 and xg.xgemm_force_getrf_poll_delay(0, 2000) == -1
     assert xg.xgemm_force_getrf_poll_delay(4, 4) == 0
+    assert xg.xgemm_force_getrf_shared(1) == -1 and xg.xgemm_force_getrf_shared(0) == 0 and xg.xgemm_force_getrf_shared(-1) == 0
     xg.xgemm_tuning_reset()
 
 
