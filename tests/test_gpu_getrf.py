@@ -241,3 +241,21 @@ def test_factorisations_on_two_streams_at_once_are_ordered_by_the_library():
     for k in range(3):
         assert int(infos[k].item()) == 0
         assert np.array_equal(pivs[k].cpu().numpy(), wpiv) and np.array_equal(dAs[k].cpu().numpy(), want), k
+
+
+def test_many_random_shapes_give_the_same_bits_on_every_run_and_through_either_buffer():
+    """The pivot of a column is agreed between workgroups that run at their own pace; nothing in the result may
+    depend on who arrives when.  Forty random shapes, both precisions: the library's buffer, a caller's buffer and
+    the library's again give the same factors and interchanges bit for bit."""
+    torch = torch_mod()
+    lw = xg.xgemm_getrf_workspace_bytes()
+    work = torch.empty(lw, dtype=torch.uint8, device="cuda")
+    shapes = np.random.default_rng(12345)
+    for it in range(40):
+        m, n = int(shapes.integers(200, 7000)), int(shapes.integers(200, 2500))
+        dtype = np.float64 if it % 3 else np.float32
+        A = si.uniform(si.rng_for(319, it), m, n, m, dtype)
+        outs = [run_getrf(m, n, A, m, ws=ws) for ws in ("auto", True, "auto")]
+        assert all(o[2] == 0 for o in outs), (it, m, n)
+        for o in outs[1:]:
+            assert np.array_equal(outs[0][0], o[0]) and np.array_equal(outs[0][1], o[1]), (it, m, n)
