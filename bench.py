@@ -526,7 +526,7 @@ def sweep(torch, np, xg, si, args):
     # LU: xgemm_*getrf (base panels shared by all the workgroups their rows need, through the library's own
     # exchange buffer), the same through a caller's buffer (xgemm_*getrf_ws), and held to the leaves of one
     # workgroup each (what a captured call without a buffer gets)
-    for prec, nsz, ws in (("d", 4096, 0), ("d", 8192, 0), ("d", 16384, 0), ("d", 32768, 0), ("s", 8192, 0), ("s", 16384, 0),
+    for prec, nsz, ws in (("d", 4096, 0), ("d", 8192, 0), ("d", 16384, 0), ("d", 32768, 0), ("s", 8192, 0), ("s", 16384, 0), ("s", 32768, 0),
                           ("d", 8192, 1), ("d", 16384, 1), ("s", 8192, 1),
                           ("d", 4096, 2), ("d", 8192, 2), ("d", 16384, 2), ("s", 8192, 2)):
         name = f"{prec}getrf{('', '_ws', ' (leaves only)')[ws]} {nsz}"
