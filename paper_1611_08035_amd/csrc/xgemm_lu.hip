@@ -665,6 +665,7 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
         int p = r;
         int spins = 0;
         bool fail = false;
+        bool released = false;                              // the communicator has passed barrier C already
         if (comm) {
             if (G > 1) {
                 const __amdgpu_buffer_rsrc_t r_hdr = __builtin_amdgcn_make_buffer_rsrc(x_hdr + (size_t)par * COOP_GMAX * 16, 0,
@@ -826,8 +827,14 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                         const int d = lane + 64 * q, dq = d < nb ? d : nb - 1;
                         pr[q] = P[dq * LS + ibs];
                     }
+                    const T lb_raw = P[c * LS + ibs];
+                    // that was the last look at the stripe: the computing waves may start on this pivot while the rows
+                    // are worked out and published
+                    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): what was read from LDS is in registers
+                    __syncthreads();                        // C
+                    released = true;
                     const bool moved_b = exch && i0 + ibs == p, moved_t = exch && i0 + it == p;
-                    const T l_b = scaled(moved_b ? t0 : P[c * LS + ibs], how, rcp);
+                    const T l_b = scaled(moved_b ? t0 : lb_raw, how, rcp);
                     const T l_t = scaled(moved_t ? t0 : lt_raw, how, rcp);
 #pragma unroll
                     for (int q = 0; q < COOP_NB / 64; ++q) {
@@ -842,7 +849,7 @@ __global__ void __launch_bounds__(RPW * TPR + 64) getrf_coop_kernel(T *A, int64_
                 }
             }
         }
-        __syncthreads();                                    // C: pivot row and row r in LDS, what to do with them known
+        if (!released) __syncthreads();                     // C: pivot row and row r in LDS, what to do with them known
         if (s_abort) { aborted = true; c_reached = c; break; }
         if (comm) continue;
         // the computing waves apply the pivot: the two rows change places, the column is scaled, the columns on its
